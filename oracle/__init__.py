@@ -1,0 +1,185 @@
+"""Python face of the CPU oracle (test infrastructure, not product code).
+
+Compiles ``retexo_oracle.c`` with gcc on first use and exposes its functions
+on numpy arrays.  Only tests, the smoke check and the benchmark's
+``cpu_baseline`` leg import this package; the GPU library never does, and this
+package never touches the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "retexo_oracle.c")
+_LIB = os.path.join(_HERE, "libretexo_oracle.so")
+
+MODES = {"mean": 0, "sum": 1, "gcn_sym": 2, "gat_softmax": 3}
+
+
+def build(force: bool = False) -> str:
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i64, i32p, i64p = C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+        f32p, f64p = C.POINTER(C.c_float), C.POINTER(C.c_double)
+        lib.oracle_threads.restype = C.c_int
+        lib.oracle_csr_from_coo.restype = i64
+        lib.oracle_csr_from_coo.argtypes = [i64, i32p, i32p, i64, C.c_int, i64p, i32p]
+        lib.oracle_degree.restype = None
+        lib.oracle_degree.argtypes = [i64, i64p, i32p, f32p]
+        lib.oracle_transform.restype = None
+        lib.oracle_transform.argtypes = [i64, i64p, i64, i64, f32p, i64, f32p, f32p, C.c_int, f64p]
+        lib.oracle_aggregate.restype = None
+        lib.oracle_aggregate.argtypes = [C.c_int, i64, i64p, i64p, i32p, f32p, i64, C.c_int,
+                                         f32p, i64, f32p, f32p, C.c_double, C.c_int, f64p]
+        lib.oracle_gat_alpha.restype = None
+        lib.oracle_gat_alpha.argtypes = [i64, C.c_int, i64p, i32p, i64, C.c_int, f32p, i64,
+                                         f32p, f32p, C.c_double, f64p]
+        _lib = lib
+    return _lib
+
+
+def _p(a: Optional[np.ndarray], ctype):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def threads() -> int:
+    return int(_load().oracle_threads())
+
+
+def csr_from_coo(src, dst, n_nodes: int, add_self_loops: bool):
+    """-> (row_ptr int64[N+1], col_idx int32[nnz])"""
+    src, dst = _c(src, np.int32), _c(dst, np.int32)
+    assert src.shape == dst.shape and src.ndim == 1
+    row_ptr = np.empty(n_nodes + 1, np.int64)
+    col = np.empty(2 * src.size + n_nodes + 1, np.int32)
+    nnz = _load().oracle_csr_from_coo(src.size, _p(src, C.c_int32), _p(dst, C.c_int32),
+                                      n_nodes, int(add_self_loops),
+                                      _p(row_ptr, C.c_int64), _p(col, C.c_int32))
+    if nnz < 0:
+        raise ValueError("oracle_csr_from_coo failed with %d" % nnz)
+    return row_ptr, col[:nnz].copy()
+
+
+def degree(row_ptr):
+    """-> (deg int32[N], dinv float32[N])"""
+    row_ptr = _c(row_ptr, np.int64)
+    n = row_ptr.size - 1
+    deg = np.empty(n, np.int32)
+    dinv = np.empty(n, np.float32)
+    _load().oracle_degree(n, _p(row_ptr, C.c_int64), _p(deg, C.c_int32), _p(dinv, C.c_float))
+    return deg, dinv
+
+
+def _matrix(a):
+    a = np.asarray(a)
+    assert a.dtype == np.float32 and a.ndim == 2 and a.strides[1] == 4 and a.strides[0] % 4 == 0
+    return a, a.strides[0] // 4
+
+
+def transform(H, d_in: int, W, b=None, relu: bool = False, rows=None) -> np.ndarray:
+    """Z = act(H[:, :d_in] W + b) in float64, for all rows or for ``rows``."""
+    H, ldh = _matrix(H)
+    W = _c(W, np.float32)
+    assert W.shape[0] == d_in and d_in <= H.shape[1]
+    d_out = W.shape[1]
+    b = None if b is None else _c(b, np.float32)
+    rows = None if rows is None else _c(rows, np.int64)
+    n = H.shape[0] if rows is None else rows.size
+    Z = np.empty((n, d_out), np.float64)
+    _load().oracle_transform(n, _p(rows, C.c_int64), d_in, d_out, _p(H, C.c_float), ldh,
+                             _p(W, C.c_float), _p(b, C.c_float), int(relu), _p(Z, C.c_double))
+    return Z
+
+
+def aggregate(mode: str, row_ptr, col_idx, Z, F: int, *, heads: int = 1, a_src=None, a_dst=None,
+              slope: float = 0.2, self_concat: bool = False, rows=None) -> np.ndarray:
+    """Aggregate Z[:, :F] over the CSR, float64 output [n, F or 2F]."""
+    Z, ldz = _matrix(Z)
+    row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
+    n_nodes = row_ptr.size - 1
+    assert Z.shape[0] >= n_nodes and F <= Z.shape[1]
+    dinv = None
+    if mode == "gcn_sym":
+        _, dinv = degree(row_ptr)
+    if mode == "gat_softmax":
+        assert F % heads == 0
+        a_src, a_dst = _c(a_src, np.float32), _c(a_dst, np.float32)
+        assert a_src.size == F and a_dst.size == F
+    rows = None if rows is None else _c(rows, np.int64)
+    n = n_nodes if rows is None else rows.size
+    out = np.empty((n, 2 * F if self_concat else F), np.float64)
+    _load().oracle_aggregate(MODES[mode], n, _p(rows, C.c_int64), _p(row_ptr, C.c_int64),
+                             _p(col_idx, C.c_int32), _p(dinv, C.c_float), F, heads,
+                             _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
+                             float(slope), int(self_concat), _p(out, C.c_double))
+    return out
+
+
+def gat_alpha(v: int, h: int, row_ptr, col_idx, Z, F: int, heads: int, a_src, a_dst,
+              slope: float = 0.2) -> np.ndarray:
+    Z, ldz = _matrix(Z)
+    row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
+    a_src, a_dst = _c(a_src, np.float32), _c(a_dst, np.float32)
+    deg = int(row_ptr[v + 1] - row_ptr[v])
+    alpha = np.empty(deg, np.float64)
+    _load().oracle_gat_alpha(v, h, _p(row_ptr, C.c_int64), _p(col_idx, C.c_int32), F, heads,
+                             _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
+                             float(slope), _p(alpha, C.c_double))
+    return alpha
+
+
+def round_(mode: str, row_ptr, col_idx, H, d_in: int, W, b, *, relu: bool = False, heads: int = 1,
+           a_src=None, a_dst=None, slope: float = 0.2, self_concat: bool = False,
+           rows=None) -> np.ndarray:
+    """One lazy-message-passing round: Z = act(H W + b) (W None: Z = H), stored
+    as float32 the way the real pipeline stores it, then aggregated.
+
+    With ``rows`` given only those output rows are produced, and the transform
+    is evaluated only where the aggregation will look (the rows themselves and
+    their neighbours); every other row of the intermediate is NaN so that a
+    stray read shows up.
+    """
+    row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
+    n_nodes = row_ptr.size - 1
+    if W is None:
+        Z32, F = H, d_in
+    else:
+        F = np.asarray(W).shape[1]
+        if rows is None:
+            Z32 = transform(H, d_in, W, b, relu).astype(np.float32)
+        else:
+            rows = _c(rows, np.int64)
+            need = [rows]
+            for v in rows:
+                need.append(col_idx[row_ptr[v]:row_ptr[v + 1]].astype(np.int64))
+            need = np.unique(np.concatenate(need))
+            Z32 = np.full((n_nodes, F), np.nan, np.float32)
+            Z32[need] = transform(H, d_in, W, b, relu, rows=need).astype(np.float32)
+    return aggregate(mode, row_ptr, col_idx, Z32, F, heads=heads, a_src=a_src, a_dst=a_dst,
+                     slope=slope, self_concat=self_concat, rows=rows)

@@ -1,0 +1,258 @@
+/*
+ * CPU oracle for the embed-and-aggregate step of lazy message passing.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It exists to say what the GPU library must
+ * compute; it is deliberately plain and slow, shares no code with the GPU
+ * path, and nothing in the product imports or links it.  Only the tests, the
+ * smoke check and the benchmark's cpu_baseline leg call it.
+ *
+ * What is defined here and where it comes from:
+ *
+ *  - One GNN layer is Q^m_v = f( COMBINE( Q^{m-1}_v , AGGR_{u in N(v)} Q^{m-1}_u ) ),
+ *    Q^0 = the raw features (Eq. 1 of the paper, section "Architecture of
+ *    Classical GNNs").  f is a fully connected layer followed by ReLU,
+ *    COMBINE is concatenation (the gloss under Eq. 1).
+ *  - Lazy message passing (section "Lazy Message Passing") freezes a trained
+ *    layer, evaluates it for every node and then performs one aggregation
+ *    over the graph; the very first aggregation is over the raw features.
+ *    So one round is  Z = act(H W + b)  (or Z = H for the first round)
+ *    followed by AGGR over the graph.
+ *  - The graph is undirected (section "Edge-partitioned Distributed Setup"),
+ *    so every pair {u,v} contributes the two directed entries (u,v), (v,u).
+ *  - The paper names its three model families (GCN, GraphSAGE, GAT) but does
+ *    not print their aggregators.  They are taken in their standard forms:
+ *      mean      out_v = (1/deg v) sum_{u in N(v)} z_u
+ *      sum       out_v = sum_{u in N(v)} z_u
+ *      gcn_sym   out_v = sum_{u in N~(v)} z_u / sqrt(d~_v d~_u), N~ contains v
+ *                itself through an explicit self-loop entry, d~ = row length
+ *      gat       per head h:  e_uv = LeakyReLU(<a_src_h, z_u,h> + <a_dst_h, z_v,h>),
+ *                alpha_uv = softmax over u in N(v) of e_uv,
+ *                out_v,h = sum_u alpha_uv z_u,h
+ *    An empty neighbourhood gives a zero aggregate in every mode.
+ *
+ * Everything accumulates in double and consumes the float inputs exactly.
+ * The one float quantity is dinv[v] = 1/sqrt(deg v), which is DEFINED as the
+ * correctly rounded single-precision sqrt followed by the correctly rounded
+ * single-precision divide, so that it can be compared bit for bit.
+ *
+ * No worked numeric example exists in the paper.  The pins that tie these
+ * functions to something other than themselves (dense-matrix brute force,
+ * closed forms on regular graphs, hand-computed values, invariants) live in
+ * tests/test_oracle_*.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_MEAN = 0, ORACLE_SUM = 1, ORACLE_GCN_SYM = 2, ORACLE_GAT_SOFTMAX = 3 };
+
+int oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * CSR of the undirected simple graph given by raw pairs.
+ *   - each pair (u,v), u != v, yields entries (row u, col v) and (row v, col u)
+ *   - pairs with u == v are dropped
+ *   - if add_self_loops, exactly one entry (v,v) is then added for every v
+ *   - repeated entries are kept once; columns ascend inside a row
+ * row_ptr has N+1 entries; col_idx must have room for 2*n_pairs + N entries.
+ * Returns nnz, or -1 if a node id is outside [0,N), -2 if out of memory.
+ */
+int64_t oracle_csr_from_coo(int64_t n_pairs, const int32_t *src, const int32_t *dst,
+                            int64_t N, int add_self_loops,
+                            int64_t *row_ptr, int32_t *col_idx)
+{
+    int64_t *start = (int64_t *)calloc((size_t)N + 1, sizeof(int64_t));
+    if (!start) return -2;
+    for (int64_t e = 0; e < n_pairs; ++e) {
+        if (src[e] < 0 || src[e] >= N || dst[e] < 0 || dst[e] >= N) { free(start); return -1; }
+        if (src[e] == dst[e]) continue;
+        start[src[e] + 1]++;
+        start[dst[e] + 1]++;
+    }
+    if (add_self_loops)
+        for (int64_t v = 0; v < N; ++v) start[v + 1]++;
+    for (int64_t v = 0; v < N; ++v) start[v + 1] += start[v];
+    int64_t total = start[N];
+    int32_t *raw = (int32_t *)malloc((size_t)(total > 0 ? total : 1) * sizeof(int32_t));
+    int64_t *fill = (int64_t *)malloc(((size_t)N + 1) * sizeof(int64_t));
+    if (!raw || !fill) { free(start); free(raw); free(fill); return -2; }
+    memcpy(fill, start, ((size_t)N + 1) * sizeof(int64_t));
+    for (int64_t e = 0; e < n_pairs; ++e) {
+        int32_t u = src[e], v = dst[e];
+        if (u == v) continue;
+        raw[fill[u]++] = v;
+        raw[fill[v]++] = u;
+    }
+    if (add_self_loops)
+        for (int64_t v = 0; v < N; ++v) raw[fill[v]++] = (int32_t)v;
+    /* sort every row, then copy it out without repeats */
+    int64_t nnz = 0;
+    row_ptr[0] = 0;
+    for (int64_t v = 0; v < N; ++v) {
+        int64_t lo = start[v], hi = start[v + 1];
+        qsort(raw + lo, (size_t)(hi - lo), sizeof(int32_t), cmp_i32);
+        for (int64_t k = lo; k < hi; ++k)
+            if (k == lo || raw[k] != raw[k - 1]) col_idx[nnz++] = raw[k];
+        row_ptr[v + 1] = nnz;
+    }
+    free(start); free(raw); free(fill);
+    return nnz;
+}
+
+/* deg[v] = row length; dinv[v] = 1/sqrt(deg v) in correctly rounded float
+ * arithmetic, 0 for an empty row. */
+void oracle_degree(int64_t N, const int64_t *row_ptr, int32_t *deg, float *dinv)
+{
+    for (int64_t v = 0; v < N; ++v) {
+        int64_t d = row_ptr[v + 1] - row_ptr[v];
+        deg[v] = (int32_t)d;
+        if (d > 0) {
+            volatile float s = sqrtf((float)d);
+            volatile float r = 1.0f / s;
+            dinv[v] = r;
+        } else {
+            dinv[v] = 0.0f;
+        }
+    }
+}
+
+/*
+ * Z[i,:] = act( H[rows[i],:] W + b ) for i < n_rows (rows == NULL: rows[i] = i).
+ * H is [*, ldh] floats of which the first D_in columns are used, W is
+ * [D_in, D_out] row-major, b is [D_out] or NULL, act is ReLU when relu != 0.
+ * Z is [n_rows, D_out] doubles.
+ */
+void oracle_transform(int64_t n_rows, const int64_t *rows, int64_t D_in, int64_t D_out,
+                      const float *H, int64_t ldh, const float *W, const float *b,
+                      int relu, double *Z)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        int64_t r = rows ? rows[i] : i;
+        for (int64_t j = 0; j < D_out; ++j) {
+            double acc = b ? (double)b[j] : 0.0;
+            for (int64_t k = 0; k < D_in; ++k)
+                acc += (double)H[r * ldh + k] * (double)W[k * D_out + j];
+            if (relu && acc < 0.0) acc = 0.0;
+            Z[i * D_out + j] = acc;
+        }
+    }
+}
+
+static double leaky(double x, double slope) { return x > 0.0 ? x : slope * x; }
+
+/*
+ * out[i,:] = aggregate of row rows[i] (rows == NULL: all rows, n_rows == N).
+ * Z is [N, ldz] floats, first F columns used.  For gat, F = heads * Dh,
+ * a_src and a_dst are [heads, Dh].  dinv (gcn_sym only) is the float array
+ * oracle_degree produced.  With self_concat the output row is 2F wide: the
+ * node's own Z row first, its aggregate second; otherwise F wide.
+ * out is doubles, row pitch F or 2F.
+ */
+void oracle_aggregate(int mode, int64_t n_rows, const int64_t *rows,
+                      const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
+                      int64_t F, int heads, const float *Z, int64_t ldz,
+                      const float *a_src, const float *a_dst, double slope,
+                      int self_concat, double *out)
+{
+    const int64_t pitch = self_concat ? 2 * F : F;
+    const int64_t Dh = (mode == ORACLE_GAT_SOFTMAX) ? F / heads : F;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t v = rows ? rows[i] : i;
+        double *o = out + i * pitch;
+        if (self_concat) {
+            for (int64_t j = 0; j < F; ++j) o[j] = (double)Z[v * ldz + j];
+            o += F;
+        }
+        const int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
+        const int64_t deg = hi - lo;
+        for (int64_t j = 0; j < F; ++j) o[j] = 0.0;
+        if (deg == 0) continue;
+
+        if (mode == ORACLE_SUM || mode == ORACLE_MEAN) {
+            for (int64_t j = 0; j < F; ++j) {
+                double s = 0.0;
+                for (int64_t e = lo; e < hi; ++e) s += (double)Z[(int64_t)col_idx[e] * ldz + j];
+                o[j] = (mode == ORACLE_MEAN) ? s / (double)deg : s;
+            }
+        } else if (mode == ORACLE_GCN_SYM) {
+            for (int64_t j = 0; j < F; ++j) {
+                double s = 0.0;
+                for (int64_t e = lo; e < hi; ++e) {
+                    int64_t u = col_idx[e];
+                    s += (double)dinv[v] * (double)dinv[u] * (double)Z[u * ldz + j];
+                }
+                o[j] = s;
+            }
+        } else { /* ORACLE_GAT_SOFTMAX */
+            double *score = (double *)malloc((size_t)deg * sizeof(double));
+            for (int h = 0; h < heads; ++h) {
+                const float *as = a_src + (int64_t)h * Dh, *ad = a_dst + (int64_t)h * Dh;
+                double er = 0.0;
+                for (int64_t d = 0; d < Dh; ++d) er += (double)ad[d] * (double)Z[v * ldz + h * Dh + d];
+                double m = -INFINITY;
+                for (int64_t e = lo; e < hi; ++e) {
+                    int64_t u = col_idx[e];
+                    double el = 0.0;
+                    for (int64_t d = 0; d < Dh; ++d) el += (double)as[d] * (double)Z[u * ldz + h * Dh + d];
+                    score[e - lo] = leaky(el + er, slope);
+                    if (score[e - lo] > m) m = score[e - lo];
+                }
+                double denom = 0.0;
+                for (int64_t e = lo; e < hi; ++e) {
+                    score[e - lo] = exp(score[e - lo] - m);
+                    denom += score[e - lo];
+                }
+                for (int64_t d = 0; d < Dh; ++d) {
+                    double s = 0.0;
+                    for (int64_t e = lo; e < hi; ++e)
+                        s += score[e - lo] * (double)Z[(int64_t)col_idx[e] * ldz + h * Dh + d];
+                    o[h * Dh + d] = s / denom;
+                }
+            }
+            free(score);
+        }
+    }
+}
+
+/*
+ * Attention coefficients alpha_uv of one row and one head, in CSR entry
+ * order (deg doubles).  Same formula as above, exposed so that a test can
+ * look at the weights themselves.
+ */
+void oracle_gat_alpha(int64_t v, int h, const int64_t *row_ptr, const int32_t *col_idx,
+                      int64_t F, int heads, const float *Z, int64_t ldz,
+                      const float *a_src, const float *a_dst, double slope, double *alpha)
+{
+    const int64_t Dh = F / heads, lo = row_ptr[v], hi = row_ptr[v + 1];
+    const float *as = a_src + (int64_t)h * Dh, *ad = a_dst + (int64_t)h * Dh;
+    double er = 0.0, m = -INFINITY, denom = 0.0;
+    for (int64_t d = 0; d < Dh; ++d) er += (double)ad[d] * (double)Z[v * ldz + h * Dh + d];
+    for (int64_t e = lo; e < hi; ++e) {
+        int64_t u = col_idx[e];
+        double el = 0.0;
+        for (int64_t d = 0; d < Dh; ++d) el += (double)as[d] * (double)Z[u * ldz + h * Dh + d];
+        alpha[e - lo] = leaky(el + er, slope);
+        if (alpha[e - lo] > m) m = alpha[e - lo];
+    }
+    for (int64_t e = lo; e < hi; ++e) { alpha[e - lo] = exp(alpha[e - lo] - m); denom += alpha[e - lo]; }
+    for (int64_t e = lo; e < hi; ++e) alpha[e - lo] /= denom;
+}
