@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the embed-and-aggregate path on one MI355X.
+
+A step is one pass of the whole path over one synthetic workload whose inputs
+already sit in HBM: CSR construction from the raw pair list, plan creation,
+then every round (dense transform + neighbourhood aggregation) and the final
+classifier transform.  The headline value is the edge*feature arithmetic of
+all aggregations in the pass (2 flop per CSR entry and feature column) divided
+by the wall time of the whole step.
+
+Prints one JSON line.  Extra objects:
+  roofline      the dominant kernel (the widest aggregation) against the 8 TB/s HBM peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant aggregation measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (0-4)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = per-workload default)")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(n, nnz, F, concat, gat_heads=0):
+    """Bytes one aggregation must move in the gather model: one F-float row per
+    CSR entry, the index arrays, the output, and the self copy if concatenated."""
+    b = 4 * nnz * F + 4 * nnz + 8 * (n + 1) + 4 * n * F
+    if concat:
+        b += 2 * 4 * n * F           # read z_v, write it into the self half
+    if gat_heads:
+        b += 4 * nnz * gat_heads + 8 * n * gat_heads
+    return b
+
+
+def cpu_baseline(w, src, dst, feats, params, n_rows):
+    """Oracle cost per unit on a bounded sample, scaled to one whole pass."""
+    import oracle
+    from paper_2302_13053_amd import workloads as wl
+    n = w.n_nodes
+    t0 = time.perf_counter()
+    m = min(src.size, 4_000_000)
+    oracle.csr_from_coo(src[:m], dst[:m], n, w.self_loops)
+    t_csr = (time.perf_counter() - t0) * (src.size / max(m, 1))
+    rp, ci = oracle.csr_from_coo(src, dst, n, w.self_loops)     # needed to run the sample; not timed
+    rng = np.random.Generator(np.random.Philox(key=12345))
+    rows = np.sort(rng.choice(n, size=min(n_rows, n), replace=False)).astype(np.int64)
+    nnz = int(rp[-1])
+    sample_edges = int((rp[rows + 1] - rp[rows]).sum())
+    total = t_csr
+    spent = 0.0
+    for i, st in enumerate(w.stages):
+        p = params[i]
+        if i == 0:
+            H = feats
+        else:
+            H = wl.random_matrix(n, st.d_in, 100 + i, ld=wl.pad_ld(st.d_in))
+        if st.w:
+            t0 = time.perf_counter()
+            oracle.transform(H, st.d_in, p.W, p.b, st.relu, rows=rows)
+            dt = time.perf_counter() - t0
+            spent += dt
+            total += dt * n / rows.size
+        if st.kind == "round":
+            Z = H if not st.w else wl.random_matrix(n, st.d_out, 200 + i, ld=wl.pad_ld(st.d_out))
+            t0 = time.perf_counter()
+            oracle.aggregate(st.mode, rp, ci, Z, st.d_out, heads=st.heads, a_src=p.a_src, a_dst=p.a_dst,
+                             self_concat=st.concat, rows=rows)
+            dt = time.perf_counter() - t0
+            spent += dt
+            total += dt * nnz / max(sample_edges, 1)
+    flops = sum(2.0 * nnz * st.d_out for st in w.stages if st.kind == "round")
+    return {
+        "value": flops / total / 1e9,
+        "unit": "GFLOP/s (edge*feature, whole pass)",
+        "cores": oracle.threads(),
+        "kind": "oracle",
+        "sample": "%d random rows of every stage (%d CSR entries) plus CSR build of the first %d pairs, "
+                  "%.1f s of oracle time, scaled per row / per entry / per pair to one whole pass"
+                  % (rows.size, sample_edges, m, spent),
+        "estimated_pass_seconds": total,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2302_13053_amd import binding as B
+    from paper_2302_13053_amd import harness as Hn
+    from paper_2302_13053_amd import workloads as wl
+
+    B.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    w = wl.workload(args.config)
+    t0 = time.perf_counter()
+    src, dst = wl.make_graph(w)
+    feats = wl.make_features(w, ld=wl.pad_ld(w.feat_dim))
+    params = wl.make_params(w)
+    t_gen = time.perf_counter() - t0
+
+    pipe = Hn.Pipeline(w, src, dst, feats, params)
+    for _ in range(args.warmup):
+        pipe.run()
+    torch.cuda.synchronize()
+
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pipe.run(events=events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    n, nnz = w.n_nodes, pipe.graph.nnz
+    # per-step-kind mean over the timed steps, from events on the launch stream
+    per = {}
+    for label, a, b in events:
+        per.setdefault(label, []).append(a.elapsed_time(b))
+    stages = []
+    flops = 0.0
+    dominant = None
+    for i, st in enumerate(w.stages):
+        label = "%s%d" % (st.kind, i)
+        ms = float(np.mean(per[label]))
+        rec = {"stage": label, "ms": ms, "d_in": st.d_in, "d_out": st.d_out}
+        if st.kind == "round":
+            ef = float(nnz) * st.d_out
+            flops += 2.0 * ef
+            rec["mode"] = st.mode
+            rec["edge_features"] = ef
+            rec["identity_transform"] = not st.w
+            if not st.w:
+                gb = algorithmic_bytes(n, nnz, st.d_out, st.concat, st.heads if st.mode == "gat_softmax" else 0)
+                rec["agg_effective_GBs"] = gb / ms / 1e6
+            if dominant is None or ef > dominant[1]:
+                dominant = (i, ef)
+        if st.w:
+            rec["transform_gflop"] = 2.0 * n * st.d_in * st.d_out / 1e9
+        stages.append(rec)
+
+    # roofline of the dominant aggregation: time it alone (aggregate call only) on the launch stream
+    di = dominant[0]
+    dst_stage = w.stages[di]
+    gat = dst_stage.mode == "gat_softmax"
+    F = dst_stage.d_out
+    if dst_stage.w:
+        # the aggregation's input is the transform's output; a resident random matrix of that shape stands in
+        Zin = torch.empty((n, wl.pad_ld(F)), dtype=torch.float32, device="cuda").normal_()
+    else:
+        Zin = pipe.H0 if di == 0 else pipe.outs[di - 1]
+    W_, b_, a_s, a_d = pipe.params[di]
+    agg_out = torch.empty((n, wl.pad_ld(dst_stage.out_width)), dtype=torch.float32, device="cuda")
+    ws = Hn.ws_tensor(B.retexo_workspace_bytes(pipe.graph.plan, F, B.MODES[dst_stage.mode], dst_stage.heads,
+                                               B.F_SELF_CONCAT if dst_stage.concat else 0))
+    reps = max(3, args.steps)
+    Hn.aggregate(pipe.graph, dst_stage.mode, Zin, F, heads=dst_stage.heads, a_src=a_s, a_dst=a_d,
+                 concat=dst_stage.concat, out=agg_out, workspace=ws)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        Hn.aggregate(pipe.graph, dst_stage.mode, Zin, F, heads=dst_stage.heads, a_src=a_s, a_dst=a_d,
+                     concat=dst_stage.concat, out=agg_out, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    agg_ms = e0.elapsed_time(e1) / reps
+    gbytes = algorithmic_bytes(n, nnz, F, dst_stage.concat, dst_stage.heads if gat else 0)
+    achieved = gbytes / agg_ms / 1e6
+    roofline = {
+        "bound": "hbm",
+        "kernel": "agg_gat_kernel" if gat else "agg_linear_kernel",
+        "stage": "round%d aggregation, F=%d" % (di, F),
+        "achieved": achieved,
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+        "algorithmic_bytes": gbytes,
+        "ms_per_launch": agg_ms,
+        "edge_features_per_s": float(nnz) * F / (agg_ms * 1e-3),
+    }
+
+    out = {
+        "metric": "aggregated edge*feature GFLOP/s per lazy-MP pass (whole path: CSR build, plan, all rounds)",
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic (seeded %s graph, %s)" % (w.graph, w.stands_in_for),
+        "config": {"workload": w.name, "config_index": w.index, "family": w.family, "nodes": n,
+                   "raw_pairs": int(src.size), "csr_entries": int(nnz),
+                   "max_degree": B.retexo_plan_max_degree(pipe.graph.plan), "feat_dim": w.feat_dim,
+                   "stages": [st.kind + ":" + (st.mode if st.kind == "round" else "dense") +
+                              ":%d->%d" % (st.d_in, st.d_out) for st in w.stages]},
+        "csr_plan_ms": float(np.mean(per["csr+plan"])),
+        "stages": stages,
+        "input_generation_s": t_gen,
+        "roofline": roofline,
+    }
+    pipe.close()
+    if not args.no_cpu:
+        default_rows = {0: 2708, 1: 19717, 2: 22470, 3: 20000, 4: 100000}[w.index]
+        out["cpu_baseline"] = cpu_baseline(w, src, dst, feats, params, args.cpu_rows or default_rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,189 @@
+/*
+ * retexo.h — C ABI of the MI355X (gfx950) embed-and-aggregate library.
+ *
+ * The library computes the local, single-device half of one lazy
+ * message-passing round (paper: section "Lazy Message Passing"): a trained
+ * layer is frozen, evaluated for every node as a dense transform, and the
+ * result is aggregated over the graph to become the next layer's input.
+ * One round is therefore
+ *        Z   = act(H W + b)                       (f of Eq. 1; identity for round 0)
+ *        out = COMBINE(Z, AGGR_{u in N(v)} Z_u)   (Eq. 1; COMBINE = concatenation)
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; h_* are host
+ *     pointers.  The library never frees or keeps them, except that a plan
+ *     BORROWS the CSR arrays it was created from (they must outlive it).
+ *   - Matrices are fp32, row-major, with a leading dimension (ld*, in floats)
+ *     that may exceed the logical width; padding columns are never written
+ *     and their contents never reach an output.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     retexo_transform / retexo_aggregate / retexo_round only enqueue work:
+ *     they do not allocate, free or synchronise.  retexo_csr_from_coo and
+ *     retexo_plan_create synchronise the stream once; retexo_plan_create also
+ *     allocates the plan's own small arrays.
+ *   - Return value 0 (RETEXO_OK) or a negative retexo_status.  Argument errors
+ *     are detected before any kernel is launched, so no output byte has been
+ *     written when one is returned.
+ *   - Results are bitwise reproducible from call to call for the same plan:
+ *     every output row is owned by one workgroup and no floating-point atomics
+ *     are used.
+ */
+#ifndef RETEXO_H
+#define RETEXO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct retexo_plan retexo_plan;
+
+/* AGGR of Eq. 1 in the forms of the paper's three model families
+ * (evaluation set-up: GCN, GraphSAGE, GAT). deg(v) is the CSR row length. */
+typedef enum {
+    RETEXO_MEAN = 0,        /* (1/deg v) sum_u z_u            — GraphSAGE mean       */
+    RETEXO_SUM = 1,         /* sum_u z_u                                             */
+    RETEXO_GCN_SYM = 2,     /* sum_u z_u / sqrt(deg v deg u)  — GCN; pass a CSR that
+                               already holds one self-loop per node                  */
+    RETEXO_GAT_SOFTMAX = 3  /* sum_u softmax_u(LeakyReLU(<a_src,z_u>+<a_dst,z_v>)) z_u,
+                               independently for each of `heads` column blocks — GAT */
+} retexo_mode;
+
+enum {
+    RETEXO_F_RELU = 1,         /* transform: act = ReLU (Eq. 1's f)                   */
+    RETEXO_F_SELF_CONCAT = 2,  /* aggregate: out row = [ z_v | aggregate ], 2F wide   */
+    RETEXO_F_VALIDATE = 4      /* plan_create: check the CSR on the device first      */
+};
+
+typedef enum {
+    RETEXO_OK = 0,
+    RETEXO_E_NULL = -1,       /* a required pointer is NULL                           */
+    RETEXO_E_SIZE = -2,       /* negative or inconsistent size                        */
+    RETEXO_E_LD = -3,         /* a leading dimension is smaller than the row width    */
+    RETEXO_E_MODE = -4,       /* unknown aggregation mode                             */
+    RETEXO_E_FLAGS = -5,      /* unknown or inapplicable flag bit                     */
+    RETEXO_E_HEADS = -6,      /* heads < 1, heads > 8, or heads does not divide F     */
+    RETEXO_E_CSR = -7,        /* node id out of range / malformed CSR                 */
+    RETEXO_E_WORKSPACE = -8,  /* workspace missing or too small                       */
+    RETEXO_E_ALIAS = -9,      /* output overlaps an input                             */
+    RETEXO_E_HIP = -10,       /* a HIP runtime call failed                            */
+    RETEXO_E_CAPACITY = -11   /* col_idx capacity too small for the CSR               */
+} retexo_status;
+
+const char* retexo_status_string(int status);
+
+/* ---------------------------------------------------------------------------
+ * Graph construction (paper: "The graphs are undirected", section
+ * "Edge-partitioned Distributed Setup").
+ *
+ * Builds the CSR of the undirected simple graph given by n_pairs raw pairs
+ * (d_src[i], d_dst[i]): each pair with u != v yields entries (u,v) and (v,u);
+ * pairs with u == v are dropped; with add_self_loops != 0 exactly one entry
+ * (v,v) is added per node; repeated entries are kept once; columns ascend
+ * within a row.  The result is a unique function of the pair SET.
+ *
+ *   d_row_ptr   [N+1] int64, written; d_row_ptr[N] = nnz
+ *   d_col_idx   [col_capacity] int32, first nnz entries written
+ *   h_nnz       host, optional: receives nnz
+ *   d_workspace at least retexo_csr_workspace_bytes(...) bytes, 256-aligned
+ * Synchronises `stream`.  Errors: RETEXO_E_CSR if any id is outside [0,N)
+ * (nothing written), RETEXO_E_CAPACITY if nnz > col_capacity (nothing written;
+ * *h_nnz still reports the required size), RETEXO_E_WORKSPACE, RETEXO_E_SIZE
+ * (N < 0, n_pairs < 0, N >= 2^31 or 2*n_pairs + N >= 2^31).
+ */
+int64_t retexo_csr_workspace_bytes(int64_t n_pairs, int64_t N, int add_self_loops);
+int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const int32_t* d_dst,
+                        int64_t N, int add_self_loops,
+                        int64_t* d_row_ptr, int32_t* d_col_idx, int64_t col_capacity,
+                        int64_t* h_nnz, void* d_workspace, int64_t workspace_bytes,
+                        void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Plan: per-graph data reused by every round — deg[v] = row length,
+ * dinv[v] = 1/sqrt(deg v) (correctly rounded fp32 sqrt then divide; 0 for an
+ * empty row), and the degree-ordered row schedule used for load balancing.
+ * The plan borrows d_row_ptr / d_col_idx.  Synchronises `stream`.
+ * With RETEXO_F_VALIDATE the CSR is checked first (row_ptr[0] == 0,
+ * non-decreasing, col_idx within [0,N)); a malformed CSR gives RETEXO_E_CSR
+ * and no plan.
+ */
+int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d_row_ptr,
+                       const int32_t* d_col_idx, unsigned flags, void* stream);
+int retexo_plan_destroy(retexo_plan* plan);
+int64_t retexo_plan_num_nodes(const retexo_plan* plan);
+int64_t retexo_plan_nnz(const retexo_plan* plan);
+int32_t retexo_plan_max_degree(const retexo_plan* plan);
+const int32_t* retexo_plan_deg(const retexo_plan* plan);   /* device, [N] */
+const float* retexo_plan_dinv(const retexo_plan* plan);    /* device, [N] */
+/* Copies the plan's arrays into caller-owned device buffers (any may be NULL):
+ * d_deg int32[N], d_dinv float[N], d_order int32[N] (row ids, longest row first,
+ * equal lengths in ascending id order).  Enqueued on `stream`. */
+int retexo_plan_export(const retexo_plan* plan, int32_t* d_deg, float* d_dinv, int32_t* d_order,
+                       void* stream);
+
+/* Bytes of workspace retexo_aggregate (D_in == 0) or retexo_round needs for
+ * rows of width D_out; < 0 is a retexo_status. */
+int64_t retexo_workspace_bytes(const retexo_plan* plan, int64_t D_out, int mode, int heads,
+                               unsigned flags);
+
+/* ---------------------------------------------------------------------------
+ * Dense transform, the f of Eq. 1 (fully connected layer + optional ReLU):
+ *     Z[i, j] = act( sum_k H[i, k] W[k, j] + b[j] ),   i < N, j < D_out
+ *   d_H [N, ldh], first D_in columns used;  d_W [D_in, D_out] row-major, dense;
+ *   d_b [D_out] or NULL;  d_Z [N, ldz], first D_out columns written.
+ * fp32 inputs, fp32 matrix-core accumulation.  flags: RETEXO_F_RELU only.
+ * Z must not overlap H.  N == 0 is a no-op.
+ */
+int retexo_transform(int64_t N, int64_t D_in, int64_t D_out,
+                     const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
+                     unsigned flags, float* d_Z, int64_t ldz, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Neighbourhood aggregation, the AGGR (and COMBINE) of Eq. 1, over the plan's
+ * CSR.  d_Z [N, ldz], first F columns used.  Output row v is
+ *     without RETEXO_F_SELF_CONCAT:  [ aggregate_v ]          (F floats)
+ *     with    RETEXO_F_SELF_CONCAT:  [ z_v | aggregate_v ]    (2F floats)
+ * An empty row aggregates to zeros in every mode.
+ * RETEXO_GAT_SOFTMAX: F = heads * Dh; d_attn_src / d_attn_dst are [heads, Dh];
+ * negative_slope is the LeakyReLU slope.  Other modes ignore those arguments
+ * (heads must still be >= 1).
+ * d_out must not overlap d_Z, with one exception: under RETEXO_F_SELF_CONCAT,
+ * d_Z == d_out and ldz == ldo means "z_v already sits in the first F columns
+ * of out"; then only the aggregate half is written.
+ * d_workspace: retexo_workspace_bytes(plan, F, mode, heads, flags) bytes,
+ * 256-aligned (may be NULL when that is 0).
+ */
+int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, int heads,
+                     const float* d_Z, int64_t ldz,
+                     const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                     unsigned flags, float* d_out, int64_t ldo,
+                     void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * One whole round: retexo_transform followed by retexo_aggregate on the same
+ * stream, Z being kept in the workspace (or directly in out's first D_out
+ * columns under RETEXO_F_SELF_CONCAT).  d_W == NULL means the identity
+ * transform (the first round aggregates the raw features); then D_out must
+ * equal D_in, d_b must be NULL and RETEXO_F_RELU is rejected.
+ * flags: RETEXO_F_RELU (applies to the transform) | RETEXO_F_SELF_CONCAT.
+ * d_workspace: retexo_workspace_bytes(plan, D_out, mode, heads, flags) bytes.
+ */
+int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out, int heads,
+                 const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
+                 const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                 unsigned flags, float* d_out, int64_t ldo,
+                 void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Tuning knobs (process-wide, for experiments; defaults are chosen per shape).
+ * name: "agg_slab_cols" (0 = auto), "agg_slab_major" (-1 auto / 0 / 1),
+ *       "agg_heavy_degree" (rows at least this long get a whole workgroup).
+ * Returns RETEXO_E_FLAGS for an unknown name.
+ */
+int retexo_set_option(const char* name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RETEXO_H */

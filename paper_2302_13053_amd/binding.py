@@ -1,0 +1,181 @@
+"""ctypes binding of libretexo.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+``include/retexo.h`` and takes raw device addresses (ints, e.g.
+``tensor.data_ptr()``) and sizes.  Nothing is computed here, and there is no
+fallback: if the library is missing, ``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libretexo.so")
+
+MEAN, SUM, GCN_SYM, GAT_SOFTMAX = 0, 1, 2, 3
+MODES = {"mean": MEAN, "sum": SUM, "gcn_sym": GCN_SYM, "gat_softmax": GAT_SOFTMAX}
+F_RELU, F_SELF_CONCAT, F_VALIDATE = 1, 2, 4
+
+OK = 0
+E_NULL, E_SIZE, E_LD, E_MODE, E_FLAGS, E_HEADS = -1, -2, -3, -4, -5, -6
+E_CSR, E_WORKSPACE, E_ALIAS, E_HIP, E_CAPACITY = -7, -8, -9, -10, -11
+
+EXPORTS = (
+    "retexo_status_string", "retexo_csr_workspace_bytes", "retexo_csr_from_coo",
+    "retexo_plan_create", "retexo_plan_destroy", "retexo_plan_num_nodes", "retexo_plan_nnz",
+    "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
+    "retexo_workspace_bytes",
+    "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
+)
+
+_lib = None
+
+
+class RetexoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, status_string(status)))
+
+
+def load():
+    """Load libretexo.so (built by ``paper_2302_13053_amd.build.build()``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    # torch owns the device memory and streams handed to the library; importing it
+    # first also makes both sides share one HIP runtime (same soname)
+    import torch  # noqa: F401
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libretexo.so is not built: run `python -m paper_2302_13053_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    i64, i32, vp, u32, f32 = C.c_int64, C.c_int, C.c_void_p, C.c_uint, C.c_float
+    lib.retexo_status_string.restype = C.c_char_p
+    lib.retexo_status_string.argtypes = [i32]
+    lib.retexo_csr_workspace_bytes.restype = i64
+    lib.retexo_csr_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.retexo_csr_from_coo.restype = i32
+    lib.retexo_csr_from_coo.argtypes = [i64, vp, vp, i64, i32, vp, vp, i64, C.POINTER(i64), vp, i64, vp]
+    lib.retexo_plan_create.restype = i32
+    lib.retexo_plan_create.argtypes = [C.POINTER(vp), i64, vp, vp, u32, vp]
+    lib.retexo_plan_destroy.restype = i32
+    lib.retexo_plan_destroy.argtypes = [vp]
+    lib.retexo_plan_num_nodes.restype = i64
+    lib.retexo_plan_num_nodes.argtypes = [vp]
+    lib.retexo_plan_nnz.restype = i64
+    lib.retexo_plan_nnz.argtypes = [vp]
+    lib.retexo_plan_max_degree.restype = C.c_int32
+    lib.retexo_plan_max_degree.argtypes = [vp]
+    lib.retexo_plan_deg.restype = vp
+    lib.retexo_plan_deg.argtypes = [vp]
+    lib.retexo_plan_dinv.restype = vp
+    lib.retexo_plan_dinv.argtypes = [vp]
+    lib.retexo_plan_export.restype = i32
+    lib.retexo_plan_export.argtypes = [vp, vp, vp, vp, vp]
+    lib.retexo_workspace_bytes.restype = i64
+    lib.retexo_workspace_bytes.argtypes = [vp, i64, i32, i32, u32]
+    lib.retexo_transform.restype = i32
+    lib.retexo_transform.argtypes = [i64, i64, i64, vp, i64, vp, vp, u32, vp, i64, vp]
+    lib.retexo_aggregate.restype = i32
+    lib.retexo_aggregate.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64, vp, i64, vp]
+    lib.retexo_round.restype = i32
+    lib.retexo_round.argtypes = [vp, i32, i64, i64, i32, vp, i64, vp, vp, vp, vp, f32, u32, vp, i64,
+                                 vp, i64, vp]
+    lib.retexo_set_option.restype = i32
+    lib.retexo_set_option.argtypes = [C.c_char_p, i64]
+    _lib = lib
+    return lib
+
+
+def _vp(addr: Optional[int]):
+    return C.c_void_p(addr) if addr else None
+
+
+def retexo_status_string(status: int) -> str:
+    return load().retexo_status_string(int(status)).decode()
+
+
+status_string = retexo_status_string
+
+
+def retexo_csr_workspace_bytes(n_pairs: int, n_nodes: int, add_self_loops: bool) -> int:
+    return int(load().retexo_csr_workspace_bytes(n_pairs, n_nodes, int(add_self_loops)))
+
+
+def retexo_csr_from_coo(n_pairs, d_src, d_dst, n_nodes, add_self_loops, d_row_ptr, d_col_idx,
+                        col_capacity, d_workspace, workspace_bytes, stream=0):
+    """-> (status, nnz)"""
+    nnz = C.c_int64(-1)
+    st = load().retexo_csr_from_coo(n_pairs, _vp(d_src), _vp(d_dst), n_nodes, int(add_self_loops),
+                                    _vp(d_row_ptr), _vp(d_col_idx), col_capacity, C.byref(nnz),
+                                    _vp(d_workspace), workspace_bytes, _vp(stream))
+    return int(st), int(nnz.value)
+
+
+def retexo_plan_create(n_nodes, d_row_ptr, d_col_idx, flags=0, stream=0):
+    """-> (status, plan handle or None)"""
+    h = C.c_void_p()
+    st = load().retexo_plan_create(C.byref(h), n_nodes, _vp(d_row_ptr), _vp(d_col_idx), flags, _vp(stream))
+    return int(st), (h.value if st == 0 else None)
+
+
+def retexo_plan_destroy(plan) -> int:
+    return int(load().retexo_plan_destroy(_vp(plan)))
+
+
+def retexo_plan_num_nodes(plan) -> int:
+    return int(load().retexo_plan_num_nodes(_vp(plan)))
+
+
+def retexo_plan_nnz(plan) -> int:
+    return int(load().retexo_plan_nnz(_vp(plan)))
+
+
+def retexo_plan_max_degree(plan) -> int:
+    return int(load().retexo_plan_max_degree(_vp(plan)))
+
+
+def retexo_plan_deg(plan) -> int:
+    return int(load().retexo_plan_deg(_vp(plan)) or 0)
+
+
+def retexo_plan_dinv(plan) -> int:
+    return int(load().retexo_plan_dinv(_vp(plan)) or 0)
+
+
+def retexo_plan_export(plan, d_deg, d_dinv, d_order, stream=0) -> int:
+    return int(load().retexo_plan_export(_vp(plan), _vp(d_deg), _vp(d_dinv), _vp(d_order), _vp(stream)))
+
+
+def retexo_workspace_bytes(plan, d_out, mode, heads=1, flags=0) -> int:
+    return int(load().retexo_workspace_bytes(_vp(plan), d_out, mode, heads, flags))
+
+
+def retexo_transform(n, d_in, d_out, d_H, ldh, d_W, d_b, flags, d_Z, ldz, stream=0) -> int:
+    return int(load().retexo_transform(n, d_in, d_out, _vp(d_H), ldh, _vp(d_W), _vp(d_b), flags,
+                                       _vp(d_Z), ldz, _vp(stream)))
+
+
+def retexo_aggregate(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, negative_slope, flags,
+                     d_out, ldo, d_workspace, workspace_bytes, stream=0) -> int:
+    return int(load().retexo_aggregate(_vp(plan), mode, F, heads, _vp(d_Z), ldz, _vp(d_attn_src),
+                                       _vp(d_attn_dst), negative_slope, flags, _vp(d_out), ldo,
+                                       _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+def retexo_round(plan, mode, d_in, d_out, heads, d_H, ldh, d_W, d_b, d_attn_src, d_attn_dst,
+                 negative_slope, flags, d_out_ptr, ldo, d_workspace, workspace_bytes, stream=0) -> int:
+    return int(load().retexo_round(_vp(plan), mode, d_in, d_out, heads, _vp(d_H), ldh, _vp(d_W),
+                                   _vp(d_b), _vp(d_attn_src), _vp(d_attn_dst), negative_slope, flags,
+                                   _vp(d_out_ptr), ldo, _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+def retexo_set_option(name: str, value: int) -> int:
+    return int(load().retexo_set_option(name.encode(), int(value)))
+
+
+def check(status: int, where: str) -> None:
+    if status != OK:
+        raise RetexoError(status, where)

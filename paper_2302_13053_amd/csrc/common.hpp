@@ -1,0 +1,69 @@
+// Shared declarations of the gfx950 embed-and-aggregate library (internal).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "retexo.h"
+
+#define RETEXO_HIP_TRY(expr)                         \
+    do {                                             \
+        hipError_t _e = (expr);                      \
+        if (_e != hipSuccess) return RETEXO_E_HIP;   \
+    } while (0)
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kMaxHeads = 8;       // attention heads supported by the edge-softmax kernel
+
+// Per-graph data.  deg/dinv/order are device arrays owned by the plan; the CSR
+// arrays are borrowed from the caller.
+struct retexo_plan {
+    int64_t N = 0;
+    int64_t nnz = 0;
+    const int64_t* row_ptr = nullptr;
+    const int32_t* col_idx = nullptr;
+    int32_t* deg = nullptr;       // [N]
+    float* dinv = nullptr;        // [N]
+    int32_t* order = nullptr;     // [N] row ids, longest rows first (ties: ascending id)
+    int32_t max_degree = 0;
+    // number of rows with deg >= threshold[i], thresholds fixed in plan.hip
+    int64_t rows_at_least[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    void* build_scratch = nullptr;
+};
+
+constexpr int kPlanThresholds[8] = {1, 256, 512, 1024, 2048, 4096, 8192, 16384};
+
+struct AggOptions {
+    int64_t slab_cols = 0;      // 0 = auto
+    int64_t slab_major = -1;    // -1 = auto
+    int64_t heavy_degree = 2048;
+};
+AggOptions& agg_options();
+
+// internal launchers (no argument validation; the C entry points did it)
+int launch_transform(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
+                     const float* W, const float* b, bool relu, float* Z, int64_t ldz,
+                     hipStream_t stream);
+
+struct AggCall {
+    const retexo_plan* plan;
+    int mode;
+    int64_t F;
+    int heads;
+    const float* Z;
+    int64_t ldz;
+    const float* attn_src;
+    const float* attn_dst;
+    float slope;
+    bool self_concat;
+    bool copy_self;       // false when Z already sits in out's first F columns
+    float* out;
+    int64_t ldo;
+    void* workspace;
+};
+int launch_aggregate(const AggCall& c, hipStream_t stream);
+int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads);
+
+// per-node score arrays are padded to 4 or 8 heads (padded heads hold zeros and are never selected)
+static inline int heads_padded(int heads) { return heads <= 4 ? 4 : 8; }
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }

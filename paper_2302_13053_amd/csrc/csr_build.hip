@@ -1,0 +1,210 @@
+// CSR construction on the device from raw undirected pairs.
+//
+// The paper's graphs are undirected (section "Edge-partitioned Distributed
+// Setup"), so each pair {u,v} becomes the two directed entries (u,v), (v,u).
+// Construction is integer-only and its result is a unique function of the pair
+// set: rows in id order, columns strictly ascending, no repeats, no (v,v)
+// entries except the single one per node requested by add_self_loops.
+//
+// Method: every directed entry is packed into one 64-bit key
+// (row << cbits | col, cbits = bits needed for N-1), the keys are radix-sorted
+// (rocPRIM device sort over only the significant bits), the first key of each
+// run of equal keys is flagged, an exclusive scan of the flags gives each kept
+// entry its position in col_idx, and row_ptr[r] is the scan value at the first
+// key whose row is >= r (binary search).  Dropped pairs (u == v) are encoded
+// as a sentinel larger than any real key so that they sort to the end.
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+
+#include "common.hpp"
+
+namespace {
+
+struct CsrHeader {          // lives at the start of the workspace
+    uint32_t bad_id;        // set to 1 if any id is outside [0, N)
+    uint32_t pad;
+    int64_t nnz;
+};
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void pairs_to_keys(
+    int64_t n_pairs, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+    int64_t N, int add_self_loops, int cbits, uint64_t* __restrict__ keys, CsrHeader* hdr)
+{
+    const uint64_t sentinel = 1ull << (2 * cbits);
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n_pairs) {
+        const int32_t u = src[i], v = dst[i];
+        uint64_t k0 = sentinel, k1 = sentinel;
+        if (u < 0 || u >= N || v < 0 || v >= N) {
+            atomicOr(&hdr->bad_id, 1u);
+        } else if (u != v) {
+            k0 = ((uint64_t)u << cbits) | (uint64_t)v;
+            k1 = ((uint64_t)v << cbits) | (uint64_t)u;
+        }
+        keys[2 * i] = k0;
+        keys[2 * i + 1] = k1;
+    } else if (add_self_loops && i < n_pairs + N) {
+        const uint64_t v = (uint64_t)(i - n_pairs);
+        keys[2 * n_pairs + (i - n_pairs)] = (v << cbits) | v;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void flag_first_of_run(
+    int64_t M, const uint64_t* __restrict__ keys, int cbits, uint32_t* __restrict__ flags)
+{
+    const uint64_t sentinel = 1ull << (2 * cbits);
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= M) return;
+    const uint64_t k = keys[i];
+    flags[i] = (k != sentinel && (i == 0 || keys[i - 1] != k)) ? 1u : 0u;
+}
+
+__global__ void total_kept(int64_t M, const uint32_t* __restrict__ flags,
+                           const uint32_t* __restrict__ pos, CsrHeader* hdr)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        hdr->nnz = (M == 0) ? 0 : (int64_t)pos[M - 1] + (int64_t)flags[M - 1];
+}
+
+__global__ __launch_bounds__(kThreads) void scatter_columns(
+    int64_t M, const uint64_t* __restrict__ keys, const uint32_t* __restrict__ flags,
+    const uint32_t* __restrict__ pos, int cbits, int32_t* __restrict__ col_idx)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= M || !flags[i]) return;
+    col_idx[pos[i]] = (int32_t)(keys[i] & ((1ull << cbits) - 1));
+}
+
+__global__ __launch_bounds__(kThreads) void row_offsets(
+    int64_t N, int64_t M, const uint64_t* __restrict__ keys, const uint32_t* __restrict__ pos,
+    int cbits, const CsrHeader* hdr, int64_t* __restrict__ row_ptr)
+{
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (r > N) return;
+    const uint64_t want = (uint64_t)r << cbits;   // smallest possible key of row r
+    int64_t lo = 0, hi = M;                       // first index with keys[idx] >= want
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (keys[mid] < want) lo = mid + 1; else hi = mid;
+    }
+    row_ptr[r] = (lo < M) ? (int64_t)pos[lo] : hdr->nnz;
+}
+
+int column_bits(int64_t N)
+{
+    int b = 1;
+    while ((1ll << b) < N) ++b;
+    return b;
+}
+
+struct Layout {
+    int64_t M, header, keys_a, keys_b, sort_tmp, scan_tmp, total;
+    size_t sort_bytes, scan_bytes;
+};
+
+int make_layout(int64_t n_pairs, int64_t N, int add_self_loops, Layout& L)
+{
+    L.M = 2 * n_pairs + (add_self_loops ? N : 0);
+    const int cbits = column_bits(N);
+    size_t sb = 0, cb = 0;
+    if (L.M > 0) {
+        if (rocprim::radix_sort_keys(nullptr, sb, (uint64_t*)nullptr, (uint64_t*)nullptr,
+                                     (size_t)L.M, 0u, (unsigned)(2 * cbits + 1), (hipStream_t)0) != hipSuccess)
+            return RETEXO_E_HIP;
+        if (rocprim::exclusive_scan(nullptr, cb, (uint32_t*)nullptr, (uint32_t*)nullptr, 0u,
+                                    (size_t)L.M, rocprim::plus<uint32_t>(), (hipStream_t)0) != hipSuccess)
+            return RETEXO_E_HIP;
+    }
+    L.sort_bytes = sb;
+    L.scan_bytes = cb;
+    int64_t off = 0;
+    L.header = off;   off += 256;
+    L.keys_a = off;   off += align_up(8 * L.M, 256);
+    L.keys_b = off;   off += align_up(8 * L.M, 256);
+    L.sort_tmp = off; off += align_up((int64_t)sb, 256);
+    L.scan_tmp = off; off += align_up((int64_t)cb, 256);
+    L.total = off + 256;
+    return RETEXO_OK;
+}
+
+int check_sizes(int64_t n_pairs, int64_t N)
+{
+    if (n_pairs < 0 || N < 0) return RETEXO_E_SIZE;
+    if (N >= (1ll << 31) || 2 * n_pairs + N >= (1ll << 31)) return RETEXO_E_SIZE;
+    return RETEXO_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t retexo_csr_workspace_bytes(int64_t n_pairs, int64_t N, int add_self_loops)
+{
+    if (int s = check_sizes(n_pairs, N)) return s;
+    Layout L;
+    if (int s = make_layout(n_pairs, N, add_self_loops, L)) return s;
+    return L.total;
+}
+
+extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const int32_t* d_dst,
+                                   int64_t N, int add_self_loops,
+                                   int64_t* d_row_ptr, int32_t* d_col_idx, int64_t col_capacity,
+                                   int64_t* h_nnz, void* d_workspace, int64_t workspace_bytes,
+                                   void* stream_)
+{
+    if (int s = check_sizes(n_pairs, N)) return s;
+    if (col_capacity < 0) return RETEXO_E_SIZE;
+    if (!d_row_ptr) return RETEXO_E_NULL;
+    if (n_pairs > 0 && (!d_src || !d_dst)) return RETEXO_E_NULL;
+    if (!d_workspace) return RETEXO_E_WORKSPACE;
+    if (((uintptr_t)d_workspace & 255) != 0) return RETEXO_E_WORKSPACE;
+    Layout L;
+    if (int s = make_layout(n_pairs, N, add_self_loops, L)) return s;
+    if (workspace_bytes < L.total) return RETEXO_E_WORKSPACE;
+    if (L.M > 0 && !d_col_idx && col_capacity > 0) return RETEXO_E_NULL;
+
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)d_workspace;
+    CsrHeader* hdr = (CsrHeader*)(ws + L.header);
+    uint64_t* keys_a = (uint64_t*)(ws + L.keys_a);
+    uint64_t* keys_b = (uint64_t*)(ws + L.keys_b);
+    // after the sort keys_a is free: its first half holds the flags, its second half the scan
+    uint32_t* flags = (uint32_t*)keys_a;
+    uint32_t* pos = flags + L.M;
+    const int cbits = column_bits(N);
+    const int64_t M = L.M;
+
+    RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(CsrHeader), stream));
+    if (M > 0) {
+        const int64_t work = n_pairs + (add_self_loops ? N : 0);
+        pairs_to_keys<<<dim3((unsigned)((work + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            n_pairs, d_src, d_dst, N, add_self_loops, cbits, keys_a, hdr);
+        size_t sb = L.sort_bytes;
+        RETEXO_HIP_TRY(rocprim::radix_sort_keys(ws + L.sort_tmp, sb, keys_a, keys_b, (size_t)M, 0u,
+                                                (unsigned)(2 * cbits + 1), stream));
+        const unsigned gm = (unsigned)((M + kThreads - 1) / kThreads);
+        flag_first_of_run<<<dim3(gm), dim3(kThreads), 0, stream>>>(M, keys_b, cbits, flags);
+        size_t cb = L.scan_bytes;
+        RETEXO_HIP_TRY(rocprim::exclusive_scan(ws + L.scan_tmp, cb, flags, pos, 0u, (size_t)M,
+                                               rocprim::plus<uint32_t>(), stream));
+        total_kept<<<dim3(1), dim3(64), 0, stream>>>(M, flags, pos, hdr);
+    }
+    CsrHeader h;
+    RETEXO_HIP_TRY(hipMemcpyAsync(&h, hdr, sizeof(h), hipMemcpyDeviceToHost, stream));
+    RETEXO_HIP_TRY(hipStreamSynchronize(stream));
+    if (h.bad_id) return RETEXO_E_CSR;
+    if (h_nnz) *h_nnz = h.nnz;
+    if (h.nnz > col_capacity) return RETEXO_E_CAPACITY;
+
+    if (M > 0) {
+        const unsigned gm = (unsigned)((M + kThreads - 1) / kThreads);
+        scatter_columns<<<dim3(gm), dim3(kThreads), 0, stream>>>(M, keys_b, flags, pos, cbits, d_col_idx);
+    }
+    row_offsets<<<dim3((unsigned)((N + 1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+        N, M, keys_b, pos, cbits, hdr, d_row_ptr);
+    RETEXO_HIP_TRY(hipGetLastError());
+    RETEXO_HIP_TRY(hipStreamSynchronize(stream));   // the workspace may be reused by the caller
+    return RETEXO_OK;
+}

@@ -1,0 +1,183 @@
+// Per-graph plan: degrees, GCN normalisers and the degree-ordered row schedule.
+//
+// deg[v] is the CSR row length.  dinv[v] = 1/sqrt(deg v) is what the
+// symmetric normalisation D^-1/2 (A+I) D^-1/2 multiplies with on both sides; it
+// is computed as a correctly rounded fp32 sqrt followed by a correctly rounded
+// fp32 divide (never the hardware rsqrt approximation) so that it can be
+// compared bit for bit with a CPU computation.
+//
+// Power-law graphs have a few very long rows.  The aggregation kernels give
+// one wavefront to an ordinary row and a whole workgroup to a long one, and
+// start the long rows first, so the plan keeps the row ids sorted by
+// decreasing degree (stable: equal degrees stay in id order) and the number of
+// rows at or above a few degree thresholds.
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+
+#include <new>
+
+#include "common.hpp"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void degree_kernel(
+    int64_t N, const int64_t* __restrict__ row_ptr, int32_t* __restrict__ deg,
+    float* __restrict__ dinv, uint32_t* __restrict__ sort_key, int32_t* __restrict__ ids,
+    uint32_t* bad)
+{
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= N) return;
+    const int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
+    int64_t d = hi - lo;
+    if (d < 0 || d > 0x7fffffff || (v == 0 && lo != 0)) { atomicOr(bad, 1u); d = 0; }
+    deg[v] = (int32_t)d;
+    dinv[v] = d > 0 ? 1.0f / sqrtf((float)d) : 0.0f;
+    sort_key[v] = (uint32_t)d;
+    ids[v] = (int32_t)v;
+}
+
+__global__ __launch_bounds__(kThreads) void check_columns(
+    int64_t nnz, int64_t N, const int32_t* __restrict__ col_idx, uint32_t* bad)
+{
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t c = col_idx[e];
+    if (c < 0 || c >= N) atomicOr(bad, 1u);
+}
+
+// counts[i] = number of rows with degree >= thresholds[i]; keys are sorted descending
+struct Thresholds { int t[8]; };
+
+__global__ void count_at_least(int64_t N, const uint32_t* __restrict__ keys_desc, Thresholds th,
+                               int64_t* counts)
+{
+    const int i = threadIdx.x;
+    if (i >= 8) return;
+    const uint32_t t = (uint32_t)th.t[i];
+    int64_t lo = 0, hi = N;                 // first index with key < t
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (keys_desc[mid] >= t) lo = mid + 1; else hi = mid;
+    }
+    counts[i] = lo;
+    if (i == 0) counts[8] = N > 0 ? (int64_t)keys_desc[0] : 0;   // max degree
+}
+
+struct Readback {
+    int64_t counts[9];
+    int64_t nnz;
+    uint32_t bad;
+    uint32_t pad;
+};
+
+}  // namespace
+
+extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d_row_ptr,
+                                  const int32_t* d_col_idx, unsigned flags, void* stream_)
+{
+    if (!out) return RETEXO_E_NULL;
+    *out = nullptr;
+    if (N < 0 || N >= (1ll << 31)) return RETEXO_E_SIZE;
+    if (flags & ~(unsigned)RETEXO_F_VALIDATE) return RETEXO_E_FLAGS;
+    if (!d_row_ptr) return RETEXO_E_NULL;
+    hipStream_t stream = (hipStream_t)stream_;
+
+    retexo_plan* p = new (std::nothrow) retexo_plan();
+    if (!p) return RETEXO_E_HIP;
+    p->N = N;
+    p->row_ptr = d_row_ptr;
+    p->col_idx = d_col_idx;
+
+    auto fail = [&](int code) { retexo_plan_destroy(p); return code; };
+
+    const int64_t n1 = N > 0 ? N : 1;
+    if (hipMalloc(&p->deg, n1 * sizeof(int32_t)) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (hipMalloc(&p->dinv, n1 * sizeof(float)) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (hipMalloc(&p->order, n1 * sizeof(int32_t)) != hipSuccess) return fail(RETEXO_E_HIP);
+
+    size_t sort_bytes = 0;
+    if (N > 0 &&
+        rocprim::radix_sort_pairs_desc(nullptr, sort_bytes, (uint32_t*)nullptr, (uint32_t*)nullptr,
+                                       (int32_t*)nullptr, (int32_t*)nullptr, (size_t)N, 0u, 32u,
+                                       stream) != hipSuccess)
+        return fail(RETEXO_E_HIP);
+    // scratch: keys_in, keys_out, ids_in, readback block, sort temp
+    const int64_t o_kin = 0, o_kout = align_up(4 * n1, 256), o_ids = 2 * o_kout, o_rb = 3 * o_kout;
+    const int64_t o_tmp = o_rb + 256;
+    if (hipMalloc(&p->build_scratch, (size_t)(o_tmp + align_up((int64_t)sort_bytes, 256) + 256)) != hipSuccess)
+        return fail(RETEXO_E_HIP);
+    char* sc = (char*)p->build_scratch;
+    uint32_t* kin = (uint32_t*)(sc + o_kin);
+    uint32_t* kout = (uint32_t*)(sc + o_kout);
+    int32_t* ids = (int32_t*)(sc + o_ids);
+    Readback* rb = (Readback*)(sc + o_rb);
+
+    if (hipMemsetAsync(rb, 0, sizeof(Readback), stream) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (N > 0) {
+        degree_kernel<<<dim3((unsigned)((N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            N, d_row_ptr, p->deg, p->dinv, kin, ids, &rb->bad);
+        if (rocprim::radix_sort_pairs_desc(sc + o_tmp, sort_bytes, kin, kout, ids, p->order, (size_t)N,
+                                           0u, 32u, stream) != hipSuccess)
+            return fail(RETEXO_E_HIP);
+        Thresholds th;
+        for (int i = 0; i < 8; ++i) th.t[i] = kPlanThresholds[i];
+        count_at_least<<<dim3(1), dim3(64), 0, stream>>>(N, kout, th, rb->counts);
+    }
+    if (hipMemcpyAsync(&rb->nnz, d_row_ptr + N, sizeof(int64_t), hipMemcpyDeviceToDevice, stream) != hipSuccess)
+        return fail(RETEXO_E_HIP);
+    Readback h;
+    if (hipMemcpyAsync(&h, rb, sizeof(h), hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (h.bad || h.nnz < 0 || h.nnz >= (1ll << 31)) return fail(h.bad || h.nnz < 0 ? RETEXO_E_CSR : RETEXO_E_SIZE);
+    p->nnz = h.nnz;
+    if (p->nnz > 0 && !d_col_idx) return fail(RETEXO_E_NULL);
+    for (int i = 0; i < 8; ++i) p->rows_at_least[i] = h.counts[i];
+    p->max_degree = (int32_t)h.counts[8];
+
+    if ((flags & RETEXO_F_VALIDATE) && p->nnz > 0) {
+        check_columns<<<dim3((unsigned)((p->nnz + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            p->nnz, N, d_col_idx, &rb->bad);
+        uint32_t bad = 0;
+        if (hipMemcpyAsync(&bad, &rb->bad, sizeof(bad), hipMemcpyDeviceToHost, stream) != hipSuccess)
+            return fail(RETEXO_E_HIP);
+        if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
+        if (bad) return fail(RETEXO_E_CSR);
+    }
+    (void)hipFree(p->build_scratch);
+    p->build_scratch = nullptr;
+    *out = p;
+    return RETEXO_OK;
+}
+
+extern "C" int retexo_plan_destroy(retexo_plan* p)
+{
+    if (!p) return RETEXO_OK;
+    if (p->deg) (void)hipFree(p->deg);
+    if (p->dinv) (void)hipFree(p->dinv);
+    if (p->order) (void)hipFree(p->order);
+    if (p->build_scratch) (void)hipFree(p->build_scratch);
+    delete p;
+    return RETEXO_OK;
+}
+
+extern "C" int64_t retexo_plan_num_nodes(const retexo_plan* p) { return p ? p->N : RETEXO_E_NULL; }
+extern "C" int64_t retexo_plan_nnz(const retexo_plan* p) { return p ? p->nnz : RETEXO_E_NULL; }
+extern "C" int32_t retexo_plan_max_degree(const retexo_plan* p) { return p ? p->max_degree : RETEXO_E_NULL; }
+extern "C" const int32_t* retexo_plan_deg(const retexo_plan* p) { return p ? p->deg : nullptr; }
+extern "C" const float* retexo_plan_dinv(const retexo_plan* p) { return p ? p->dinv : nullptr; }
+
+extern "C" int retexo_plan_export(const retexo_plan* p, int32_t* d_deg, float* d_dinv, int32_t* d_order,
+                                  void* stream_)
+{
+    if (!p) return RETEXO_E_NULL;
+    hipStream_t stream = (hipStream_t)stream_;
+    const size_t n = (size_t)p->N;
+    if (n == 0) return RETEXO_OK;
+    if (d_deg) RETEXO_HIP_TRY(hipMemcpyAsync(d_deg, p->deg, n * 4, hipMemcpyDeviceToDevice, stream));
+    if (d_dinv) RETEXO_HIP_TRY(hipMemcpyAsync(d_dinv, p->dinv, n * 4, hipMemcpyDeviceToDevice, stream));
+    if (d_order) RETEXO_HIP_TRY(hipMemcpyAsync(d_order, p->order, n * 4, hipMemcpyDeviceToDevice, stream));
+    return RETEXO_OK;
+}

@@ -1,0 +1,197 @@
+// C entry points of the embed-and-aggregate library: argument checking and the
+// sequencing of one lazy message-passing round (transform, then aggregation,
+// on one stream).  All checks that need no device access run first, so an
+// argument error leaves every output untouched.
+#include <string.h>
+
+#include "common.hpp"
+
+namespace {
+
+bool overlaps(const void* a, int64_t a_bytes, const void* b, int64_t b_bytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, a1 = a0 + (uintptr_t)a_bytes;
+    const uintptr_t b0 = (uintptr_t)b, b1 = b0 + (uintptr_t)b_bytes;
+    return a0 < b1 && b0 < a1;
+}
+
+int64_t extent_bytes(int64_t rows, int64_t ld, int64_t width)
+{
+    if (rows <= 0) return 0;
+    return ((rows - 1) * ld + width) * (int64_t)sizeof(float);
+}
+
+int check_mode(int mode, int64_t F, int heads)
+{
+    if (mode < RETEXO_MEAN || mode > RETEXO_GAT_SOFTMAX) return RETEXO_E_MODE;
+    if (heads < 1 || heads > kMaxHeads) return RETEXO_E_HEADS;
+    if (mode == RETEXO_GAT_SOFTMAX && F % heads != 0) return RETEXO_E_HEADS;
+    return RETEXO_OK;
+}
+
+// bytes of Z held in the workspace by retexo_round (0 when Z lives in `out`)
+int64_t round_z_bytes(int64_t N, int64_t D_out, bool have_w, bool concat, int64_t* ldz_out)
+{
+    const int64_t ldz = align_up(D_out > 0 ? D_out : 1, 32);   // 128-byte rows
+    if (ldz_out) *ldz_out = ldz;
+    if (!have_w || concat) return 0;
+    return align_up((N > 0 ? N : 1) * ldz * (int64_t)sizeof(float), 256);
+}
+
+int check_transform_args(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
+                         const float* W, unsigned flags, const float* Z, int64_t ldz)
+{
+    if (N < 0 || D_in < 0 || D_out < 0) return RETEXO_E_SIZE;
+    if (D_in >= (1ll << 31) || D_out >= (1ll << 31)) return RETEXO_E_SIZE;
+    if (flags & ~(unsigned)RETEXO_F_RELU) return RETEXO_E_FLAGS;
+    if (N > 0 && D_out > 0 && !Z) return RETEXO_E_NULL;
+    if (N > 0 && D_in > 0 && (!H || (D_out > 0 && !W))) return RETEXO_E_NULL;
+    if (ldh < D_in || ldz < D_out) return RETEXO_E_LD;
+    return RETEXO_OK;
+}
+
+}  // namespace
+
+extern "C" const char* retexo_status_string(int s)
+{
+    switch (s) {
+        case RETEXO_OK: return "ok";
+        case RETEXO_E_NULL: return "required pointer is NULL";
+        case RETEXO_E_SIZE: return "negative or inconsistent size";
+        case RETEXO_E_LD: return "leading dimension smaller than row width";
+        case RETEXO_E_MODE: return "unknown aggregation mode";
+        case RETEXO_E_FLAGS: return "unknown or inapplicable flag";
+        case RETEXO_E_HEADS: return "bad head count";
+        case RETEXO_E_CSR: return "node id out of range or malformed CSR";
+        case RETEXO_E_WORKSPACE: return "workspace missing, misaligned or too small";
+        case RETEXO_E_ALIAS: return "output overlaps an input";
+        case RETEXO_E_HIP: return "HIP runtime call failed";
+        case RETEXO_E_CAPACITY: return "col_idx capacity too small";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int retexo_set_option(const char* name, int64_t value)
+{
+    if (!name) return RETEXO_E_NULL;
+    AggOptions& o = agg_options();
+    if (!strcmp(name, "agg_slab_cols")) { o.slab_cols = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_slab_major")) { o.slab_major = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_heavy_degree")) { o.heavy_degree = value; return RETEXO_OK; }
+    return RETEXO_E_FLAGS;
+}
+
+extern "C" int64_t retexo_workspace_bytes(const retexo_plan* plan, int64_t D_out, int mode, int heads,
+                                          unsigned flags)
+{
+    if (!plan) return RETEXO_E_NULL;
+    if (D_out < 0) return RETEXO_E_SIZE;
+    if (int s = check_mode(mode, D_out, heads)) return s;
+    if (flags & ~(unsigned)(RETEXO_F_RELU | RETEXO_F_SELF_CONCAT)) return RETEXO_E_FLAGS;
+    // sized for retexo_round with a weight matrix; retexo_aggregate needs only the second term
+    return round_z_bytes(plan->N, D_out, true, (flags & RETEXO_F_SELF_CONCAT) != 0, nullptr) +
+           aggregate_workspace_bytes(plan->N, mode, heads);
+}
+
+extern "C" int retexo_transform(int64_t N, int64_t D_in, int64_t D_out,
+                                const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
+                                unsigned flags, float* d_Z, int64_t ldz, void* stream)
+{
+    if (int s = check_transform_args(N, D_in, D_out, d_H, ldh, d_W, flags, d_Z, ldz)) return s;
+    if (N > 0 && D_in > 0 && D_out > 0 &&
+        overlaps(d_H, extent_bytes(N, ldh, D_in), d_Z, extent_bytes(N, ldz, D_out)))
+        return RETEXO_E_ALIAS;
+    return launch_transform(N, D_in, D_out, d_H, ldh, d_W, d_b, (flags & RETEXO_F_RELU) != 0, d_Z, ldz,
+                            (hipStream_t)stream);
+}
+
+extern "C" int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, int heads,
+                                const float* d_Z, int64_t ldz,
+                                const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                                unsigned flags, float* d_out, int64_t ldo,
+                                void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    if (!plan) return RETEXO_E_NULL;
+    if (F < 0 || F >= (1ll << 30)) return RETEXO_E_SIZE;
+    if (int s = check_mode(mode, F, heads)) return s;
+    if (flags & ~(unsigned)RETEXO_F_SELF_CONCAT) return RETEXO_E_FLAGS;
+    const bool concat = (flags & RETEXO_F_SELF_CONCAT) != 0;
+    const int64_t N = plan->N, ow = concat ? 2 * F : F;
+    if (N > 0 && F > 0 && (!d_Z || !d_out)) return RETEXO_E_NULL;
+    if (mode == RETEXO_GAT_SOFTMAX && N > 0 && F > 0 && (!d_attn_src || !d_attn_dst)) return RETEXO_E_NULL;
+    if (ldz < F || ldo < ow) return RETEXO_E_LD;
+    const bool in_place = concat && (const float*)d_out == d_Z && ldz == ldo;
+    if (!in_place && N > 0 && F > 0 &&
+        overlaps(d_Z, extent_bytes(N, ldz, F), d_out, extent_bytes(N, ldo, ow)))
+        return RETEXO_E_ALIAS;
+    const int64_t need = aggregate_workspace_bytes(N, mode, heads);
+    if (need > 0 && (!d_workspace || workspace_bytes < need || ((uintptr_t)d_workspace & 255)))
+        return RETEXO_E_WORKSPACE;
+
+    AggCall c;
+    c.plan = plan; c.mode = mode; c.F = F; c.heads = heads; c.Z = d_Z; c.ldz = ldz;
+    c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
+    c.self_concat = concat; c.copy_self = !in_place; c.out = d_out; c.ldo = ldo;
+    c.workspace = d_workspace;
+    return launch_aggregate(c, (hipStream_t)stream);
+}
+
+extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out, int heads,
+                            const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
+                            const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                            unsigned flags, float* d_out, int64_t ldo,
+                            void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    if (!plan) return RETEXO_E_NULL;
+    if (D_in < 0 || D_out < 0 || D_out >= (1ll << 30)) return RETEXO_E_SIZE;
+    if (int s = check_mode(mode, D_out, heads)) return s;
+    if (flags & ~(unsigned)(RETEXO_F_RELU | RETEXO_F_SELF_CONCAT)) return RETEXO_E_FLAGS;
+    const bool concat = (flags & RETEXO_F_SELF_CONCAT) != 0;
+    const bool have_w = d_W != nullptr;
+    const int64_t N = plan->N, ow = concat ? 2 * D_out : D_out;
+    if (!have_w) {
+        if (D_out != D_in) return RETEXO_E_SIZE;
+        if (d_b) return RETEXO_E_FLAGS;
+        if (flags & RETEXO_F_RELU) return RETEXO_E_FLAGS;
+    }
+    if (N > 0 && D_out > 0 && (!d_out || (D_in > 0 && !d_H))) return RETEXO_E_NULL;
+    if (mode == RETEXO_GAT_SOFTMAX && N > 0 && D_out > 0 && (!d_attn_src || !d_attn_dst)) return RETEXO_E_NULL;
+    if (ldh < D_in || ldo < ow) return RETEXO_E_LD;
+    if (N > 0 && D_out > 0 && D_in > 0 &&
+        overlaps(d_H, extent_bytes(N, ldh, D_in), d_out, extent_bytes(N, ldo, ow)))
+        return RETEXO_E_ALIAS;
+
+    int64_t ldz_ws = 0;
+    const int64_t z_bytes = round_z_bytes(N, D_out, have_w, concat, &ldz_ws);
+    const int64_t need = z_bytes + aggregate_workspace_bytes(N, mode, heads);
+    if (need > 0 && (!d_workspace || workspace_bytes < need || ((uintptr_t)d_workspace & 255)))
+        return RETEXO_E_WORKSPACE;
+    if (need > 0 && N > 0 && D_out > 0 &&
+        (overlaps(d_workspace, need, d_out, extent_bytes(N, ldo, ow)) ||
+         (D_in > 0 && overlaps(d_workspace, need, d_H, extent_bytes(N, ldh, D_in)))))
+        return RETEXO_E_ALIAS;
+
+    hipStream_t s = (hipStream_t)stream;
+    AggCall c;
+    c.plan = plan; c.mode = mode; c.F = D_out; c.heads = heads;
+    c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
+    c.self_concat = concat; c.out = d_out; c.ldo = ldo;
+    c.workspace = (char*)d_workspace + z_bytes;
+    if (!have_w) {
+        // identity transform: the first round aggregates the raw features
+        c.Z = d_H; c.ldz = ldh; c.copy_self = true;
+    } else if (concat) {
+        // Z is produced straight into out's first D_out columns and gathered from there
+        if (int e = launch_transform(N, D_in, D_out, d_H, ldh, d_W, d_b, (flags & RETEXO_F_RELU) != 0,
+                                     d_out, ldo, s))
+            return e;
+        c.Z = d_out; c.ldz = ldo; c.copy_self = false;
+    } else {
+        float* Zws = (float*)d_workspace;
+        if (int e = launch_transform(N, D_in, D_out, d_H, ldh, d_W, d_b, (flags & RETEXO_F_RELU) != 0,
+                                     Zws, ldz_ws, s))
+            return e;
+        c.Z = Zws; c.ldz = ldz_ws; c.copy_self = false;
+    }
+    return launch_aggregate(c, s);
+}

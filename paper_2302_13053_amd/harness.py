@@ -1,0 +1,210 @@
+"""Device-side plumbing shared by the tests, the smoke check and the benchmark.
+
+PyTorch is used only to own device memory and streams; every step of the path
+is a call into libretexo.so through ``binding``.  Nothing here computes.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import Stage, StageParams, Workload, pad_ld
+
+
+def _stream_ptr() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def ws_tensor(nbytes: int) -> torch.Tensor:
+    """256-byte aligned byte buffer (torch's allocator aligns to 512)."""
+    t = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+    assert t.data_ptr() % 256 == 0
+    return t
+
+
+@dataclass
+class DeviceGraph:
+    n_nodes: int
+    nnz: int
+    row_ptr: torch.Tensor      # int64 [N+1]
+    col_idx: torch.Tensor      # int32 [capacity], first nnz valid
+    plan: Optional[int] = None
+
+    def destroy(self) -> None:
+        if self.plan:
+            B.retexo_plan_destroy(self.plan)
+            self.plan = None
+
+
+def csr_from_coo(src: torch.Tensor, dst: torch.Tensor, n_nodes: int, self_loops: bool,
+                 workspace: Optional[torch.Tensor] = None,
+                 row_ptr: Optional[torch.Tensor] = None,
+                 col_idx: Optional[torch.Tensor] = None) -> DeviceGraph:
+    n_pairs = int(src.numel())
+    need = B.retexo_csr_workspace_bytes(n_pairs, n_nodes, self_loops)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_csr_workspace_bytes")
+    if workspace is None or workspace.numel() < need:
+        workspace = ws_tensor(need)
+    cap = 2 * n_pairs + (n_nodes if self_loops else 0)
+    if row_ptr is None:
+        row_ptr = torch.empty(n_nodes + 1, dtype=torch.int64, device="cuda")
+    if col_idx is None:
+        col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device="cuda")
+    st, nnz = B.retexo_csr_from_coo(n_pairs, src.data_ptr() if n_pairs else 0,
+                                    dst.data_ptr() if n_pairs else 0, n_nodes, self_loops,
+                                    row_ptr.data_ptr(), col_idx.data_ptr(), col_idx.numel(),
+                                    workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    B.check(st, "retexo_csr_from_coo")
+    return DeviceGraph(n_nodes, nnz, row_ptr, col_idx)
+
+
+def make_plan(g: DeviceGraph, validate: bool = False) -> DeviceGraph:
+    st, plan = B.retexo_plan_create(g.n_nodes, g.row_ptr.data_ptr(), g.col_idx.data_ptr(),
+                                    B.F_VALIDATE if validate else 0, _stream_ptr())
+    B.check(st, "retexo_plan_create")
+    g.plan = plan
+    return g
+
+
+def plan_arrays(g: DeviceGraph):
+    """(deg int32[N], dinv float32[N], order int32[N]) copied out of the plan, as numpy."""
+    n = g.n_nodes
+    deg = torch.empty(max(n, 1), dtype=torch.int32, device="cuda")
+    dinv = torch.empty(max(n, 1), dtype=torch.float32, device="cuda")
+    order = torch.empty(max(n, 1), dtype=torch.int32, device="cuda")
+    B.check(B.retexo_plan_export(g.plan, deg.data_ptr(), dinv.data_ptr(), order.data_ptr(), _stream_ptr()),
+            "retexo_plan_export")
+    torch.cuda.synchronize()
+    return deg[:n].cpu().numpy(), dinv[:n].cpu().numpy(), order[:n].cpu().numpy()
+
+
+def transform(H: torch.Tensor, d_in: int, W: torch.Tensor, b: Optional[torch.Tensor], relu: bool,
+              out: Optional[torch.Tensor] = None, ld_out: Optional[int] = None) -> torch.Tensor:
+    n = H.shape[0]
+    d_out = W.shape[1]
+    if out is None:
+        out = torch.empty((n, ld_out or pad_ld(d_out)), dtype=torch.float32, device="cuda")
+    st = B.retexo_transform(n, d_in, d_out, H.data_ptr(), H.stride(0), W.data_ptr(),
+                            b.data_ptr() if b is not None else 0, B.F_RELU if relu else 0,
+                            out.data_ptr(), out.stride(0), _stream_ptr())
+    B.check(st, "retexo_transform")
+    return out
+
+
+def aggregate(g: DeviceGraph, mode: str, Z: torch.Tensor, F: int, *, heads: int = 1,
+              a_src: Optional[torch.Tensor] = None, a_dst: Optional[torch.Tensor] = None,
+              slope: float = 0.2, concat: bool = False, out: Optional[torch.Tensor] = None,
+              ld_out: Optional[int] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    ow = 2 * F if concat else F
+    if out is None:
+        out = torch.empty((g.n_nodes, ld_out or pad_ld(ow)), dtype=torch.float32, device="cuda")
+    flags = B.F_SELF_CONCAT if concat else 0
+    need = B.retexo_workspace_bytes(g.plan, F, B.MODES[mode], heads, flags)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_workspace_bytes")
+    if workspace is None:
+        workspace = ws_tensor(need)
+    st = B.retexo_aggregate(g.plan, B.MODES[mode], F, heads, Z.data_ptr(), Z.stride(0),
+                            a_src.data_ptr() if a_src is not None else 0,
+                            a_dst.data_ptr() if a_dst is not None else 0, slope, flags,
+                            out.data_ptr(), out.stride(0), workspace.data_ptr(), workspace.numel(),
+                            _stream_ptr())
+    B.check(st, "retexo_aggregate")
+    return out
+
+
+def round_(g: DeviceGraph, st: Stage, H: torch.Tensor, W, b, a_src, a_dst, out: torch.Tensor,
+           workspace: torch.Tensor, slope: float = 0.2) -> None:
+    flags = (B.F_RELU if st.relu else 0) | (B.F_SELF_CONCAT if st.concat else 0)
+    rc = B.retexo_round(g.plan, B.MODES[st.mode], st.d_in, st.d_out, st.heads, H.data_ptr(), H.stride(0),
+                        W.data_ptr() if W is not None else 0, b.data_ptr() if b is not None else 0,
+                        a_src.data_ptr() if a_src is not None else 0,
+                        a_dst.data_ptr() if a_dst is not None else 0, slope, flags,
+                        out.data_ptr(), out.stride(0), workspace.data_ptr(), workspace.numel(),
+                        _stream_ptr())
+    B.check(rc, "retexo_round")
+
+
+class Pipeline:
+    """All device buffers of one workload, allocated once; ``run`` replays the
+    whole hot path: CSR construction, plan, then every stage in order."""
+
+    def __init__(self, wl: Workload, src: np.ndarray, dst: np.ndarray, feats: np.ndarray,
+                 params: Sequence[StageParams]):
+        self.wl = wl
+        self.n = wl.n_nodes
+        self.src = dev(src.astype(np.int32))
+        self.dst = dev(dst.astype(np.int32))
+        self.H0 = dev(feats)
+        n_pairs = int(self.src.numel())
+        self.csr_ws = ws_tensor(B.retexo_csr_workspace_bytes(n_pairs, self.n, wl.self_loops))
+        cap = 2 * n_pairs + (self.n if wl.self_loops else 0)
+        self.row_ptr = torch.empty(self.n + 1, dtype=torch.int64, device="cuda")
+        self.col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device="cuda")
+        self.params = []
+        for p in params:
+            self.params.append(tuple(None if a is None else dev(a) for a in (p.W, p.b, p.a_src, p.a_dst)))
+        self.outs: List[torch.Tensor] = []
+        for st in wl.stages:
+            self.outs.append(torch.empty((self.n, pad_ld(st.out_width)), dtype=torch.float32, device="cuda"))
+        self.graph: Optional[DeviceGraph] = None
+        self.round_ws: Optional[torch.Tensor] = None
+
+    def build_graph(self) -> DeviceGraph:
+        if self.graph is not None:
+            self.graph.destroy()
+        g = csr_from_coo(self.src, self.dst, self.n, self.wl.self_loops, self.csr_ws,
+                         self.row_ptr, self.col_idx)
+        self.graph = make_plan(g)
+        if self.round_ws is None:
+            need = 0
+            for st in self.wl.stages:
+                if st.kind == "round":
+                    flags = B.F_SELF_CONCAT if st.concat else 0
+                    need = max(need, B.retexo_workspace_bytes(self.graph.plan, st.d_out, B.MODES[st.mode],
+                                                              st.heads, flags))
+            self.round_ws = ws_tensor(need)
+        return self.graph
+
+    def run_stage(self, i: int) -> torch.Tensor:
+        st = self.wl.stages[i]
+        H = self.H0 if i == 0 else self.outs[i - 1]
+        W, b, a_src, a_dst = self.params[i]
+        if st.kind == "transform":
+            transform(H, st.d_in, W, b, st.relu, out=self.outs[i])
+        else:
+            round_(self.graph, st, H, W, b, a_src, a_dst, self.outs[i], self.round_ws)
+        return self.outs[i]
+
+    def run(self, events=None) -> List[torch.Tensor]:
+        """One pass of the whole path.  ``events``: optional list that receives
+        (label, start_event, end_event) per step for timing."""
+        def mark():
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            return e
+        t0 = mark() if events is not None else None
+        self.build_graph()
+        if events is not None:
+            t1 = mark()
+            events.append(("csr+plan", t0, t1))
+        for i, st in enumerate(self.wl.stages):
+            s = mark() if events is not None else None
+            self.run_stage(i)
+            if events is not None:
+                events.append(("%s%d" % (st.kind, i), s, mark()))
+        return self.outs
+
+    def close(self) -> None:
+        if self.graph is not None:
+            self.graph.destroy()
+            self.graph = None

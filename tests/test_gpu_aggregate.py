@@ -1,0 +1,212 @@
+"""GPU neighbourhood aggregation against the fp64 oracle, all four modes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_13053_amd import binding as B
+from paper_2302_13053_amd import harness as Hn
+from paper_2302_13053_amd import workloads as wl
+from parity import assert_close, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+MODES = ["sum", "mean", "gcn_sym", "gat_softmax"]
+
+
+@pytest.fixture(scope="module")
+def graphs():
+    """name -> (DeviceGraph, row_ptr, col_idx) for a few shapes; gcn variants carry self loops."""
+    specs = {
+        "skewed": (5000, 60000, 3.0, 4),     # a few rows far above the heavy threshold, many empty
+        "flat": (3000, 20000, 0.0, 5),
+        "tiny": (3, 2, 0.0, 6),
+    }
+    out = {}
+    for name, (n, pairs, skew, seed) in specs.items():
+        src, dst = wl.random_pairs(n, pairs, seed, skew=skew)
+        for sl in (False, True):
+            g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, sl), validate=True)
+            rp, ci = oracle.csr_from_coo(src, dst, n, sl)
+            out[(name, sl)] = (g, rp, ci)
+    deg = np.diff(out[("skewed", False)][1])
+    assert deg.max() >= 2048 and (deg == 0).any()
+    yield out
+    for g, _, _ in out.values():
+        g.destroy()
+
+
+def run_case(graphs, name, mode, F, ld, heads, concat, seed, kind="normal", base_offset=0):
+    g, rp, ci = graphs[(name, mode == "gcn_sym")]
+    n = g.n_nodes
+    Zh = wl.random_matrix(n, F, seed, ld=ld, kind=kind)
+    Zh[:, F:] = 0.0
+    a_src = a_dst = None
+    kw = {}
+    if mode == "gat_softmax":
+        a_src = wl.random_matrix(heads, F // heads, seed + 1) * np.float32(0.3)
+        a_dst = wl.random_matrix(heads, F // heads, seed + 2) * np.float32(0.3)
+        kw = dict(heads=heads, a_src=Hn.dev(a_src), a_dst=Hn.dev(a_dst))
+    if base_offset:
+        # shift the matrix start by a few floats to break 16-byte alignment
+        buf = torch.zeros(n * ld + base_offset, dtype=torch.float32, device="cuda")
+        Zd = buf[base_offset:].view(n, ld)
+        Zd.copy_(torch.from_numpy(Zh))
+    else:
+        Zd = Hn.dev(Zh)
+    ow = 2 * F if concat else F
+    out = torch.full((n, ow + 3), 555.0, dtype=torch.float32, device="cuda")
+    Hn.aggregate(g, mode, Zd, F, concat=concat, out=out, **kw)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.all(got[:, ow:] == 555.0)
+    want = oracle.aggregate(mode, rp, ci, Zh, F, heads=heads, a_src=a_src, a_dst=a_dst, self_concat=concat)
+    return got[:, :ow], want
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("F,ld,heads,concat,offset", [
+    (256, 256, 4, False, 0),      # one float4 chunk per lane
+    (602, 608, 1, True, 0),       # float4 gathers with a ragged last vector, 3 chunks
+    (602, 602, 2, True, 0),       # float2 gathers
+    (1433, 1433, 1, True, 0),     # scalar gathers, several slabs
+    (1432, 1440, 4, False, 0),    # float4, two slabs
+    (188, 192, 4, False, 0),      # heads of 47 columns: lanes straddle heads
+    (100, 100, 4, True, 0),
+    (64, 64, 8, False, 0),
+    (7, 7, 1, True, 0),
+    (1, 1, 1, False, 0),
+    (128, 128, 2, False, 1),      # misaligned base pointer
+])
+def test_modes_match_oracle_on_skewed_graph(graphs, mode, F, ld, heads, concat, offset):
+    if mode == "gat_softmax" and F % heads:
+        heads = 1
+    got, want = run_case(graphs, "skewed", mode, F, ld, heads, concat, seed=F + 17, base_offset=offset)
+    assert_close(got, want, what="%s F=%d" % (mode, F))
+    if concat:
+        assert np.array_equal(got[:, :F].astype(np.float64), want[:, :F])      # self copy is a bit copy
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name", ["flat", "tiny"])
+def test_modes_match_oracle_other_graphs(graphs, mode, name):
+    got, want = run_case(graphs, name, mode, 96, 96, 3, True, seed=3)
+    assert_close(got, want, what="%s %s" % (mode, name))
+
+
+def test_integer_features_are_bit_exact_and_ones_give_degree(graphs):
+    g, rp, ci = graphs[("skewed", False)]
+    deg = np.diff(rp)
+    got, want = run_case(graphs, "skewed", "sum", 40, 40, 1, False, seed=1, kind="smallint")
+    assert np.array_equal(got.astype(np.float64), want)     # any wrong, missed or repeated neighbour shows
+    ones = torch.ones((g.n_nodes, 4), dtype=torch.float32, device="cuda")
+    out = Hn.aggregate(g, "sum", ones, 4, ld_out=4)
+    assert np.array_equal(out.cpu().numpy()[:, 0], deg.astype(np.float32))
+    out = Hn.aggregate(g, "mean", ones, 4, ld_out=4).cpu().numpy()
+    assert np.all(out[deg > 0] == 1.0) and np.all(out[deg == 0] == 0.0)
+
+
+def test_gcn_indexing_exact_on_power_of_four_degrees():
+    # disjoint stars whose closed degrees are 4, 16 and 64 (leaves: 2 -> not a power of 4, so
+    # leaves get closed degree 4 by joining triangles instead): use complete graphs K4, K16, K64
+    blocks, src, dst, off = [4, 16, 64, 4, 16], [], [], 0
+    for k in blocks:
+        iu, ju = np.triu_indices(k, 1)
+        src.append(iu + off)
+        dst.append(ju + off)
+        off += k
+    src = np.concatenate(src).astype(np.int32)
+    dst = np.concatenate(dst).astype(np.int32)
+    n = off
+    g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, True))
+    rp, ci = oracle.csr_from_coo(src, dst, n, True)
+    Z = wl.random_matrix(n, 12, 2, kind="smallint")
+    out = Hn.aggregate(g, "gcn_sym", Hn.dev(Z), 12, ld_out=12).cpu().numpy()
+    want = oracle.aggregate("gcn_sym", rp, ci, Z, 12)
+    assert np.array_equal(out.astype(np.float64), want)     # all weights are powers of two: exact
+    g.destroy()
+
+
+def test_gat_properties(graphs):
+    g, rp, ci = graphs[("skewed", False)]
+    n, F, heads = g.n_nodes, 64, 4
+    deg = np.diff(rp)
+    Zh = wl.random_matrix(n, F, 8)
+    Z = Hn.dev(Zh)
+    zero = torch.zeros((heads, F // heads), dtype=torch.float32, device="cuda")
+    # zero attention vectors: uniform softmax == mean
+    a = Hn.aggregate(g, "gat_softmax", Z, F, heads=heads, a_src=zero, a_dst=zero).cpu().numpy()[:, :F]
+    assert_close(a, oracle.aggregate("mean", rp, ci, Zh, F), what="gat(a=0) vs mean")
+    # constant rows stay constant (weights sum to one), empty rows give zero
+    const = torch.full((n, F), 2.5, dtype=torch.float32, device="cuda")
+    asrc = Hn.dev(wl.random_matrix(heads, F // heads, 9))
+    c = Hn.aggregate(g, "gat_softmax", const, F, heads=heads, a_src=asrc, a_dst=asrc).cpu().numpy()[:, :F]
+    assert np.abs(c[deg > 0] - 2.5).max() <= 2.5 * 1e-5 and np.all(c[deg == 0] == 0)
+    # scores of magnitude ~80: finite, still matches
+    big = np.full((heads, F // heads), 5.0, np.float32)
+    Zs = np.sign(Zh).astype(np.float32)
+    o = Hn.aggregate(g, "gat_softmax", Hn.dev(Zs), F, heads=heads, a_src=Hn.dev(big), a_dst=Hn.dev(big))
+    want = oracle.aggregate("gat_softmax", rp, ci, Zs, F, heads=heads, a_src=big, a_dst=big)
+    assert_close(o.cpu().numpy()[:, :F], want, what="gat large scores")
+    # a row with a single neighbour returns that neighbour's row exactly
+    o = Hn.aggregate(g, "gat_softmax", Z, F, heads=heads, a_src=asrc, a_dst=asrc).cpu().numpy()[:, :F]
+    one = np.flatnonzero(deg == 1)
+    assert one.size and np.array_equal(o[one], Zh[ci[rp[one]]])
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_bitwise_reproducible_and_option_sweep(graphs, mode):
+    g, rp, ci = graphs[("skewed", mode == "gcn_sym")]
+    n, F, heads = g.n_nodes, 512, 4
+    Zh = wl.random_matrix(n, F, 10)
+    Z = Hn.dev(Zh)
+    kw = {}
+    a = None
+    if mode == "gat_softmax":
+        a = wl.random_matrix(heads, F // heads, 11) * np.float32(0.2)
+        kw = dict(heads=heads, a_src=Hn.dev(a), a_dst=Hn.dev(a))
+    want = oracle.aggregate(mode, rp, ci, Zh, F, heads=heads, a_src=a, a_dst=a)
+    first = Hn.aggregate(g, mode, Z, F, **kw).clone()
+    again = Hn.aggregate(g, mode, Z, F, **kw)
+    assert torch.equal(first, again)
+    try:
+        for slab, major, heavy in [(64, 0, 2048), (256, 1, 256), (512, 0, 1 << 20), (256, 1, 8192)]:
+            B.retexo_set_option("agg_slab_cols", slab)
+            B.retexo_set_option("agg_slab_major", major)
+            B.retexo_set_option("agg_heavy_degree", heavy)
+            got = Hn.aggregate(g, mode, Z, F, **kw).cpu().numpy()[:, :F]
+            assert_close(got, want, what="%s slab=%d major=%d heavy=%d" % (mode, slab, major, heavy))
+    finally:
+        B.retexo_set_option("agg_slab_cols", 0)
+        B.retexo_set_option("agg_slab_major", -1)
+        B.retexo_set_option("agg_heavy_degree", 2048)
+
+
+def test_in_place_concat_and_argument_errors(graphs):
+    g, rp, ci = graphs[("flat", False)]
+    n, F = g.n_nodes, 80
+    Zh = wl.random_matrix(n, F, 12)
+    buf = torch.zeros((n, 2 * F), dtype=torch.float32, device="cuda")
+    buf[:, :F] = torch.from_numpy(Zh).cuda()
+    st = B.retexo_aggregate(g.plan, B.MEAN, F, 1, buf.data_ptr(), 2 * F, 0, 0, 0.2, B.F_SELF_CONCAT,
+                            buf.data_ptr(), 2 * F, 0, 0)
+    assert st == B.OK
+    assert_close(buf.cpu().numpy(), oracle.aggregate("mean", rp, ci, Zh, F, self_concat=True), what="in place")
+    Z = Hn.dev(Zh)
+    out = torch.empty((n, 2 * F), dtype=torch.float32, device="cuda")
+    args = lambda **k: B.retexo_aggregate(
+        k.get("plan", g.plan), k.get("mode", B.MEAN), k.get("F", F), k.get("heads", 1),
+        k.get("Z", Z.data_ptr()), k.get("ldz", F), k.get("a", 0), k.get("a", 0), 0.2,
+        k.get("flags", 0), k.get("out", out.data_ptr()), k.get("ldo", 2 * F),
+        k.get("ws", 0), k.get("wsb", 0))
+    assert args() == B.OK
+    assert args(mode=9) == B.E_MODE
+    assert args(heads=0) == B.E_HEADS
+    assert args(mode=B.GAT_SOFTMAX, heads=3, a=Z.data_ptr()) == B.E_HEADS       # 3 does not divide 80
+    assert args(mode=B.GAT_SOFTMAX, heads=4) == B.E_NULL                         # attention vectors missing
+    assert args(mode=B.GAT_SOFTMAX, heads=4, a=Z.data_ptr()) == B.E_WORKSPACE
+    assert args(ldz=F - 1) == B.E_LD
+    assert args(flags=B.F_SELF_CONCAT, ldo=2 * F - 1) == B.E_LD
+    assert args(flags=B.F_RELU) == B.E_FLAGS
+    assert args(out=Z.data_ptr() + 64, ldo=F) == B.E_ALIAS
+    assert args(Z=0) == B.E_NULL

@@ -1,0 +1,107 @@
+"""GPU CSR construction and plan arrays against the oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_13053_amd import binding as B
+from paper_2302_13053_amd import harness as Hn
+from paper_2302_13053_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_csr(src, dst, n, self_loops, validate=True):
+    g = Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, self_loops)
+    Hn.make_plan(g, validate=validate)
+    torch.cuda.synchronize()
+    rp = g.row_ptr.cpu().numpy()
+    ci = g.col_idx[:g.nnz].cpu().numpy()
+    return g, rp, ci
+
+
+def check_against_oracle(src, dst, n, self_loops):
+    g, rp, ci = gpu_csr(src, dst, n, self_loops)
+    try:
+        orp, oci = oracle.csr_from_coo(src, dst, n, self_loops)
+        assert g.nnz == orp[-1] == B.retexo_plan_nnz(g.plan)
+        assert np.array_equal(rp, orp)
+        assert np.array_equal(ci, oci)
+        deg, dinv, order = Hn.plan_arrays(g)
+        odeg, odinv = oracle.degree(orp)
+        assert np.array_equal(deg, odeg)
+        assert np.array_equal(dinv.view(np.uint32), odinv.view(np.uint32))     # bit for bit
+        assert B.retexo_plan_max_degree(g.plan) == (odeg.max() if n else 0)
+        assert B.retexo_plan_num_nodes(g.plan) == n
+        # schedule: a permutation of the rows, longest first, ties in id order
+        assert np.array_equal(np.sort(order), np.arange(n))
+        key = odeg[order].astype(np.int64) * (n + 1) - order
+        assert np.all(np.diff(key) < 0) if n > 1 else True
+    finally:
+        g.destroy()
+
+
+@pytest.mark.parametrize("n,pairs,skew,seed", [
+    (1, 3, 0.0, 0), (2, 1, 0.0, 1), (64, 500, 1.0, 2), (1000, 300, 0.0, 3),
+    (5000, 60000, 3.0, 4), (100003, 400000, 1.0, 5), (4096, 9000, 0.5, 6),
+])
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_csr_bit_exact_random(n, pairs, skew, seed, self_loops):
+    src, dst = wl.random_pairs(n, pairs, seed, skew=skew)
+    check_against_oracle(src, dst, n, self_loops)
+
+
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_csr_empty_pair_list(self_loops):
+    check_against_oracle(np.empty(0, np.int32), np.empty(0, np.int32), 37, self_loops)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_csr_small_workloads(idx):
+    w = wl.workload(idx)
+    src, dst = wl.make_graph(w)
+    check_against_oracle(src, dst, w.n_nodes, w.self_loops)
+
+
+def test_csr_rejects_bad_ids_and_small_capacity():
+    n = 50
+    src, dst = wl.random_pairs(n, 200, 7)
+    bad = src.copy()
+    bad[17] = n
+    ws = Hn.ws_tensor(B.retexo_csr_workspace_bytes(200, n, False))
+    rp = torch.full((n + 1,), -7, dtype=torch.int64, device="cuda")
+    ci = torch.full((400,), -7, dtype=torch.int32, device="cuda")
+    st, _ = B.retexo_csr_from_coo(200, Hn.dev(bad).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+                                  rp.data_ptr(), ci.data_ptr(), 400, ws.data_ptr(), ws.numel())
+    assert st == B.E_CSR
+    neg = src.copy()
+    neg[3] = -1
+    st, _ = B.retexo_csr_from_coo(200, Hn.dev(neg).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+                                  rp.data_ptr(), ci.data_ptr(), 400, ws.data_ptr(), ws.numel())
+    assert st == B.E_CSR
+    st, nnz = B.retexo_csr_from_coo(200, Hn.dev(src).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+                                    rp.data_ptr(), ci.data_ptr(), 10, ws.data_ptr(), ws.numel())
+    assert st == B.E_CAPACITY and nnz == oracle.csr_from_coo(src, dst, n, False)[0][-1]
+    torch.cuda.synchronize()
+    assert bool((rp == -7).all()) and bool((ci == -7).all())      # nothing was written
+    st, _ = B.retexo_csr_from_coo(200, Hn.dev(src).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+                                  rp.data_ptr(), ci.data_ptr(), 400, ws.data_ptr(), 64)
+    assert st == B.E_WORKSPACE
+
+
+def test_plan_validation_catches_malformed_csr():
+    rp = Hn.dev(np.array([0, 2, 1, 3], np.int64))             # decreasing
+    ci = Hn.dev(np.array([0, 1, 2], np.int32))
+    st, plan = B.retexo_plan_create(3, rp.data_ptr(), ci.data_ptr(), B.F_VALIDATE)
+    assert st == B.E_CSR and plan is None
+    rp = Hn.dev(np.array([1, 2, 3, 3], np.int64))             # does not start at 0
+    st, plan = B.retexo_plan_create(3, rp.data_ptr(), ci.data_ptr(), B.F_VALIDATE)
+    assert st == B.E_CSR and plan is None
+    rp = Hn.dev(np.array([0, 1, 2, 3], np.int64))
+    ci = Hn.dev(np.array([0, 3, 2], np.int32))                # column out of range
+    st, plan = B.retexo_plan_create(3, rp.data_ptr(), ci.data_ptr(), B.F_VALIDATE)
+    assert st == B.E_CSR and plan is None
+    ci = Hn.dev(np.array([0, 1, 2], np.int32))
+    st, plan = B.retexo_plan_create(3, rp.data_ptr(), ci.data_ptr(), B.F_VALIDATE)
+    assert st == B.OK and plan
+    B.retexo_plan_destroy(plan)

@@ -1,0 +1,131 @@
+"""Whole rounds (retexo_round / retexo_transform chained as the workloads
+prescribe) against the oracle: the three small workloads end to end, and the
+two large ones stage by stage on sampled rows at full size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_13053_amd import binding as B
+from paper_2302_13053_amd import harness as Hn
+from paper_2302_13053_amd import workloads as wl
+from parity import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_stage(st, rp, ci, H, p, rows=None):
+    if st.kind == "transform":
+        return oracle.transform(H, st.d_in, p.W, p.b, st.relu, rows=rows)
+    return oracle.round_(st.mode, rp, ci, H, st.d_in, p.W, p.b, relu=st.relu, heads=st.heads,
+                         a_src=p.a_src, a_dst=p.a_dst, self_concat=st.concat, rows=rows)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_small_workloads_end_to_end(idx):
+    w = wl.workload(idx)
+    src, dst = wl.make_graph(w)
+    feats = wl.make_features(w, ld=wl.pad_ld(w.feat_dim))
+    params = wl.make_params(w)
+    pipe = Hn.Pipeline(w, src, dst, feats, params)
+    outs = pipe.run()
+    torch.cuda.synchronize()
+    rp, ci = oracle.csr_from_coo(src, dst, w.n_nodes, w.self_loops)
+    assert np.array_equal(pipe.row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(pipe.col_idx[:pipe.graph.nnz].cpu().numpy(), ci)
+    H = feats
+    for i, st in enumerate(w.stages):
+        want = oracle_stage(st, rp, ci, H, params[i])
+        got = outs[i].cpu().numpy()[:, :st.out_width]
+        assert_close(got, want, what="workload %d stage %d (%s)" % (idx, i, st.kind))
+        H = want.astype(np.float32)          # the oracle feeds itself, never the GPU's values
+    # second pass over the same buffers reproduces the first bit for bit
+    keep = [o.clone() for o in outs]
+    outs = pipe.run()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(keep, outs))
+    pipe.close()
+
+
+def test_round_separately_equals_fused_and_gcn_gat_modes():
+    n = 4000
+    src, dst = wl.random_pairs(n, 30000, 21, skew=2.0)
+    H = wl.random_matrix(n, 150, 22, ld=160)
+    W = wl.glorot(np.random.Generator(np.random.Philox(key=23)), 150, 192, (150, 192))
+    b = wl.random_matrix(1, 192, 24)[0] * np.float32(0.1)
+    a_s = wl.random_matrix(4, 48, 25) * np.float32(0.2)
+    a_d = wl.random_matrix(4, 48, 26) * np.float32(0.2)
+    for mode, concat, relu, sl in [("gcn_sym", False, True, True), ("gat_softmax", False, False, False),
+                                   ("mean", True, True, False), ("sum", False, False, False)]:
+        g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, sl))
+        rp, ci = oracle.csr_from_coo(src, dst, n, sl)
+        st = wl.Stage("round", 150, 192, relu=relu, mode=mode, concat=concat, heads=4)
+        out = torch.empty((n, wl.pad_ld(st.out_width)), dtype=torch.float32, device="cuda")
+        ws = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, 192, B.MODES[mode], 4,
+                                                   B.F_SELF_CONCAT if concat else 0))
+        gat = mode == "gat_softmax"
+        Hn.round_(g, st, Hn.dev(H), Hn.dev(W), Hn.dev(b), Hn.dev(a_s) if gat else None,
+                  Hn.dev(a_d) if gat else None, out, ws)
+        want = oracle.round_(mode, rp, ci, H, 150, W, b, relu=relu, heads=4, a_src=a_s, a_dst=a_d,
+                             self_concat=concat)
+        assert_close(out.cpu().numpy()[:, :st.out_width], want, what="round " + mode)
+        # the two-call form gives the same bits as the fused call
+        Z = Hn.transform(Hn.dev(H), 150, Hn.dev(W), Hn.dev(b), relu)
+        out2 = Hn.aggregate(g, mode, Z, 192, heads=4, a_src=Hn.dev(a_s) if gat else None,
+                            a_dst=Hn.dev(a_d) if gat else None, concat=concat)
+        assert torch.equal(out2[:, :st.out_width], out[:, :st.out_width])
+        g.destroy()
+
+
+def sample_rows(rp, k, seed):
+    deg = np.diff(rp)
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    heavy = np.argsort(deg)[-3:]
+    light = np.argsort(deg)[:3]
+    rnd = rng.integers(0, deg.size, k)
+    return np.unique(np.concatenate([heavy, light, rnd])).astype(np.int64)
+
+
+@pytest.mark.parametrize("idx", [3, 4])
+def test_large_workloads_full_size_sampled_rows(idx):
+    """Each stage of the two large workloads at full size, in the launch
+    configuration the benchmark uses.  Stage 0 takes the workload's own
+    features; later stages take a seeded random matrix of the right shape (a
+    chained comparison would need the oracle's full previous output).  The
+    oracle evaluates a sample of rows that includes the longest rows."""
+    w = wl.workload(idx)
+    print("generating workload", idx, flush=True)
+    src, dst = wl.make_graph(w)
+    feats = wl.make_features(w, ld=wl.pad_ld(w.feat_dim))
+    params = wl.make_params(w)
+    pipe = Hn.Pipeline(w, src, dst, feats, params)
+    print("gpu csr + plan", flush=True)
+    pipe.build_graph()
+    torch.cuda.synchronize()
+    print("oracle csr", flush=True)
+    rp, ci = oracle.csr_from_coo(src, dst, w.n_nodes, w.self_loops)
+    assert np.array_equal(pipe.row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(pipe.col_idx[:pipe.graph.nnz].cpu().numpy(), ci)
+    deg, dinv, _ = Hn.plan_arrays(pipe.graph)
+    odeg, odinv = oracle.degree(rp)
+    assert np.array_equal(deg, odeg) and np.array_equal(dinv.view(np.uint32), odinv.view(np.uint32))
+    del src, dst
+    rows = sample_rows(rp, 24 if idx == 3 else 200, seed=idx)
+    for i, st in enumerate(w.stages):
+        print("stage", i, st, flush=True)
+        if i == 0:
+            H = feats
+        else:
+            H = wl.random_matrix(w.n_nodes, st.d_in, 100 + i, ld=wl.pad_ld(st.d_in))
+            pipe.outs[i - 1].copy_(torch.from_numpy(H))
+        pipe.run_stage(i)
+        torch.cuda.synchronize()
+        got = pipe.outs[i][torch.from_numpy(rows).cuda()].cpu().numpy()[:, :st.out_width]
+        want = oracle_stage(st, rp, ci, H, params[i], rows=rows)
+        assert_close(got, want, what="workload %d stage %d full size" % (idx, i))
+        # property that holds at any size: the self half of a concatenated output is a bit copy
+        if st.kind == "round" and st.concat and not st.w:
+            chk = torch.from_numpy(rows[:8]).cuda()
+            assert torch.equal(pipe.outs[i][chk][:, :st.d_out], pipe.H0[chk][:, :st.d_out])
+        del H
+    pipe.close()

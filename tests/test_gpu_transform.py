@@ -1,0 +1,71 @@
+"""GPU dense transform (fp32 matrix cores) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_13053_amd import binding as B
+from paper_2302_13053_amd import harness as Hn
+from paper_2302_13053_amd import workloads as wl
+from parity import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def run(n, d_in, d_out, ldh, ldz, relu, bias, seed):
+    H = wl.random_matrix(n, d_in, seed, ld=ldh)
+    H[:, d_in:] = np.nan                                   # padding must never be read into a result
+    W = wl.glorot(np.random.Generator(np.random.Philox(key=seed + 1)), d_in, d_out, (d_in, d_out))
+    b = wl.random_matrix(1, d_out, seed + 2)[0] if bias else None
+    Z = torch.full((n, ldz), 777.0, dtype=torch.float32, device="cuda")
+    Hn.transform(Hn.dev(H), d_in, Hn.dev(W), Hn.dev(b) if bias else None, relu, out=Z)
+    torch.cuda.synchronize()
+    Zh = Z.cpu().numpy()
+    assert np.all(Zh[:, d_out:] == 777.0)                  # padding columns untouched
+    return H, W, b, Zh[:, :d_out]
+
+
+@pytest.mark.parametrize("n,d_in,d_out,ldh,ldz,relu,bias", [
+    (1000, 37, 5, 37, 5, False, True),          # everything unaligned, skinny output
+    (333, 100, 256, 128, 256, False, True),     # GAT first round shape
+    (700, 1204, 256, 1216, 512, True, True),    # SAGE large: K tail of 4
+    (129, 2866, 64, 2880, 128, True, True),     # tiny-SAGE hidden layer
+    (257, 512, 41, 512, 41, False, True),       # classifier, odd width
+    (515, 256, 188, 256, 192, False, False),    # GAT last round, no bias
+    (64, 16, 32, 16, 32, True, False),          # exactly one tile, one K step
+    (1, 3, 300, 3, 300, False, True),           # single row, more than one column tile
+    (2049, 128, 7, 128, 32, False, True),
+])
+def test_transform_matches_oracle(n, d_in, d_out, ldh, ldz, relu, bias):
+    H, W, b, Z = run(n, d_in, d_out, ldh, ldz, relu, bias, seed=n + d_in)
+    want = oracle.transform(H, d_in, W, b, relu)
+    assert_close(Z, want, what="transform %dx%d->%d" % (n, d_in, d_out))
+
+
+def test_transform_identity_weight_is_exact_and_relu_clamps():
+    n, d = 300, 96
+    H = wl.random_matrix(n, d, 5)
+    Z = Hn.transform(Hn.dev(H), d, Hn.dev(np.eye(d, dtype=np.float32)), None, False)
+    assert np.array_equal(Z.cpu().numpy()[:, :d], H)
+    Z = Hn.transform(Hn.dev(H), d, Hn.dev(np.eye(d, dtype=np.float32)), None, True)
+    assert np.array_equal(Z.cpu().numpy()[:, :d], np.maximum(H, 0))
+
+
+def test_transform_small_integers_are_exact():
+    # products and sums of small integers are exact in fp32 in any order: checks operand indexing
+    n, d_in, d_out = 400, 70, 130
+    H = wl.random_matrix(n, d_in, 6, kind="smallint")
+    W = wl.random_matrix(d_in, d_out, 7, kind="smallint")
+    b = wl.random_matrix(1, d_out, 8, kind="smallint")[0]
+    Z = Hn.transform(Hn.dev(H), d_in, Hn.dev(W), Hn.dev(b), False)
+    assert np.array_equal(Z.cpu().numpy()[:, :d_out].astype(np.float64), oracle.transform(H, d_in, W, b))
+
+
+def test_transform_is_deterministic_and_rejects_alias():
+    n, d_in, d_out = 777, 200, 256
+    H = Hn.dev(wl.random_matrix(n, d_in, 9))
+    W = Hn.dev(wl.random_matrix(d_in, d_out, 10))
+    a = Hn.transform(H, d_in, W, None, True).clone()
+    b = Hn.transform(H, d_in, W, None, True)
+    assert torch.equal(a, b)
+    assert B.retexo_transform(n, d_in, d_in, H.data_ptr(), d_in, W.data_ptr(), 0, 0, H.data_ptr(), d_in) == B.E_ALIAS
