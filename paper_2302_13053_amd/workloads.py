@@ -381,6 +381,8 @@ def random_matrix(rows: int, cols: int, seed: int, ld: Optional[int] = None,
     out = np.zeros((rows, ld), np.float32)
     if kind == "normal":
         out[:, :cols] = rng.standard_normal((rows, cols), dtype=np.float32)
+    elif kind == "absnormal":
+        out[:, :cols] = np.abs(rng.standard_normal((rows, cols), dtype=np.float32))
     elif kind == "smallint":
         out[:, :cols] = rng.integers(-3, 4, (rows, cols)).astype(np.float32)
     else:

@@ -81,7 +81,10 @@ def run_case(graphs, name, mode, F, ld, heads, concat, seed, kind="normal", base
 def test_modes_match_oracle_on_skewed_graph(graphs, mode, F, ld, heads, concat, offset):
     if mode == "gat_softmax" and F % heads:
         heads = 1
-    got, want = run_case(graphs, "skewed", mode, F, ld, heads, concat, seed=F + 17, base_offset=offset)
+    # a row narrower than a few dozen columns has no robust magnitude to measure against when signed
+    # terms cancel (any fp32 summation then shows a large ratio), so narrow cases use non-negative data
+    kind = "normal" if F >= 64 else "absnormal"
+    got, want = run_case(graphs, "skewed", mode, F, ld, heads, concat, seed=F + 17, kind=kind, base_offset=offset)
     assert_close(got, want, what="%s F=%d" % (mode, F))
     if concat:
         assert np.array_equal(got[:, :F].astype(np.float64), want[:, :F])      # self copy is a bit copy

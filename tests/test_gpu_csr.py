@@ -69,22 +69,25 @@ def test_csr_rejects_bad_ids_and_small_capacity():
     bad = src.copy()
     bad[17] = n
     ws = Hn.ws_tensor(B.retexo_csr_workspace_bytes(200, n, False))
+    d_src, d_dst = Hn.dev(src), Hn.dev(dst)      # named so that the device buffers stay alive
     rp = torch.full((n + 1,), -7, dtype=torch.int64, device="cuda")
     ci = torch.full((400,), -7, dtype=torch.int32, device="cuda")
-    st, _ = B.retexo_csr_from_coo(200, Hn.dev(bad).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+    d_bad = Hn.dev(bad)
+    st, _ = B.retexo_csr_from_coo(200, d_bad.data_ptr(), d_dst.data_ptr(), n, False,
                                   rp.data_ptr(), ci.data_ptr(), 400, ws.data_ptr(), ws.numel())
     assert st == B.E_CSR
     neg = src.copy()
     neg[3] = -1
-    st, _ = B.retexo_csr_from_coo(200, Hn.dev(neg).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+    d_neg = Hn.dev(neg)
+    st, _ = B.retexo_csr_from_coo(200, d_neg.data_ptr(), d_dst.data_ptr(), n, False,
                                   rp.data_ptr(), ci.data_ptr(), 400, ws.data_ptr(), ws.numel())
     assert st == B.E_CSR
-    st, nnz = B.retexo_csr_from_coo(200, Hn.dev(src).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+    st, nnz = B.retexo_csr_from_coo(200, d_src.data_ptr(), d_dst.data_ptr(), n, False,
                                     rp.data_ptr(), ci.data_ptr(), 10, ws.data_ptr(), ws.numel())
     assert st == B.E_CAPACITY and nnz == oracle.csr_from_coo(src, dst, n, False)[0][-1]
     torch.cuda.synchronize()
     assert bool((rp == -7).all()) and bool((ci == -7).all())      # nothing was written
-    st, _ = B.retexo_csr_from_coo(200, Hn.dev(src).data_ptr(), Hn.dev(dst).data_ptr(), n, False,
+    st, _ = B.retexo_csr_from_coo(200, d_src.data_ptr(), d_dst.data_ptr(), n, False,
                                   rp.data_ptr(), ci.data_ptr(), 400, ws.data_ptr(), 64)
     assert st == B.E_WORKSPACE
 
