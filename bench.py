@@ -30,7 +30,9 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant aggregation measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "sage_large_powerlaw": 262309950892,   # profiles/bench_sage_large_powerlaw.md: 261.13 GB fetched + 1.18 GB written
+}
 
 
 def parse():
@@ -41,6 +43,9 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (0-4)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = per-workload default)")
+    ap.add_argument("--probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one pass, then one 1 GiB device copy (the known-size "
+                         "reference for the byte counters) and one launch of the dominant aggregation; no JSON")
     return ap.parse_args()
 
 
@@ -129,6 +134,26 @@ def main():
     t_gen = time.perf_counter() - t0
 
     pipe = Hn.Pipeline(w, src, dst, feats, params)
+    if args.probe:
+        pipe.run()
+        torch.cuda.synchronize()
+        ref_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        ref_dst = torch.empty_like(ref_src)
+        torch.cuda.synchronize()
+        ref_dst.copy_(ref_src)                       # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        di = max((i for i, st in enumerate(w.stages) if st.kind == "round"),
+                 key=lambda i: w.stages[i].d_out)
+        st = w.stages[di]
+        Zin = pipe.H0 if not st.w else torch.empty((w.n_nodes, wl.pad_ld(st.d_out)), dtype=torch.float32,
+                                                   device="cuda").normal_()
+        _, _, a_s, a_d = pipe.params[di]
+        Hn.aggregate(pipe.graph, st.mode, Zin, st.d_out, heads=st.heads, a_src=a_s, a_dst=a_d, concat=st.concat)
+        torch.cuda.synchronize()
+        print("probe done: copy of %d bytes each way, then stage %d aggregation (F=%d)"
+              % (ref_src.numel() * 4, di, st.d_out))
+        pipe.close()
+        return
     for _ in range(args.warmup):
         pipe.run()
     torch.cuda.synchronize()
@@ -236,7 +261,7 @@ def main():
     }
     pipe.close()
     if not args.no_cpu:
-        default_rows = {0: 2708, 1: 19717, 2: 22470, 3: 20000, 4: 100000}[w.index]
+        default_rows = {0: 2708, 1: 19717, 2: 22470, 3: 232965, 4: 600000}[w.index]
         out["cpu_baseline"] = cpu_baseline(w, src, dst, feats, params, args.cpu_rows or default_rows)
     print(json.dumps(out))
 
