@@ -53,7 +53,9 @@ typedef enum {
 enum {
     RETEXO_F_RELU = 1,         /* transform: act = ReLU (Eq. 1's f)                   */
     RETEXO_F_SELF_CONCAT = 2,  /* aggregate: out row = [ z_v | aggregate ], 2F wide   */
-    RETEXO_F_VALIDATE = 4      /* plan_create: check the CSR on the device first      */
+    RETEXO_F_VALIDATE = 4,     /* plan_create: check the CSR on the device first      */
+    RETEXO_F_SPLIT_ROWS = 8    /* plan_create: always build the per-row source-range split
+                                  (by default only for dense graphs too large for L2)  */
 };
 
 typedef enum {
@@ -178,7 +180,9 @@ int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out,
 /* ---------------------------------------------------------------------------
  * Tuning knobs (process-wide, for experiments; defaults are chosen per shape).
  * name: "agg_slab_cols" (0 = auto), "agg_slab_major" (-1 auto / 0 / 1),
- *       "agg_heavy_degree" (rows at least this long get a whole workgroup).
+ *       "agg_heavy_degree" (rows at least this long get a whole workgroup),
+ *       "agg_parts" (source-id ranges walked one after the other: -1 auto, 1 off, 2/4/8/16),
+ *       "agg_max_vec" (cap on floats per lane per gather).
  * Returns RETEXO_E_FLAGS for an unknown name.
  */
 int retexo_set_option(const char* name, int64_t value);

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libretexo.so")
 
 MEAN, SUM, GCN_SYM, GAT_SOFTMAX = 0, 1, 2, 3
 MODES = {"mean": MEAN, "sum": SUM, "gcn_sym": GCN_SYM, "gat_softmax": GAT_SOFTMAX}
-F_RELU, F_SELF_CONCAT, F_VALIDATE = 1, 2, 4
+F_RELU, F_SELF_CONCAT, F_VALIDATE, F_SPLIT_ROWS = 1, 2, 4, 8
 
 OK = 0
 E_NULL, E_SIZE, E_LD, E_MODE, E_FLAGS, E_HEADS = -1, -2, -3, -4, -5, -6

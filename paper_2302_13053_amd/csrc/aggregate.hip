@@ -62,6 +62,12 @@ struct AggArgs {
     int copy_self;         // also write z_v into out[:, 0:F]
     int out_vec;           // aggregate slot of out is aligned for VEC-wide stores
     int self_vec;          // self slot of out is aligned for VEC-wide stores
+    // source-range walk (grouped kernel only): this launch covers the entries of each row whose
+    // column lies in ranges [part_lo, part_hi) of the plan's split; NULL = whole rows
+    const int32_t* part_ptr;
+    int part_lo, part_hi;
+    int first;             // first range of the walk: start from zero, write the self copy
+    int last;              // last range: apply the mean / gcn scaling
 };
 
 template <int VEC>
@@ -243,6 +249,379 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
             load_row<VEC>(a.Z + (int64_t)v * a.ldz + col, zs);
             store_row<VEC>(orow + col, zs, valid, a.self_vec != 0);
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// sum / mean / gcn_sym with narrow column slabs ("grouped gather").
+//
+// When one column slab of the whole table (N rows x SW columns) is small
+// enough to stay in the last-level caches, walking the graph once per slab
+// turns most gathers into cache hits instead of HBM reads.  A slab is
+// SW = 4*LPG columns wide; a wave splits into G = 64/LPG groups of LPG lanes,
+// each lane owning one float4 of the slab, and every wave-wide load fetches the
+// slab of G different neighbours (G x SW x 4 = 1 KiB per instruction, as in the
+// full-row kernel).  Neighbour ids are loaded 64 at a time and handed to the
+// groups with a wave shuffle; the groups' partial sums are combined with
+// xor-shuffles when the row is done.  Same ownership rules as above: one wave
+// (or one workgroup for long rows) writes an output element, in a fixed order.
+// ---------------------------------------------------------------------------
+// One 64-edge tile of the grouped gather.  Each lane holds the byte offset of
+// one neighbour's row (and its gcn weight); step t hands entry t*G + g to group
+// g with a wave shuffle.  All loads of a batch of up to 8 steps are issued
+// before their FMAs, and nothing in the batch branches: lanes past the end of
+// a partial tile fetch a valid address (offset 0) and have the loaded values
+// replaced by zero; lanes past the row width fetch the last valid vector of
+// the slab and simply never store.
+//   OFF32: every row offset fits 32 bits, so the gather is base + 32-bit offset
+template <int LPG, bool FULL, bool WEIGHTED, bool OFF32>
+__device__ __forceinline__ void grouped_tile(const char* zbase, uint32_t colbytes, int64_t rowbytes,
+                                             uint32_t my_off, int my_u, float my_w, int cnt, int g,
+                                             float (&acc)[4])
+{
+    constexpr int G = 64 / LPG;
+    constexpr int STEPS = 64 / G;
+    constexpr int U = STEPS < 8 ? STEPS : 8;
+#pragma unroll
+    for (int t0 = 0; t0 < STEPS; t0 += U) {
+        if (!FULL && t0 * G >= cnt) break;
+        f32x4 z[U];
+        float w[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            const int j = (t0 + t) * G + g;
+            if constexpr (OFF32) {
+                const uint32_t off = (uint32_t)__shfl((int)my_off, j, 64) + colbytes;
+                z[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+            } else {
+                const int u = __shfl(my_u, j, 64);
+                z[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
+            }
+            if constexpr (WEIGHTED) w[t] = __shfl(my_w, j, 64);
+            if constexpr (!FULL) {
+                const bool ok = j < cnt;
+                z[t].x = ok ? z[t].x : 0.0f;
+                z[t].y = ok ? z[t].y : 0.0f;
+                z[t].z = ok ? z[t].z : 0.0f;
+                z[t].w = ok ? z[t].w : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            if constexpr (WEIGHTED) {
+                acc[0] = fmaf(w[t], z[t].x, acc[0]);
+                acc[1] = fmaf(w[t], z[t].y, acc[1]);
+                acc[2] = fmaf(w[t], z[t].z, acc[2]);
+                acc[3] = fmaf(w[t], z[t].w, acc[3]);
+            } else {
+                acc[0] += z[t].x;
+                acc[1] += z[t].y;
+                acc[2] += z[t].z;
+                acc[3] += z[t].w;
+            }
+        }
+    }
+}
+
+constexpr int kRowsPerWave = 8;    // consecutive rows handled by one wave of the light grouped kernel
+
+template <int LPG, int NW, bool WEIGHTED, bool OFF32>
+__global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_grouped_kernel(AggArgs a)
+{
+    constexpr int SW = 4 * LPG;
+    constexpr int K = NW == 1 ? kRowsPerWave : 1;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // work item = (slab, run of K consecutive schedule slots); slab-major unless told otherwise
+    const int64_t runs = (a.row_count + K - 1) / K;
+    const int64_t items = runs * a.nslab;
+    const int64_t item = (NW == 1) ? (int64_t)blockIdx.x * kLightWaves + wave : (int64_t)blockIdx.x;
+    if (item >= items) return;        // NW > 1: uniform over the workgroup
+    int64_t run;
+    int slab;
+    if (a.slab_major) { slab = (int)(item / runs); run = item % runs; }
+    else              { run = item / a.nslab; slab = (int)(item % a.nslab); }
+    const int64_t slot0 = run * K;
+    const int nrows = (int)min((int64_t)K, a.row_count - slot0);
+
+    // row metadata, one row per lane: a single dependent chain for all K rows
+    int v_l = 0, lo_l = 0, hi_l = 0;
+    if (lane < nrows) {
+        v_l = a.order[a.row_begin + slot0 + lane];
+        if (a.part_ptr) {
+            lo_l = a.part_ptr[(int64_t)v_l * (kMaxParts + 1) + a.part_lo];
+            hi_l = a.part_ptr[(int64_t)v_l * (kMaxParts + 1) + a.part_hi];
+        } else {
+            lo_l = (int)a.row_ptr[v_l];
+            hi_l = (int)a.row_ptr[v_l + 1];
+        }
+    }
+
+    const int li = lane % LPG, g = lane / LPG;
+    const int64_t col = (int64_t)slab * SW + li * 4;
+    const bool act = col < a.F;
+    const bool writer = act && g == 0;
+    const int valid = (int)min((int64_t)4, a.F - col);
+    // lanes past the row width gather the slab's last valid vector instead (never stored)
+    const int64_t gcol = act ? col : ((a.F - 1) / 4) * 4;
+    const char* zbase = reinterpret_cast<const char*>(a.Z);
+    const uint32_t colbytes = (uint32_t)(gcol * 4);
+    const int64_t rowbytes = a.ldz * 4;
+
+    // ids of the first tile of the first row
+    int nxt_u = 0;
+    float nxt_w = 0.0f;
+    {
+        const int lo = bcast_i(lo_l, 0), hi = bcast_i(hi_l, 0);
+        const int e = lo + 64 * (NW == 1 ? 0 : wave) + lane;
+        if (e < hi) {
+            nxt_u = a.col_idx[e];
+            if (WEIGHTED) nxt_w = a.dinv[nxt_u];
+        }
+    }
+
+    for (int r = 0; r < nrows; ++r) {
+        const int v = bcast_i(v_l, r);
+        const int lo = bcast_i(lo_l, r), hi = bcast_i(hi_l, r);
+        float* orow = a.out + (int64_t)v * a.ldo;
+        int my_u = nxt_u;
+        float my_w = nxt_w;
+        if (K > 1 && r + 1 < nrows) {          // ids of the next row's first tile, fetched a row ahead
+            const int lo1 = bcast_i(lo_l, r + 1), hi1 = bcast_i(hi_l, r + 1);
+            const int e = lo1 + lane;
+            nxt_u = 0;
+            nxt_w = 0.0f;
+            if (e < hi1) {
+                nxt_u = a.col_idx[e];
+                if (WEIGHTED) nxt_w = a.dinv[nxt_u];
+            }
+        }
+        // running sum over the source ranges walked so far (written by the previous launch)
+        float prev[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (!a.first && writer && (NW == 1 || wave == 0)) {
+            if (a.out_vec && valid >= 4) load_row<4>(orow + a.ocol + col, prev);
+            else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (k < valid) prev[k] = orow[a.ocol + col + k];
+            }
+        }
+
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int base = lo + 64 * (NW == 1 ? 0 : wave); base < hi; base += 64 * NW) {
+            const int cnt = min(64, hi - base);
+            const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
+            if (cnt == 64)
+                grouped_tile<LPG, true, WEIGHTED, OFF32>(zbase, colbytes, rowbytes, my_off, my_u, my_w, cnt, g, acc);
+            else
+                grouped_tile<LPG, false, WEIGHTED, OFF32>(zbase, colbytes, rowbytes, my_off, my_u, my_w, cnt, g, acc);
+            if (base + 64 * NW < hi) {
+                const int e = base + 64 * NW + lane;
+                my_u = e < hi ? a.col_idx[e] : 0;
+                if (WEIGHTED) my_w = e < hi ? a.dinv[my_u] : 0.0f;
+            }
+        }
+        // combine the G groups: afterwards every lane holds the sum for its columns
+#pragma unroll
+        for (int m = LPG; m < 64; m <<= 1)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] += __shfl_xor(acc[k], m, 64);
+
+        if constexpr (NW > 1) {
+            __shared__ float red[NW][4][LPG];
+            if (g == 0) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) red[wave][k][li] = acc[k];
+            }
+            __syncthreads();
+            if (wave != 0) return;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float s = red[0][k][li];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) s += red[w][k][li];
+                acc[k] = s;
+            }
+        }
+        if (writer) {
+            const int d = a.deg[v];
+            float out_v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float x = acc[k] + prev[k];
+                if (a.last) {
+                    if (a.scale == SCALE_MEAN) x = d > 0 ? x / (float)d : 0.0f;
+                    else if (a.scale == SCALE_GCN) x = x * a.dinv[v];
+                }
+                out_v[k] = x;
+            }
+            store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0);
+            if (a.copy_self && a.first) {
+                float zs[4];
+                load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
+                store_row<4>(orow + col, zs, valid, a.self_vec != 0);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Narrow slabs, ordinary rows: one ROW per lane group.
+//
+// The G = 64/LPG lane groups of a wave take G consecutive rows of the schedule
+// (similar lengths, since the schedule is sorted by degree) and walk their
+// neighbour lists in lock step: every wave-wide load fetches the slab of one
+// neighbour for each of the G rows.  No cross-group reduction is needed, the
+// running-sum read, the scaling and the store are one wave-wide operation for
+// G rows, and the per-row bookkeeping is shared — which is what matters once a
+// row's share of one source range is only a few dozen entries long.
+// Neighbour ids are fetched LPG at a time per group (one per lane, the next
+// chunk a step ahead) and handed round inside the group with ds_bpermute.
+// ---------------------------------------------------------------------------
+template <int LPG, bool WEIGHTED, bool OFF32>
+__global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs a)
+{
+    constexpr int G = 64 / LPG;
+    constexpr int SW = 4 * LPG;
+    constexpr int U = LPG < 8 ? LPG : 8;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t bundles = (a.row_count + G - 1) / G;
+    const int64_t items = bundles * a.nslab;
+    const int64_t item = (int64_t)blockIdx.x * kLightWaves + wave;
+    if (item >= items) return;
+    int64_t bundle;
+    int slab;
+    if (a.slab_major) { slab = (int)(item / bundles); bundle = item % bundles; }
+    else              { bundle = item / a.nslab; slab = (int)(item % a.nslab); }
+
+    const int li = lane % LPG, g = lane / LPG;
+    const int64_t slot = bundle * G + g;
+    const bool has_row = slot < a.row_count;
+    int v = 0, lo = 0, hi = 0;
+    if (has_row) {
+        v = a.order[a.row_begin + slot];
+        if (a.part_ptr) {
+            lo = a.part_ptr[(int64_t)v * (kMaxParts + 1) + a.part_lo];
+            hi = a.part_ptr[(int64_t)v * (kMaxParts + 1) + a.part_hi];
+        } else {
+            lo = (int)a.row_ptr[v];
+            hi = (int)a.row_ptr[v + 1];
+        }
+    }
+    const int len = hi - lo;
+    int maxlen = len, minlen = len;
+#pragma unroll
+    for (int m = LPG; m < 64; m <<= 1) {
+        maxlen = max(maxlen, __shfl_xor(maxlen, m, 64));
+        minlen = min(minlen, __shfl_xor(minlen, m, 64));
+    }
+    maxlen = __builtin_amdgcn_readfirstlane(maxlen);
+    minlen = __builtin_amdgcn_readfirstlane(minlen);
+
+    const int64_t col = (int64_t)slab * SW + li * 4;
+    const bool act = col < a.F;
+    const bool writer = act && has_row;
+    const int valid = (int)min((int64_t)4, a.F - col);
+    const int64_t gcol = act ? col : ((a.F - 1) / 4) * 4;
+    const char* zbase = reinterpret_cast<const char*>(a.Z);
+    const uint32_t colbytes = (uint32_t)(gcol * 4);
+    const int64_t rowbytes = a.ldz * 4;
+    float* orow = a.out + (int64_t)v * a.ldo;
+
+    float prev[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (!a.first && writer) {
+        if (a.out_vec && valid >= 4) load_row<4>(orow + a.ocol + col, prev);
+        else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k < valid) prev[k] = orow[a.ocol + col + k];
+        }
+    }
+
+    const int gaddr = (lane - li) * 4;      // ds_bpermute byte address of this group's lane 0
+    int nxt_u = 0;
+    float nxt_w = 0.0f;
+    if (li < len) {
+        nxt_u = a.col_idx[lo + li];
+        if (WEIGHTED) nxt_w = a.dinv[nxt_u];
+    }
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int c0 = 0; c0 < maxlen; c0 += LPG) {
+        const int my_u = nxt_u;
+        const float my_w = nxt_w;
+        const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
+        {
+            const int nb = c0 + LPG + li;          // this lane's entry of the next chunk
+            nxt_u = 0;
+            nxt_w = 0.0f;
+            if (nb < len) {
+                nxt_u = a.col_idx[lo + nb];
+                if (WEIGHTED) nxt_w = a.dinv[nxt_u];
+            }
+        }
+        const bool full = c0 + LPG <= minlen;      // every group still has LPG entries: no masking
+#pragma unroll
+        for (int i0 = 0; i0 < LPG; i0 += U) {
+            f32x4 z[U];
+            float w[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                const int i = i0 + t;
+                if constexpr (OFF32) {
+                    const uint32_t off =
+                        (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * i, (int)my_off) + colbytes;
+                    z[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+                } else {
+                    const int u = __builtin_amdgcn_ds_bpermute(gaddr + 4 * i, my_u);
+                    z[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
+                }
+                if constexpr (WEIGHTED)
+                    w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * i, __float_as_int(my_w)));
+            }
+            if (!full) {
+#pragma unroll
+                for (int t = 0; t < U; ++t) {
+                    const bool ok = c0 + i0 + t < len;
+                    z[t].x = ok ? z[t].x : 0.0f;
+                    z[t].y = ok ? z[t].y : 0.0f;
+                    z[t].z = ok ? z[t].z : 0.0f;
+                    z[t].w = ok ? z[t].w : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                if constexpr (WEIGHTED) {
+                    acc[0] = fmaf(w[t], z[t].x, acc[0]);
+                    acc[1] = fmaf(w[t], z[t].y, acc[1]);
+                    acc[2] = fmaf(w[t], z[t].z, acc[2]);
+                    acc[3] = fmaf(w[t], z[t].w, acc[3]);
+                } else {
+                    acc[0] += z[t].x;
+                    acc[1] += z[t].y;
+                    acc[2] += z[t].z;
+                    acc[3] += z[t].w;
+                }
+            }
+        }
+    }
+    if (!writer) return;
+    const int d = a.deg[v];
+    float out_v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float x = acc[k] + prev[k];
+        if (a.last) {
+            if (a.scale == SCALE_MEAN) x = d > 0 ? x / (float)d : 0.0f;
+            else if (a.scale == SCALE_GCN) x = x * a.dinv[v];
+        }
+        out_v[k] = x;
+    }
+    store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0);
+    if (a.copy_self && a.first) {
+        float zs[4];
+        load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
+        store_row<4>(orow + col, zs, valid, a.self_vec != 0);
     }
 }
 
@@ -478,6 +857,47 @@ void launch_linear_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStre
     }
 }
 
+template <int LPG, bool WEIGHTED, bool OFF32>
+void launch_grouped_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
+{
+    if (n_heavy > 0) {
+        AggArgs a = base;
+        a.row_begin = 0;
+        a.row_count = n_heavy;
+        const int64_t blocks = n_heavy * a.nslab;
+        agg_grouped_kernel<LPG, kHeavyWaves, WEIGHTED, OFF32>
+            <<<dim3((unsigned)blocks), dim3(64 * kHeavyWaves), 0, stream>>>(a);
+    }
+    if (N > n_heavy) {
+        AggArgs a = base;
+        a.row_begin = n_heavy;
+        a.row_count = N - n_heavy;
+        if (agg_options().row_groups) {
+            const int64_t bundles = (a.row_count + (64 / LPG) - 1) / (64 / LPG);
+            const int64_t blocks = (bundles * a.nslab + kLightWaves - 1) / kLightWaves;
+            agg_rowgroup_kernel<LPG, WEIGHTED, OFF32>
+                <<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+        } else {
+            const int64_t runs = (a.row_count + kRowsPerWave - 1) / kRowsPerWave;
+            const int64_t blocks = (runs * a.nslab + kLightWaves - 1) / kLightWaves;
+            agg_grouped_kernel<LPG, 1, WEIGHTED, OFF32>
+                <<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+        }
+    }
+}
+
+template <int LPG>
+void dispatch_grouped(const AggArgs& a, int64_t n_heavy, int64_t N, bool weighted, bool off32, hipStream_t s)
+{
+    if (weighted) {
+        if (off32) launch_grouped_pair<LPG, true, true>(a, n_heavy, N, s);
+        else launch_grouped_pair<LPG, true, false>(a, n_heavy, N, s);
+    } else {
+        if (off32) launch_grouped_pair<LPG, false, true>(a, n_heavy, N, s);
+        else launch_grouped_pair<LPG, false, false>(a, n_heavy, N, s);
+    }
+}
+
 template <int VEC, int NC, int HP, bool HU>
 void launch_gat_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
 {
@@ -544,6 +964,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     int vec = 1;
     if (aligned_for(c.Z, c.ldz, 4) && align_up(c.F, 4) <= c.ldz) vec = 4;
     else if (aligned_for(c.Z, c.ldz, 2) && align_up(c.F, 2) <= c.ldz) vec = 2;
+    if (vec > opt.max_vec) vec = opt.max_vec >= 2 ? 2 : 1;
     if (gat && vec == 2) vec = 1;
     const int max_nc = gat ? 2 : 3;
     int nc;
@@ -577,13 +998,53 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.copy_self = (c.self_concat && c.copy_self) ? 1 : 0;
     a.out_vec = aligned_for(c.out + a.ocol, c.ldo, vec) ? 1 : 0;
     a.self_vec = aligned_for(c.out, c.ldo, vec) ? 1 : 0;
+    a.part_ptr = nullptr;
+    a.part_lo = 0;
+    a.part_hi = 0;
+    a.first = 1;
+    a.last = 1;
 
     // rows at or above the heavy threshold (rounded up to a tabulated one)
     int64_t n_heavy = 0;
     for (int i = 0; i < 8; ++i)
         if (kPlanThresholds[i] >= opt.heavy_degree) { n_heavy = p->rows_at_least[i]; break; }
 
-    if (!gat) {
+    // narrow slabs (32/64/128 columns) use the grouped gather; they need float4 gathers
+    int64_t narrow = (!gat && vec == 4) ? opt.slab_cols : -1;
+    // default for graphs the plan split by source range (dense, table larger than L2): one
+    // 128-byte line per row and slab, ranges sized so that a range's slab stays in L2
+    if (narrow == 0 && p->part_ptr) narrow = 32;
+    if (narrow == 32 || narrow == 64 || narrow == 128) {
+        a.nslab = (int)((c.F + narrow - 1) / narrow);
+        a.slab_major = opt.slab_major < 0 ? 1 : (int)opt.slab_major;
+        int parts = (int)opt.parts;
+        if (parts < 0) {
+            parts = 1;
+            while (parts < kMaxParts && N * narrow * 4 > (int64_t)parts * (8ll << 20)) parts *= 2;
+        }
+        if (!p->part_ptr || (parts != 2 && parts != 4 && parts != 8 && parts != 16)) parts = 1;
+        if (parts > 1) {
+            // long-row class by the length of a row's share of one range
+            n_heavy = 0;
+            for (int i = 0; i < 8; ++i)
+                if (kPlanThresholds[i] >= 1024 * parts || kPlanThresholds[i] >= 16384) {
+                    n_heavy = p->rows_at_least[i];
+                    break;
+                }
+            a.part_ptr = p->part_ptr;
+        }
+        for (int k = 0; k < parts; ++k) {
+            a.part_lo = k * (kMaxParts / parts);
+            a.part_hi = (k + 1) * (kMaxParts / parts);
+            a.first = k == 0;
+            a.last = k == parts - 1;
+            const bool wtd = a.scale == SCALE_GCN;
+            const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32);
+            if (narrow == 32) dispatch_grouped<8>(a, n_heavy, N, wtd, off32, stream);
+            else if (narrow == 64) dispatch_grouped<16>(a, n_heavy, N, wtd, off32, stream);
+            else dispatch_grouped<32>(a, n_heavy, N, wtd, off32, stream);
+        }
+    } else if (!gat) {
         if (vec == 4) dispatch_linear<4>(nc, a, n_heavy, N, stream);
         else if (vec == 2) dispatch_linear<2>(nc, a, n_heavy, N, stream);
         else dispatch_linear<1>(nc, a, n_heavy, N, stream);

@@ -14,6 +14,7 @@
 
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kMaxHeads = 8;       // attention heads supported by the edge-softmax kernel
+constexpr int kMaxParts = 16;      // source-id ranges a row can be split into
 
 // Per-graph data.  deg/dinv/order are device arrays owned by the plan; the CSR
 // arrays are borrowed from the caller.
@@ -25,6 +26,11 @@ struct retexo_plan {
     int32_t* deg = nullptr;       // [N]
     float* dinv = nullptr;        // [N]
     int32_t* order = nullptr;     // [N] row ids, longest rows first (ties: ascending id)
+    // [N][kMaxParts + 1] CSR positions splitting every row by source-id range:
+    // entries of row v with column in [k*part_span, (k+1)*part_span) are
+    // col_idx[part_ptr[v][k] .. part_ptr[v][k+1]).  NULL when not built.
+    int32_t* part_ptr = nullptr;
+    int64_t part_span = 0;
     int32_t max_degree = 0;
     // number of rows with deg >= threshold[i], thresholds fixed in plan.hip
     int64_t rows_at_least[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -37,6 +43,9 @@ struct AggOptions {
     int64_t slab_cols = 0;      // 0 = auto
     int64_t slab_major = -1;    // -1 = auto
     int64_t heavy_degree = 2048;
+    int64_t max_vec = 4;        // cap on floats per lane per gather (experiments)
+    int64_t row_groups = 1;     // narrow slabs: one row per lane group (1) or one row per wave (0)
+    int64_t parts = -1;         // source-id ranges per aggregation: -1 auto, 1 = off, 2/4/8/16
 };
 AggOptions& agg_options();
 

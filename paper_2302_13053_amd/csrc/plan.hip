@@ -48,6 +48,28 @@ __global__ __launch_bounds__(kThreads) void check_columns(
     if (c < 0 || c >= N) atomicOr(bad, 1u);
 }
 
+// part_ptr[v][k] = first position in row v whose column is >= k * span (columns ascend in a row)
+__global__ __launch_bounds__(kThreads) void split_rows_kernel(
+    int64_t N, int64_t span, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+    int32_t* __restrict__ part_ptr)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * (kMaxParts + 1)) return;
+    const int64_t v = i / (kMaxParts + 1);
+    const int k = (int)(i % (kMaxParts + 1));
+    int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
+    if (k < kMaxParts) {
+        const int64_t want = (int64_t)k * span;
+        while (lo < hi) {
+            const int64_t mid = lo + ((hi - lo) >> 1);
+            if (col_idx[mid] < want) lo = mid + 1; else hi = mid;
+        }
+    } else {
+        lo = hi;
+    }
+    part_ptr[i] = (int32_t)lo;
+}
+
 // counts[i] = number of rows with degree >= thresholds[i]; keys are sorted descending
 struct Thresholds { int t[8]; };
 
@@ -81,7 +103,7 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
     if (!out) return RETEXO_E_NULL;
     *out = nullptr;
     if (N < 0 || N >= (1ll << 31)) return RETEXO_E_SIZE;
-    if (flags & ~(unsigned)RETEXO_F_VALIDATE) return RETEXO_E_FLAGS;
+    if (flags & ~(unsigned)(RETEXO_F_VALIDATE | RETEXO_F_SPLIT_ROWS)) return RETEXO_E_FLAGS;
     if (!d_row_ptr) return RETEXO_E_NULL;
     hipStream_t stream = (hipStream_t)stream_;
 
@@ -146,6 +168,17 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
         if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
         if (bad) return fail(RETEXO_E_CSR);
     }
+    // Dense-enough graphs whose feature table cannot stay in L2 get the row split that lets
+    // the aggregation walk one source-id range at a time.
+    if (N > 0 && p->nnz > 0 && ((flags & RETEXO_F_SPLIT_ROWS) || (p->nnz >= 64 * N && N * 128 > (4ll << 20) && N * 128 <= kMaxParts * (8ll << 20)))) {
+        if (hipMalloc(&p->part_ptr, (size_t)N * (kMaxParts + 1) * sizeof(int32_t)) != hipSuccess)
+            return fail(RETEXO_E_HIP);
+        p->part_span = (N + kMaxParts - 1) / kMaxParts;
+        const int64_t work = N * (kMaxParts + 1);
+        split_rows_kernel<<<dim3((unsigned)((work + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            N, p->part_span, d_row_ptr, d_col_idx, p->part_ptr);
+        if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
+    }
     (void)hipFree(p->build_scratch);
     p->build_scratch = nullptr;
     *out = p;
@@ -158,6 +191,7 @@ extern "C" int retexo_plan_destroy(retexo_plan* p)
     if (p->deg) (void)hipFree(p->deg);
     if (p->dinv) (void)hipFree(p->dinv);
     if (p->order) (void)hipFree(p->order);
+    if (p->part_ptr) (void)hipFree(p->part_ptr);
     if (p->build_scratch) (void)hipFree(p->build_scratch);
     delete p;
     return RETEXO_OK;

@@ -78,6 +78,9 @@ extern "C" int retexo_set_option(const char* name, int64_t value)
     if (!strcmp(name, "agg_slab_cols")) { o.slab_cols = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_slab_major")) { o.slab_major = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_heavy_degree")) { o.heavy_degree = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_max_vec")) { o.max_vec = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_parts")) { o.parts = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_row_groups")) { o.row_groups = value; return RETEXO_OK; }
     return RETEXO_E_FLAGS;
 }
 

@@ -67,9 +67,10 @@ def csr_from_coo(src: torch.Tensor, dst: torch.Tensor, n_nodes: int, self_loops:
     return DeviceGraph(n_nodes, nnz, row_ptr, col_idx)
 
 
-def make_plan(g: DeviceGraph, validate: bool = False) -> DeviceGraph:
+def make_plan(g: DeviceGraph, validate: bool = False, split_rows: bool = False) -> DeviceGraph:
+    flags = (B.F_VALIDATE if validate else 0) | (B.F_SPLIT_ROWS if split_rows else 0)
     st, plan = B.retexo_plan_create(g.n_nodes, g.row_ptr.data_ptr(), g.col_idx.data_ptr(),
-                                    B.F_VALIDATE if validate else 0, _stream_ptr())
+                                    flags, _stream_ptr())
     B.check(st, "retexo_plan_create")
     g.plan = plan
     return g

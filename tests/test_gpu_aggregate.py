@@ -26,7 +26,7 @@ def graphs():
     for name, (n, pairs, skew, seed) in specs.items():
         src, dst = wl.random_pairs(n, pairs, seed, skew=skew)
         for sl in (False, True):
-            g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, sl), validate=True)
+            g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, sl), validate=True, split_rows=(name == "skewed"))
             rp, ci = oracle.csr_from_coo(src, dst, n, sl)
             out[(name, sl)] = (g, rp, ci)
     deg = np.diff(out[("skewed", False)][1])
@@ -173,16 +173,26 @@ def test_bitwise_reproducible_and_option_sweep(graphs, mode):
     again = Hn.aggregate(g, mode, Z, F, **kw)
     assert torch.equal(first, again)
     try:
-        for slab, major, heavy in [(64, 0, 2048), (256, 1, 256), (512, 0, 1 << 20), (256, 1, 8192)]:
+        for slab, major, heavy, parts, rg in [(64, 0, 2048, 1, 1), (256, 1, 256, 1, 1), (512, 0, 1 << 20, 1, 1),
+                                              (256, 1, 8192, 1, 1), (32, 1, 2048, 1, 1), (128, 1, 512, 1, 1),
+                                              (32, 1, 2048, 2, 1), (64, 1, 2048, 4, 1), (32, 0, 2048, 8, 1),
+                                              (128, 1, 2048, 16, 1), (32, 1, 2048, 4, 0), (64, 0, 512, 1, 0),
+                                              (128, 1, 2048, 2, 0)]:
+            B.retexo_set_option("agg_row_groups", rg)
             B.retexo_set_option("agg_slab_cols", slab)
             B.retexo_set_option("agg_slab_major", major)
             B.retexo_set_option("agg_heavy_degree", heavy)
+            B.retexo_set_option("agg_parts", parts)
             got = Hn.aggregate(g, mode, Z, F, **kw).cpu().numpy()[:, :F]
-            assert_close(got, want, what="%s slab=%d major=%d heavy=%d" % (mode, slab, major, heavy))
+            assert_close(got, want, what="%s slab=%d major=%d heavy=%d parts=%d" % (mode, slab, major, heavy, parts))
+            again = Hn.aggregate(g, mode, Z, F, **kw).cpu().numpy()[:, :F]
+            assert np.array_equal(got, again)
     finally:
         B.retexo_set_option("agg_slab_cols", 0)
         B.retexo_set_option("agg_slab_major", -1)
         B.retexo_set_option("agg_heavy_degree", 2048)
+        B.retexo_set_option("agg_parts", -1)
+        B.retexo_set_option("agg_row_groups", 1)
 
 
 def test_in_place_concat_and_argument_errors(graphs):
