@@ -836,6 +836,215 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_ker
 }
 
 // ---------------------------------------------------------------------------
+// gat_softmax, float4 gathers with 32-bit row offsets, software-pipelined.
+//
+// Same arithmetic as agg_gat_kernel, arranged so that memory latency and the
+// score arithmetic overlap: as soon as a tile's neighbour ids are known the
+// first batch of feature rows is requested, and the scores, wave reductions and
+// exponentials of the tile are computed while those rows are in flight.  The
+// per-edge, per-head weights go through a wave-private LDS array, so that a
+// lane picks up the weight of its own head with one ds_read whose address is
+// an immediate offset (no readlane + select chain per neighbour).  Lanes past
+// the end of a tile carry the tile's first neighbour with weight zero, so every
+// gather address is valid and nothing in the loop branches per lane.
+// ---------------------------------------------------------------------------
+template <int NC, int NW, int HP, bool HU>
+__global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fast_kernel(AggArgs a)
+{
+    constexpr int WAVES = NW == 1 ? kLightWaves : NW;
+    constexpr int U = 4;
+    __shared__ float wl[WAVES][HP][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t items = a.row_count * a.nslab;
+    const int64_t item = (NW == 1) ? (int64_t)blockIdx.x * kLightWaves + wave : (int64_t)blockIdx.x;
+    if (item >= items) return;
+    int64_t slot;
+    int slab;
+    if (a.slab_major) { slab = (int)(item / a.row_count); slot = item % a.row_count; }
+    else              { slot = item / a.nslab; slab = (int)(item % a.nslab); }
+    const int v = __builtin_amdgcn_readfirstlane(a.order[a.row_begin + slot]);
+    const int lo = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v]);
+    const int hi = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v + 1]);
+
+    const int64_t col0 = (int64_t)slab * (256 * NC) + lane * 4;
+    bool act[NC];
+    uint32_t colbytes[NC];
+    int hc[NC][HU ? 1 : 4];
+    float acc[NC][4];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = col0 + c * 256;
+        act[c] = col < a.F;
+        // lanes past the row width gather the last valid vector instead (never stored)
+        colbytes[c] = (uint32_t)((act[c] ? col : ((a.F - 1) / 4) * 4) * 4);
+#pragma unroll
+        for (int k = 0; k < (HU ? 1 : 4); ++k) hc[c][k] = min((int)((col + k) / a.Dh), a.heads - 1);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[c][k] = 0.0f;
+    }
+    const char* zbase = reinterpret_cast<const char*>(a.Z);
+    const uint32_t rowbytes = (uint32_t)(a.ldz * 4);
+    float* myw = &wl[wave][0][0];
+
+    float m[HP], s[HP], erv[HP];
+#pragma unroll
+    for (int h = 0; h < HP; ++h) {
+        m[h] = -INFINITY;
+        s[h] = 0.0f;
+        erv[h] = a.er[(int64_t)v * HP + h];
+    }
+
+    for (int base = lo + 64 * (NW == 1 ? 0 : wave); base < hi; base += 64 * NW) {
+        const int e = base + lane;
+        const bool valid = e < hi;
+        const int cnt = min(64, hi - base);
+        int my_u = valid ? a.col_idx[e] : 0;
+        my_u = valid ? my_u : bcast_i(my_u, 0);          // lane 0 is always valid
+        const int my_off = (int)((uint32_t)my_u * rowbytes);
+
+        // first batch of rows is requested before the scores are computed
+        f32x4 zq[U][NC];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            const uint32_t off = (uint32_t)bcast_i(my_off, t);
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                zq[t][c] = *reinterpret_cast<const f32x4*>(zbase + off + colbytes[c]);
+        }
+
+        float elu[HP];
+        if constexpr (HP == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(a.el + (int64_t)my_u * 4);
+            elu[0] = t.x; elu[1] = t.y; elu[2] = t.z; elu[3] = t.w;
+        } else {
+#pragma unroll
+            for (int h = 0; h < HP; ++h) elu[h] = a.el[(int64_t)my_u * HP + h];
+        }
+        float scale[HP];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of wl are done
+#pragma unroll
+        for (int h = 0; h < HP; ++h) {
+            const float x = elu[h] + erv[h];
+            const float sc = valid ? (x > 0.0f ? x : a.slope * x) : -INFINITY;
+            const float mn = fmaxf(m[h], wave_max(sc));
+            scale[h] = expf(m[h] - mn);
+            const float pe = valid ? expf(sc - mn) : 0.0f;
+            s[h] = s[h] * scale[h] + wave_sum(pe);
+            m[h] = mn;
+            myw[h * 64 + lane] = pe;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (base != lo + 64 * (NW == 1 ? 0 : wave)) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[c][k] *= select_head<HP>(scale, hc[c][HU ? 0 : k]);
+        }
+
+        for (int j = 0; j < cnt; j += U) {
+            // request the next batch, then consume the current one
+            f32x4 zn[U][NC];
+            const bool more = j + U < cnt;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t) {
+                    const uint32_t off = (uint32_t)bcast_i(my_off, (j + U + t) & 63);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+                        zn[t][c] = *reinterpret_cast<const f32x4*>(zbase + off + colbytes[c]);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    if constexpr (HU) {
+                        const float w = myw[hc[c][0] * 64 + j + t];
+                        acc[c][0] = fmaf(w, zq[t][c].x, acc[c][0]);
+                        acc[c][1] = fmaf(w, zq[t][c].y, acc[c][1]);
+                        acc[c][2] = fmaf(w, zq[t][c].z, acc[c][2]);
+                        acc[c][3] = fmaf(w, zq[t][c].w, acc[c][3]);
+                    } else {
+                        acc[c][0] = fmaf(myw[hc[c][0] * 64 + j + t], zq[t][c].x, acc[c][0]);
+                        acc[c][1] = fmaf(myw[hc[c][1] * 64 + j + t], zq[t][c].y, acc[c][1]);
+                        acc[c][2] = fmaf(myw[hc[c][2] * 64 + j + t], zq[t][c].z, acc[c][2]);
+                        acc[c][3] = fmaf(myw[hc[c][3] * 64 + j + t], zq[t][c].w, acc[c][3]);
+                    }
+                }
+            }
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t)
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) zq[t][c] = zn[t][c];
+            }
+        }
+    }
+
+    if constexpr (NW > 1) {
+        __shared__ float red[NW][NC * 4][64];
+        __shared__ float mred[NW][HP], sred[NW][HP];
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) red[wave][c * 4 + k][lane] = acc[c][k];
+        if (lane == 0) {
+#pragma unroll
+            for (int h = 0; h < HP; ++h) { mred[wave][h] = m[h]; sred[wave][h] = s[h]; }
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        float f[NW][HP];
+#pragma unroll
+        for (int h = 0; h < HP; ++h) {
+            float mm = mred[0][h];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) mm = fmaxf(mm, mred[w][h]);
+            float ss = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                f[w][h] = (mred[w][h] == -INFINITY) ? 0.0f : expf(mred[w][h] - mm);
+                ss += sred[w][h] * f[w][h];
+            }
+            s[h] = ss;
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float t = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+                    t += red[w][c * 4 + k][lane] * select_head<HP>(f[w], hc[c][HU ? 0 : k]);
+                acc[c][k] = t;
+            }
+    }
+
+    float* orow = a.out + (int64_t)v * a.ldo;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        if (!act[c]) continue;
+        const int64_t col = col0 + c * 256;
+        const int valid = (int)min((int64_t)4, a.F - col);
+        float r[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float den = select_head<HP>(s, hc[c][HU ? 0 : k]);
+            r[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
+        }
+        store_row<4>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+        if (a.copy_self) {
+            float zs[4];
+            load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
+            store_row<4>(orow + col, zs, valid, a.self_vec != 0);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 template <int VEC, int NC>
@@ -915,6 +1124,32 @@ void launch_gat_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_
         const int64_t blocks = (a.row_count * a.nslab + kLightWaves - 1) / kLightWaves;
         agg_gat_kernel<VEC, NC, 1, HP, HU><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
     }
+}
+
+template <int NC, int HP, bool HU>
+void launch_gat_fast_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
+{
+    if (n_heavy > 0) {
+        AggArgs a = base;
+        a.row_begin = 0;
+        a.row_count = n_heavy;
+        const int64_t blocks = n_heavy * a.nslab;
+        agg_gat_fast_kernel<NC, kHeavyWaves, HP, HU><<<dim3((unsigned)blocks), dim3(64 * kHeavyWaves), 0, stream>>>(a);
+    }
+    if (N > n_heavy) {
+        AggArgs a = base;
+        a.row_begin = n_heavy;
+        a.row_count = N - n_heavy;
+        const int64_t blocks = (a.row_count * a.nslab + kLightWaves - 1) / kLightWaves;
+        agg_gat_fast_kernel<NC, 1, HP, HU><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+    }
+}
+
+template <int HP, bool HU>
+void dispatch_gat_fast(int nc, const AggArgs& a, int64_t nh, int64_t N, hipStream_t s)
+{
+    if (nc == 1) launch_gat_fast_pair<1, HP, HU>(a, nh, N, s);
+    else launch_gat_fast_pair<2, HP, HU>(a, nh, N, s);
 }
 
 template <int VEC>
@@ -1062,7 +1297,11 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, c.F, c.heads, a.Dh, c.Z, c.ldz,
                                                                      c.attn_src, c.attn_dst, el, er);
         const bool hu = (a.Dh % vec) == 0;
-        if (vec == 4) {
+        const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32);
+        if (vec == 4 && off32 && opt.gat_fast) {
+            if (hp == 4) { if (hu) dispatch_gat_fast<4, true>(nc, a, n_heavy, N, stream); else dispatch_gat_fast<4, false>(nc, a, n_heavy, N, stream); }
+            else         { if (hu) dispatch_gat_fast<8, true>(nc, a, n_heavy, N, stream); else dispatch_gat_fast<8, false>(nc, a, n_heavy, N, stream); }
+        } else if (vec == 4) {
             if (hp == 4) { if (hu) dispatch_gat_nc<4, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat_nc<4, 4, false>(nc, a, n_heavy, N, stream); }
             else         { if (hu) dispatch_gat_nc<4, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat_nc<4, 8, false>(nc, a, n_heavy, N, stream); }
         } else {
