@@ -23,16 +23,41 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 16;
 
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(256) void transform_kernel(
+// Four consecutive floats starting at base[off], fetched without a branch: an
+// element that is not wanted (or would be out of range) is fetched from base[0]
+// instead; zero4 later replaces it by zero.  Keeping the replacement out of the
+// load lets all loads of a K step stay in flight behind the MFMAs of the
+// previous step.
+//   VEC: the four are one aligned 16-byte load and are wanted all or none
+template <bool VEC>
+__device__ __forceinline__ void load4(const float* __restrict__ base, int64_t off, int wanted, float (&r)[4])
+{
+    if constexpr (VEC) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(base + (wanted >= 4 ? off : 0));
+        r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r[q] = base[q < wanted ? off + q : 0];
+    }
+}
+
+template <bool VEC>
+__device__ __forceinline__ void zero4(int wanted, float (&r)[4])
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] = (VEC ? wanted >= 4 : q < wanted) ? r[q] : 0.0f;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool HV, bool WV>
+__global__ __launch_bounds__(256, 2) void transform_kernel(
     int64_t N, int D_in, int D_out, const float* __restrict__ H, int64_t ldh,
     const float* __restrict__ W, const float* __restrict__ bias, int relu,
-    float* __restrict__ Z, int64_t ldz, int h_vec, int w_vec)
+    float* __restrict__ Z, int64_t ldz)
 {
     static_assert(WGM * WGN == 4, "four waves per workgroup");
     constexpr int TM = BM / (32 * WGM);      // 32x32 MFMA tiles per wave along M
     constexpr int TN = BN / (32 * WGN);      // and along N
-    constexpr int LDA = BM + 4;              // LDS row pitches (floats)
+    constexpr int LDA = BM + 2;              // LDS row pitches (floats): see the A-tile mapping below
     constexpr int LDB = BN + 4;
     constexpr int A_F4 = BM * BK / 4 / 256;  // float4 loads per thread per step
     constexpr int B_F4 = (BN * BK / 4 + 255) / 256;
@@ -57,24 +82,20 @@ __global__ __launch_bounds__(256) void transform_kernel(
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     float ra[A_F4][4], rb[B_F4][4];
+    int wa[A_F4], wb[B_F4];                  // how many of the four are real (see load4)
 
-    // A tile: thread -> (row = id % BM, k4 = id / BM); rows vary fastest so that
-    // the transposing LDS writes of a wave hit consecutive banks
+    // A tile: thread -> (row = id / 4, k4 = id % 4): four lanes read the 64 contiguous bytes of
+    // a row, and with a row pitch of BM + 2 floats the transposing LDS writes of each half-wave
+    // (4 k-rows x 8 rows) fall into 32 different banks
     auto load_a = [&](int kt) {
 #pragma unroll
         for (int i = 0; i < A_F4; ++i) {
             const int id = tid + i * 256;
-            const int r = id % BM, k4 = id / BM;
+            const int r = id / 4, k4 = id % 4;
             const int64_t row = m0 + r;
             const int k = kt * BK + k4 * 4;
-            if (row < N && h_vec && k + 3 < D_in) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(H + row * ldh + k);
-                ra[i][0] = t.x; ra[i][1] = t.y; ra[i][2] = t.z; ra[i][3] = t.w;
-            } else {
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    ra[i][q] = (row < N && k + q < D_in) ? H[row * ldh + k + q] : 0.0f;
-            }
+            wa[i] = row < N ? D_in - k : 0;                   // may be <= 0 or > 4
+            load4<HV>(H, row * ldh + k, wa[i], ra[i]);
         }
     };
     // B tile: thread -> (k = id / (BN/4), n4 = id % (BN/4))
@@ -82,25 +103,20 @@ __global__ __launch_bounds__(256) void transform_kernel(
 #pragma unroll
         for (int i = 0; i < B_F4; ++i) {
             const int id = tid + i * 256;
+            if (BN * BK / 4 % 256 != 0 && id >= BN * BK / 4) continue;
             const int kk = id / (BN / 4), n4 = id % (BN / 4);
             const int k = kt * BK + kk;
             const int n = n0 + n4 * 4;
-            if (BN * BK / 4 % 256 != 0 && id >= BN * BK / 4) continue;
-            if (k < D_in && w_vec && n + 3 < D_out) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(W + (int64_t)k * D_out + n);
-                rb[i][0] = t.x; rb[i][1] = t.y; rb[i][2] = t.z; rb[i][3] = t.w;
-            } else {
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    rb[i][q] = (k < D_in && n + q < D_out) ? W[(int64_t)k * D_out + n + q] : 0.0f;
-            }
+            wb[i] = k < D_in ? D_out - n : 0;
+            load4<WV>(W, (int64_t)k * D_out + n, wb[i], rb[i]);
         }
     };
     auto store_tiles = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < A_F4; ++i) {
             const int id = tid + i * 256;
-            const int r = id % BM, k4 = id / BM;
+            const int r = id / 4, k4 = id % 4;
+            zero4<HV>(wa[i], ra[i]);
 #pragma unroll
             for (int q = 0; q < 4; ++q) As[buf][k4 * 4 + q][r] = ra[i][q];
         }
@@ -109,10 +125,20 @@ __global__ __launch_bounds__(256) void transform_kernel(
             const int id = tid + i * 256;
             if (BN * BK / 4 % 256 != 0 && id >= BN * BK / 4) continue;
             const int kk = id / (BN / 4), n4 = id % (BN / 4);
+            zero4<WV>(wb[i], rb[i]);
             f32x4 t = {rb[i][0], rb[i][1], rb[i][2], rb[i][3]};
             *reinterpret_cast<f32x4*>(&Bs[buf][kk][n4 * 4]) = t;
         }
     };
+
+    const int lrow = lane & 31, lk = lane >> 5;
+    // bias of this lane's output columns, fetched up front so that the stores at the end wait for nothing
+    float bv[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * TN * 32 + j * 32 + lrow;
+        bv[j] = (bias && col < D_out) ? bias[col] : 0.0f;
+    }
 
     const int nk = (D_in + BK - 1) / BK;
     load_a(0);
@@ -120,7 +146,6 @@ __global__ __launch_bounds__(256) void transform_kernel(
     store_tiles(0);
     __syncthreads();
 
-    const int lrow = lane & 31, lk = lane >> 5;
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nk) { load_a(kt + 1); load_b(kt + 1); }
@@ -146,14 +171,13 @@ __global__ __launch_bounds__(256) void transform_kernel(
     for (int j = 0; j < TN; ++j) {
         const int col = n0 + wn * TN * 32 + j * 32 + lrow;
         if (col >= D_out) continue;
-        const float bv = bias ? bias[col] : 0.0f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
                 if (row < N) {
-                    float x = acc[i][j][r] + bv;
+                    float x = acc[i][j][r] + bv[j];
                     if (relu) x = fmaxf(x, 0.0f);
                     Z[row * ldz + col] = x;
                 }
@@ -166,11 +190,19 @@ template <int BM, int BN, int WGM, int WGN>
 void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh, const float* W,
             const float* b, bool relu, float* Z, int64_t ldz, hipStream_t stream)
 {
-    const int h_vec = ((uintptr_t)H % 16 == 0 && ldh % 4 == 0) ? 1 : 0;
-    const int w_vec = ((uintptr_t)W % 16 == 0 && D_out % 4 == 0) ? 1 : 0;
+    // 16-byte loads need aligned rows and widths that are multiples of four floats
+    const bool hv = (uintptr_t)H % 16 == 0 && ldh % 4 == 0 && D_in % 4 == 0;
+    const bool wv = (uintptr_t)W % 16 == 0 && D_out % 4 == 0;
     dim3 grid((unsigned)((N + BM - 1) / BM), (unsigned)((D_out + BN - 1) / BN));
-    transform_kernel<BM, BN, WGM, WGN><<<grid, dim3(256), 0, stream>>>(
-        N, (int)D_in, (int)D_out, H, ldh, W, b, relu ? 1 : 0, Z, ldz, h_vec, w_vec);
+    const int r = relu ? 1 : 0;
+    if (hv && wv)
+        transform_kernel<BM, BN, WGM, WGN, true, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+    else if (hv)
+        transform_kernel<BM, BN, WGM, WGN, true, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+    else if (wv)
+        transform_kernel<BM, BN, WGM, WGN, false, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+    else
+        transform_kernel<BM, BN, WGM, WGN, false, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
 }
 
 }  // namespace
