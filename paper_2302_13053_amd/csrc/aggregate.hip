@@ -65,6 +65,7 @@ struct AggArgs {
     // source-range walk (grouped kernel only): this launch covers the entries of each row whose
     // column lies in ranges [part_lo, part_hi) of the plan's split; NULL = whole rows
     const int32_t* part_ptr;
+    int64_t n_rows;        // N (row pitch of part_ptr)
     int part_lo, part_hi;
     int first;             // first range of the walk: start from zero, write the self copy
     int last;              // last range: apply the mean / gcn scaling
@@ -103,6 +104,11 @@ __device__ __forceinline__ void store_row(float* p, const float (&v)[VEC], int v
             if (k < valid) p[k] = v[k];
     }
 }
+
+// data that is read once per pass (indices, row bookkeeping, running sums) is fetched with a
+// non-temporal hint so that it does not push the reused feature rows out of L2
+template <typename T>
+__device__ __forceinline__ T ldg_stream(const T* p) { return __builtin_nontemporal_load(p); }
 
 __device__ __forceinline__ float wave_max(float x)
 {
@@ -349,8 +355,8 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_grouped
     if (lane < nrows) {
         v_l = a.order[a.row_begin + slot0 + lane];
         if (a.part_ptr) {
-            lo_l = a.part_ptr[(int64_t)v_l * (kMaxParts + 1) + a.part_lo];
-            hi_l = a.part_ptr[(int64_t)v_l * (kMaxParts + 1) + a.part_hi];
+            lo_l = a.part_ptr[(int64_t)a.part_lo * a.n_rows + a.row_begin + slot0 + lane];
+            hi_l = a.part_ptr[(int64_t)a.part_hi * a.n_rows + a.row_begin + slot0 + lane];
         } else {
             lo_l = (int)a.row_ptr[v_l];
             hi_l = (int)a.row_ptr[v_l + 1];
@@ -502,8 +508,8 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
     if (has_row) {
         v = a.order[a.row_begin + slot];
         if (a.part_ptr) {
-            lo = a.part_ptr[(int64_t)v * (kMaxParts + 1) + a.part_lo];
-            hi = a.part_ptr[(int64_t)v * (kMaxParts + 1) + a.part_hi];
+            lo = a.part_ptr[(int64_t)a.part_lo * a.n_rows + a.row_begin + slot];
+            hi = a.part_ptr[(int64_t)a.part_hi * a.n_rows + a.row_begin + slot];
         } else {
             lo = (int)a.row_ptr[v];
             hi = (int)a.row_ptr[v + 1];
@@ -531,8 +537,10 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
 
     float prev[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (!a.first && writer) {
-        if (a.out_vec && valid >= 4) load_row<4>(orow + a.ocol + col, prev);
-        else {
+        if (a.out_vec && valid >= 4) {
+            const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(orow + a.ocol + col));
+            prev[0] = t.x; prev[1] = t.y; prev[2] = t.z; prev[3] = t.w;
+        } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 if (k < valid) prev[k] = orow[a.ocol + col + k];
@@ -617,7 +625,12 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
         }
         out_v[k] = x;
     }
-    store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0);
+    if (a.out_vec && valid >= 4) {
+        f32x4 t = {out_v[0], out_v[1], out_v[2], out_v[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(orow + a.ocol + col));
+    } else {
+        store_row<4>(orow + a.ocol + col, out_v, valid, false);
+    }
     if (a.copy_self && a.first) {
         float zs[4];
         load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -1234,6 +1247,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.out_vec = aligned_for(c.out + a.ocol, c.ldo, vec) ? 1 : 0;
     a.self_vec = aligned_for(c.out, c.ldo, vec) ? 1 : 0;
     a.part_ptr = nullptr;
+    a.n_rows = N;
     a.part_lo = 0;
     a.part_hi = 0;
     a.first = 1;

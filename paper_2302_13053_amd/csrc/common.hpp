@@ -26,9 +26,11 @@ struct retexo_plan {
     int32_t* deg = nullptr;       // [N]
     float* dinv = nullptr;        // [N]
     int32_t* order = nullptr;     // [N] row ids, longest rows first (ties: ascending id)
-    // [N][kMaxParts + 1] CSR positions splitting every row by source-id range:
-    // entries of row v with column in [k*part_span, (k+1)*part_span) are
-    // col_idx[part_ptr[v][k] .. part_ptr[v][k+1]).  NULL when not built.
+    // [kMaxParts + 1][N] CSR positions splitting every row by source-id range, stored in
+    // SCHEDULE order (index = position in `order`, not row id) so that the rows a wave works
+    // on read neighbouring entries: the entries of row order[s] with column in
+    // [k*part_span, (k+1)*part_span) are col_idx[part_ptr[k*N + s] .. part_ptr[(k+1)*N + s]).
+    // NULL when not built.
     int32_t* part_ptr = nullptr;
     int64_t part_span = 0;
     int32_t max_degree = 0;

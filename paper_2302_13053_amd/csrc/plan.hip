@@ -48,15 +48,16 @@ __global__ __launch_bounds__(kThreads) void check_columns(
     if (c < 0 || c >= N) atomicOr(bad, 1u);
 }
 
-// part_ptr[v][k] = first position in row v whose column is >= k * span (columns ascend in a row)
+// part_ptr[k][s] = first position in row order[s] whose column is >= k * span (columns ascend in a row)
 __global__ __launch_bounds__(kThreads) void split_rows_kernel(
     int64_t N, int64_t span, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    int32_t* __restrict__ part_ptr)
+    const int32_t* __restrict__ order, int32_t* __restrict__ part_ptr)
 {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= N * (kMaxParts + 1)) return;
-    const int64_t v = i / (kMaxParts + 1);
-    const int k = (int)(i % (kMaxParts + 1));
+    const int k = (int)(i / N);
+    const int64_t s = i % N;
+    const int64_t v = order[s];
     int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
     if (k < kMaxParts) {
         const int64_t want = (int64_t)k * span;
@@ -176,7 +177,7 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
         p->part_span = (N + kMaxParts - 1) / kMaxParts;
         const int64_t work = N * (kMaxParts + 1);
         split_rows_kernel<<<dim3((unsigned)((work + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            N, p->part_span, d_row_ptr, d_col_idx, p->part_ptr);
+            N, p->part_span, d_row_ptr, d_col_idx, p->order, p->part_ptr);
         if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
     }
     (void)hipFree(p->build_scratch);
