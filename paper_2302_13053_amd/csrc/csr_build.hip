@@ -8,15 +8,19 @@
 //
 // Method: every directed entry is packed into one 64-bit key
 // (row << cbits | col, cbits = bits needed for N-1), the keys are radix-sorted
-// (rocPRIM device sort over only the significant bits), the first key of each
-// run of equal keys is flagged, an exclusive scan of the flags gives each kept
-// entry its position in col_idx, and row_ptr[r] is the scan value at the first
-// key whose row is >= r (binary search).  Dropped pairs (u == v) are encoded
-// as a sentinel larger than any real key so that they sort to the end.
+// (rocPRIM device sort over only the significant bits), an exclusive scan over
+// "first key of a run of equal keys" flags (computed on the fly from the sorted
+// keys) gives each kept entry its position in col_idx, and row_ptr[r] is the scan value at the first
+// key whose row is >= r (binary search).  A pair with u == v becomes the key
+// (u, u), which is exactly the self-loop entry: it is kept (once) when
+// self-loops are requested and never flagged otherwise, so no sentinel value
+// and no extra key bit is needed: the sort covers exactly 2*cbits bits.
 #include <cstring>
 
 #include <rocprim/device/device_radix_sort.hpp>
 #include <rocprim/device/device_scan.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
+#include <rocprim/iterator/transform_iterator.hpp>
 
 #include "common.hpp"
 
@@ -34,14 +38,13 @@ __global__ __launch_bounds__(kThreads) void pairs_to_keys(
     int64_t n_pairs, const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
     int64_t N, int add_self_loops, int cbits, uint64_t* __restrict__ keys, CsrHeader* hdr)
 {
-    const uint64_t sentinel = 1ull << (2 * cbits);
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i < n_pairs) {
         const int32_t u = src[i], v = dst[i];
-        uint64_t k0 = sentinel, k1 = sentinel;
+        uint64_t k0 = 0, k1 = 0;
         if (u < 0 || u >= N || v < 0 || v >= N) {
             atomicOr(&hdr->bad_id, 1u);
-        } else if (u != v) {
+        } else {
             k0 = ((uint64_t)u << cbits) | (uint64_t)v;
             k1 = ((uint64_t)v << cbits) | (uint64_t)u;
         }
@@ -53,30 +56,31 @@ __global__ __launch_bounds__(kThreads) void pairs_to_keys(
     }
 }
 
-__global__ __launch_bounds__(kThreads) void flag_first_of_run(
-    int64_t M, const uint64_t* __restrict__ keys, int cbits, uint32_t* __restrict__ flags)
-{
-    const uint64_t sentinel = 1ull << (2 * cbits);
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= M) return;
-    const uint64_t k = keys[i];
-    flags[i] = (k != sentinel && (i == 0 || keys[i - 1] != k)) ? 1u : 0u;
-}
+// 1 for the first key of every run of equal keys, except diagonal keys when no self-loops are wanted
+struct FirstOfRun {
+    const uint64_t* keys;
+    int cbits;
+    int keep_diagonal;
+    __device__ uint32_t operator()(int64_t i) const
+    {
+        const uint64_t k = keys[i];
+        const bool diagonal = (k >> cbits) == (k & ((1ull << cbits) - 1));
+        return ((keep_diagonal || !diagonal) && (i == 0 || keys[i - 1] != k)) ? 1u : 0u;
+    }
+};
 
-__global__ void total_kept(int64_t M, const uint32_t* __restrict__ flags,
-                           const uint32_t* __restrict__ pos, CsrHeader* hdr)
+__global__ void total_kept(int64_t M, FirstOfRun flag, const uint32_t* __restrict__ pos, CsrHeader* hdr)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0)
-        hdr->nnz = (M == 0) ? 0 : (int64_t)pos[M - 1] + (int64_t)flags[M - 1];
+        hdr->nnz = (M == 0) ? 0 : (int64_t)pos[M - 1] + (int64_t)flag(M - 1);
 }
 
 __global__ __launch_bounds__(kThreads) void scatter_columns(
-    int64_t M, const uint64_t* __restrict__ keys, const uint32_t* __restrict__ flags,
-    const uint32_t* __restrict__ pos, int cbits, int32_t* __restrict__ col_idx)
+    int64_t M, FirstOfRun flag, const uint32_t* __restrict__ pos, int32_t* __restrict__ col_idx)
 {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= M || !flags[i]) return;
-    col_idx[pos[i]] = (int32_t)(keys[i] & ((1ull << cbits) - 1));
+    if (i >= M || !flag(i)) return;
+    col_idx[pos[i]] = (int32_t)(flag.keys[i] & ((1ull << flag.cbits) - 1));
 }
 
 __global__ __launch_bounds__(kThreads) void row_offsets(
@@ -112,11 +116,13 @@ int make_layout(int64_t n_pairs, int64_t N, int add_self_loops, Layout& L)
     const int cbits = column_bits(N);
     size_t sb = 0, cb = 0;
     if (L.M > 0) {
-        if (rocprim::radix_sort_keys(nullptr, sb, (uint64_t*)nullptr, (uint64_t*)nullptr,
-                                     (size_t)L.M, 0u, (unsigned)(2 * cbits + 1), (hipStream_t)0) != hipSuccess)
+        if (rocprim::radix_sort_keys(nullptr, sb, (uint64_t*)nullptr, (uint64_t*)nullptr, (size_t)L.M, 0u,
+                                     (unsigned)(2 * cbits), (hipStream_t)0) != hipSuccess)
             return RETEXO_E_HIP;
-        if (rocprim::exclusive_scan(nullptr, cb, (uint32_t*)nullptr, (uint32_t*)nullptr, 0u,
-                                    (size_t)L.M, rocprim::plus<uint32_t>(), (hipStream_t)0) != hipSuccess)
+        auto flags_it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0),
+                                                         FirstOfRun{nullptr, cbits, 0});
+        if (rocprim::exclusive_scan(nullptr, cb, flags_it, (uint32_t*)nullptr, 0u, (size_t)L.M,
+                                    rocprim::plus<uint32_t>(), (hipStream_t)0) != hipSuccess)
             return RETEXO_E_HIP;
     }
     L.sort_bytes = sb;
@@ -170,12 +176,12 @@ extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const 
     CsrHeader* hdr = (CsrHeader*)(ws + L.header);
     uint64_t* keys_a = (uint64_t*)(ws + L.keys_a);
     uint64_t* keys_b = (uint64_t*)(ws + L.keys_b);
-    // after the sort keys_a is free: its first half holds the flags, its second half the scan
-    uint32_t* flags = (uint32_t*)keys_a;
-    uint32_t* pos = flags + L.M;
+    // after the sort keys_a is free and holds the scan of the first-of-run flags
+    uint32_t* pos = (uint32_t*)keys_a;
     const int cbits = column_bits(N);
     const int64_t M = L.M;
 
+    const FirstOfRun flag{keys_b, cbits, add_self_loops ? 1 : 0};
     RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(CsrHeader), stream));
     if (M > 0) {
         const int64_t work = n_pairs + (add_self_loops ? N : 0);
@@ -183,13 +189,12 @@ extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const 
             n_pairs, d_src, d_dst, N, add_self_loops, cbits, keys_a, hdr);
         size_t sb = L.sort_bytes;
         RETEXO_HIP_TRY(rocprim::radix_sort_keys(ws + L.sort_tmp, sb, keys_a, keys_b, (size_t)M, 0u,
-                                                (unsigned)(2 * cbits + 1), stream));
-        const unsigned gm = (unsigned)((M + kThreads - 1) / kThreads);
-        flag_first_of_run<<<dim3(gm), dim3(kThreads), 0, stream>>>(M, keys_b, cbits, flags);
+                                                (unsigned)(2 * cbits), stream));
         size_t cb = L.scan_bytes;
-        RETEXO_HIP_TRY(rocprim::exclusive_scan(ws + L.scan_tmp, cb, flags, pos, 0u, (size_t)M,
+        auto flags_it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), flag);
+        RETEXO_HIP_TRY(rocprim::exclusive_scan(ws + L.scan_tmp, cb, flags_it, pos, 0u, (size_t)M,
                                                rocprim::plus<uint32_t>(), stream));
-        total_kept<<<dim3(1), dim3(64), 0, stream>>>(M, flags, pos, hdr);
+        total_kept<<<dim3(1), dim3(64), 0, stream>>>(M, flag, pos, hdr);
     }
     CsrHeader h;
     RETEXO_HIP_TRY(hipMemcpyAsync(&h, hdr, sizeof(h), hipMemcpyDeviceToHost, stream));
@@ -200,7 +205,7 @@ extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const 
 
     if (M > 0) {
         const unsigned gm = (unsigned)((M + kThreads - 1) / kThreads);
-        scatter_columns<<<dim3(gm), dim3(kThreads), 0, stream>>>(M, keys_b, flags, pos, cbits, d_col_idx);
+        scatter_columns<<<dim3(gm), dim3(kThreads), 0, stream>>>(M, flag, pos, d_col_idx);
     }
     row_offsets<<<dim3((unsigned)((N + 1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
         N, M, keys_b, pos, cbits, hdr, d_row_ptr);
