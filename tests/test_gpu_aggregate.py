@@ -195,6 +195,53 @@ def test_bitwise_reproducible_and_option_sweep(graphs, mode):
         B.retexo_set_option("agg_row_groups", 1)
 
 
+@pytest.mark.parametrize("mode", ["mean", "gcn_sym", "sum"])
+def test_source_range_walk_with_concat_and_ragged_width(graphs, mode):
+    """Narrow slabs + several source ranges, with the self half written and a width (602) whose
+    last slab is ragged; also the in-place form where Z already sits in out's first F columns."""
+    g, rp, ci = graphs[("skewed", mode == "gcn_sym")]
+    n, F = g.n_nodes, 602
+    Zh = wl.random_matrix(n, F, 31, ld=608)
+    want = oracle.aggregate(mode, rp, ci, Zh, F, self_concat=True)
+    try:
+        for slab, parts in [(32, 4), (64, 8), (128, 2), (32, 16)]:
+            B.retexo_set_option("agg_slab_cols", slab)
+            B.retexo_set_option("agg_parts", parts)
+            got = Hn.aggregate(g, mode, Hn.dev(Zh), F, concat=True).cpu().numpy()[:, :2 * F]
+            assert_close(got, want, what="%s concat slab=%d parts=%d" % (mode, slab, parts))
+            assert np.array_equal(got[:, :F], Zh[:, :F])
+            buf = torch.zeros((n, 1216), dtype=torch.float32, device="cuda")
+            buf[:, :F] = torch.from_numpy(Zh[:, :F]).cuda()
+            st = B.retexo_aggregate(g.plan, B.MODES[mode], F, 1, buf.data_ptr(), 1216, 0, 0, 0.2,
+                                    B.F_SELF_CONCAT, buf.data_ptr(), 1216, 0, 0)
+            assert st == B.OK
+            assert_close(buf.cpu().numpy()[:, :2 * F], want, what="in place, slab=%d parts=%d" % (slab, parts))
+    finally:
+        B.retexo_set_option("agg_slab_cols", 0)
+        B.retexo_set_option("agg_parts", -1)
+
+
+def test_empty_graph_and_zero_width(graphs):
+    # a graph without any entry: every aggregate is zero, the self half is still copied
+    n = 70
+    g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(np.empty(0, np.int32)), Hn.dev(np.empty(0, np.int32)), n, False),
+                     validate=True)
+    Zh = wl.random_matrix(n, 40, 32)
+    a = wl.random_matrix(2, 20, 33)
+    for mode in MODES:
+        out = Hn.aggregate(g, mode, Hn.dev(Zh), 40, heads=2, a_src=Hn.dev(a), a_dst=Hn.dev(a), concat=True)
+        got = out.cpu().numpy()
+        assert np.array_equal(got[:, :40], Zh) and np.all(got[:, 40:80] == 0)
+    # zero feature width and the zero-node plan are no-ops that succeed
+    assert B.retexo_aggregate(g.plan, B.MEAN, 0, 1, 0, 0, 0, 0, 0.2, 0, 0, 0, 0, 0) == B.OK
+    g.destroy()
+    rp0 = torch.zeros(1, dtype=torch.int64, device="cuda")
+    st, plan = B.retexo_plan_create(0, rp0.data_ptr(), 0)
+    assert st == B.OK and B.retexo_plan_nnz(plan) == 0
+    assert B.retexo_aggregate(plan, B.MEAN, 8, 1, 0, 8, 0, 0, 0.2, 0, 0, 8, 0, 0) == B.OK
+    B.retexo_plan_destroy(plan)
+
+
 def test_in_place_concat_and_argument_errors(graphs):
     g, rp, ci = graphs[("flat", False)]
     n, F = g.n_nodes, 80

@@ -77,6 +77,34 @@ def test_round_separately_equals_fused_and_gcn_gat_modes():
         g.destroy()
 
 
+def test_one_partitions_share_matches_the_global_result():
+    """The edge-partitioned set-up of the paper on one GPU: a worker holds its inner nodes, its
+    boundary nodes and the edges touching an inner node, numbered [inner | boundary].  Running
+    the same entry points on that local graph must reproduce the global result on inner rows."""
+    w = wl.workload(2)
+    src, dst = wl.make_graph(w)
+    n = w.n_nodes
+    Z = wl.make_features(w, ld=wl.pad_ld(w.feat_dim))
+    F = w.feat_dim
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    want = oracle.aggregate("mean", rp, ci, Z, F, self_concat=True)
+    owner = (np.arange(n) * 2654435761 % 4294967296) >> 31          # two workers, scattered ownership
+    for worker in (0, 1):
+        inner = np.flatnonzero(owner == worker)
+        keep = (owner[src] == worker) | (owner[dst] == worker)      # edges with an inner endpoint
+        s, d = src[keep], dst[keep]
+        boundary = np.setdiff1d(np.unique(np.concatenate([s, d])), inner)
+        local_ids = np.concatenate([inner, boundary])
+        to_local = np.full(n, -1, np.int64)
+        to_local[local_ids] = np.arange(local_ids.size)
+        g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(to_local[s].astype(np.int32)),
+                                         Hn.dev(to_local[d].astype(np.int32)), local_ids.size, False))
+        Zl = np.ascontiguousarray(Z[local_ids])                     # inner rows, then received boundary rows
+        out = Hn.aggregate(g, "mean", Hn.dev(Zl), F, concat=True).cpu().numpy()[:inner.size, :2 * F]
+        assert_close(out, want[inner], what="worker %d inner rows" % worker)
+        g.destroy()
+
+
 def sample_rows(rp, k, seed):
     deg = np.diff(rp)
     rng = np.random.Generator(np.random.Philox(key=seed))
