@@ -31,7 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant aggregation measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "sage_large_powerlaw": 262309950892,   # profiles/bench_sage_large_powerlaw.md: 261.13 GB fetched + 1.18 GB written
+    "sage_large_powerlaw": 110468349724,     # profiles/bench_sage_large_powerlaw.md
+    "gat_products_powerlaw": 152133550449,   # profiles/bench_gat_products_powerlaw.md
 }
 
 
@@ -224,7 +225,10 @@ def main():
     achieved = gbytes / agg_ms / 1e6
     roofline = {
         "bound": "hbm",
-        "kernel": "agg_gat_kernel" if gat else "agg_linear_kernel",
+        "kernel": ("gat_scores_kernel + agg_gat_fast_kernel (long rows: workgroup per row; others: wave per row)"
+                   if gat else
+                   "aggregation call = agg_rowgroup_kernel + agg_grouped_kernel per source range (narrow slabs) "
+                   "or agg_linear_kernel (whole rows), chosen by the plan"),
         "stage": "round%d aggregation, F=%d" % (di, F),
         "achieved": achieved,
         "peak": HBM_PEAK_GBS,
