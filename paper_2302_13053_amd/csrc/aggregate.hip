@@ -329,145 +329,94 @@ __device__ __forceinline__ void grouped_tile(const char* zbase, uint32_t colbyte
     }
 }
 
-constexpr int kRowsPerWave = 8;    // consecutive rows handled by one wave of the light grouped kernel
-
+// Long rows of the narrow-slab scheme: the NW waves of a workgroup share one
+// (row, slab) item, take interleaved 64-edge tiles and combine through LDS.
 template <int LPG, int NW, bool WEIGHTED, bool OFF32>
-__global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_grouped_kernel(AggArgs a)
+__global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
 {
     constexpr int SW = 4 * LPG;
-    constexpr int K = NW == 1 ? kRowsPerWave : 1;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // work item = (slab, run of K consecutive schedule slots); slab-major unless told otherwise
-    const int64_t runs = (a.row_count + K - 1) / K;
-    const int64_t items = runs * a.nslab;
-    const int64_t item = (NW == 1) ? (int64_t)blockIdx.x * kLightWaves + wave : (int64_t)blockIdx.x;
-    if (item >= items) return;        // NW > 1: uniform over the workgroup
-    int64_t run;
+    const int64_t items = a.row_count * a.nslab;
+    const int64_t item = (int64_t)blockIdx.x;
+    if (item >= items) return;        // uniform over the workgroup
+    int64_t slot;
     int slab;
-    if (a.slab_major) { slab = (int)(item / runs); run = item % runs; }
-    else              { run = item / a.nslab; slab = (int)(item % a.nslab); }
-    const int64_t slot0 = run * K;
-    const int nrows = (int)min((int64_t)K, a.row_count - slot0);
-
-    // row metadata, one row per lane: a single dependent chain for all K rows
-    int v_l = 0, lo_l = 0, hi_l = 0;
-    if (lane < nrows) {
-        v_l = a.order[a.row_begin + slot0 + lane];
-        if (a.part_ptr) {
-            lo_l = a.part_ptr[(int64_t)a.part_lo * a.n_rows + a.row_begin + slot0 + lane];
-            hi_l = a.part_ptr[(int64_t)a.part_hi * a.n_rows + a.row_begin + slot0 + lane];
-        } else {
-            lo_l = (int)a.row_ptr[v_l];
-            hi_l = (int)a.row_ptr[v_l + 1];
-        }
+    if (a.slab_major) { slab = (int)(item / a.row_count); slot = item % a.row_count; }
+    else              { slot = item / a.nslab; slab = (int)(item % a.nslab); }
+    const int v = __builtin_amdgcn_readfirstlane(a.order[a.row_begin + slot]);
+    int lo, hi;
+    if (a.part_ptr) {
+        lo = __builtin_amdgcn_readfirstlane(a.part_ptr[(int64_t)a.part_lo * a.n_rows + a.row_begin + slot]);
+        hi = __builtin_amdgcn_readfirstlane(a.part_ptr[(int64_t)a.part_hi * a.n_rows + a.row_begin + slot]);
+    } else {
+        lo = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v]);
+        hi = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v + 1]);
     }
 
     const int li = lane % LPG, g = lane / LPG;
     const int64_t col = (int64_t)slab * SW + li * 4;
     const bool act = col < a.F;
-    const bool writer = act && g == 0;
+    const bool writer = act && g == 0 && wave == 0;
     const int valid = (int)min((int64_t)4, a.F - col);
     // lanes past the row width gather the slab's last valid vector instead (never stored)
     const int64_t gcol = act ? col : ((a.F - 1) / 4) * 4;
     const char* zbase = reinterpret_cast<const char*>(a.Z);
     const uint32_t colbytes = (uint32_t)(gcol * 4);
     const int64_t rowbytes = a.ldz * 4;
+    float* orow = a.out + (int64_t)v * a.ldo;
 
-    // ids of the first tile of the first row
-    int nxt_u = 0;
-    float nxt_w = 0.0f;
-    {
-        const int lo = bcast_i(lo_l, 0), hi = bcast_i(hi_l, 0);
-        const int e = lo + 64 * (NW == 1 ? 0 : wave) + lane;
-        if (e < hi) {
-            nxt_u = a.col_idx[e];
-            if (WEIGHTED) nxt_w = a.dinv[nxt_u];
-        }
+    // running sum over the source ranges walked so far (written by the previous launch)
+    float prev[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (!a.first && writer) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (k < valid) prev[k] = orow[a.ocol + col + k];
     }
 
-    for (int r = 0; r < nrows; ++r) {
-        const int v = bcast_i(v_l, r);
-        const int lo = bcast_i(lo_l, r), hi = bcast_i(hi_l, r);
-        float* orow = a.out + (int64_t)v * a.ldo;
-        int my_u = nxt_u;
-        float my_w = nxt_w;
-        if (K > 1 && r + 1 < nrows) {          // ids of the next row's first tile, fetched a row ahead
-            const int lo1 = bcast_i(lo_l, r + 1), hi1 = bcast_i(hi_l, r + 1);
-            const int e = lo1 + lane;
-            nxt_u = 0;
-            nxt_w = 0.0f;
-            if (e < hi1) {
-                nxt_u = a.col_idx[e];
-                if (WEIGHTED) nxt_w = a.dinv[nxt_u];
-            }
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int base = lo + 64 * wave; base < hi; base += 64 * NW) {
+        const int e = base + lane;
+        const int my_u = e < hi ? a.col_idx[e] : 0;
+        const float my_w = WEIGHTED ? (e < hi ? a.dinv[my_u] : 0.0f) : 1.0f;
+        const int cnt = min(64, hi - base);
+        const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
+        if (cnt == 64)
+            grouped_tile<LPG, true, WEIGHTED, OFF32>(zbase, colbytes, rowbytes, my_off, my_u, my_w, cnt, g, acc);
+        else
+            grouped_tile<LPG, false, WEIGHTED, OFF32>(zbase, colbytes, rowbytes, my_off, my_u, my_w, cnt, g, acc);
+    }
+    // combine the lane groups, then the waves (in wave order)
+#pragma unroll
+    for (int m = LPG; m < 64; m <<= 1)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += __shfl_xor(acc[k], m, 64);
+    __shared__ float red[NW][4][LPG];
+    if (g == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) red[wave][k][li] = acc[k];
+    }
+    __syncthreads();
+    if (!writer) return;
+    const int d = a.deg[v];
+    float out_v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float x = red[0][k][li];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) x += red[w][k][li];
+        x += prev[k];
+        if (a.last) {
+            if (a.scale == SCALE_MEAN) x = d > 0 ? x / (float)d : 0.0f;
+            else if (a.scale == SCALE_GCN) x = x * a.dinv[v];
         }
-        // running sum over the source ranges walked so far (written by the previous launch)
-        float prev[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (!a.first && writer && (NW == 1 || wave == 0)) {
-            if (a.out_vec && valid >= 4) load_row<4>(orow + a.ocol + col, prev);
-            else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (k < valid) prev[k] = orow[a.ocol + col + k];
-            }
-        }
-
-        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int base = lo + 64 * (NW == 1 ? 0 : wave); base < hi; base += 64 * NW) {
-            const int cnt = min(64, hi - base);
-            const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
-            if (cnt == 64)
-                grouped_tile<LPG, true, WEIGHTED, OFF32>(zbase, colbytes, rowbytes, my_off, my_u, my_w, cnt, g, acc);
-            else
-                grouped_tile<LPG, false, WEIGHTED, OFF32>(zbase, colbytes, rowbytes, my_off, my_u, my_w, cnt, g, acc);
-            if (base + 64 * NW < hi) {
-                const int e = base + 64 * NW + lane;
-                my_u = e < hi ? a.col_idx[e] : 0;
-                if (WEIGHTED) my_w = e < hi ? a.dinv[my_u] : 0.0f;
-            }
-        }
-        // combine the G groups: afterwards every lane holds the sum for its columns
-#pragma unroll
-        for (int m = LPG; m < 64; m <<= 1)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) acc[k] += __shfl_xor(acc[k], m, 64);
-
-        if constexpr (NW > 1) {
-            __shared__ float red[NW][4][LPG];
-            if (g == 0) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) red[wave][k][li] = acc[k];
-            }
-            __syncthreads();
-            if (wave != 0) return;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float s = red[0][k][li];
-#pragma unroll
-                for (int w = 1; w < NW; ++w) s += red[w][k][li];
-                acc[k] = s;
-            }
-        }
-        if (writer) {
-            const int d = a.deg[v];
-            float out_v[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float x = acc[k] + prev[k];
-                if (a.last) {
-                    if (a.scale == SCALE_MEAN) x = d > 0 ? x / (float)d : 0.0f;
-                    else if (a.scale == SCALE_GCN) x = x * a.dinv[v];
-                }
-                out_v[k] = x;
-            }
-            store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0);
-            if (a.copy_self && a.first) {
-                float zs[4];
-                load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
-                store_row<4>(orow + col, zs, valid, a.self_vec != 0);
-            }
-        }
+        out_v[k] = x;
+    }
+    store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0);
+    if (a.copy_self && a.first) {
+        float zs[4];
+        load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
+        store_row<4>(orow + col, zs, valid, a.self_vec != 0);
     }
 }
 
@@ -1094,17 +1043,10 @@ void launch_grouped_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStr
         AggArgs a = base;
         a.row_begin = n_heavy;
         a.row_count = N - n_heavy;
-        if (agg_options().row_groups) {
-            const int64_t bundles = (a.row_count + (64 / LPG) - 1) / (64 / LPG);
-            const int64_t blocks = (bundles * a.nslab + kLightWaves - 1) / kLightWaves;
-            agg_rowgroup_kernel<LPG, WEIGHTED, OFF32>
-                <<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
-        } else {
-            const int64_t runs = (a.row_count + kRowsPerWave - 1) / kRowsPerWave;
-            const int64_t blocks = (runs * a.nslab + kLightWaves - 1) / kLightWaves;
-            agg_grouped_kernel<LPG, 1, WEIGHTED, OFF32>
-                <<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
-        }
+        const int64_t bundles = (a.row_count + (64 / LPG) - 1) / (64 / LPG);
+        const int64_t blocks = (bundles * a.nslab + kLightWaves - 1) / kLightWaves;
+        agg_rowgroup_kernel<LPG, WEIGHTED, OFF32>
+            <<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
     }
 }
 

@@ -46,7 +46,6 @@ struct AggOptions {
     int64_t slab_major = -1;    // -1 = auto
     int64_t heavy_degree = 2048;
     int64_t max_vec = 4;        // cap on floats per lane per gather (experiments)
-    int64_t row_groups = 1;     // narrow slabs: one row per lane group (1) or one row per wave (0)
     int64_t gat_fast = 1;       // pipelined edge-softmax kernel (0: the plain one)
     int64_t parts = -1;         // source-id ranges per aggregation: -1 auto, 1 = off, 2/4/8/16
 };

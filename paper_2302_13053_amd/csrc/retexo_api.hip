@@ -80,7 +80,6 @@ extern "C" int retexo_set_option(const char* name, int64_t value)
     if (!strcmp(name, "agg_heavy_degree")) { o.heavy_degree = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_max_vec")) { o.max_vec = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_parts")) { o.parts = value; return RETEXO_OK; }
-    if (!strcmp(name, "agg_row_groups")) { o.row_groups = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_fast")) { o.gat_fast = value; return RETEXO_OK; }
     return RETEXO_E_FLAGS;
 }

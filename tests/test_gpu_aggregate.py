@@ -173,12 +173,10 @@ def test_bitwise_reproducible_and_option_sweep(graphs, mode):
     again = Hn.aggregate(g, mode, Z, F, **kw)
     assert torch.equal(first, again)
     try:
-        for slab, major, heavy, parts, rg in [(64, 0, 2048, 1, 1), (256, 1, 256, 1, 1), (512, 0, 1 << 20, 1, 1),
-                                              (256, 1, 8192, 1, 1), (32, 1, 2048, 1, 1), (128, 1, 512, 1, 1),
-                                              (32, 1, 2048, 2, 1), (64, 1, 2048, 4, 1), (32, 0, 2048, 8, 1),
-                                              (128, 1, 2048, 16, 1), (32, 1, 2048, 4, 0), (64, 0, 512, 1, 0),
-                                              (128, 1, 2048, 2, 0)]:
-            B.retexo_set_option("agg_row_groups", rg)
+        for slab, major, heavy, parts in [(64, 0, 2048, 1), (256, 1, 256, 1), (512, 0, 1 << 20, 1),
+                                          (256, 1, 8192, 1), (32, 1, 2048, 1), (128, 1, 512, 1),
+                                          (32, 1, 2048, 2), (64, 1, 2048, 4), (32, 0, 2048, 8),
+                                          (128, 1, 2048, 16), (64, 0, 512, 1)]:
             B.retexo_set_option("agg_slab_cols", slab)
             B.retexo_set_option("agg_slab_major", major)
             B.retexo_set_option("agg_heavy_degree", heavy)
@@ -192,7 +190,6 @@ def test_bitwise_reproducible_and_option_sweep(graphs, mode):
         B.retexo_set_option("agg_slab_major", -1)
         B.retexo_set_option("agg_heavy_degree", 2048)
         B.retexo_set_option("agg_parts", -1)
-        B.retexo_set_option("agg_row_groups", 1)
 
 
 @pytest.mark.parametrize("mode", ["mean", "gcn_sym", "sum"])
