@@ -53,6 +53,11 @@ def _load():
         lib.oracle_gat_alpha.restype = None
         lib.oracle_gat_alpha.argtypes = [i64, C.c_int, i64p, i32p, i64, C.c_int, f32p, i64,
                                          f32p, f32p, C.c_double, f64p]
+        lib.oracle_layer_grad.restype = C.c_double
+        lib.oracle_layer_grad.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f32p, f32p, f32p, f32p,
+                                          f64p, f64p, f64p, f64p]
+        lib.oracle_layer_loss.restype = C.c_double
+        lib.oracle_layer_loss.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f64p, f64p, f64p, f64p]
         _lib = lib
     return _lib
 
@@ -183,3 +188,46 @@ def round_(mode: str, row_ptr, col_idx, H, d_in: int, W, b, *, relu: bool = Fals
             Z32[need] = transform(H, d_in, W, b, relu, rows=need).astype(np.float32)
     return aggregate(mode, row_ptr, col_idx, Z32, F, heads=heads, a_src=a_src, a_dst=a_dst,
                      slope=slope, self_concat=self_concat, rows=rows)
+
+
+def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None):
+    """Loss and parameter gradients of one locally trained layer (see oracle_layer_grad).
+    Wc None: the layer is the final classifier (logits = X W1 + b1).
+    -> (loss, gW1, gb1, gWc or None, gbc or None), float64."""
+    X, ldx = _matrix(X)
+    labels = _c(labels, np.int32)
+    W1, b1 = _c(W1, np.float32), _c(b1, np.float32)
+    n = labels.size
+    assert X.shape[0] >= n and W1.shape[0] == d_in
+    if Wc is None:
+        H, Cc = 0, W1.shape[1]
+        Wc_ = bc_ = None
+        gWc = gbc = None
+    else:
+        Wc_, bc_ = _c(Wc, np.float32), _c(bc, np.float32)
+        H, Cc = W1.shape[1], Wc_.shape[1]
+        assert Wc_.shape[0] == H
+        gWc = np.empty((H, Cc), np.float64)
+        gbc = np.empty(Cc, np.float64)
+    gW1 = np.empty(W1.shape, np.float64)
+    gb1 = np.empty(W1.shape[1], np.float64)
+    loss = _load().oracle_layer_grad(n, d_in, H, Cc, _p(X, C.c_float), ldx, _p(labels, C.c_int32),
+                                     _p(W1, C.c_float), _p(b1, C.c_float), _p(Wc_, C.c_float),
+                                     _p(bc_, C.c_float), _p(gW1, C.c_double), _p(gb1, C.c_double),
+                                     _p(gWc, C.c_double), _p(gbc, C.c_double))
+    return float(loss), gW1, gb1, gWc, gbc
+
+
+def layer_loss(X, d_in: int, labels, W1, b1, Wc=None, bc=None) -> float:
+    """The loss alone, with float64 parameters (for numerical differencing in tests)."""
+    X, ldx = _matrix(X)
+    labels = _c(labels, np.int32)
+    W1, b1 = _c(W1, np.float64), _c(b1, np.float64)
+    if Wc is None:
+        H, Cc, Wc_, bc_ = 0, W1.shape[1], None, None
+    else:
+        Wc_, bc_ = _c(Wc, np.float64), _c(bc, np.float64)
+        H, Cc = W1.shape[1], Wc_.shape[1]
+    return float(_load().oracle_layer_loss(labels.size, d_in, H, Cc, _p(X, C.c_float), ldx,
+                                           _p(labels, C.c_int32), _p(W1, C.c_double), _p(b1, C.c_double),
+                                           _p(Wc_, C.c_double), _p(bc_, C.c_double)))

@@ -256,3 +256,136 @@ void oracle_gat_alpha(int64_t v, int h, const int64_t *row_ptr, const int32_t *c
     for (int64_t e = lo; e < hi; ++e) { alpha[e - lo] = exp(alpha[e - lo] - m); denom += alpha[e - lo]; }
     for (int64_t e = lo; e < hi; ++e) alpha[e - lo] /= denom;
 }
+
+/* ---------------------------------------------------------------------------
+ * Local training of one layer (section "Lazy Message Passing": a layer is
+ * trained by itself on its fixed aggregated inputs, with a temporary
+ * classification layer C added on top, using stochastic gradient descent; the
+ * appendix sizes C as an H_m x H_K linear map).  Read here as
+ *      A      = ReLU(X W1 + b1)                       the layer's f (Eq. 1)
+ *      logits = A Wc + bc                             the temporary classifier
+ *      loss   = mean over labelled nodes of  -log softmax(logits)[label]
+ * and, when H == 0, the layer is the final classification function itself:
+ *      logits = X W1 + b1   (W1 is [D_in, C]).
+ * A node with label < 0 is not a training node and contributes nothing.
+ * This function returns the loss and its gradient with respect to every
+ * parameter, all in double:  gW1 [D_in, H or C], gb1, gWc [H, C], gbc [C].
+ * With no labelled node the loss and all gradients are zero.
+ */
+double oracle_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                         const float *X, int64_t ldx, const int32_t *labels,
+                         const float *W1, const float *b1, const float *Wc, const float *bc,
+                         double *gW1, double *gb1, double *gWc, double *gbc)
+{
+    const int64_t W1cols = H > 0 ? H : C;
+    for (int64_t i = 0; i < D_in * W1cols; ++i) gW1[i] = 0.0;
+    for (int64_t i = 0; i < W1cols; ++i) gb1[i] = 0.0;
+    if (H > 0) {
+        for (int64_t i = 0; i < H * C; ++i) gWc[i] = 0.0;
+        for (int64_t i = 0; i < C; ++i) gbc[i] = 0.0;
+    }
+    int64_t n_lab = 0;
+    for (int64_t v = 0; v < N; ++v) n_lab += labels[v] >= 0;
+    if (n_lab == 0) return 0.0;
+
+    double *a = (double *)malloc((size_t)(H > 0 ? H : 1) * sizeof(double));
+    double *z = (double *)malloc((size_t)C * sizeof(double));
+    double *da = (double *)malloc((size_t)(H > 0 ? H : 1) * sizeof(double));
+    double loss = 0.0;
+    for (int64_t v = 0; v < N; ++v) {
+        const int32_t y = labels[v];
+        if (y < 0) continue;
+        const float *x = X + v * ldx;
+        if (H > 0) {
+            for (int64_t j = 0; j < H; ++j) {
+                double s = (double)b1[j];
+                for (int64_t k = 0; k < D_in; ++k) s += (double)x[k] * (double)W1[k * H + j];
+                a[j] = s > 0.0 ? s : 0.0;
+            }
+            for (int64_t c = 0; c < C; ++c) {
+                double s = (double)bc[c];
+                for (int64_t j = 0; j < H; ++j) s += a[j] * (double)Wc[j * C + c];
+                z[c] = s;
+            }
+        } else {
+            for (int64_t c = 0; c < C; ++c) {
+                double s = (double)b1[c];
+                for (int64_t k = 0; k < D_in; ++k) s += (double)x[k] * (double)W1[k * C + c];
+                z[c] = s;
+            }
+        }
+        double m = z[0];
+        for (int64_t c = 1; c < C; ++c) if (z[c] > m) m = z[c];
+        double den = 0.0;
+        for (int64_t c = 0; c < C; ++c) den += exp(z[c] - m);
+        loss += -(z[y] - m - log(den));
+        /* z becomes d loss / d logits for this node */
+        for (int64_t c = 0; c < C; ++c) z[c] = (exp(z[c] - m) / den - (c == y ? 1.0 : 0.0)) / (double)n_lab;
+        if (H > 0) {
+            for (int64_t c = 0; c < C; ++c) gbc[c] += z[c];
+            for (int64_t j = 0; j < H; ++j) {
+                double s = 0.0;
+                for (int64_t c = 0; c < C; ++c) {
+                    gWc[j * C + c] += a[j] * z[c];
+                    s += z[c] * (double)Wc[j * C + c];
+                }
+                da[j] = a[j] > 0.0 ? s : 0.0;
+            }
+            for (int64_t j = 0; j < H; ++j) gb1[j] += da[j];
+            for (int64_t k = 0; k < D_in; ++k) {
+                const double xk = (double)x[k];
+                for (int64_t j = 0; j < H; ++j) gW1[k * H + j] += xk * da[j];
+            }
+        } else {
+            for (int64_t c = 0; c < C; ++c) gb1[c] += z[c];
+            for (int64_t k = 0; k < D_in; ++k) {
+                const double xk = (double)x[k];
+                for (int64_t c = 0; c < C; ++c) gW1[k * C + c] += xk * z[c];
+            }
+        }
+    }
+    free(a); free(z); free(da);
+    return loss / (double)n_lab;
+}
+
+/* The loss alone (same formula), used by the tests to difference numerically. */
+double oracle_layer_loss(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                         const float *X, int64_t ldx, const int32_t *labels,
+                         const double *W1, const double *b1, const double *Wc, const double *bc)
+{
+    int64_t n_lab = 0;
+    double loss = 0.0;
+    double *a = (double *)malloc((size_t)(H > 0 ? H : 1) * sizeof(double));
+    double *z = (double *)malloc((size_t)C * sizeof(double));
+    for (int64_t v = 0; v < N; ++v) {
+        const int32_t y = labels[v];
+        if (y < 0) continue;
+        ++n_lab;
+        const float *x = X + v * ldx;
+        if (H > 0) {
+            for (int64_t j = 0; j < H; ++j) {
+                double s = b1[j];
+                for (int64_t k = 0; k < D_in; ++k) s += (double)x[k] * W1[k * H + j];
+                a[j] = s > 0.0 ? s : 0.0;
+            }
+            for (int64_t c = 0; c < C; ++c) {
+                double s = bc[c];
+                for (int64_t j = 0; j < H; ++j) s += a[j] * Wc[j * C + c];
+                z[c] = s;
+            }
+        } else {
+            for (int64_t c = 0; c < C; ++c) {
+                double s = b1[c];
+                for (int64_t k = 0; k < D_in; ++k) s += (double)x[k] * W1[k * C + c];
+                z[c] = s;
+            }
+        }
+        double m = z[0];
+        for (int64_t c = 1; c < C; ++c) if (z[c] > m) m = z[c];
+        double den = 0.0;
+        for (int64_t c = 0; c < C; ++c) den += exp(z[c] - m);
+        loss += -(z[y] - m - log(den));
+    }
+    free(a); free(z);
+    return n_lab ? loss / (double)n_lab : 0.0;
+}
