@@ -178,6 +178,36 @@ int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out,
                  void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Local training of one layer (section "Lazy Message Passing": every layer is
+ * trained by itself on its fixed aggregated inputs, with a temporary
+ * classification layer on top that is discarded afterwards; the last layer is
+ * the classification function itself).  This is the worker's share of one
+ * training round: loss and parameter gradients over its labelled nodes.
+ *
+ *     A      = ReLU(X W1 + b1)        X [N, ldx] first D_in columns, W1 [D_in, H], b1 [H]
+ *     logits = A Wc + bc              Wc [H, C], bc [C]
+ *     loss   = mean over nodes with label >= 0 of -log softmax(logits)[label]
+ * H == 0 selects the last layer: logits = X W1 + b1 with W1 [D_in, C], b1 [C];
+ * d_Wc, d_bc, d_gWc, d_gbc are then ignored.
+ *   d_labels [N] int32: class in [0, C) or any negative value for "not a training node"
+ *   d_gW1, d_gb1, d_gWc, d_gbc: gradients, same shapes as the parameters, dense, written
+ *   d_loss: one float, written
+ *   d_workspace: retexo_train_workspace_bytes(N, D_in, H, C) bytes, 256-aligned
+ * Enqueues on `stream`; no allocation, no synchronisation.  With no labelled
+ * node the loss and all gradients are zero.  Weight gradients are summed over
+ * node chunks in a fixed order (no atomics): bitwise reproducible.
+ * retexo_sgd_update applies  param <- param - lr * grad  to n floats (the
+ * plain SGD step; averaging gradients across workers is the caller's business).
+ */
+int64_t retexo_train_workspace_bytes(int64_t N, int64_t D_in, int64_t H, int64_t C);
+int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                      const float* d_X, int64_t ldx, const int32_t* d_labels,
+                      const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                      float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                      void* d_workspace, int64_t workspace_bytes, void* stream);
+int retexo_sgd_update(int64_t n, float* d_param, const float* d_grad, float lr, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Tuning knobs (process-wide, for experiments; defaults are chosen per shape).
  * name: "agg_slab_cols" (0 = auto), "agg_slab_major" (-1 auto / 0 / 1),
  *       "agg_heavy_degree" (rows at least this long get a whole workgroup),

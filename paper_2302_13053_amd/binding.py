@@ -28,6 +28,7 @@ EXPORTS = (
     "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
     "retexo_workspace_bytes",
     "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
+    "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
 )
 
 _lib = None
@@ -83,6 +84,13 @@ def load():
     lib.retexo_round.restype = i32
     lib.retexo_round.argtypes = [vp, i32, i64, i64, i32, vp, i64, vp, vp, vp, vp, f32, u32, vp, i64,
                                  vp, i64, vp]
+    lib.retexo_train_workspace_bytes.restype = i64
+    lib.retexo_train_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.retexo_layer_grad.restype = i32
+    lib.retexo_layer_grad.argtypes = [i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                      vp, i64, vp]
+    lib.retexo_sgd_update.restype = i32
+    lib.retexo_sgd_update.argtypes = [i64, vp, vp, f32, vp]
     lib.retexo_set_option.restype = i32
     lib.retexo_set_option.argtypes = [C.c_char_p, i64]
     _lib = lib
@@ -170,6 +178,22 @@ def retexo_round(plan, mode, d_in, d_out, heads, d_H, ldh, d_W, d_b, d_attn_src,
     return int(load().retexo_round(_vp(plan), mode, d_in, d_out, heads, _vp(d_H), ldh, _vp(d_W),
                                    _vp(d_b), _vp(d_attn_src), _vp(d_attn_dst), negative_slope, flags,
                                    _vp(d_out_ptr), ldo, _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+def retexo_train_workspace_bytes(n, d_in, h, c) -> int:
+    return int(load().retexo_train_workspace_bytes(n, d_in, h, c))
+
+
+def retexo_layer_grad(n, d_in, h, c, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc, d_gW1, d_gb1, d_gWc,
+                      d_gbc, d_loss, d_workspace, workspace_bytes, stream=0) -> int:
+    return int(load().retexo_layer_grad(n, d_in, h, c, _vp(d_X), ldx, _vp(d_labels), _vp(d_W1), _vp(d_b1),
+                                        _vp(d_Wc), _vp(d_bc), _vp(d_gW1), _vp(d_gb1), _vp(d_gWc),
+                                        _vp(d_gbc), _vp(d_loss), _vp(d_workspace), workspace_bytes,
+                                        _vp(stream)))
+
+
+def retexo_sgd_update(n, d_param, d_grad, lr, stream=0) -> int:
+    return int(load().retexo_sgd_update(n, _vp(d_param), _vp(d_grad), lr, _vp(stream)))
 
 
 def retexo_set_option(name: str, value: int) -> int:

@@ -54,7 +54,7 @@ AggOptions& agg_options();
 // internal launchers (no argument validation; the C entry points did it)
 int launch_transform(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
                      const float* W, const float* b, bool relu, float* Z, int64_t ldz,
-                     hipStream_t stream);
+                     hipStream_t stream, const float* mask = nullptr, int64_t ldm = 0);
 
 struct AggCall {
     const retexo_plan* plan;

@@ -1,0 +1,483 @@
+// Local training of one layer: the work a worker does between two message
+// passing rounds (section "Lazy Message Passing").  A layer f (fully connected
+// + ReLU, Eq. 1) is trained by itself on its fixed aggregated inputs X with a
+// temporary linear classification layer C on top (the appendix sizes C as
+// H_m x H_K) and softmax cross-entropy over the labelled nodes; the last layer
+// is the classification function itself (H == 0 here).
+//
+//      A      = ReLU(X W1 + b1)          transform kernel (fp32 MFMA)
+//      logits = A Wc + bc                transform kernel
+//      dL     = (softmax(logits) - onehot(label)) / n_labelled, 0 for unlabelled nodes
+//      gWc    = A^T dL,  gbc = colsum(dL)
+//      dA     = (dL Wc^T) where A > 0    transform kernel with Wc^T and a ReLU mask
+//      gW1    = X^T dA,  gb1 = colsum(dA)
+//
+// The two weight gradients are "TN" products whose contraction runs over the
+// nodes (hundreds of thousands), with a small output.  wgrad_kernel splits the
+// node range over many workgroups, each producing a partial [M, Nq] tile with
+// the same fp32 MFMA tile loop as the transform (both operands are already
+// k-major in memory, so their tiles are plain 16-byte copies into LDS), and a
+// second kernel adds the partials in a fixed order: deterministic, and more
+// accurate than one long fp32 accumulation.
+#include "common.hpp"
+#include "tiles.hpp"
+
+namespace {
+
+constexpr int BK = kTileK;
+constexpr int kThreads = 256;
+
+// ---------------------------------------------------------------------------
+// part[z][m][n] = sum over k in chunk z of P[k][m] * Q[k][n]
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, bool PV, bool QV>
+__global__ __launch_bounds__(256, 2) void wgrad_kernel(
+    int64_t K, int M, int Nq, const float* __restrict__ P, int64_t ldp,
+    const float* __restrict__ Q, int64_t ldq, int64_t k_chunk, float* __restrict__ part)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    constexpr int TM = BM / (32 * WGM);
+    constexpr int TN = BN / (32 * WGN);
+    constexpr int LDA = BM + 4;
+    constexpr int LDB = BN + 4;
+    constexpr int A_F4 = (BM * BK / 4 + 255) / 256;
+    constexpr int B_F4 = (BN * BK / 4 + 255) / 256;
+
+    __shared__ float As[2][BK][LDA];
+    __shared__ float Bs[2][BK][LDB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int m0 = blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int64_t k_begin = (int64_t)blockIdx.z * k_chunk;
+    const int64_t k_end = min(K, k_begin + k_chunk);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    float ra[A_F4][4], rb[B_F4][4];
+    int wa[A_F4], wb[B_F4];
+
+    auto load_tiles = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) {
+            const int id = tid + i * 256;
+            if (BM * BK / 4 % 256 != 0 && id >= BM * BK / 4) continue;
+            const int kk = id / (BM / 4), m4 = id % (BM / 4);
+            const int64_t k = k_begin + (int64_t)kt * BK + kk;
+            const int m = m0 + m4 * 4;
+            wa[i] = k < k_end ? M - m : 0;
+            load4<PV>(P, k * ldp + m, wa[i], ra[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < B_F4; ++i) {
+            const int id = tid + i * 256;
+            if (BN * BK / 4 % 256 != 0 && id >= BN * BK / 4) continue;
+            const int kk = id / (BN / 4), n4 = id % (BN / 4);
+            const int64_t k = k_begin + (int64_t)kt * BK + kk;
+            const int n = n0 + n4 * 4;
+            wb[i] = k < k_end ? Nq - n : 0;
+            load4<QV>(Q, k * ldq + n, wb[i], rb[i]);
+        }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) {
+            const int id = tid + i * 256;
+            if (BM * BK / 4 % 256 != 0 && id >= BM * BK / 4) continue;
+            const int kk = id / (BM / 4), m4 = id % (BM / 4);
+            zero4<PV>(wa[i], ra[i]);
+            f32x4 t = {ra[i][0], ra[i][1], ra[i][2], ra[i][3]};
+            *reinterpret_cast<f32x4*>(&As[buf][kk][m4 * 4]) = t;
+        }
+#pragma unroll
+        for (int i = 0; i < B_F4; ++i) {
+            const int id = tid + i * 256;
+            if (BN * BK / 4 % 256 != 0 && id >= BN * BK / 4) continue;
+            const int kk = id / (BN / 4), n4 = id % (BN / 4);
+            zero4<QV>(wb[i], rb[i]);
+            f32x4 t = {rb[i][0], rb[i][1], rb[i][2], rb[i][3]};
+            *reinterpret_cast<f32x4*>(&Bs[buf][kk][n4 * 4]) = t;
+        }
+    };
+
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int nk = (int)((k_end - k_begin + BK - 1) / BK);
+    if (nk > 0) {
+        load_tiles(0);
+        store_tiles(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_tiles(kt + 1);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float af[TM], bf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = As[buf][kk + lk][wm * TM * 32 + i * 32 + lrow];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[j] = Bs[buf][kk + lk][wn * TN * 32 + j * 32 + lrow];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_tiles(buf ^ 1);
+        __syncthreads();
+    }
+
+    float* out = part + (int64_t)blockIdx.z * M * Nq;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * TN * 32 + j * 32 + lrow;
+        if (col >= Nq) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                if (row < M) out[(int64_t)row * Nq + col] = acc[i][j][r];
+            }
+    }
+}
+
+// out[m][n] = sum_z part[z][m][n] for n < n_keep (partials are Nq wide), in z order
+__global__ __launch_bounds__(kThreads) void reduce_partials(
+    int S, int M, int Nq, int n_keep, const float* __restrict__ part, float* __restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (int64_t)M * n_keep) return;
+    const int m = (int)(i / n_keep), n = (int)(i % n_keep);
+    float s = 0.0f;
+    for (int z = 0; z < S; ++z) s += part[((int64_t)z * M + m) * Nq + n];
+    out[i] = s;
+}
+
+struct TrainHeader {
+    int32_t n_labelled;
+    int32_t pad[3];
+};
+
+__global__ __launch_bounds__(kThreads) void count_labelled(int64_t N, const int32_t* __restrict__ labels,
+                                                           TrainHeader* hdr)
+{
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool lab = v < N && labels[v] >= 0;
+    const uint64_t b = __ballot(lab);
+    if ((threadIdx.x & 63) == 0 && b) atomicAdd(&hdr->n_labelled, (int)__popcll(b));
+}
+
+__device__ __forceinline__ float wmax(float x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
+    return x;
+}
+__device__ __forceinline__ float wsum(float x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+
+// One wave per node.  L[v, 0:C] holds the logits on entry and d loss / d logits on exit
+// (zero for unlabelled nodes and in the padding columns C..ld).  Per-workgroup loss sums go
+// to loss_part[blockIdx.x] (unscaled).
+__global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
+    int64_t N, int C, float* __restrict__ L, int64_t ld, const int32_t* __restrict__ labels,
+    const TrainHeader* hdr, float* __restrict__ loss_part)
+{
+    __shared__ float wl[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t v = (int64_t)blockIdx.x * 4 + wave;
+    float loss = 0.0f;
+    if (v < N) {
+        float* row = L + v * ld;
+        const int y = labels[v];
+        const int nl = hdr->n_labelled;
+        const float scale = (y >= 0 && nl > 0) ? 1.0f / (float)nl : 0.0f;
+        float m = -INFINITY;
+        for (int j = lane; j < C; j += 64) m = fmaxf(m, row[j]);
+        m = wmax(m);
+        float s = 0.0f;
+        for (int j = lane; j < C; j += 64) s += expf(row[j] - m);
+        s = wsum(s);
+        if (y >= 0 && y < C) loss = -(row[y] - m - logf(s));
+        for (int j = lane; j < ld; j += 64) {
+            float g = 0.0f;
+            if (j < C) g = (expf(row[j] - m) / s - (j == y ? 1.0f : 0.0f)) * scale;
+            row[j] = g;
+        }
+    }
+    if (lane == 0) wl[wave] = loss;
+    __syncthreads();
+    if (threadIdx.x == 0) loss_part[blockIdx.x] = (wl[0] + wl[1]) + (wl[2] + wl[3]);
+}
+
+// loss = (sum of the partial sums, pairwise in a fixed order) / n_labelled
+__global__ __launch_bounds__(kThreads) void loss_reduce_kernel(int64_t n_part, const float* __restrict__ part,
+                                                               const TrainHeader* hdr, float* __restrict__ loss)
+{
+    __shared__ float sh[kThreads];
+    float s = 0.0f;
+    for (int64_t i = threadIdx.x; i < n_part; i += kThreads) s += part[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = kThreads / 2; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = hdr->n_labelled > 0 ? sh[0] / (float)hdr->n_labelled : 0.0f;
+}
+
+// column sums in two deterministic stages: part[b][c] over a row block, then over blocks
+__global__ __launch_bounds__(kThreads) void colsum_stage1(int64_t N, int C, const float* __restrict__ D, int64_t ld,
+                                                          int64_t rows_per_block, float* __restrict__ part)
+{
+    const int c = blockIdx.y * kThreads + threadIdx.x;
+    if (c >= C) return;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block, r1 = min(N, r0 + rows_per_block);
+    float s = 0.0f;
+    for (int64_t r = r0; r < r1; ++r) s += D[r * ld + c];
+    part[(int64_t)blockIdx.x * C + c] = s;
+}
+__global__ __launch_bounds__(kThreads) void colsum_stage2(int B, int C, const float* __restrict__ part,
+                                                          float* __restrict__ out)
+{
+    const int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) s += part[(int64_t)b * C + c];
+    out[c] = s;
+}
+
+__global__ __launch_bounds__(kThreads) void transpose_kernel(int R, int Cn, const float* __restrict__ in,
+                                                             float* __restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (int64_t)R * Cn) return;
+    const int r = (int)(i / Cn), c = (int)(i % Cn);
+    out[(int64_t)c * R + r] = in[i];
+}
+
+__global__ __launch_bounds__(kThreads) void sgd_kernel(int64_t n, float* __restrict__ p, const float* __restrict__ g,
+                                                       float lr)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) p[i] = p[i] - lr * g[i];
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+struct Split { int S; int64_t k_chunk; };
+
+Split choose_split(int64_t K, int64_t M, int64_t Nq, int bn)
+{
+    const int64_t tiles = ((M + 127) / 128) * ((Nq + bn - 1) / bn);
+    int64_t S = (1024 + tiles - 1) / tiles;                 // about four workgroups per CU in total
+    const int64_t max_s = (K + 255) / 256;                  // at least 256 nodes per chunk
+    if (S > max_s) S = max_s;
+    if (S < 1) S = 1;
+    int64_t chunk = (K + S - 1) / S;
+    chunk = (chunk + BK - 1) / BK * BK;
+    S = (K + chunk - 1) / chunk;
+    if (S < 1) S = 1;
+    return {(int)S, chunk};
+}
+
+int bn_for(int64_t Nq) { return Nq <= 32 ? 32 : Nq <= 64 ? 64 : Nq <= 128 ? 128 : 256; }
+
+template <int BN, int WGM, int WGN>
+void launch_wgrad_bn(int64_t K, int64_t M, int64_t Nq, const float* P, int64_t ldp, const float* Q, int64_t ldq,
+                     Split sp, float* part, hipStream_t stream)
+{
+    const bool pv = (uintptr_t)P % 16 == 0 && ldp % 4 == 0 && M % 4 == 0;
+    const bool qv = (uintptr_t)Q % 16 == 0 && ldq % 4 == 0 && Nq % 4 == 0;
+    dim3 grid((unsigned)((M + 127) / 128), (unsigned)((Nq + BN - 1) / BN), (unsigned)sp.S);
+    if (pv && qv)
+        wgrad_kernel<128, BN, WGM, WGN, true, true><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);
+    else if (pv)
+        wgrad_kernel<128, BN, WGM, WGN, true, false><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);
+    else if (qv)
+        wgrad_kernel<128, BN, WGM, WGN, false, true><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);
+    else
+        wgrad_kernel<128, BN, WGM, WGN, false, false><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);
+}
+
+// out[M][n_keep] = P^T Q, Q being Nq (>= n_keep) columns wide
+void wgrad(int64_t K, int64_t M, int64_t Nq, int64_t n_keep, const float* P, int64_t ldp, const float* Q,
+           int64_t ldq, float* part, float* out, hipStream_t stream)
+{
+    const int bn = bn_for(Nq);
+    const Split sp = choose_split(K, M, Nq, bn);
+    if (bn == 32) launch_wgrad_bn<32, 4, 1>(K, M, Nq, P, ldp, Q, ldq, sp, part, stream);
+    else if (bn == 64) launch_wgrad_bn<64, 4, 1>(K, M, Nq, P, ldp, Q, ldq, sp, part, stream);
+    else if (bn == 128) launch_wgrad_bn<128, 2, 2>(K, M, Nq, P, ldp, Q, ldq, sp, part, stream);
+    else launch_wgrad_bn<256, 2, 2>(K, M, Nq, P, ldp, Q, ldq, sp, part, stream);
+    const int64_t total = M * n_keep;
+    reduce_partials<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+        sp.S, (int)M, (int)Nq, (int)n_keep, part, out);
+}
+
+void colsum(int64_t N, int64_t C, const float* D, int64_t ld, float* part, float* out, hipStream_t stream)
+{
+    const int64_t rows_per_block = 1024;
+    const int B = (int)((N + rows_per_block - 1) / rows_per_block);
+    dim3 g1((unsigned)B, (unsigned)((C + kThreads - 1) / kThreads));
+    colsum_stage1<<<g1, dim3(kThreads), 0, stream>>>(N, (int)C, D, ld, rows_per_block, part);
+    colsum_stage2<<<dim3((unsigned)((C + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(B, (int)C, part, out);
+}
+
+struct TrainLayout {
+    int64_t ldh, ldc;
+    int64_t hdr, A, L, dA, WcT, part, colpart, losspart, total;
+};
+
+int64_t partial_floats(int64_t K, int64_t M, int64_t Nq)
+{
+    const Split sp = choose_split(K, M, Nq, bn_for(Nq));
+    return (int64_t)sp.S * M * Nq;
+}
+
+TrainLayout make_layout(int64_t N, int64_t D_in, int64_t H, int64_t C)
+{
+    TrainLayout t;
+    const int64_t n1 = N > 0 ? N : 1;
+    t.ldh = align_up(H > 0 ? H : 1, 32);
+    t.ldc = align_up(C > 0 ? C : 1, 32);
+    int64_t off = 0;
+    auto take = [&](int64_t floats) { const int64_t at = off; off += align_up(floats * 4, 256); return at; };
+    t.hdr = off; off += 256;
+    t.A = take(H > 0 ? n1 * t.ldh : 0);
+    t.L = take(n1 * t.ldc);
+    t.dA = take(H > 0 ? n1 * t.ldh : 0);
+    t.WcT = take(H > 0 ? C * H : 0);
+    int64_t pf = 0;
+    if (H > 0) {
+        pf = partial_floats(N, D_in, t.ldh);
+        const int64_t p2 = partial_floats(N, H, t.ldc);
+        if (p2 > pf) pf = p2;
+    } else {
+        pf = partial_floats(N, D_in, t.ldc);
+    }
+    t.part = take(pf);
+    const int64_t widest = t.ldh > t.ldc ? t.ldh : t.ldc;
+    t.colpart = take(((n1 + 1023) / 1024) * widest);
+    t.losspart = take((n1 + 3) / 4);
+    t.total = off;
+    return t;
+}
+
+int check_sizes(int64_t N, int64_t D_in, int64_t H, int64_t C)
+{
+    if (N < 0 || D_in < 1 || H < 0 || C < 1) return RETEXO_E_SIZE;
+    if (N >= (1ll << 31) || D_in >= (1 << 20) || H >= (1 << 20) || C >= (1 << 20)) return RETEXO_E_SIZE;
+    return RETEXO_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t retexo_train_workspace_bytes(int64_t N, int64_t D_in, int64_t H, int64_t C)
+{
+    if (int s = check_sizes(N, D_in, H, C)) return s;
+    return make_layout(N, D_in, H, C).total;
+}
+
+extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                                 const float* d_X, int64_t ldx, const int32_t* d_labels,
+                                 const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                                 float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                                 void* d_workspace, int64_t workspace_bytes, void* stream_)
+{
+    if (int s = check_sizes(N, D_in, H, C)) return s;
+    if (ldx < D_in) return RETEXO_E_LD;
+    if (!d_W1 || !d_b1 || !d_gW1 || !d_gb1 || !d_loss) return RETEXO_E_NULL;
+    if (N > 0 && (!d_X || !d_labels)) return RETEXO_E_NULL;
+    if (H > 0 && (!d_Wc || !d_bc || !d_gWc || !d_gbc)) return RETEXO_E_NULL;
+    const TrainLayout t = make_layout(N, D_in, H, C);
+    if (!d_workspace || workspace_bytes < t.total || ((uintptr_t)d_workspace & 255)) return RETEXO_E_WORKSPACE;
+
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)d_workspace;
+    TrainHeader* hdr = (TrainHeader*)(ws + t.hdr);
+    float* A = (float*)(ws + t.A);
+    float* L = (float*)(ws + t.L);
+    float* dA = (float*)(ws + t.dA);
+    float* WcT = (float*)(ws + t.WcT);
+    float* part = (float*)(ws + t.part);
+    float* colpart = (float*)(ws + t.colpart);
+    float* losspart = (float*)(ws + t.losspart);
+    const int64_t W1cols = H > 0 ? H : C;
+
+    if (N == 0) {
+        // nothing to learn from: zero loss and gradients
+        RETEXO_HIP_TRY(hipMemsetAsync(d_gW1, 0, (size_t)(D_in * W1cols) * 4, stream));
+        RETEXO_HIP_TRY(hipMemsetAsync(d_gb1, 0, (size_t)W1cols * 4, stream));
+        if (H > 0) {
+            RETEXO_HIP_TRY(hipMemsetAsync(d_gWc, 0, (size_t)(H * C) * 4, stream));
+            RETEXO_HIP_TRY(hipMemsetAsync(d_gbc, 0, (size_t)C * 4, stream));
+        }
+        RETEXO_HIP_TRY(hipMemsetAsync(d_loss, 0, 4, stream));
+        return RETEXO_OK;
+    }
+
+    RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(TrainHeader), stream));
+    count_labelled<<<dim3((unsigned)((N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(N, d_labels, hdr);
+
+    // forward
+    const float* feat = d_X;        // input of the classifier product
+    int64_t ldfeat = ldx, dfeat = D_in;
+    if (H > 0) {
+        if (int e = launch_transform(N, D_in, H, d_X, ldx, d_W1, d_b1, true, A, t.ldh, stream)) return e;
+        feat = A; ldfeat = t.ldh; dfeat = H;
+    }
+    if (int e = launch_transform(N, dfeat, C, feat, ldfeat, H > 0 ? d_Wc : d_W1, H > 0 ? d_bc : d_b1, false,
+                                 L, t.ldc, stream))
+        return e;
+
+    // loss and d loss / d logits (in place, padding columns zeroed)
+    const unsigned nb = (unsigned)((N + 3) / 4);
+    softmax_xent_kernel<<<dim3(nb), dim3(kThreads), 0, stream>>>(N, (int)C, L, t.ldc, d_labels, hdr, losspart);
+    loss_reduce_kernel<<<dim3(1), dim3(kThreads), 0, stream>>>((int64_t)nb, losspart, hdr, d_loss);
+
+    // classifier (or only) layer: weight and bias gradients
+    float* gW_top = H > 0 ? d_gWc : d_gW1;
+    float* gb_top = H > 0 ? d_gbc : d_gb1;
+    wgrad(N, dfeat, t.ldc, C, feat, ldfeat, L, t.ldc, part, gW_top, stream);
+    colsum(N, C, L, t.ldc, colpart, gb_top, stream);
+
+    if (H > 0) {
+        // back through the classifier and the ReLU, then the layer's own gradients
+        const int64_t tot = H * C;
+        transpose_kernel<<<dim3((unsigned)((tot + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            (int)H, (int)C, d_Wc, WcT);
+        if (int e = launch_transform(N, C, H, L, t.ldc, WcT, nullptr, false, dA, t.ldh, stream, A, t.ldh)) return e;
+        // (padding columns of dA only produce partial columns that reduce_partials never reads)
+        wgrad(N, D_in, t.ldh, H, d_X, ldx, dA, t.ldh, part, d_gW1, stream);
+        colsum(N, H, dA, t.ldh, colpart, d_gb1, stream);
+    }
+    if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
+    return RETEXO_OK;
+}
+
+extern "C" int retexo_sgd_update(int64_t n, float* d_param, const float* d_grad, float lr, void* stream)
+{
+    if (n < 0) return RETEXO_E_SIZE;
+    if (n == 0) return RETEXO_OK;
+    if (!d_param || !d_grad) return RETEXO_E_NULL;
+    sgd_kernel<<<dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        n, d_param, d_grad, lr);
+    if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
+    return RETEXO_OK;
+}

@@ -15,44 +15,17 @@
 // written to the other LDS buffer afterwards (one barrier per step).
 // Bias and ReLU are applied to the accumulators before the store.
 #include "common.hpp"
+#include "tiles.hpp"
 
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int BK = 16;
-
-// Four consecutive floats starting at base[off], fetched without a branch: an
-// element that is not wanted (or would be out of range) is fetched from base[0]
-// instead; zero4 later replaces it by zero.  Keeping the replacement out of the
-// load lets all loads of a K step stay in flight behind the MFMAs of the
-// previous step.
-//   VEC: the four are one aligned 16-byte load and are wanted all or none
-template <bool VEC>
-__device__ __forceinline__ void load4(const float* __restrict__ base, int64_t off, int wanted, float (&r)[4])
-{
-    if constexpr (VEC) {
-        const f32x4 t = *reinterpret_cast<const f32x4*>(base + (wanted >= 4 ? off : 0));
-        r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
-    } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) r[q] = base[q < wanted ? off + q : 0];
-    }
-}
-
-template <bool VEC>
-__device__ __forceinline__ void zero4(int wanted, float (&r)[4])
-{
-#pragma unroll
-    for (int q = 0; q < 4; ++q) r[q] = (VEC ? wanted >= 4 : q < wanted) ? r[q] : 0.0f;
-}
+constexpr int BK = kTileK;
 
 template <int BM, int BN, int WGM, int WGN, bool HV, bool WV>
 __global__ __launch_bounds__(256, 2) void transform_kernel(
     int64_t N, int D_in, int D_out, const float* __restrict__ H, int64_t ldh,
     const float* __restrict__ W, const float* __restrict__ bias, int relu,
-    float* __restrict__ Z, int64_t ldz)
+    float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm)
 {
     static_assert(WGM * WGN == 4, "four waves per workgroup");
     constexpr int TM = BM / (32 * WGM);      // 32x32 MFMA tiles per wave along M
@@ -179,6 +152,8 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
                 if (row < N) {
                     float x = acc[i][j][r] + bv[j];
                     if (relu) x = fmaxf(x, 0.0f);
+                    // backward of a ReLU layer: pass the value only where the forward activation was positive
+                    if (mask) x = mask[row * ldm + col] > 0.0f ? x : 0.0f;
                     Z[row * ldz + col] = x;
                 }
             }
@@ -188,7 +163,8 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
 
 template <int BM, int BN, int WGM, int WGN>
 void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh, const float* W,
-            const float* b, bool relu, float* Z, int64_t ldz, hipStream_t stream)
+            const float* b, bool relu, float* Z, int64_t ldz, const float* mask, int64_t ldm,
+            hipStream_t stream)
 {
     // 16-byte loads need aligned rows and widths that are multiples of four floats
     const bool hv = (uintptr_t)H % 16 == 0 && ldh % 4 == 0 && D_in % 4 == 0;
@@ -196,26 +172,26 @@ void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
     dim3 grid((unsigned)((N + BM - 1) / BM), (unsigned)((D_out + BN - 1) / BN));
     const int r = relu ? 1 : 0;
     if (hv && wv)
-        transform_kernel<BM, BN, WGM, WGN, true, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+        transform_kernel<BM, BN, WGM, WGN, true, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else if (hv)
-        transform_kernel<BM, BN, WGM, WGN, true, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+        transform_kernel<BM, BN, WGM, WGN, true, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else if (wv)
-        transform_kernel<BM, BN, WGM, WGN, false, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+        transform_kernel<BM, BN, WGM, WGN, false, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else
-        transform_kernel<BM, BN, WGM, WGN, false, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz);
+        transform_kernel<BM, BN, WGM, WGN, false, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
 }
 
 }  // namespace
 
 int launch_transform(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
                      const float* W, const float* b, bool relu, float* Z, int64_t ldz,
-                     hipStream_t stream)
+                     hipStream_t stream, const float* mask, int64_t ldm)
 {
     if (N == 0 || D_out == 0) return RETEXO_OK;
-    if (D_out <= 32)       launch<128, 32, 4, 1>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, stream);
-    else if (D_out <= 64)  launch<128, 64, 4, 1>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, stream);
-    else if (D_out <= 128) launch<128, 128, 2, 2>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, stream);
-    else                   launch<128, 256, 2, 2>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, stream);
+    if (D_out <= 32)       launch<128, 32, 4, 1>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else if (D_out <= 64)  launch<128, 64, 4, 1>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else if (D_out <= 128) launch<128, 128, 2, 2>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else                   launch<128, 256, 2, 2>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
     return RETEXO_OK;
 }

@@ -135,6 +135,29 @@ def round_(g: DeviceGraph, st: Stage, H: torch.Tensor, W, b, a_src, a_dst, out: 
     B.check(rc, "retexo_round")
 
 
+def layer_grad(X: torch.Tensor, d_in: int, labels: torch.Tensor, W1, b1, Wc=None, bc=None,
+               workspace: Optional[torch.Tensor] = None):
+    """Loss and gradients of one locally trained layer -> (loss [1], gW1, gb1, gWc, gbc) device tensors."""
+    n = int(labels.numel())
+    h = 0 if Wc is None else int(W1.shape[1])
+    c = int(W1.shape[1]) if Wc is None else int(Wc.shape[1])
+    need = B.retexo_train_workspace_bytes(n, d_in, h, c)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_train_workspace_bytes")
+    if workspace is None:
+        workspace = ws_tensor(need)
+    gW1, gb1 = torch.empty_like(W1), torch.empty_like(b1)
+    gWc = torch.empty_like(Wc) if Wc is not None else None
+    gbc = torch.empty_like(bc) if Wc is not None else None
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    p = lambda t: t.data_ptr() if t is not None else 0
+    st = B.retexo_layer_grad(n, d_in, h, c, X.data_ptr(), X.stride(0), labels.data_ptr(), p(W1), p(b1), p(Wc),
+                             p(bc), p(gW1), p(gb1), p(gWc), p(gbc), loss.data_ptr(), workspace.data_ptr(),
+                             workspace.numel(), _stream_ptr())
+    B.check(st, "retexo_layer_grad")
+    return loss, gW1, gb1, gWc, gbc
+
+
 class Pipeline:
     """All device buffers of one workload, allocated once; ``run`` replays the
     whole hot path: CSR construction, plan, then every stage in order."""
