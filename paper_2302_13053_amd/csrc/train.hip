@@ -171,10 +171,19 @@ struct TrainHeader {
 __global__ __launch_bounds__(kThreads) void count_labelled(int64_t N, const int32_t* __restrict__ labels,
                                                            TrainHeader* hdr)
 {
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const bool lab = v < N && labels[v] >= 0;
-    const uint64_t b = __ballot(lab);
-    if ((threadIdx.x & 63) == 0 && b) atomicAdd(&hdr->n_labelled, (int)__popcll(b));
+    __shared__ int sh[kThreads / 64];
+    int cnt = 0;
+    for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < N; v += (int64_t)gridDim.x * kThreads)
+        cnt += labels[v] >= 0;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) cnt += __shfl_xor(cnt, m, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int w = 0; w < kThreads / 64; ++w) t += sh[w];
+        if (t) atomicAdd(&hdr->n_labelled, t);       // integer: the total does not depend on the order
+    }
 }
 
 __device__ __forceinline__ float wmax(float x)
@@ -190,21 +199,24 @@ __device__ __forceinline__ float wsum(float x)
     return x;
 }
 
-// One wave per node.  L[v, 0:C] holds the logits on entry and d loss / d logits on exit
-// (zero for unlabelled nodes and in the padding columns C..ld).  Per-workgroup loss sums go
-// to loss_part[blockIdx.x] (unscaled).
+constexpr int kXentRows = 64;     // nodes per workgroup of the loss kernel (16 per wave)
+
+// One wave per node at a time.  L[v, 0:C] holds the logits on entry and d loss / d logits on
+// exit (zero for unlabelled nodes and in the padding columns C..ld).  Per-workgroup loss sums
+// go to loss_part[blockIdx.x] (unscaled).
 __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
     int64_t N, int C, float* __restrict__ L, int64_t ld, const int32_t* __restrict__ labels,
     const TrainHeader* hdr, float* __restrict__ loss_part)
 {
     __shared__ float wl[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t v = (int64_t)blockIdx.x * 4 + wave;
+    const int nl = hdr->n_labelled;
     float loss = 0.0f;
-    if (v < N) {
+    for (int r = wave; r < kXentRows; r += 4) {
+        const int64_t v = (int64_t)blockIdx.x * kXentRows + r;
+        if (v >= N) break;
         float* row = L + v * ld;
         const int y = labels[v];
-        const int nl = hdr->n_labelled;
         const float scale = (y >= 0 && nl > 0) ? 1.0f / (float)nl : 0.0f;
         float m = -INFINITY;
         for (int j = lane; j < C; j += 64) m = fmaxf(m, row[j]);
@@ -212,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
         float s = 0.0f;
         for (int j = lane; j < C; j += 64) s += expf(row[j] - m);
         s = wsum(s);
-        if (y >= 0 && y < C) loss = -(row[y] - m - logf(s));
+        if (y >= 0 && y < C) loss += -(row[y] - m - logf(s));
         for (int j = lane; j < ld; j += 64) {
             float g = 0.0f;
             if (j < C) g = (expf(row[j] - m) / s - (j == y ? 1.0f : 0.0f)) * scale;
@@ -240,34 +252,53 @@ __global__ __launch_bounds__(kThreads) void loss_reduce_kernel(int64_t n_part, c
     if (threadIdx.x == 0) *loss = hdr->n_labelled > 0 ? sh[0] / (float)hdr->n_labelled : 0.0f;
 }
 
-// column sums in two deterministic stages: part[b][c] over a row block, then over blocks
+// Column sums in two deterministic stages.  Stage 1: a workgroup takes kColRows rows; its four
+// waves stride the rows, lanes stride the columns, and the waves are added in order through LDS.
+// Stage 2: one workgroup per column adds the stage-1 results with a fixed tree.
+constexpr int kColRows = 512;
+
 __global__ __launch_bounds__(kThreads) void colsum_stage1(int64_t N, int C, const float* __restrict__ D, int64_t ld,
-                                                          int64_t rows_per_block, float* __restrict__ part)
+                                                          float* __restrict__ part)
 {
-    const int c = blockIdx.y * kThreads + threadIdx.x;
-    if (c >= C) return;
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block, r1 = min(N, r0 + rows_per_block);
-    float s = 0.0f;
-    for (int64_t r = r0; r < r1; ++r) s += D[r * ld + c];
-    part[(int64_t)blockIdx.x * C + c] = s;
+    __shared__ float sh[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r0 = (int64_t)blockIdx.x * kColRows, r1 = min(N, r0 + kColRows);
+    for (int c0 = 0; c0 < C; c0 += 64) {
+        const int c = c0 + lane;
+        float s = 0.0f;
+        if (c < C)
+            for (int64_t r = r0 + wave; r < r1; r += 4) s += D[r * ld + c];
+        sh[wave][lane] = s;
+        __syncthreads();
+        if (wave == 0 && c < C)
+            part[(int64_t)blockIdx.x * C + c] = (sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane]);
+        __syncthreads();
+    }
 }
 __global__ __launch_bounds__(kThreads) void colsum_stage2(int B, int C, const float* __restrict__ part,
                                                           float* __restrict__ out)
 {
-    const int c = blockIdx.x * kThreads + threadIdx.x;
-    if (c >= C) return;
+    __shared__ float sh[kThreads];
+    const int c = blockIdx.x;
     float s = 0.0f;
-    for (int b = 0; b < B; ++b) s += part[(int64_t)b * C + c];
-    out[c] = s;
+    for (int b = threadIdx.x; b < B; b += kThreads) s += part[(int64_t)b * C + c];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = kThreads / 2; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[c] = sh[0];
 }
 
-__global__ __launch_bounds__(kThreads) void transpose_kernel(int R, int Cn, const float* __restrict__ in,
+// out [Cp, R] = transpose of in [R, Cn], rows Cn..Cp of out zero
+__global__ __launch_bounds__(kThreads) void transpose_kernel(int R, int Cn, int Cp, const float* __restrict__ in,
                                                              float* __restrict__ out)
 {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= (int64_t)R * Cn) return;
-    const int r = (int)(i / Cn), c = (int)(i % Cn);
-    out[(int64_t)c * R + r] = in[i];
+    if (i >= (int64_t)R * Cp) return;
+    const int c = (int)(i / R), r = (int)(i % R);
+    out[i] = c < Cn ? in[(int64_t)r * Cn + c] : 0.0f;
 }
 
 __global__ __launch_bounds__(kThreads) void sgd_kernel(int64_t n, float* __restrict__ p, const float* __restrict__ g,
@@ -332,11 +363,9 @@ void wgrad(int64_t K, int64_t M, int64_t Nq, int64_t n_keep, const float* P, int
 
 void colsum(int64_t N, int64_t C, const float* D, int64_t ld, float* part, float* out, hipStream_t stream)
 {
-    const int64_t rows_per_block = 1024;
-    const int B = (int)((N + rows_per_block - 1) / rows_per_block);
-    dim3 g1((unsigned)B, (unsigned)((C + kThreads - 1) / kThreads));
-    colsum_stage1<<<g1, dim3(kThreads), 0, stream>>>(N, (int)C, D, ld, rows_per_block, part);
-    colsum_stage2<<<dim3((unsigned)((C + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(B, (int)C, part, out);
+    const int B = (int)((N + kColRows - 1) / kColRows);
+    colsum_stage1<<<dim3((unsigned)B), dim3(kThreads), 0, stream>>>(N, (int)C, D, ld, part);
+    colsum_stage2<<<dim3((unsigned)C), dim3(kThreads), 0, stream>>>(B, (int)C, part, out);
 }
 
 struct TrainLayout {
@@ -362,7 +391,7 @@ TrainLayout make_layout(int64_t N, int64_t D_in, int64_t H, int64_t C)
     t.A = take(H > 0 ? n1 * t.ldh : 0);
     t.L = take(n1 * t.ldc);
     t.dA = take(H > 0 ? n1 * t.ldh : 0);
-    t.WcT = take(H > 0 ? C * H : 0);
+    t.WcT = take(H > 0 ? t.ldc * H : 0);
     int64_t pf = 0;
     if (H > 0) {
         pf = partial_floats(N, D_in, t.ldh);
@@ -373,8 +402,8 @@ TrainLayout make_layout(int64_t N, int64_t D_in, int64_t H, int64_t C)
     }
     t.part = take(pf);
     const int64_t widest = t.ldh > t.ldc ? t.ldh : t.ldc;
-    t.colpart = take(((n1 + 1023) / 1024) * widest);
-    t.losspart = take((n1 + 3) / 4);
+    t.colpart = take(((n1 + kColRows - 1) / kColRows) * widest);
+    t.losspart = take((n1 + kXentRows - 1) / kXentRows);
     t.total = off;
     return t;
 }
@@ -433,7 +462,7 @@ extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
     }
 
     RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(TrainHeader), stream));
-    count_labelled<<<dim3((unsigned)((N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(N, d_labels, hdr);
+    count_labelled<<<dim3((unsigned)min((int64_t)1024, (N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(N, d_labels, hdr);
 
     // forward
     const float* feat = d_X;        // input of the classifier product
@@ -447,7 +476,7 @@ extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
         return e;
 
     // loss and d loss / d logits (in place, padding columns zeroed)
-    const unsigned nb = (unsigned)((N + 3) / 4);
+    const unsigned nb = (unsigned)((N + kXentRows - 1) / kXentRows);
     softmax_xent_kernel<<<dim3(nb), dim3(kThreads), 0, stream>>>(N, (int)C, L, t.ldc, d_labels, hdr, losspart);
     loss_reduce_kernel<<<dim3(1), dim3(kThreads), 0, stream>>>((int64_t)nb, losspart, hdr, d_loss);
 
@@ -459,10 +488,12 @@ extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
 
     if (H > 0) {
         // back through the classifier and the ReLU, then the layer's own gradients
-        const int64_t tot = H * C;
+        // (the contraction runs over the padded width of dL: its padding columns and the padding rows
+        // of the transposed classifier are zero, and a multiple of four keeps the loads 16 bytes wide)
+        const int64_t tot = H * t.ldc;
         transpose_kernel<<<dim3((unsigned)((tot + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            (int)H, (int)C, d_Wc, WcT);
-        if (int e = launch_transform(N, C, H, L, t.ldc, WcT, nullptr, false, dA, t.ldh, stream, A, t.ldh)) return e;
+            (int)H, (int)C, (int)t.ldc, d_Wc, WcT);
+        if (int e = launch_transform(N, t.ldc, H, L, t.ldc, WcT, nullptr, false, dA, t.ldh, stream, A, t.ldh)) return e;
         // (padding columns of dA only produce partial columns that reduce_partials never reads)
         wgrad(N, D_in, t.ldh, H, d_X, ldx, dA, t.ldh, part, d_gW1, stream);
         colsum(N, H, dA, t.ldh, colpart, d_gb1, stream);
