@@ -263,6 +263,40 @@ def main():
         "input_generation_s": t_gen,
         "roofline": roofline,
     }
+    # the row after the hot path: one local training step (loss + gradients + SGD update) of the first
+    # trained layer with its temporary classifier, on the aggregated features that are already resident
+    hidden = next((i for i, st in enumerate(w.stages) if st.kind == "round" and st.w and st.mode != "gat_softmax"),
+                  None)
+    if hidden is not None:
+        st = w.stages[hidden]
+        n_cls = w.stages[-1].d_out
+        X = pipe.outs[hidden - 1] if hidden > 0 else pipe.H0
+        g = torch.Generator(device="cuda").manual_seed(1234)
+        labels = torch.randint(0, n_cls, (n,), generator=g, device="cuda", dtype=torch.int32)
+        labels[torch.rand(n, generator=g, device="cuda") > 0.66] = -1       # two thirds are training nodes
+        W1, b1 = pipe.params[hidden][0].clone(), pipe.params[hidden][1].clone()
+        Wc = torch.empty((st.d_out, n_cls), dtype=torch.float32, device="cuda").uniform_(-0.1, 0.1, generator=g)
+        bc = torch.zeros(n_cls, dtype=torch.float32, device="cuda")
+        tws = Hn.ws_tensor(B.retexo_train_workspace_bytes(n, st.d_in, st.d_out, n_cls))
+
+        def train_once():
+            loss, *grads = Hn.layer_grad(X, st.d_in, labels, W1, b1, Wc, bc, workspace=tws)
+            for p_, g_ in zip((W1, b1, Wc, bc), grads):
+                B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), 0.01, Hn._stream_ptr()),
+                        "retexo_sgd_update")
+            return loss
+        l0 = float(train_once().cpu()[0])
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            last = train_once()
+        e1.record()
+        torch.cuda.synchronize()
+        tms = e0.elapsed_time(e1) / reps
+        tfl = (4.0 * n * st.d_in * st.d_out + 6.0 * n * st.d_out * n_cls) / tms / 1e9
+        out["train_step"] = {"layer": "%d->%d (ReLU) + classifier %d->%d" % (st.d_in, st.d_out, st.d_out, n_cls),
+                             "ms": tms, "TFLOP/s": tfl, "frac_fp32_mfma": tfl / 157.3,
+                             "loss_first": l0, "loss_last": float(last.cpu()[0]), "sgd_steps": reps + 1}
     pipe.close()
     if not args.no_cpu:
         default_rows = w.n_nodes      # the oracle is fast enough to run every row of every stage in 10-30 s
