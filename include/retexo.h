@@ -212,7 +212,9 @@ int retexo_sgd_update(int64_t n, float* d_param, const float* d_grad, float lr, 
  * name: "agg_slab_cols" (0 = auto), "agg_slab_major" (-1 auto / 0 / 1),
  *       "agg_heavy_degree" (rows at least this long get a whole workgroup),
  *       "agg_parts" (source-id ranges walked one after the other: -1 auto, 1 off, 2/4/8/16),
- *       "agg_max_vec" (cap on floats per lane per gather).
+ *       "agg_max_vec" (cap on floats per lane per gather),
+ *       "agg_gat_fast" (0: plain edge-softmax kernel), "agg_wide_offsets" (1: 64-bit row offsets
+ *       even for tables below 4 GiB; both exist so that tests reach every code path).
  * Returns RETEXO_E_FLAGS for an unknown name.
  */
 int retexo_set_option(const char* name, int64_t value);

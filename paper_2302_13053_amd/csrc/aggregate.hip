@@ -1230,7 +1230,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             a.first = k == 0;
             a.last = k == parts - 1;
             const bool wtd = a.scale == SCALE_GCN;
-            const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32);
+            const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
             if (narrow == 32) dispatch_grouped<8>(a, n_heavy, N, wtd, off32, stream);
             else if (narrow == 64) dispatch_grouped<16>(a, n_heavy, N, wtd, off32, stream);
             else dispatch_grouped<32>(a, n_heavy, N, wtd, off32, stream);
@@ -1253,7 +1253,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, c.F, c.heads, a.Dh, c.Z, c.ldz,
                                                                      c.attn_src, c.attn_dst, el, er);
         const bool hu = (a.Dh % vec) == 0;
-        const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32);
+        const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
         if (vec == 4 && off32 && opt.gat_fast) {
             if (hp == 4) { if (hu) dispatch_gat_fast<4, true>(nc, a, n_heavy, N, stream); else dispatch_gat_fast<4, false>(nc, a, n_heavy, N, stream); }
             else         { if (hu) dispatch_gat_fast<8, true>(nc, a, n_heavy, N, stream); else dispatch_gat_fast<8, false>(nc, a, n_heavy, N, stream); }

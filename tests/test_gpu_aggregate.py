@@ -218,6 +218,31 @@ def test_source_range_walk_with_concat_and_ragged_width(graphs, mode):
         B.retexo_set_option("agg_parts", -1)
 
 
+@pytest.mark.parametrize("mode", MODES)
+def test_code_paths_for_tables_above_4_gib_and_plain_softmax_kernel(graphs, mode):
+    """Tables of 4 GiB and more use 64-bit row offsets, and the pipelined edge-softmax kernel falls
+    back to the plain one; force those paths on a small table and compare with the oracle."""
+    g, rp, ci = graphs[("skewed", mode == "gcn_sym")]
+    n, F, heads = g.n_nodes, 188, 4
+    Zh = wl.random_matrix(n, F, 41, ld=192)
+    a = wl.random_matrix(heads, F // heads, 42) * np.float32(0.2)
+    kw = dict(heads=heads, a_src=Hn.dev(a), a_dst=Hn.dev(a)) if mode == "gat_softmax" else {}
+    want = oracle.aggregate(mode, rp, ci, Zh, F, heads=heads, a_src=a, a_dst=a, self_concat=True)
+    try:
+        for wide, fast, slab, parts in [(1, 1, 0, -1), (1, 1, 32, 4), (1, 1, 64, 1), (0, 0, 0, -1), (1, 0, 256, 1)]:
+            B.retexo_set_option("agg_wide_offsets", wide)
+            B.retexo_set_option("agg_gat_fast", fast)
+            B.retexo_set_option("agg_slab_cols", slab)
+            B.retexo_set_option("agg_parts", parts)
+            got = Hn.aggregate(g, mode, Hn.dev(Zh), F, concat=True, **kw).cpu().numpy()[:, :2 * F]
+            assert_close(got, want, what="%s wide=%d fast=%d slab=%d parts=%d" % (mode, wide, fast, slab, parts))
+    finally:
+        B.retexo_set_option("agg_wide_offsets", 0)
+        B.retexo_set_option("agg_gat_fast", 1)
+        B.retexo_set_option("agg_slab_cols", 0)
+        B.retexo_set_option("agg_parts", -1)
+
+
 def test_empty_graph_and_zero_width(graphs):
     # a graph without any entry: every aggregate is zero, the self half is still copied
     n = 70
