@@ -1204,7 +1204,8 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     int64_t narrow = (!gat && vec == 4) ? opt.slab_cols : -1;
     // default for graphs the plan split by source range (dense, table larger than L2): one
     // 128-byte line per row and slab, ranges sized so that a range's slab stays in L2
-    if (narrow == 0 && p->part_ptr) narrow = 32;
+    // ... and for dense graphs whose table does not fit L2 although one slab of it does
+    if (narrow == 0 && (p->part_ptr || (p->nnz >= 32 * N && N * c.ldz * 4 > (4ll << 20)))) narrow = 32;
     if (narrow == 32 || narrow == 64 || narrow == 128) {
         a.nslab = (int)((c.F + narrow - 1) / narrow);
         a.slab_major = opt.slab_major < 0 ? 1 : (int)opt.slab_major;
@@ -1214,15 +1215,16 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             while (parts < kMaxParts && N * narrow * 4 > (int64_t)parts * (8ll << 20)) parts *= 2;
         }
         if (!p->part_ptr || (parts != 2 && parts != 4 && parts != 8 && parts != 16)) parts = 1;
-        if (parts > 1) {
+        {
             // long-row class by the length of a row's share of one range
+            const int64_t want = opt.narrow_heavy * parts;
             n_heavy = 0;
             for (int i = 0; i < 8; ++i)
-                if (kPlanThresholds[i] >= 1024 * parts || kPlanThresholds[i] >= 16384) {
+                if (kPlanThresholds[i] >= want || kPlanThresholds[i] >= 16384) {
                     n_heavy = p->rows_at_least[i];
                     break;
                 }
-            a.part_ptr = p->part_ptr;
+            if (parts > 1) a.part_ptr = p->part_ptr;
         }
         for (int k = 0; k < parts; ++k) {
             a.part_lo = k * (kMaxParts / parts);
