@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "retexo_oracle.c")
 _LIB = os.path.join(_HERE, "libretexo_oracle.so")
 
-MODES = {"mean": 0, "sum": 1, "gcn_sym": 2, "gat_softmax": 3}
+MODES = {"mean": 0, "sum": 1, "gcn_sym": 2, "gat_softmax": 3, "max": 4}
 
 
 def build(force: bool = False) -> str:

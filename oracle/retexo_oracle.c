@@ -28,6 +28,9 @@
  *      gat       per head h:  e_uv = LeakyReLU(<a_src_h, z_u,h> + <a_dst_h, z_v,h>),
  *                alpha_uv = softmax over u in N(v) of e_uv,
  *                out_v,h = sum_u alpha_uv z_u,h
+ *      max       out_v = element-wise max over u in N(v) of z_u — the "max-pooling
+ *                layer" the gloss under Eq. 1 gives as GraphSAGE's AGGR (the pooling
+ *                network in front of it is the round's dense transform)
  *    An empty neighbourhood gives a zero aggregate in every mode.
  *
  * Everything accumulates in double and consumes the float inputs exactly.
@@ -48,7 +51,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_MEAN = 0, ORACLE_SUM = 1, ORACLE_GCN_SYM = 2, ORACLE_GAT_SOFTMAX = 3 };
+enum { ORACLE_MEAN = 0, ORACLE_SUM = 1, ORACLE_GCN_SYM = 2, ORACLE_GAT_SOFTMAX = 3, ORACLE_MAX = 4 };
 
 int oracle_threads(void)
 {
@@ -192,6 +195,15 @@ void oracle_aggregate(int mode, int64_t n_rows, const int64_t *rows,
                 double s = 0.0;
                 for (int64_t e = lo; e < hi; ++e) s += (double)Z[(int64_t)col_idx[e] * ldz + j];
                 o[j] = (mode == ORACLE_MEAN) ? s / (double)deg : s;
+            }
+        } else if (mode == ORACLE_MAX) {
+            for (int64_t j = 0; j < F; ++j) {
+                double m = (double)Z[(int64_t)col_idx[lo] * ldz + j];
+                for (int64_t e = lo + 1; e < hi; ++e) {
+                    const double z = (double)Z[(int64_t)col_idx[e] * ldz + j];
+                    if (z > m) m = z;
+                }
+                o[j] = m;
             }
         } else if (mode == ORACLE_GCN_SYM) {
             for (int64_t j = 0; j < F; ++j) {

@@ -14,6 +14,7 @@ from paper_2302_13053_amd import workloads as wl
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "four_node_example.txt")
 MODES = ["sum", "mean", "gcn_sym", "gat_softmax"]
+ALL_MODES = MODES + ["max"]
 
 
 def small_graph(n, pairs, seed, self_loops, skew=1.0):
@@ -100,6 +101,32 @@ def test_matches_dense_matrix_algebra(mode, n, pairs, F, heads, seed):
     ref = dense_reference(mode, dense(rp, ci, n), Z[:, :F], heads, a_src, a_dst)
     tol = 3e-7 if mode == "gcn_sym" else 1e-12
     assert np.allclose(got, ref, rtol=tol, atol=tol * np.abs(ref).max())
+
+
+def test_max_pool_aggregator():
+    # hand example on the four-node graph 0-1, 0-2, 1-2, 2-3 (same rows as the golden file)
+    src = np.array([0, 0, 1, 2], np.int32)
+    dst = np.array([1, 2, 2, 3], np.int32)
+    Z = np.array([[1, 2], [3, -1], [0, 4], [-2, 1]], np.float32)
+    rp, ci = oracle.csr_from_coo(src, dst, 4, False)
+    assert np.array_equal(oracle.aggregate("max", rp, ci, Z, 2), [[3, 4], [1, 4], [3, 2], [0, 4]])
+    # dense masked maximum with numpy on random graphs; empty rows give zero
+    n = 60
+    rp, ci = small_graph(n, 150, 31, False, skew=2.0)
+    Zr = wl.random_matrix(n, 5, 32, ld=7)
+    Zr[:, 5:] = 1e30
+    a = dense(rp, ci, n)
+    got = oracle.aggregate("max", rp, ci, Zr, 5, self_concat=True)
+    masked = np.where(a[:, :, None] > 0, Zr[None, :, :5].astype(np.float64), -np.inf).max(1)
+    masked[a.sum(1) == 0] = 0.0
+    assert (a.sum(1) == 0).any()
+    assert np.array_equal(got[:, 5:], masked) and np.array_equal(got[:, :5], Zr[:, :5].astype(np.float64))
+    # max dominates the mean, and relabelling the nodes permutes the result exactly
+    assert np.all(oracle.aggregate("max", rp, ci, Zr, 5) >= oracle.aggregate("mean", rp, ci, Zr, 5) - 1e-12)
+    # all-negative rows must not be clamped at zero
+    neg = -np.abs(Zr) - 1
+    out = oracle.aggregate("max", rp, ci, neg, 5)
+    assert np.all(out[a.sum(1) > 0] < 0)
 
 
 def test_mean_of_constant_is_that_constant_and_empty_rows_are_zero():
@@ -220,7 +247,7 @@ def test_gat_slope_and_direction_of_src_dst():
         assert np.allclose(al, want, rtol=1e-14)
 
 
-@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("mode", ALL_MODES)
 def test_permutation_equivariance(mode):
     n = 70
     src, dst = wl.random_pairs(n, 400, 17, skew=1.0)
@@ -234,7 +261,7 @@ def test_permutation_equivariance(mode):
     Z2[perm] = Z
     out = oracle.aggregate(mode, rp, ci, Z, 6, heads=2, a_src=a, a_dst=a)
     out2 = oracle.aggregate(mode, rp2, ci2, Z2, 6, heads=2, a_src=a, a_dst=a)
-    if mode in ("sum", "mean"):
+    if mode in ("sum", "mean", "max"):
         assert np.array_equal(out2[perm], out)           # small integers: exact in any order
     else:
         assert np.allclose(out2[perm], out, rtol=1e-13, atol=1e-13)
@@ -250,7 +277,7 @@ def test_linearity(mode):
     assert np.allclose(f(A + 2 * B), f(A) + 2 * f(B), rtol=1e-14, atol=1e-14)
 
 
-@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("mode", ALL_MODES)
 def test_self_concat_layout_and_row_subsets(mode):
     n = 45
     rp, ci = small_graph(n, 200, 23, mode == "gcn_sym")
