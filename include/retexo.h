@@ -46,8 +46,11 @@ typedef enum {
     RETEXO_SUM = 1,         /* sum_u z_u                                             */
     RETEXO_GCN_SYM = 2,     /* sum_u z_u / sqrt(deg v deg u)  — GCN; pass a CSR that
                                already holds one self-loop per node                  */
-    RETEXO_GAT_SOFTMAX = 3  /* sum_u softmax_u(LeakyReLU(<a_src,z_u>+<a_dst,z_v>)) z_u,
+    RETEXO_GAT_SOFTMAX = 3, /* sum_u softmax_u(LeakyReLU(<a_src,z_u>+<a_dst,z_v>)) z_u,
                                independently for each of `heads` column blocks — GAT */
+    RETEXO_MAX = 4          /* element-wise max_u z_u — the max-pooling AGGR the gloss under
+                               Eq. 1 names for GraphSAGE (its pooling network is the round's
+                               transform); exact in any order, so results are bit-exact     */
 } retexo_mode;
 
 enum {

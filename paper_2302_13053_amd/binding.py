@@ -14,8 +14,8 @@ from typing import Optional
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libretexo.so")
 
-MEAN, SUM, GCN_SYM, GAT_SOFTMAX = 0, 1, 2, 3
-MODES = {"mean": MEAN, "sum": SUM, "gcn_sym": GCN_SYM, "gat_softmax": GAT_SOFTMAX}
+MEAN, SUM, GCN_SYM, GAT_SOFTMAX, MAX = 0, 1, 2, 3, 4
+MODES = {"mean": MEAN, "sum": SUM, "gcn_sym": GCN_SYM, "gat_softmax": GAT_SOFTMAX, "max": MAX}
 F_RELU, F_SELF_CONCAT, F_VALIDATE, F_SPLIT_ROWS = 1, 2, 4, 8
 
 OK = 0

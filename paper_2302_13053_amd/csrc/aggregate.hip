@@ -141,11 +141,11 @@ __device__ __forceinline__ float select_head(const float (&s)[HP], int h)
 }
 
 // ---------------------------------------------------------------------------
-// sum / mean / gcn_sym
+// sum / mean / gcn_sym, and (MAXOP) the element-wise maximum
 //   NW == 1: kLightWaves independent (row, slab) items per workgroup
 //   NW  > 1: the NW waves of a workgroup share one (row, slab) item
 // ---------------------------------------------------------------------------
-template <int VEC, int NC, int NW>
+template <int VEC, int NC, int NW, bool MAXOP>
 __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_kernel(AggArgs a)
 {
     const int lane = threadIdx.x & 63;
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
     for (int c = 0; c < NC; ++c) {
         act[c] = col0 + c * 64 * VEC < a.F;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) acc[c][k] = 0.0f;
+        for (int k = 0; k < VEC; ++k) acc[c][k] = MAXOP ? -INFINITY : 0.0f;
     }
     const float* zl = a.Z + col0;
     const bool weighted = a.scale == SCALE_GCN;
@@ -197,7 +197,8 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
                 for (int c = 0; c < NC; ++c)
                     if (act[c]) {
 #pragma unroll
-                        for (int k = 0; k < VEC; ++k) acc[c][k] = fmaf(w[t], z[t][c][k], acc[c][k]);
+                        for (int k = 0; k < VEC; ++k)
+                            acc[c][k] = MAXOP ? fmaxf(acc[c][k], z[t][c][k]) : fmaf(w[t], z[t][c][k], acc[c][k]);
                     }
         }
         for (; j < cnt; ++j) {
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
                     float z[VEC];
                     load_row<VEC>(zr + c * 64 * VEC, z);
 #pragma unroll
-                    for (int k = 0; k < VEC; ++k) acc[c][k] = fmaf(w, z[k], acc[c][k]);
+                    for (int k = 0; k < VEC; ++k) acc[c][k] = MAXOP ? fmaxf(acc[c][k], z[k]) : fmaf(w, z[k], acc[c][k]);
                 }
         }
     }
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
             for (int k = 0; k < VEC; ++k) {
                 float s = red[0][c * VEC + k][lane];
 #pragma unroll
-                for (int w = 1; w < NW; ++w) s += red[w][c * VEC + k][lane];
+                for (int w = 1; w < NW; ++w) s = MAXOP ? fmaxf(s, red[w][c * VEC + k][lane]) : s + red[w][c * VEC + k][lane];
                 acc[c][k] = s;
             }
     }
@@ -245,7 +246,8 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             float x = acc[c][k];
-            if (a.scale == SCALE_MEAN) x = d > 0 ? x / (float)d : 0.0f;
+            if (MAXOP) x = d > 0 ? x : 0.0f;                     // empty neighbourhood: zero
+            else if (a.scale == SCALE_MEAN) x = d > 0 ? x / (float)d : 0.0f;
             else if (a.scale == SCALE_GCN) x = x * a.dinv[v];
             r[k] = x;
         }
@@ -1009,7 +1011,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-template <int VEC, int NC>
+template <int VEC, int NC, bool MAXOP>
 void launch_linear_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
 {
     if (n_heavy > 0) {
@@ -1017,14 +1019,14 @@ void launch_linear_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStre
         a.row_begin = 0;
         a.row_count = n_heavy;
         const int64_t blocks = n_heavy * a.nslab;
-        agg_linear_kernel<VEC, NC, kHeavyWaves><<<dim3((unsigned)blocks), dim3(64 * kHeavyWaves), 0, stream>>>(a);
+        agg_linear_kernel<VEC, NC, kHeavyWaves, MAXOP><<<dim3((unsigned)blocks), dim3(64 * kHeavyWaves), 0, stream>>>(a);
     }
     if (N > n_heavy) {
         AggArgs a = base;
         a.row_begin = n_heavy;
         a.row_count = N - n_heavy;
         const int64_t blocks = (a.row_count * a.nslab + kLightWaves - 1) / kLightWaves;
-        agg_linear_kernel<VEC, NC, 1><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+        agg_linear_kernel<VEC, NC, 1, MAXOP><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
     }
 }
 
@@ -1107,12 +1109,19 @@ void dispatch_gat_fast(int nc, const AggArgs& a, int64_t nh, int64_t N, hipStrea
     else launch_gat_fast_pair<2, HP, HU>(a, nh, N, s);
 }
 
-template <int VEC>
-void dispatch_linear(int nc, const AggArgs& a, int64_t nh, int64_t N, hipStream_t s)
+template <int VEC, bool MAXOP>
+void dispatch_linear_nc(int nc, const AggArgs& a, int64_t nh, int64_t N, hipStream_t s)
 {
-    if (nc == 1) launch_linear_pair<VEC, 1>(a, nh, N, s);
-    else if (nc == 2) launch_linear_pair<VEC, 2>(a, nh, N, s);
-    else launch_linear_pair<VEC, 3>(a, nh, N, s);
+    if (nc == 1) launch_linear_pair<VEC, 1, MAXOP>(a, nh, N, s);
+    else if (nc == 2) launch_linear_pair<VEC, 2, MAXOP>(a, nh, N, s);
+    else launch_linear_pair<VEC, 3, MAXOP>(a, nh, N, s);
+}
+
+template <int VEC>
+void dispatch_linear(int nc, bool maxop, const AggArgs& a, int64_t nh, int64_t N, hipStream_t s)
+{
+    if (maxop) dispatch_linear_nc<VEC, true>(nc, a, nh, N, s);
+    else dispatch_linear_nc<VEC, false>(nc, a, nh, N, s);
 }
 
 template <int VEC, int HP, bool HU>
@@ -1201,7 +1210,8 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         if (kPlanThresholds[i] >= opt.heavy_degree) { n_heavy = p->rows_at_least[i]; break; }
 
     // narrow slabs (32/64/128 columns) use the grouped gather; they need float4 gathers
-    int64_t narrow = (!gat && vec == 4) ? opt.slab_cols : -1;
+    // (the maximum is only implemented on whole rows)
+    int64_t narrow = (!gat && vec == 4 && c.mode != RETEXO_MAX) ? opt.slab_cols : -1;
     // default for graphs the plan split by source range (dense, table larger than L2): one
     // 128-byte line per row and slab, ranges sized so that a range's slab stays in L2
     // ... and for dense graphs whose table does not fit L2 although one slab of it does
@@ -1238,9 +1248,10 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             else dispatch_grouped<32>(a, n_heavy, N, wtd, off32, stream);
         }
     } else if (!gat) {
-        if (vec == 4) dispatch_linear<4>(nc, a, n_heavy, N, stream);
-        else if (vec == 2) dispatch_linear<2>(nc, a, n_heavy, N, stream);
-        else dispatch_linear<1>(nc, a, n_heavy, N, stream);
+        const bool maxop = c.mode == RETEXO_MAX;
+        if (vec == 4) dispatch_linear<4>(nc, maxop, a, n_heavy, N, stream);
+        else if (vec == 2) dispatch_linear<2>(nc, maxop, a, n_heavy, N, stream);
+        else dispatch_linear<1>(nc, maxop, a, n_heavy, N, stream);
     } else {
         const int hp = heads_padded(c.heads);
         float* el = (float*)c.workspace;

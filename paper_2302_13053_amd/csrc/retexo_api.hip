@@ -23,7 +23,7 @@ int64_t extent_bytes(int64_t rows, int64_t ld, int64_t width)
 
 int check_mode(int mode, int64_t F, int heads)
 {
-    if (mode < RETEXO_MEAN || mode > RETEXO_GAT_SOFTMAX) return RETEXO_E_MODE;
+    if (mode < RETEXO_MEAN || mode > RETEXO_MAX) return RETEXO_E_MODE;
     if (heads < 1 || heads > kMaxHeads) return RETEXO_E_HEADS;
     if (mode == RETEXO_GAT_SOFTMAX && F % heads != 0) return RETEXO_E_HEADS;
     return RETEXO_OK;

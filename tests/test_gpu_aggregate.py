@@ -97,6 +97,34 @@ def test_modes_match_oracle_other_graphs(graphs, mode, name):
     assert_close(got, want, what="%s %s" % (mode, name))
 
 
+@pytest.mark.parametrize("F,ld,concat,offset", [
+    (256, 256, False, 0), (602, 608, True, 0), (602, 602, True, 0), (1433, 1433, True, 0),
+    (1432, 1440, False, 0), (100, 100, True, 0), (7, 7, True, 0), (1, 1, False, 0), (128, 128, False, 1),
+])
+def test_max_pooling_is_bit_exact(graphs, F, ld, concat, offset):
+    # a maximum does not depend on the order it is taken in, so every element must match exactly:
+    # heavy rows (combined across waves), empty rows (zero, not -inf), all-negative rows (not clamped)
+    got, want = run_case(graphs, "skewed", "max", F, ld, 1, concat, seed=F + 5, base_offset=offset)
+    assert np.array_equal(got.astype(np.float64), want), "max F=%d" % F
+    deg = np.diff(graphs[("skewed", False)][1])
+    agg = got[:, F:] if concat else got
+    assert np.all(agg[deg == 0] == 0.0) and (agg[deg == 1] < 0).any()
+    for name in ("flat", "tiny"):
+        got, want = run_case(graphs, name, "max", 96, 96, 1, True, seed=4)
+        assert np.array_equal(got.astype(np.float64), want)
+    defaults = {"agg_slab_cols": 0, "agg_max_vec": 4, "agg_heavy_degree": 2048, "agg_slab_major": -1}
+    got, _ = run_case(graphs, "skewed", "max", F, ld, 1, concat, seed=F + 5, base_offset=offset)
+    try:   # other slab widths, gather widths and heavy-row thresholds give the same bits
+        for k, v in (("agg_slab_cols", 32), ("agg_max_vec", 1), ("agg_heavy_degree", 64), ("agg_slab_major", 1)):
+            B.retexo_set_option(k, v)
+            got2, _ = run_case(graphs, "skewed", "max", F, ld, 1, concat, seed=F + 5, base_offset=offset)
+            assert np.array_equal(got2, got), k
+            B.retexo_set_option(k, defaults[k])
+    finally:
+        for k, v in defaults.items():
+            B.retexo_set_option(k, v)
+
+
 def test_integer_features_are_bit_exact_and_ones_give_degree(graphs):
     g, rp, ci = graphs[("skewed", False)]
     deg = np.diff(rp)
