@@ -53,6 +53,10 @@ def _load():
         lib.oracle_gat_alpha.restype = None
         lib.oracle_gat_alpha.argtypes = [i64, C.c_int, i64p, i32p, i64, C.c_int, f32p, i64,
                                          f32p, f32p, C.c_double, f64p]
+        lib.oracle_aggregate_backward.restype = C.c_int
+        lib.oracle_aggregate_backward.argtypes = [C.c_int, i64, i64, i64p, i64p, i32p, f32p, i64, C.c_int,
+                                                  f32p, i64, f32p, f32p, C.c_double, f32p, i64, C.c_int,
+                                                  f64p, f64p, f64p]
         lib.oracle_layer_grad.restype = C.c_double
         lib.oracle_layer_grad.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f32p, f32p, f32p, f32p,
                                           f64p, f64p, f64p, f64p]
@@ -144,6 +148,43 @@ def aggregate(mode: str, row_ptr, col_idx, Z, F: int, *, heads: int = 1, a_src=N
                              _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
                              float(slope), int(self_concat), _p(out, C.c_double))
     return out
+
+
+def aggregate_backward(mode: str, row_ptr, col_idx, Z, F: int, G, *, heads: int = 1, a_src=None, a_dst=None,
+                       slope: float = 0.2, self_concat: bool = False, rows=None):
+    """Gradient of ``aggregate`` with respect to its inputs, given G = dL/d(out) ([N, F or 2F] float32).
+    -> dZ float64 [n, F] for linear modes; (dZ, da_src, da_dst) for gat (da_* None when ``rows`` is given)."""
+    Z, ldz = _matrix(Z)
+    G, ldg = _matrix(G)
+    row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
+    n_nodes = row_ptr.size - 1
+    assert Z.shape[0] >= n_nodes and G.shape[0] >= n_nodes and F <= Z.shape[1]
+    assert G.shape[1] >= (2 * F if self_concat else F)
+    dinv = None
+    if mode == "gcn_sym":
+        _, dinv = degree(row_ptr)
+    gat = mode == "gat_softmax"
+    da_s = da_d = None
+    if gat:
+        assert F % heads == 0
+        a_src, a_dst = _c(a_src, np.float32), _c(a_dst, np.float32)
+        assert a_src.size == F and a_dst.size == F
+        if rows is None:
+            da_s, da_d = np.empty(F, np.float64), np.empty(F, np.float64)
+    rows = None if rows is None else _c(rows, np.int64)
+    n = n_nodes if rows is None else rows.size
+    dZ = np.empty((n, F), np.float64)
+    rc = _load().oracle_aggregate_backward(MODES[mode], n_nodes, n, _p(rows, C.c_int64), _p(row_ptr, C.c_int64),
+                                           _p(col_idx, C.c_int32), _p(dinv, C.c_float), F, heads,
+                                           _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
+                                           float(slope), _p(G, C.c_float), ldg, int(self_concat),
+                                           _p(dZ, C.c_double), _p(da_s, C.c_double), _p(da_d, C.c_double))
+    if rc != 0:
+        raise ValueError("mode %r has no backward" % mode)
+    if gat:
+        return dZ, (None if da_s is None else da_s.reshape(heads, F // heads)), \
+            (None if da_d is None else da_d.reshape(heads, F // heads))
+    return dZ
 
 
 def gat_alpha(v: int, h: int, row_ptr, col_idx, Z, F: int, heads: int, a_src, a_dst,

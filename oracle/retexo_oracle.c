@@ -38,6 +38,10 @@
  * correctly rounded single-precision sqrt followed by the correctly rounded
  * single-precision divide, so that it can be compared bit for bit.
  *
+ * oracle_aggregate_backward differentiates these aggregations (chain rule
+ * written out above the function); it is needed when a layer whose AGGR has
+ * trainable parameters is trained with the aggregation in the loop.
+ *
  * No worked numeric example exists in the paper.  The pins that tie these
  * functions to something other than themselves (dense-matrix brute force,
  * closed forms on regular graphs, hand-computed values, invariants) live in
@@ -267,6 +271,163 @@ void oracle_gat_alpha(int64_t v, int h, const int64_t *row_ptr, const int32_t *c
     }
     for (int64_t e = lo; e < hi; ++e) { alpha[e - lo] = exp(alpha[e - lo] - m); denom += alpha[e - lo]; }
     for (int64_t e = lo; e < hi; ++e) alpha[e - lo] /= denom;
+}
+
+/* ---------------------------------------------------------------------------
+ * Backward of the aggregation (needed to train a layer whose AGGR has
+ * trainable parameters — the gloss under Eq. 1 allows that, and GAT's
+ * attention vectors are such parameters — with the aggregation inside the
+ * local training loop).  Given G = dL/d(out) this returns dL/dZ and, for gat,
+ * dL/da_src and dL/da_dst, by the chain rule through the definitions above.
+ *
+ * Every CSR entry (v,u) of the forward pass carries a coefficient c_vu with
+ * out_v = sum_u c_vu z_u:   mean 1/deg v,  sum 1,  gcn_sym dinv_v dinv_u,
+ * gat alpha_vu (per head).  The direct term is dL/dz_u += c_vu G_v.
+ * For gat the coefficients themselves depend on Z, a_src, a_dst:
+ *      dL/dalpha_vu = <G_v, z_u>                               (out_v is linear in alpha)
+ *      dL/de_vu     = alpha_vu ( dL/dalpha_vu - sum_w alpha_vw dL/dalpha_vw )   (softmax)
+ *      dL/dp_vu     = dL/de_vu * (p_vu > 0 ? 1 : slope),  p_vu = <a_src,z_u> + <a_dst,z_v>
+ *      dL/dz_u += dL/dp_vu a_src,   dL/dz_v += dL/dp_vu a_dst,
+ *      dL/da_src += dL/dp_vu z_u,   dL/da_dst += dL/dp_vu z_v        (all per head)
+ * With self_concat the forward output was [z_v | aggregate], G is 2F wide and
+ * its first F columns flow straight into dL/dz_v.
+ *
+ * Nothing here assumes that the graph is symmetric: the entries that point at
+ * a node u are found through an explicit transpose of the CSR.
+ *
+ * rows == NULL: dZ is [N, F] and da_src / da_dst ([F] each, gat only) are
+ * filled.  rows given: only those rows of dZ ([n_rows, F]); da_* untouched.
+ * max has no backward here (returns -1).  Returns 0 on success.
+ */
+int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t *rows,
+                              const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
+                              int64_t F, int heads, const float *Z, int64_t ldz,
+                              const float *a_src, const float *a_dst, double slope,
+                              const float *G, int64_t ldg, int self_concat,
+                              double *dZ, double *da_src, double *da_dst)
+{
+    if (mode == ORACLE_MAX) return -1;
+    const int gat = mode == ORACLE_GAT_SOFTMAX;
+    if (!gat) heads = 1;
+    const int64_t Dh = F / heads, nnz = row_ptr[N];
+    const float *Ga = G + (self_concat ? F : 0);      /* gradient of the aggregate half */
+
+    /* transpose: for every node u the entries e (and their rows v) with col_idx[e] == u */
+    int64_t *t_ptr = (int64_t *)calloc((size_t)N + 2, sizeof(int64_t));
+    int64_t *t_ent = (int64_t *)malloc((size_t)(nnz ? nnz : 1) * sizeof(int64_t));
+    int32_t *t_row = (int32_t *)malloc((size_t)(nnz ? nnz : 1) * sizeof(int32_t));
+    for (int64_t e = 0; e < nnz; ++e) t_ptr[col_idx[e] + 2]++;
+    for (int64_t u = 0; u < N; ++u) t_ptr[u + 2] += t_ptr[u + 1];
+    for (int64_t v = 0; v < N; ++v)
+        for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+            const int64_t k = t_ptr[col_idx[e] + 1]++;
+            t_ent[k] = e;
+            t_row[k] = (int32_t)v;
+        }
+    /* now t_ptr[u] .. t_ptr[u+1] delimit node u's incoming entries */
+
+    /* which rows' entry coefficients are needed, and where they are kept */
+    unsigned char *need = (unsigned char *)calloc((size_t)N + 1, 1);
+    int64_t *off = (int64_t *)malloc(((size_t)N + 1) * sizeof(int64_t));
+    if (rows) {
+        for (int64_t i = 0; i < n_rows; ++i) {
+            const int64_t u = rows[i];
+            need[u] = 1;
+            for (int64_t k = t_ptr[u]; k < t_ptr[u + 1]; ++k) need[t_row[k]] = 1;
+        }
+    } else {
+        memset(need, 1, (size_t)N);
+    }
+    int64_t kept = 0;
+    for (int64_t v = 0; v < N; ++v) {
+        off[v] = kept;
+        if (need[v]) kept += row_ptr[v + 1] - row_ptr[v];
+    }
+    double *coef = (double *)malloc((size_t)(kept ? kept : 1) * heads * sizeof(double));  /* c_vu  */
+    double *dp = (double *)calloc((size_t)(kept ? kept : 1) * heads, sizeof(double));     /* dL/dp */
+
+    /* step 1: coefficient and score gradient of every needed entry */
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t v = 0; v < N; ++v) {
+        if (!need[v]) continue;
+        const int64_t lo = row_ptr[v], hi = row_ptr[v + 1], deg = hi - lo;
+        double *cv = coef + off[v] * heads, *dv = dp + off[v] * heads;
+        if (!gat) {
+            for (int64_t e = lo; e < hi; ++e)
+                cv[e - lo] = mode == ORACLE_MEAN ? 1.0 / (double)deg
+                           : mode == ORACLE_SUM  ? 1.0
+                           : (double)dinv[v] * (double)dinv[col_idx[e]];
+            continue;
+        }
+        if (deg == 0) continue;
+        double *p = (double *)malloc((size_t)deg * sizeof(double));
+        double *da = (double *)malloc((size_t)deg * sizeof(double));
+        for (int h = 0; h < heads; ++h) {
+            const float *as = a_src + (int64_t)h * Dh, *ad = a_dst + (int64_t)h * Dh;
+            const float *zv = Z + v * ldz + h * Dh, *gv = Ga + v * ldg + h * Dh;
+            double er = 0.0, m = -INFINITY, denom = 0.0, mean_da = 0.0;
+            for (int64_t d = 0; d < Dh; ++d) er += (double)ad[d] * (double)zv[d];
+            for (int64_t e = lo; e < hi; ++e) {
+                const float *zu = Z + (int64_t)col_idx[e] * ldz + h * Dh;
+                double el = 0.0, g = 0.0;
+                for (int64_t d = 0; d < Dh; ++d) {
+                    el += (double)as[d] * (double)zu[d];
+                    g += (double)gv[d] * (double)zu[d];
+                }
+                p[e - lo] = el + er;
+                da[e - lo] = g;
+                if (leaky(p[e - lo], slope) > m) m = leaky(p[e - lo], slope);
+            }
+            for (int64_t j = 0; j < deg; ++j) denom += exp(leaky(p[j], slope) - m);
+            for (int64_t j = 0; j < deg; ++j) {
+                cv[j * heads + h] = exp(leaky(p[j], slope) - m) / denom;
+                mean_da += cv[j * heads + h] * da[j];
+            }
+            for (int64_t j = 0; j < deg; ++j)
+                dv[j * heads + h] = cv[j * heads + h] * (da[j] - mean_da) * (p[j] > 0.0 ? 1.0 : slope);
+        }
+        free(p);
+        free(da);
+    }
+
+    /* step 2: collect what flows into each requested node */
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t u = rows ? rows[i] : i;
+        double *o = dZ + i * F;
+        for (int64_t j = 0; j < F; ++j) o[j] = self_concat ? (double)G[u * ldg + j] : 0.0;
+        for (int64_t k = t_ptr[u]; k < t_ptr[u + 1]; ++k) {       /* entries (v,u) */
+            const int64_t e = t_ent[k], v = t_row[k];
+            const int64_t q = (off[v] + (e - row_ptr[v])) * heads;
+            for (int h = 0; h < heads; ++h)
+                for (int64_t d = 0; d < Dh; ++d) {
+                    o[h * Dh + d] += coef[q + h] * (double)Ga[v * ldg + h * Dh + d];
+                    if (gat) o[h * Dh + d] += dp[q + h] * (double)a_src[h * Dh + d];
+                }
+        }
+        if (gat)
+            for (int64_t e = row_ptr[u]; e < row_ptr[u + 1]; ++e) {   /* u's own entries (u,w) */
+                const int64_t q = (off[u] + (e - row_ptr[u])) * heads;
+                for (int h = 0; h < heads; ++h)
+                    for (int64_t d = 0; d < Dh; ++d) o[h * Dh + d] += dp[q + h] * (double)a_dst[h * Dh + d];
+            }
+    }
+
+    /* step 3: gradients of the attention vectors (sums over every entry of the graph) */
+    if (gat && !rows && da_src && da_dst) {
+        for (int64_t j = 0; j < F; ++j) { da_src[j] = 0.0; da_dst[j] = 0.0; }
+        for (int64_t v = 0; v < N; ++v)
+            for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                const int64_t q = (off[v] + (e - row_ptr[v])) * heads, u = col_idx[e];
+                for (int h = 0; h < heads; ++h)
+                    for (int64_t d = 0; d < Dh; ++d) {
+                        da_src[h * Dh + d] += dp[q + h] * (double)Z[u * ldz + h * Dh + d];
+                        da_dst[h * Dh + d] += dp[q + h] * (double)Z[v * ldz + h * Dh + d];
+                    }
+            }
+    }
+    free(coef); free(dp); free(need); free(off); free(t_ptr); free(t_ent); free(t_row);
+    return 0;
 }
 
 /* ---------------------------------------------------------------------------
