@@ -166,6 +166,40 @@ int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, int heads,
                      void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Backward of retexo_aggregate: the gradient of a scalar loss with respect to
+ * the aggregation's inputs, given d_G = dL/d(out).  This is what training a
+ * layer needs when its AGGR has trainable parameters (the gloss under Eq. 1
+ * allows that; GAT's attention vectors are such parameters) and the
+ * aggregation therefore sits inside the local training loop of the section
+ * "Lazy Message Passing" — no message passing is involved, the inputs Z of
+ * the node's neighbours were received once and stay fixed.
+ *   d_G   [N, ldg]: F columns, or 2F under RETEXO_F_SELF_CONCAT (gradient of
+ *         the self half first, then of the aggregate half)
+ *   d_dZ  [N, lddz]: first F columns written: dL/dZ
+ *   RETEXO_GAT_SOFTMAX additionally reads d_Z (the forward input), d_attn_src,
+ *   d_attn_dst, negative_slope and writes d_dattn_src, d_dattn_dst ([heads, Dh],
+ *   summed over the whole graph in a fixed order); F = heads * Dh <= 1024.
+ *   The other modes ignore those arguments (heads >= 1).  RETEXO_MAX has no
+ *   backward here (RETEXO_E_MODE).
+ * PRECONDITION: the plan's CSR is structurally symmetric (u in N(v) <=> v in
+ * N(u)), as retexo_csr_from_coo always builds it for the paper's undirected
+ * graphs; the transposed product walks a node's own row to find the entries
+ * that point at it.  A plan made from foreign, asymmetric arrays gives wrong
+ * gradients (not an error).
+ * d_dZ must not overlap d_G or d_Z.  d_workspace:
+ * retexo_aggregate_backward_workspace_bytes(plan, mode, F, heads) bytes,
+ * 256-aligned (may be NULL when that is 0).  Enqueues on `stream`; no
+ * allocation, no synchronisation, no atomics (bitwise reproducible).
+ */
+int64_t retexo_aggregate_backward_workspace_bytes(const retexo_plan* plan, int mode, int64_t F, int heads);
+int retexo_aggregate_backward(const retexo_plan* plan, int mode, int64_t F, int heads,
+                              const float* d_Z, int64_t ldz,
+                              const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                              unsigned flags, const float* d_G, int64_t ldg,
+                              float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
+                              void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
  * One whole round: retexo_transform followed by retexo_aggregate on the same
  * stream, Z being kept in the workspace (or directly in out's first D_out
  * columns under RETEXO_F_SELF_CONCAT).  d_W == NULL means the identity

@@ -28,6 +28,7 @@ EXPORTS = (
     "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
     "retexo_workspace_bytes",
     "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
+    "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
 )
 
@@ -81,6 +82,11 @@ def load():
     lib.retexo_transform.argtypes = [i64, i64, i64, vp, i64, vp, vp, u32, vp, i64, vp]
     lib.retexo_aggregate.restype = i32
     lib.retexo_aggregate.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64, vp, i64, vp]
+    lib.retexo_aggregate_backward_workspace_bytes.restype = i64
+    lib.retexo_aggregate_backward_workspace_bytes.argtypes = [vp, i32, i64, i32]
+    lib.retexo_aggregate_backward.restype = i32
+    lib.retexo_aggregate_backward.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64,
+                                              vp, i64, vp, vp, vp, i64, vp]
     lib.retexo_round.restype = i32
     lib.retexo_round.argtypes = [vp, i32, i64, i64, i32, vp, i64, vp, vp, vp, vp, f32, u32, vp, i64,
                                  vp, i64, vp]
@@ -171,6 +177,19 @@ def retexo_aggregate(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, neg
     return int(load().retexo_aggregate(_vp(plan), mode, F, heads, _vp(d_Z), ldz, _vp(d_attn_src),
                                        _vp(d_attn_dst), negative_slope, flags, _vp(d_out), ldo,
                                        _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+def retexo_aggregate_backward_workspace_bytes(plan, mode, F, heads) -> int:
+    return int(load().retexo_aggregate_backward_workspace_bytes(_vp(plan), mode, F, heads))
+
+
+def retexo_aggregate_backward(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, negative_slope, flags,
+                              d_G, ldg, d_dZ, lddz, d_dattn_src, d_dattn_dst, d_workspace, workspace_bytes,
+                              stream=0) -> int:
+    return int(load().retexo_aggregate_backward(_vp(plan), mode, F, heads, _vp(d_Z), ldz, _vp(d_attn_src),
+                                                _vp(d_attn_dst), negative_slope, flags, _vp(d_G), ldg,
+                                                _vp(d_dZ), lddz, _vp(d_dattn_src), _vp(d_dattn_dst),
+                                                _vp(d_workspace), workspace_bytes, _vp(stream)))
 
 
 def retexo_round(plan, mode, d_in, d_out, heads, d_H, ldh, d_W, d_b, d_attn_src, d_attn_dst,

@@ -25,15 +25,10 @@
 //    softmax at tile granularity) — one exp per edge and head instead of one
 //    per edge and lane.
 #include "common.hpp"
+#include "gather.hpp"
 
 namespace {
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kLightWaves = 4;   // independent rows per workgroup in the light kernel
-constexpr int kHeavyWaves = 8;   // cooperating waves per row in the heavy kernel
-constexpr int kUnroll = 4;       // neighbours fetched per unrolled step
 
 enum { SCALE_SUM = 0, SCALE_MEAN = 1, SCALE_GCN = 2 };
 
@@ -43,6 +38,7 @@ struct AggArgs {
     const int32_t* order;
     const int32_t* deg;
     const float* dinv;
+    const float* wsrc;     // per-source weight of every gathered row, or NULL (all 1)
     const float* Z;
     int64_t ldz;
     float* out;
@@ -70,75 +66,6 @@ struct AggArgs {
     int first;             // first range of the walk: start from zero, write the self copy
     int last;              // last range: apply the mean / gcn scaling
 };
-
-template <int VEC>
-__device__ __forceinline__ void load_row(const float* p, float (&v)[VEC])
-{
-    if constexpr (VEC == 4) {
-        const f32x4 t = *reinterpret_cast<const f32x4*>(p);
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    } else if constexpr (VEC == 2) {
-        const f32x2 t = *reinterpret_cast<const f32x2*>(p);
-        v[0] = t.x; v[1] = t.y;
-    } else {
-        v[0] = *p;
-    }
-}
-
-template <int VEC>
-__device__ __forceinline__ void store_row(float* p, const float (&v)[VEC], int valid, bool vec_ok)
-{
-    if (vec_ok && valid >= VEC) {
-        if constexpr (VEC == 4) {
-            f32x4 t = {v[0], v[1], v[2], v[3]};
-            *reinterpret_cast<f32x4*>(p) = t;
-        } else if constexpr (VEC == 2) {
-            f32x2 t = {v[0], v[1]};
-            *reinterpret_cast<f32x2*>(p) = t;
-        } else {
-            *p = v[0];
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < VEC; ++k)
-            if (k < valid) p[k] = v[k];
-    }
-}
-
-// data that is read once per pass (indices, row bookkeeping, running sums) is fetched with a
-// non-temporal hint so that it does not push the reused feature rows out of L2
-template <typename T>
-__device__ __forceinline__ T ldg_stream(const T* p) { return __builtin_nontemporal_load(p); }
-
-__device__ __forceinline__ float wave_max(float x)
-{
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
-    return x;
-}
-
-__device__ __forceinline__ float wave_sum(float x)
-{
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
-    return x;
-}
-
-__device__ __forceinline__ int bcast_i(int x, int lane) { return __builtin_amdgcn_readlane(x, lane); }
-__device__ __forceinline__ float bcast_f(float x, int lane)
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
-}
-
-// pick s[h] for a per-lane head index from per-head wave-uniform values
-template <int HP>
-__device__ __forceinline__ float select_head(const float (&s)[HP], int h)
-{
-    float r = s[0];
-#pragma unroll
-    for (int i = 1; i < HP; ++i) r = (h == i) ? s[i] : r;
-    return r;
-}
 
 // ---------------------------------------------------------------------------
 // sum / mean / gcn_sym, and (MAXOP) the element-wise maximum
@@ -171,12 +98,12 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
         for (int k = 0; k < VEC; ++k) acc[c][k] = MAXOP ? -INFINITY : 0.0f;
     }
     const float* zl = a.Z + col0;
-    const bool weighted = a.scale == SCALE_GCN;
+    const bool weighted = a.wsrc != nullptr;
 
     for (int base = lo + 64 * (NW == 1 ? 0 : wave); base < hi; base += 64 * NW) {
         const int e = base + lane;
         const int my_u = e < hi ? a.col_idx[e] : 0;
-        const float my_w = weighted ? (e < hi ? a.dinv[my_u] : 0.0f) : 1.0f;
+        const float my_w = weighted ? (e < hi ? a.wsrc[my_u] : 0.0f) : 1.0f;
         const int cnt = min(64, hi - base);
         int j = 0;
         for (; j + kUnroll <= cnt; j += kUnroll) {
@@ -380,7 +307,7 @@ __global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
     for (int base = lo + 64 * wave; base < hi; base += 64 * NW) {
         const int e = base + lane;
         const int my_u = e < hi ? a.col_idx[e] : 0;
-        const float my_w = WEIGHTED ? (e < hi ? a.dinv[my_u] : 0.0f) : 1.0f;
+        const float my_w = WEIGHTED ? (e < hi ? a.wsrc[my_u] : 0.0f) : 1.0f;
         const int cnt = min(64, hi - base);
         const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
         if (cnt == 64)
@@ -503,7 +430,7 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
     float nxt_w = 0.0f;
     if (li < len) {
         nxt_u = a.col_idx[lo + li];
-        if (WEIGHTED) nxt_w = a.dinv[nxt_u];
+        if (WEIGHTED) nxt_w = a.wsrc[nxt_u];
     }
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int c0 = 0; c0 < maxlen; c0 += LPG) {
@@ -516,7 +443,7 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
             nxt_w = 0.0f;
             if (nb < len) {
                 nxt_u = a.col_idx[lo + nb];
-                if (WEIGHTED) nxt_w = a.dinv[nxt_u];
+                if (WEIGHTED) nxt_w = a.wsrc[nxt_u];
             }
         }
         const bool full = c0 + LPG <= minlen;      // every group still has LPG entries: no masking
@@ -1150,6 +1077,17 @@ int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads)
     return 2 * align_up((N > 0 ? N : 1) * heads_padded(heads) * (int64_t)sizeof(float), 256);
 }
 
+void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
+                       const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream)
+{
+    const unsigned gb = (unsigned)((N + 3) / 4);
+    const int Dh = (int)(F / heads);
+    if (heads_padded(heads) == 4)
+        gat_scores_kernel<4><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, er);
+    else
+        gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, er);
+}
+
 int launch_aggregate(const AggCall& c, hipStream_t stream)
 {
     const retexo_plan* p = c.plan;
@@ -1178,6 +1116,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.order = p->order;
     a.deg = p->deg;
     a.dinv = p->dinv;
+    a.wsrc = c.mode == RETEXO_GCN_SYM ? p->dinv : c.src_weight;
     a.Z = c.Z;
     a.ldz = c.ldz;
     a.out = c.out;
@@ -1241,7 +1180,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             a.part_hi = (k + 1) * (kMaxParts / parts);
             a.first = k == 0;
             a.last = k == parts - 1;
-            const bool wtd = a.scale == SCALE_GCN;
+            const bool wtd = a.wsrc != nullptr;
             const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
             if (narrow == 32) dispatch_grouped<8>(a, n_heavy, N, wtd, off32, stream);
             else if (narrow == 64) dispatch_grouped<16>(a, n_heavy, N, wtd, off32, stream);
@@ -1258,13 +1197,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         float* er = (float*)((char*)c.workspace + align_up(N * heads_padded(c.heads) * (int64_t)sizeof(float), 256));
         a.el = el;
         a.er = er;
-        const unsigned gb = (unsigned)((N + 3) / 4);
-        if (hp == 4)
-            gat_scores_kernel<4><<<dim3(gb), dim3(256), 0, stream>>>(N, c.F, c.heads, a.Dh, c.Z, c.ldz,
-                                                                     c.attn_src, c.attn_dst, el, er);
-        else
-            gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, c.F, c.heads, a.Dh, c.Z, c.ldz,
-                                                                     c.attn_src, c.attn_dst, el, er);
+        launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream);
         const bool hu = (a.Dh % vec) == 0;
         const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
         if (vec == 4 && off32 && opt.gat_fast) {

@@ -73,9 +73,39 @@ struct AggCall {
     float* out;
     int64_t ldo;
     void* workspace;
+    // per-source weights (out_v = sum_u w[u] z_u); NULL: none.  Only with RETEXO_SUM — gcn_sym uses
+    // the plan's dinv on both sides by itself.  Used by the backward of the mean.
+    const float* src_weight = nullptr;
 };
 int launch_aggregate(const AggCall& c, hipStream_t stream);
 int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads);
+// el[v,h] = <a_src[h], z_v,h>, er[v,h] = <a_dst[h], z_v,h>, both [N, heads_padded(heads)]
+void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
+                       const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream);
+
+// Backward of the aggregation (see retexo_aggregate_backward)
+struct AggBackwardCall {
+    const retexo_plan* plan;
+    int mode;
+    int64_t F;
+    int heads;
+    const float* Z;        // forward input (edge softmax only)
+    int64_t ldz;
+    const float* attn_src;
+    const float* attn_dst;
+    float slope;
+    bool self_concat;      // G is [N, 2F]: gradient of the self half, then of the aggregate
+    const float* G;
+    int64_t ldg;
+    float* dZ;
+    int64_t lddz;
+    float* d_attn_src;
+    float* d_attn_dst;
+    void* workspace;
+};
+int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream);
+int64_t aggregate_backward_workspace_bytes(int64_t N, int mode, int64_t F, int heads);
+constexpr int64_t kMaxBackwardSoftmaxWidth = 1024;   // heads * Dh the edge-softmax backward handles
 
 // per-node score arrays are padded to 4 or 8 heads (padded heads hold zeros and are never selected)
 static inline int heads_padded(int heads) { return heads <= 4 ? 4 : 8; }

@@ -141,6 +141,59 @@ extern "C" int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, in
     return launch_aggregate(c, (hipStream_t)stream);
 }
 
+extern "C" int64_t retexo_aggregate_backward_workspace_bytes(const retexo_plan* plan, int mode, int64_t F, int heads)
+{
+    if (!plan) return RETEXO_E_NULL;
+    if (F < 0 || F >= (1ll << 30)) return RETEXO_E_SIZE;
+    if (int s = check_mode(mode, F, heads)) return s;
+    if (mode == RETEXO_MAX) return RETEXO_E_MODE;
+    if (mode == RETEXO_GAT_SOFTMAX && F > kMaxBackwardSoftmaxWidth) return RETEXO_E_SIZE;
+    return aggregate_backward_workspace_bytes(plan->N, mode, F, heads);
+}
+
+extern "C" int retexo_aggregate_backward(const retexo_plan* plan, int mode, int64_t F, int heads,
+                                         const float* d_Z, int64_t ldz,
+                                         const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                                         unsigned flags, const float* d_G, int64_t ldg,
+                                         float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
+                                         void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    if (!plan) return RETEXO_E_NULL;
+    if (F < 0 || F >= (1ll << 30)) return RETEXO_E_SIZE;
+    if (int s = check_mode(mode, F, heads)) return s;
+    if (mode == RETEXO_MAX) return RETEXO_E_MODE;
+    if (flags & ~(unsigned)RETEXO_F_SELF_CONCAT) return RETEXO_E_FLAGS;
+    const bool gat = mode == RETEXO_GAT_SOFTMAX;
+    if (gat && F > kMaxBackwardSoftmaxWidth) return RETEXO_E_SIZE;
+    const bool concat = (flags & RETEXO_F_SELF_CONCAT) != 0;
+    const int64_t N = plan->N, gw = concat ? 2 * F : F;
+    const bool work = N > 0 && F > 0;
+    if (work && (!d_G || !d_dZ)) return RETEXO_E_NULL;
+    if (gat && work && (!d_Z || !d_attn_src || !d_attn_dst || !d_dattn_src || !d_dattn_dst)) return RETEXO_E_NULL;
+    if (ldg < gw || lddz < F || (gat && ldz < F)) return RETEXO_E_LD;
+    if (work) {
+        if (overlaps(d_G, extent_bytes(N, ldg, gw), d_dZ, extent_bytes(N, lddz, F))) return RETEXO_E_ALIAS;
+        if (gat && overlaps(d_Z, extent_bytes(N, ldz, F), d_dZ, extent_bytes(N, lddz, F))) return RETEXO_E_ALIAS;
+    }
+    const int64_t need = aggregate_backward_workspace_bytes(N, mode, F, heads);
+    if (need > 0 && (!d_workspace || workspace_bytes < need || ((uintptr_t)d_workspace & 255)))
+        return RETEXO_E_WORKSPACE;
+    if (gat && !work && d_dattn_src && d_dattn_dst && F > 0) {
+        // no nodes: the parameter gradients are zero
+        if (hipMemsetAsync(d_dattn_src, 0, (size_t)F * sizeof(float), (hipStream_t)stream) != hipSuccess ||
+            hipMemsetAsync(d_dattn_dst, 0, (size_t)F * sizeof(float), (hipStream_t)stream) != hipSuccess)
+            return RETEXO_E_HIP;
+        return RETEXO_OK;
+    }
+
+    AggBackwardCall c;
+    c.plan = plan; c.mode = mode; c.F = F; c.heads = heads; c.Z = d_Z; c.ldz = ldz;
+    c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
+    c.self_concat = concat; c.G = d_G; c.ldg = ldg; c.dZ = d_dZ; c.lddz = lddz;
+    c.d_attn_src = d_dattn_src; c.d_attn_dst = d_dattn_dst; c.workspace = d_workspace;
+    return launch_aggregate_backward(c, (hipStream_t)stream);
+}
+
 extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out, int heads,
                             const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
                             const float* d_attn_src, const float* d_attn_dst, float negative_slope,

@@ -123,6 +123,31 @@ def aggregate(g: DeviceGraph, mode: str, Z: torch.Tensor, F: int, *, heads: int 
     return out
 
 
+def aggregate_backward(g: DeviceGraph, mode: str, F: int, G: torch.Tensor, *, Z: Optional[torch.Tensor] = None,
+                       heads: int = 1, a_src: Optional[torch.Tensor] = None, a_dst: Optional[torch.Tensor] = None,
+                       slope: float = 0.2, concat: bool = False, dZ: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None):
+    """-> (dZ, da_src, da_dst) device tensors (da_* None unless mode is gat_softmax)."""
+    if dZ is None:
+        dZ = torch.empty((g.n_nodes, pad_ld(F)), dtype=torch.float32, device="cuda")
+    need = B.retexo_aggregate_backward_workspace_bytes(g.plan, B.MODES[mode], F, heads)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_aggregate_backward_workspace_bytes")
+    if workspace is None:
+        workspace = ws_tensor(need)
+    das = dad = None
+    if mode == "gat_softmax":
+        das = torch.empty((heads, F // heads), dtype=torch.float32, device="cuda")
+        dad = torch.empty_like(das)
+    p = lambda t: t.data_ptr() if t is not None else 0
+    st = B.retexo_aggregate_backward(g.plan, B.MODES[mode], F, heads, p(Z), Z.stride(0) if Z is not None else 0,
+                                     p(a_src), p(a_dst), slope, B.F_SELF_CONCAT if concat else 0,
+                                     G.data_ptr(), G.stride(0), dZ.data_ptr(), dZ.stride(0), p(das), p(dad),
+                                     workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    B.check(st, "retexo_aggregate_backward")
+    return dZ, das, dad
+
+
 def round_(g: DeviceGraph, st: Stage, H: torch.Tensor, W, b, a_src, a_dst, out: torch.Tensor,
            workspace: torch.Tensor, slope: float = 0.2) -> None:
     flags = (B.F_RELU if st.relu else 0) | (B.F_SELF_CONCAT if st.concat else 0)

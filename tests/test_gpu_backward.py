@@ -1,0 +1,211 @@
+"""GPU backward of the aggregation (retexo_aggregate_backward) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_13053_amd import binding as B
+from paper_2302_13053_amd import harness as Hn
+from paper_2302_13053_amd import workloads as wl
+from parity import assert_close
+
+pytestmark = pytest.mark.gpu
+
+LINEAR = ["sum", "mean", "gcn_sym"]
+
+
+@pytest.fixture(scope="module")
+def graphs():
+    """name -> (DeviceGraph, row_ptr, col_idx); undirected graphs, hence symmetric CSRs."""
+    specs = {
+        "skewed": (5000, 60000, 3.0, 4),     # a few rows far above the heavy threshold, many empty
+        "flat": (3000, 20000, 0.0, 5),
+        "tiny": (3, 2, 0.0, 6),
+    }
+    out = {}
+    for name, (n, pairs, skew, seed) in specs.items():
+        src, dst = wl.random_pairs(n, pairs, seed, skew=skew)
+        for sl in (False, True):
+            g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, sl), validate=True, split_rows=(name == "skewed"))
+            rp, ci = oracle.csr_from_coo(src, dst, n, sl)
+            out[(name, sl)] = (g, rp, ci)
+    deg = np.diff(out[("skewed", False)][1])
+    assert deg.max() >= 2048 and (deg == 0).any()
+    yield out
+    for g, _, _ in out.values():
+        g.destroy()
+
+
+def offset_tensor(a: np.ndarray, offset: int) -> torch.Tensor:
+    """Device copy of ``a`` whose first element sits ``offset`` floats past an aligned address."""
+    if not offset:
+        return Hn.dev(a)
+    buf = torch.zeros(a.size + offset, dtype=torch.float32, device="cuda")
+    t = buf[offset:].view(a.shape)
+    t.copy_(torch.from_numpy(a))
+    return t
+
+
+def run_case(graphs, name, mode, F, ld, heads, concat, seed, offset=0, slope=0.2):
+    g, rp, ci = graphs[(name, mode == "gcn_sym")]
+    n = g.n_nodes
+    gw = 2 * F if concat else F
+    ldg = ld if not concat else ld + F
+    Zh = wl.random_matrix(n, F, seed, ld=ld)
+    Gh = wl.random_matrix(n, gw, seed + 1, ld=ldg)
+    a_s = a_d = None
+    kw = {}
+    if mode == "gat_softmax":
+        # attention vectors at an initialisation-like scale: scores of a few units whatever the head width
+        # (far larger scores make the softmax one-hot, and the gradient through it a difference of
+        # nearly equal inner products that no fp32 evaluation resolves to 1e-5 of the row)
+        scale = np.float32(min(0.3, 2.4 / np.sqrt(F // heads)))
+        a_s = wl.random_matrix(heads, F // heads, seed + 2) * scale
+        a_d = wl.random_matrix(heads, F // heads, seed + 3) * scale
+        kw = dict(Z=offset_tensor(Zh, offset), heads=heads, a_src=Hn.dev(a_s), a_dst=Hn.dev(a_d), slope=slope)
+    dZ = torch.full((n, ld + 3), 777.0, dtype=torch.float32, device="cuda")
+    if ld % 4 == 0:
+        dZ = torch.full((n, ld + 4), 777.0, dtype=torch.float32, device="cuda")
+    out = Hn.aggregate_backward(g, mode, F, offset_tensor(Gh, offset), concat=concat, dZ=dZ, **kw)
+    torch.cuda.synchronize()
+    got = out[0].cpu().numpy()
+    assert np.all(got[:, F:] == 777.0)                      # nothing written past the F columns
+    want = oracle.aggregate_backward(mode, rp, ci, Zh, F, Gh, heads=heads, a_src=a_s, a_dst=a_d,
+                                     slope=slope, self_concat=concat)
+    return got[:, :F], out[1], out[2], want
+
+
+def check_params(das, dad, want, what):
+    # one row-normwise ratio over each whole parameter gradient
+    for got, ref, name in ((das, want[1], " da_src"), (dad, want[2], " da_dst")):
+        got = got.cpu().numpy().reshape(1, -1)
+        if np.abs(ref).max() == 0.0:
+            # a gradient that vanishes by structure (every softmax over a single entry) is a difference
+            # of two equal inner products on the GPU: rounding noise, not an exact zero
+            assert np.abs(got).max() <= 1e-5, what + name
+        else:
+            assert_close(got, ref.reshape(1, -1), what=what + name)
+
+
+@pytest.mark.parametrize("mode", LINEAR)
+@pytest.mark.parametrize("F,ld,concat,offset", [
+    (256, 256, False, 0), (602, 608, True, 0), (602, 602, False, 0), (1433, 1433, True, 0),
+    (100, 100, True, 0), (7, 7, True, 0), (128, 128, False, 1),
+])
+def test_linear_modes_match_oracle(graphs, mode, F, ld, concat, offset):
+    got, _, _, want = run_case(graphs, "skewed", mode, F, ld, 1, concat, seed=F + 3, offset=offset)
+    # narrow rows of signed terms can cancel to nothing (see the forward tests): bound by the row's terms instead
+    assert_close(got, want, tol=1e-5 if F >= 64 else 2e-4, what="%s backward F=%d" % (mode, F))
+    for name in ("flat", "tiny"):
+        got, _, _, want = run_case(graphs, name, mode, 96, 96, 1, concat, seed=5)
+        assert_close(got, want, what="%s backward %s" % (mode, name))
+
+
+@pytest.mark.parametrize("F,ld,heads,concat,offset", [
+    (256, 256, 4, False, 0),      # the benchmark shape: 16 lanes per head
+    (256, 256, 4, True, 0),
+    (188, 192, 4, False, 0),      # heads of 47 columns: a lane's four columns straddle heads
+    (512, 512, 8, False, 0),      # two chunks per lane, eight heads
+    (1024, 1024, 8, True, 0),     # widest supported
+    (768, 768, 1, False, 0),      # three chunks
+    (100, 100, 4, True, 0),
+    (94, 94, 2, False, 0),        # width not a multiple of four: scalar gathers
+    (702, 702, 2, False, 0),      # scalar gathers, 11 chunks
+    (301, 304, 7, False, 0),      # seven heads of 43, scalar gathers
+    (7, 7, 7, True, 0),
+    (1, 1, 1, False, 0),
+    (128, 128, 2, False, 1),      # misaligned base pointers
+])
+def test_edge_softmax_backward_matches_oracle(graphs, F, ld, heads, concat, offset):
+    got, das, dad, want = run_case(graphs, "skewed", "gat_softmax", F, ld, heads, concat, seed=F + 9, offset=offset)
+    what = "gat backward F=%d heads=%d" % (F, heads)
+    # narrow rows: a handful of signed terms has no robust magnitude to measure against
+    assert_close(got, want[0], tol=1e-5 if F >= 64 else 5e-4, what=what)
+    check_params(das, dad, want, what)
+
+
+@pytest.mark.parametrize("name", ["flat", "tiny"])
+def test_edge_softmax_backward_other_graphs(graphs, name):
+    got, das, dad, want = run_case(graphs, name, "gat_softmax", 96, 96, 3, True, seed=3)
+    assert_close(got, want[0], what="gat backward " + name)
+    check_params(das, dad, want, "gat backward " + name)
+
+
+def test_heavy_row_threshold_and_reproducibility(graphs):
+    """Every row through the one-wave kernel, or many rows through the eight-wave kernel: same
+    result within the bound, and each configuration reproduces itself bit for bit."""
+    g, rp, ci = graphs[("skewed", False)]
+    n, F, heads = g.n_nodes, 192, 3
+    Zh, Gh = wl.random_matrix(n, F, 41), wl.random_matrix(n, F, 42)
+    a_s, a_d = wl.random_matrix(heads, F // heads, 43) * np.float32(0.3), wl.random_matrix(heads, F // heads, 44) * np.float32(0.3)
+    want = oracle.aggregate_backward("gat_softmax", rp, ci, Zh, F, Gh, heads=heads, a_src=a_s, a_dst=a_d)
+    Z, G, As, Ad = Hn.dev(Zh), Hn.dev(Gh), Hn.dev(a_s), Hn.dev(a_d)
+    try:
+        for heavy in (1 << 20, 256, 2048):
+            B.retexo_set_option("agg_heavy_degree", heavy)
+            for vec in (4, 1):
+                B.retexo_set_option("agg_max_vec", vec)
+                a = Hn.aggregate_backward(g, "gat_softmax", F, G, Z=Z, heads=heads, a_src=As, a_dst=Ad)
+                a = [t.clone() for t in a]
+                b = Hn.aggregate_backward(g, "gat_softmax", F, G, Z=Z, heads=heads, a_src=As, a_dst=Ad)
+                assert all(torch.equal(x, y) for x, y in zip(a, b))
+                what = "gat backward heavy=%d vec=%d" % (heavy, vec)
+                assert_close(a[0].cpu().numpy()[:, :F], want[0], what=what)
+                check_params(a[1], a[2], want, what)
+    finally:
+        B.retexo_set_option("agg_heavy_degree", 2048)
+        B.retexo_set_option("agg_max_vec", 4)
+
+
+def test_slope_one_sends_nothing_to_the_destination_vector(graphs):
+    """With slope 1 the score is linear and the softmax ignores a row-wide shift, so da_dst is zero up to
+    rounding; the GPU must show that cancellation too (a property that holds at any size)."""
+    got, das, dad, want = run_case(graphs, "flat", "gat_softmax", 128, 128, 4, False, seed=77, slope=1.0)
+    assert_close(got, want[0], what="gat backward slope 1")
+    assert np.abs(dad.cpu().numpy()).max() <= 1e-4 * np.abs(das.cpu().numpy()).max()
+
+
+def test_argument_errors(graphs):
+    g, _, _ = graphs[("flat", False)]
+    n = g.n_nodes
+    Z = torch.zeros((n, 64), dtype=torch.float32, device="cuda")
+    G = torch.zeros((n, 64), dtype=torch.float32, device="cuda")
+    a = torch.zeros((2, 32), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.RetexoError) as e:
+        Hn.aggregate_backward(g, "max", 64, G)
+    assert e.value.status == -4
+    assert B.retexo_aggregate_backward_workspace_bytes(g.plan, B.MODES["gat_softmax"], 2048, 2) == -2      # too wide
+    need = B.retexo_aggregate_backward_workspace_bytes(g.plan, B.MODES["gat_softmax"], 64, 2)
+    ws = Hn.ws_tensor(need)
+    p = lambda t: t.data_ptr()
+    dZ, da1, da2 = torch.empty_like(Z), a.clone(), a.clone()
+    args = lambda **k: dict(dict(plan=g.plan, mode=B.MODES["gat_softmax"], F=64, heads=2, d_Z=p(Z), ldz=64,
+                                 d_attn_src=p(a), d_attn_dst=p(a), negative_slope=0.2, flags=0, d_G=p(G), ldg=64,
+                                 d_dZ=p(dZ), lddz=64, d_dattn_src=p(da1), d_dattn_dst=p(da2),
+                                 d_workspace=p(ws), workspace_bytes=need), **k)
+    assert B.retexo_aggregate_backward(**args()) == 0
+    assert B.retexo_aggregate_backward(**args(d_dZ=p(G))) == -9           # output over the gradient
+    assert B.retexo_aggregate_backward(**args(d_dZ=p(Z))) == -9           # output over the forward input
+    assert B.retexo_aggregate_backward(**args(workspace_bytes=need - 1)) == -8
+    assert B.retexo_aggregate_backward(**args(d_dattn_src=0)) == -1
+    assert B.retexo_aggregate_backward(**args(ldg=63)) == -3
+    assert B.retexo_aggregate_backward(**args(heads=3)) == -6
+    assert B.retexo_aggregate_backward(**args(flags=B.F_RELU)) == -5
+    torch.cuda.synchronize()
+
+
+def test_mid_size_graph_parameter_gradients():
+    """A graph large enough for the two-stage parameter reduction to have many partial rows."""
+    n, F, heads = 60000, 256, 4
+    src, dst = wl.random_pairs(n, 600000, 51, skew=1.5)
+    g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False))
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    Zh, Gh = wl.random_matrix(n, F, 52), wl.random_matrix(n, F, 53)
+    a_s, a_d = wl.random_matrix(heads, F // heads, 54) * np.float32(0.1), wl.random_matrix(heads, F // heads, 55) * np.float32(0.1)
+    dZ, das, dad = Hn.aggregate_backward(g, "gat_softmax", F, Hn.dev(Gh), Z=Hn.dev(Zh), heads=heads,
+                                         a_src=Hn.dev(a_s), a_dst=Hn.dev(a_d))
+    torch.cuda.synchronize()
+    want = oracle.aggregate_backward("gat_softmax", rp, ci, Zh, F, Gh, heads=heads, a_src=a_s, a_dst=a_d)
+    assert_close(dZ.cpu().numpy()[:, :F], want[0], what="gat backward mid-size")
+    check_params(das, dad, want, "gat backward mid-size")
+    g.destroy()
