@@ -297,6 +297,33 @@ def main():
         out["train_step"] = {"layer": "%d->%d (ReLU) + classifier %d->%d" % (st.d_in, st.d_out, st.d_out, n_cls),
                              "ms": tms, "TFLOP/s": tfl, "frac_fp32_mfma": tfl / 157.3,
                              "loss_first": l0, "loss_last": float(last.cpu()[0]), "sgd_steps": reps + 1}
+    # a layer whose aggregation has trainable parameters (edge softmax) trains with the aggregation in the
+    # loop: time its backward (dL/dZ and the attention-vector gradients) on the first such round's shape
+    att = next((i for i, st in enumerate(w.stages) if st.kind == "round" and st.mode == "gat_softmax"
+                and st.d_out <= 1024), None)
+    if att is not None:
+        st = w.stages[att]
+        Fz, width = st.d_out, pipe.outs[att].shape[1]
+        Zb = pipe.outs[att]                               # stands in for the round's transformed features
+        Gb = torch.empty_like(Zb).normal_(generator=torch.Generator(device="cuda").manual_seed(4321))
+        a_s, a_d = pipe.params[att][2], pipe.params[att][3]
+        dZb = torch.empty_like(Zb)
+        bws = Hn.ws_tensor(B.retexo_aggregate_backward_workspace_bytes(pipe.graph.plan, B.MODES[st.mode], Fz, st.heads))
+
+        def backward_once():
+            return Hn.aggregate_backward(pipe.graph, st.mode, Fz, Gb, Z=Zb, heads=st.heads, a_src=a_s, a_dst=a_d,
+                                         dZ=dZb, workspace=bws)
+        backward_once()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            backward_once()
+        e1.record()
+        torch.cuda.synchronize()
+        bms = e0.elapsed_time(e1) / reps
+        gbs = 2.0 * nnz * Fz * 4 / bms / 1e6              # two gather passes, one row of F floats per entry each
+        out["aggregate_backward"] = {"shape": "%s F=%d heads=%d ld=%d" % (st.mode, Fz, st.heads, width), "ms": bms,
+                                     "GB/s_algorithmic": gbs, "frac_hbm": gbs / 8000.0}
     pipe.close()
     if not args.no_cpu:
         default_rows = w.n_nodes      # the oracle is fast enough to run every row of every stage in 10-30 s

@@ -1116,7 +1116,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.order = p->order;
     a.deg = p->deg;
     a.dinv = p->dinv;
-    a.wsrc = c.mode == RETEXO_GCN_SYM ? p->dinv : c.src_weight;
+    a.wsrc = c.mode == RETEXO_GCN_SYM ? p->dinv : nullptr;
     a.Z = c.Z;
     a.ldz = c.ldz;
     a.out = c.out;

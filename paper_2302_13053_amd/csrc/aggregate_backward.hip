@@ -11,7 +11,8 @@
 //
 //  * sum, gcn_sym: the operator is symmetric, the backward is the forward
 //    applied to G.  mean: out_v = (1/deg v) sum_u z_u transposes into
-//    dZ_u = sum_v G_v / deg v — a sum with one weight per gathered row.
+//    dZ_u = sum_v G_v / deg v: the rows of G are scaled once into the workspace
+//    (one streaming pass) and then summed like any other table.
 //  * edge softmax (per head, p_vu = el_u + er_v, e = LeakyReLU(p), alpha = softmax_u e):
 //        dZ_u = sum_v alpha_vu G_v  +  a_src * dsrc_u  +  a_dst * ddst_u
 //        dsrc_u = sum_v t_vu (<G_v, z_u> - c_v)        t_vu = alpha_vu * LeakyReLU'(p_vu)
@@ -494,12 +495,21 @@ __global__ __launch_bounds__(256) void gat_bwd_param_final_kernel(
     da_dst[col] = sd;
 }
 
-// rdeg[v] = 1 / deg v (0 for an empty row): the per-source weights of the mean's backward
-__global__ __launch_bounds__(256) void reciprocal_degree_kernel(int64_t N, const int32_t* __restrict__ deg,
-                                                                 float* __restrict__ rdeg)
+// S[v, :] = G[v, :] / deg v (zero for an empty row): the mean's backward sums these rows.
+// One thread per four columns; S has a row pitch that is a multiple of four floats.
+__global__ __launch_bounds__(256) void scale_rows_by_degree_kernel(
+    int64_t N, int64_t F, const float* __restrict__ G, int64_t ldg, const int32_t* __restrict__ deg,
+    float* __restrict__ S, int64_t lds)
 {
-    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (v < N) rdeg[v] = deg[v] > 0 ? 1.0f / (float)deg[v] : 0.0f;
+    const int64_t quads = (F + 3) / 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * quads) return;
+    const int64_t v = i / quads, c0 = (i % quads) * 4;
+    const int d = deg[v];
+    const float r = d > 0 ? 1.0f / (float)d : 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (c0 + k < F) S[v * lds + c0 + k] = G[v * ldg + c0 + k] * r;
 }
 
 // dZ[:, 0:F] += Gself[:, 0:F]
@@ -581,12 +591,15 @@ SoftmaxWorkspace softmax_workspace(int64_t N, int64_t F, int heads)
     return w;
 }
 
+// row pitch (floats) of the scaled copy of G the mean's backward keeps in the workspace: 128-byte rows
+int64_t scaled_pitch(int64_t F) { return align_up(F > 0 ? F : 1, 32); }
+
 }  // namespace
 
 int64_t aggregate_backward_workspace_bytes(int64_t N, int mode, int64_t F, int heads)
 {
     if (mode == RETEXO_GAT_SOFTMAX) return softmax_workspace(N, F, heads).total;
-    if (mode == RETEXO_MEAN) return align_up((N > 0 ? N : 1) * (int64_t)sizeof(float), 256);
+    if (mode == RETEXO_MEAN) return align_up((N > 0 ? N : 1) * scaled_pitch(F) * (int64_t)sizeof(float), 256);
     return 0;
 }
 
@@ -615,9 +628,12 @@ int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream)
         f.ldo = c.lddz;
         f.workspace = nullptr;
         if (c.mode == RETEXO_MEAN) {
-            float* rdeg = (float*)c.workspace;
-            reciprocal_degree_kernel<<<dim3((unsigned)((N + 255) / 256)), dim3(256), 0, stream>>>(N, p->deg, rdeg);
-            f.src_weight = rdeg;
+            float* S = (float*)c.workspace;
+            const int64_t lds = scaled_pitch(F), threads = N * ((F + 3) / 4);
+            scale_rows_by_degree_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream>>>(
+                N, F, Ga, c.ldg, p->deg, S, lds);
+            f.Z = S;
+            f.ldz = lds;
         }
         if (int s = launch_aggregate(f, stream)) return s;
         if (c.self_concat)

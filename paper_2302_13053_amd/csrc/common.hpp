@@ -73,9 +73,6 @@ struct AggCall {
     float* out;
     int64_t ldo;
     void* workspace;
-    // per-source weights (out_v = sum_u w[u] z_u); NULL: none.  Only with RETEXO_SUM — gcn_sym uses
-    // the plan's dinv on both sides by itself.  Used by the backward of the mean.
-    const float* src_weight = nullptr;
 };
 int launch_aggregate(const AggCall& c, hipStream_t stream);
 int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads);
