@@ -73,7 +73,8 @@ typedef enum {
     RETEXO_E_WORKSPACE = -8,  /* workspace missing or too small                       */
     RETEXO_E_ALIAS = -9,      /* output overlaps an input                             */
     RETEXO_E_HIP = -10,       /* a HIP runtime call failed                            */
-    RETEXO_E_CAPACITY = -11   /* col_idx capacity too small for the CSR               */
+    RETEXO_E_CAPACITY = -11,  /* an output array's capacity is too small              */
+    RETEXO_E_PARTITION = -12  /* a node's worker id is outside [0, n_parts)           */
 } retexo_status;
 
 const char* retexo_status_string(int status);
@@ -243,6 +244,60 @@ int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
                       float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
                       void* d_workspace, int64_t workspace_bytes, void* stream);
 int retexo_sgd_update(int64_t n, float* d_param, const float* d_grad, float lr, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * One worker's share of an edge-partitioned graph (section "Edge-partitioned
+ * Distributed Setup": worker i holds its inner nodes V_i, the edges touching
+ * an inner node and, as boundary nodes, their other endpoints) and the pack /
+ * unpack of boundary rows around a round (the embedding exchange between peers
+ * of the implementation section; the transport itself is not part of this
+ * library).  Input: the global CSR (as retexo_csr_from_coo builds it: columns
+ * ascending) and d_part [N], the worker that owns each node, values in
+ * [0, n_parts), n_parts <= 64.  Output for worker `part`:
+ *   local numbering [ inner nodes, ascending global id | boundary nodes, ascending global id ]
+ *   d_local_ids      [n_local]     global id of each local node, n_local = n_inner + n_halo
+ *   d_local_row_ptr  [n_local + 1] int64; an inner node's row is its global row renumbered,
+ *   d_local_col_idx  [nnz_local]   columns ascending; boundary rows are empty
+ *   d_global_deg     [n_local]     global row length of each local node (for retexo_plan_set_degrees)
+ *   d_send_ids [n_send], h_send_offsets [n_parts + 1]: local ids of the inner nodes peer q needs,
+ *                    entries h_send_offsets[q] .. h_send_offsets[q+1]
+ *   d_recv_ids [n_halo], h_recv_offsets [n_parts + 1]: local ids of the boundary nodes peer q owns
+ *   Both lists are ascending in global id, so what worker p packs for q and what q unpacks
+ *   from p line up element by element.
+ *   h_sizes [4] (host): n_inner, n_halo, nnz_local, n_send — always written (unless an argument
+ *   error is returned); if a capacity (local_capacity for the n_local-sized arrays,
+ *   col_capacity, send_capacity) is too small, or d_local_row_ptr is NULL, the call returns
+ *   RETEXO_E_CAPACITY with nothing else written: a first call with zero capacities and NULL
+ *   outputs is a size query.
+ * d_workspace: retexo_partition_workspace_bytes(N, n_parts, send_capacity) bytes, 256-aligned.
+ * Synchronises `stream`.  Integer arithmetic only; the result is a unique function of the input.
+ * Errors: RETEXO_E_PARTITION (a worker id out of range), RETEXO_E_CAPACITY, RETEXO_E_SIZE,
+ * RETEXO_E_NULL, RETEXO_E_WORKSPACE, RETEXO_E_HIP.
+ */
+int64_t retexo_partition_workspace_bytes(int64_t n_nodes, int n_parts, int64_t send_capacity);
+int retexo_partition_share(int64_t n_nodes, const int64_t* d_row_ptr, const int32_t* d_col_idx,
+                           const int32_t* d_part, int n_parts, int part,
+                           int64_t local_capacity, int64_t col_capacity, int64_t send_capacity,
+                           int32_t* d_local_ids, int64_t* d_local_row_ptr, int32_t* d_local_col_idx,
+                           int32_t* d_global_deg, int32_t* d_send_ids, int32_t* d_recv_ids,
+                           int64_t* h_sizes, int64_t* h_send_offsets, int64_t* h_recv_offsets,
+                           void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* d_buf[i, 0:F] = d_H[d_ids[i], 0:F] for i < n (gather the rows a peer needs into a dense send
+ * buffer) and the reverse, d_H[d_ids[i], 0:F] = d_buf[i, 0:F] (scatter received rows into the
+ * boundary part of the table).  table_rows = rows of d_H; an id outside [0, table_rows) is
+ * skipped.  For unpack the ids must be distinct.  Buffers must not overlap.  Enqueues on `stream`. */
+int retexo_halo_pack(int64_t n, const int32_t* d_ids, int64_t table_rows, int64_t F,
+                     const float* d_H, int64_t ldh, float* d_buf, int64_t ldb, void* stream);
+int retexo_halo_unpack(int64_t n, const int32_t* d_ids, int64_t table_rows, int64_t F,
+                       const float* d_buf, int64_t ldb, float* d_H, int64_t ldh, void* stream);
+
+/* Replace the degrees a plan uses for scaling (mean: 1/deg; gcn_sym: dinv = 1/sqrt(deg), the
+ * correctly rounded fp32 sqrt and divide) by d_deg [N].  For a worker's local graph, whose
+ * boundary rows are empty: pass the d_global_deg of retexo_partition_share so that gcn_sym
+ * normalises boundary neighbours by their true degree.  The schedule keeps following the
+ * actual row lengths.  Enqueues on `stream`. */
+int retexo_plan_set_degrees(retexo_plan* plan, const int32_t* d_deg, void* stream);
 
 /* ---------------------------------------------------------------------------
  * Tuning knobs (process-wide, for experiments; defaults are chosen per shape).

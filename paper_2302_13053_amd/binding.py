@@ -29,6 +29,8 @@ EXPORTS = (
     "retexo_workspace_bytes",
     "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
     "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward",
+    "retexo_partition_workspace_bytes", "retexo_partition_share", "retexo_halo_pack", "retexo_halo_unpack",
+    "retexo_plan_set_degrees",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
 )
 
@@ -87,6 +89,17 @@ def load():
     lib.retexo_aggregate_backward.restype = i32
     lib.retexo_aggregate_backward.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64,
                                               vp, i64, vp, vp, vp, i64, vp]
+    lib.retexo_partition_workspace_bytes.restype = i64
+    lib.retexo_partition_workspace_bytes.argtypes = [i64, i32, i64]
+    lib.retexo_partition_share.restype = i32
+    lib.retexo_partition_share.argtypes = [i64, vp, vp, vp, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp,
+                                           C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), vp, i64, vp]
+    lib.retexo_halo_pack.restype = i32
+    lib.retexo_halo_pack.argtypes = [i64, vp, i64, i64, vp, i64, vp, i64, vp]
+    lib.retexo_halo_unpack.restype = i32
+    lib.retexo_halo_unpack.argtypes = [i64, vp, i64, i64, vp, i64, vp, i64, vp]
+    lib.retexo_plan_set_degrees.restype = i32
+    lib.retexo_plan_set_degrees.argtypes = [vp, vp, vp]
     lib.retexo_round.restype = i32
     lib.retexo_round.argtypes = [vp, i32, i64, i64, i32, vp, i64, vp, vp, vp, vp, f32, u32, vp, i64,
                                  vp, i64, vp]
@@ -190,6 +203,37 @@ def retexo_aggregate_backward(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn
                                                 _vp(d_attn_dst), negative_slope, flags, _vp(d_G), ldg,
                                                 _vp(d_dZ), lddz, _vp(d_dattn_src), _vp(d_dattn_dst),
                                                 _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+def retexo_partition_workspace_bytes(n_nodes, n_parts, send_capacity) -> int:
+    return int(load().retexo_partition_workspace_bytes(n_nodes, n_parts, send_capacity))
+
+
+def retexo_partition_share(n_nodes, d_row_ptr, d_col_idx, d_part, n_parts, part, local_capacity, col_capacity,
+                           send_capacity, d_local_ids, d_local_row_ptr, d_local_col_idx, d_global_deg,
+                           d_send_ids, d_recv_ids, d_workspace, workspace_bytes, stream=0):
+    """-> (status, [n_inner, n_halo, nnz_local, n_send], send_offsets, recv_offsets) with host lists"""
+    sizes = (C.c_int64 * 4)(-1, -1, -1, -1)
+    so = (C.c_int64 * (n_parts + 1))()
+    ro = (C.c_int64 * (n_parts + 1))()
+    st = load().retexo_partition_share(n_nodes, _vp(d_row_ptr), _vp(d_col_idx), _vp(d_part), n_parts, part,
+                                       local_capacity, col_capacity, send_capacity, _vp(d_local_ids),
+                                       _vp(d_local_row_ptr), _vp(d_local_col_idx), _vp(d_global_deg),
+                                       _vp(d_send_ids), _vp(d_recv_ids), sizes, so, ro,
+                                       _vp(d_workspace), workspace_bytes, _vp(stream))
+    return int(st), list(sizes), list(so), list(ro)
+
+
+def retexo_halo_pack(n, d_ids, table_rows, F, d_H, ldh, d_buf, ldb, stream=0) -> int:
+    return int(load().retexo_halo_pack(n, _vp(d_ids), table_rows, F, _vp(d_H), ldh, _vp(d_buf), ldb, _vp(stream)))
+
+
+def retexo_halo_unpack(n, d_ids, table_rows, F, d_buf, ldb, d_H, ldh, stream=0) -> int:
+    return int(load().retexo_halo_unpack(n, _vp(d_ids), table_rows, F, _vp(d_buf), ldb, _vp(d_H), ldh, _vp(stream)))
+
+
+def retexo_plan_set_degrees(plan, d_deg, stream=0) -> int:
+    return int(load().retexo_plan_set_degrees(_vp(plan), _vp(d_deg), _vp(stream)))
 
 
 def retexo_round(plan, mode, d_in, d_out, heads, d_H, ldh, d_W, d_b, d_attn_src, d_attn_dst,

@@ -66,7 +66,8 @@ extern "C" const char* retexo_status_string(int s)
         case RETEXO_E_WORKSPACE: return "workspace missing, misaligned or too small";
         case RETEXO_E_ALIAS: return "output overlaps an input";
         case RETEXO_E_HIP: return "HIP runtime call failed";
-        case RETEXO_E_CAPACITY: return "col_idx capacity too small";
+        case RETEXO_E_CAPACITY: return "output capacity too small";
+        case RETEXO_E_PARTITION: return "worker id out of range";
         default: return "unknown status";
     }
 }

@@ -76,6 +76,64 @@ def make_plan(g: DeviceGraph, validate: bool = False, split_rows: bool = False) 
     return g
 
 
+@dataclass
+class DeviceShare:
+    """One worker's share of an edge-partitioned graph (device arrays of retexo_partition_share)."""
+    n_inner: int
+    n_halo: int
+    graph: DeviceGraph            # local CSR over n_inner + n_halo nodes (no plan yet)
+    local_ids: torch.Tensor       # int32 [n_local] global ids
+    global_deg: torch.Tensor      # int32 [n_local]
+    send_ids: torch.Tensor        # int32 [n_send] local ids, grouped by peer
+    recv_ids: torch.Tensor        # int32 [n_halo] local ids, grouped by owner
+    send_offsets: list            # host, [n_parts + 1]
+    recv_offsets: list
+
+
+def partition_share(g: DeviceGraph, part: torch.Tensor, n_parts: int, p: int) -> DeviceShare:
+    """Size query, allocation of exactly sized outputs, then the real call."""
+    n = g.n_nodes
+    nil = 0
+
+    def call(cap_local, cap_col, cap_send, outs, ws):
+        return B.retexo_partition_share(n, g.row_ptr.data_ptr(), g.col_idx.data_ptr(), part.data_ptr(), n_parts, p,
+                                        cap_local, cap_col, cap_send, *outs, ws.data_ptr(), ws.numel(), _stream_ptr())
+    need = B.retexo_partition_workspace_bytes(n, n_parts, 0)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_partition_workspace_bytes")
+    st, sizes, _, _ = call(0, 0, 0, (nil,) * 6, ws_tensor(need))
+    if st != -11:                 # the size query always ends in the capacity error
+        raise B.RetexoError(st, "retexo_partition_share (size query)")
+    n_inner, n_halo, nnz_local, n_send = sizes
+    n_local = n_inner + n_halo
+    i32 = lambda k: torch.empty(max(k, 1), dtype=torch.int32, device="cuda")
+    local_ids, col, gdeg, send, recv = i32(n_local), i32(nnz_local), i32(n_local), i32(n_send), i32(n_halo)
+    rp = torch.empty(n_local + 1, dtype=torch.int64, device="cuda")
+    ws = ws_tensor(B.retexo_partition_workspace_bytes(n, n_parts, n_send))
+    st, sizes2, so, ro = call(n_local, nnz_local, n_send,
+                              (local_ids.data_ptr(), rp.data_ptr(), col.data_ptr(), gdeg.data_ptr(),
+                               send.data_ptr(), recv.data_ptr()), ws)
+    B.check(st, "retexo_partition_share")
+    assert sizes2 == sizes
+    return DeviceShare(n_inner, n_halo, DeviceGraph(n_local, nnz_local, rp, col), local_ids[:n_local], gdeg[:n_local],
+                       send[:n_send], recv[:n_halo], so, ro)
+
+
+def halo_pack(ids: torch.Tensor, H: torch.Tensor, F: int, buf: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n = int(ids.numel())
+    if buf is None:
+        buf = torch.empty((max(n, 1), pad_ld(F)), dtype=torch.float32, device="cuda")
+    B.check(B.retexo_halo_pack(n, ids.data_ptr() if n else 0, H.shape[0], F, H.data_ptr(), H.stride(0),
+                               buf.data_ptr(), buf.stride(0), _stream_ptr()), "retexo_halo_pack")
+    return buf
+
+
+def halo_unpack(ids: torch.Tensor, buf: torch.Tensor, H: torch.Tensor, F: int) -> None:
+    n = int(ids.numel())
+    B.check(B.retexo_halo_unpack(n, ids.data_ptr() if n else 0, H.shape[0], F, buf.data_ptr(), buf.stride(0),
+                                 H.data_ptr(), H.stride(0), _stream_ptr()), "retexo_halo_unpack")
+
+
 def plan_arrays(g: DeviceGraph):
     """(deg int32[N], dinv float32[N], order int32[N]) copied out of the plan, as numpy."""
     n = g.n_nodes
