@@ -239,7 +239,11 @@ __global__ __launch_bounds__(kThreads) void rows_kernel(
     float* d = SCATTER ? dst + r * ldd + c : dst + i * ldd + c;
     if constexpr (VEC == 4) {
         typedef float f4 __attribute__((ext_vector_type(4)));
-        *reinterpret_cast<f4*>(d) = *reinterpret_cast<const f4*>(s);
+        if (c + 4 <= F) {
+            *reinterpret_cast<f4*>(d) = *reinterpret_cast<const f4*>(s);
+        } else {                                          // ragged last vector of a row
+            for (int k = 0; k < (int)(F - c); ++k) d[k] = s[k];
+        }
     } else {
         *d = *s;
     }
@@ -298,8 +302,8 @@ int launch_rows(int64_t n, const int32_t* ids, int64_t table_rows, int64_t F, co
                 float* dst, int64_t ldd, hipStream_t stream)
 {
     if (n == 0 || F == 0) return RETEXO_OK;
-    const bool v4 = F % 4 == 0 && lds % 4 == 0 && ldd % 4 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)dst % 16 == 0;
-    const int64_t threads = n * (v4 ? F / 4 : F);
+    const bool v4 = lds % 4 == 0 && ldd % 4 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)dst % 16 == 0;
+    const int64_t threads = n * (v4 ? (F + 3) / 4 : F);
     const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
     if (v4) rows_kernel<4, SCATTER><<<grid, dim3(kThreads), 0, stream>>>(n, ids, table_rows, F, src, lds, dst, ldd);
     else rows_kernel<1, SCATTER><<<grid, dim3(kThreads), 0, stream>>>(n, ids, table_rows, F, src, lds, dst, ldd);
