@@ -59,7 +59,9 @@ def _load():
                                                   f64p, f64p, f64p]
         lib.oracle_layer_grad.restype = C.c_double
         lib.oracle_layer_grad.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f32p, f32p, f32p, f32p,
-                                          f64p, f64p, f64p, f64p]
+                                          f64p, f64p, f64p, f64p, f64p]
+        lib.oracle_transform_backward.restype = None
+        lib.oracle_transform_backward.argtypes = [i64, i64, i64, f32p, i64, f32p, i64, f64p, f64p]
         lib.oracle_layer_loss.restype = C.c_double
         lib.oracle_layer_loss.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f64p, f64p, f64p, f64p]
         _lib = lib
@@ -231,10 +233,11 @@ def round_(mode: str, row_ptr, col_idx, H, d_in: int, W, b, *, relu: bool = Fals
                      slope=slope, self_concat=self_concat, rows=rows)
 
 
-def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None):
+def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None, input_grad: bool = False):
     """Loss and parameter gradients of one locally trained layer (see oracle_layer_grad).
     Wc None: the layer is the final classifier (logits = X W1 + b1).
-    -> (loss, gW1, gb1, gWc or None, gbc or None), float64."""
+    -> (loss, gW1, gb1, gWc or None, gbc or None), float64; with ``input_grad`` a sixth item,
+    dL/dX [n, d_in]."""
     X, ldx = _matrix(X)
     labels = _c(labels, np.int32)
     W1, b1 = _c(W1, np.float32), _c(b1, np.float32)
@@ -252,11 +255,26 @@ def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None):
         gbc = np.empty(Cc, np.float64)
     gW1 = np.empty(W1.shape, np.float64)
     gb1 = np.empty(W1.shape[1], np.float64)
+    gX = np.empty((n, d_in), np.float64) if input_grad else None
     loss = _load().oracle_layer_grad(n, d_in, H, Cc, _p(X, C.c_float), ldx, _p(labels, C.c_int32),
                                      _p(W1, C.c_float), _p(b1, C.c_float), _p(Wc_, C.c_float),
                                      _p(bc_, C.c_float), _p(gW1, C.c_double), _p(gb1, C.c_double),
-                                     _p(gWc, C.c_double), _p(gbc, C.c_double))
+                                     _p(gWc, C.c_double), _p(gbc, C.c_double), _p(gX, C.c_double))
+    if input_grad:
+        return float(loss), gW1, gb1, gWc, gbc, gX
     return float(loss), gW1, gb1, gWc, gbc
+
+
+def transform_backward(H, d_in: int, dZ, d_out: int):
+    """-> (gW [d_in, d_out], gb [d_out]) float64: gradients of Z = H W + b given dZ = dL/dZ."""
+    H, ldh = _matrix(H)
+    dZ, lddz = _matrix(dZ)
+    n = H.shape[0]
+    assert dZ.shape[0] == n and d_in <= H.shape[1] and d_out <= dZ.shape[1]
+    gW, gb = np.empty((d_in, d_out), np.float64), np.empty(d_out, np.float64)
+    _load().oracle_transform_backward(n, d_in, d_out, _p(H, C.c_float), ldh, _p(dZ, C.c_float), lddz,
+                                      _p(gW, C.c_double), _p(gb, C.c_double))
+    return gW, gb
 
 
 def layer_loss(X, d_in: int, labels, W1, b1, Wc=None, bc=None) -> float:

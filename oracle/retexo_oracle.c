@@ -442,15 +442,19 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
  *      logits = X W1 + b1   (W1 is [D_in, C]).
  * A node with label < 0 is not a training node and contributes nothing.
  * This function returns the loss and its gradient with respect to every
- * parameter, all in double:  gW1 [D_in, H or C], gb1, gWc [H, C], gbc [C].
+ * parameter, all in double:  gW1 [D_in, H or C], gb1, gWc [H, C], gbc [C];
+ * and, when gX is not NULL, with respect to the layer's input, gX [N, D_in]
+ * (zero rows for nodes that are not training nodes) — what flows back into an
+ * aggregation with trainable parameters that produced X.
  * With no labelled node the loss and all gradients are zero.
  */
 double oracle_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
                          const float *X, int64_t ldx, const int32_t *labels,
                          const float *W1, const float *b1, const float *Wc, const float *bc,
-                         double *gW1, double *gb1, double *gWc, double *gbc)
+                         double *gW1, double *gb1, double *gWc, double *gbc, double *gX)
 {
     const int64_t W1cols = H > 0 ? H : C;
+    if (gX) for (int64_t i = 0; i < N * D_in; ++i) gX[i] = 0.0;
     for (int64_t i = 0; i < D_in * W1cols; ++i) gW1[i] = 0.0;
     for (int64_t i = 0; i < W1cols; ++i) gb1[i] = 0.0;
     if (H > 0) {
@@ -507,18 +511,51 @@ double oracle_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
             for (int64_t j = 0; j < H; ++j) gb1[j] += da[j];
             for (int64_t k = 0; k < D_in; ++k) {
                 const double xk = (double)x[k];
-                for (int64_t j = 0; j < H; ++j) gW1[k * H + j] += xk * da[j];
+                double gx = 0.0;
+                for (int64_t j = 0; j < H; ++j) {
+                    gW1[k * H + j] += xk * da[j];
+                    gx += da[j] * (double)W1[k * H + j];
+                }
+                if (gX) gX[v * D_in + k] = gx;
             }
         } else {
             for (int64_t c = 0; c < C; ++c) gb1[c] += z[c];
             for (int64_t k = 0; k < D_in; ++k) {
                 const double xk = (double)x[k];
-                for (int64_t c = 0; c < C; ++c) gW1[k * C + c] += xk * z[c];
+                double gx = 0.0;
+                for (int64_t c = 0; c < C; ++c) {
+                    gW1[k * C + c] += xk * z[c];
+                    gx += z[c] * (double)W1[k * C + c];
+                }
+                if (gX) gX[v * D_in + k] = gx;
             }
         }
     }
     free(a); free(z); free(da);
     return loss / (double)n_lab;
+}
+
+/*
+ * Parameter gradients of the dense transform Z = H W + b given dZ = dL/dZ:
+ *      gW[k, j] = sum_v H[v, k] dZ[v, j],    gb[j] = sum_v dZ[v, j]
+ * (the transform in front of an aggregation is trained through the
+ * aggregation's backward, which supplies dZ).
+ */
+void oracle_transform_backward(int64_t N, int64_t D_in, int64_t D_out, const float *H, int64_t ldh,
+                               const float *dZ, int64_t lddz, double *gW, double *gb)
+{
+    for (int64_t j = 0; j < D_out; ++j) {
+        double s = 0.0;
+        for (int64_t v = 0; v < N; ++v) s += (double)dZ[v * lddz + j];
+        gb[j] = s;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < D_in; ++k)
+        for (int64_t j = 0; j < D_out; ++j) {
+            double s = 0.0;
+            for (int64_t v = 0; v < N; ++v) s += (double)H[v * ldh + k] * (double)dZ[v * lddz + j];
+            gW[k * D_out + j] = s;
+        }
 }
 
 /* The loss alone (same formula), used by the tests to difference numerically. */

@@ -211,3 +211,50 @@ def test_max_has_no_backward():
     ci = np.array([1, 0], np.int32)
     with pytest.raises(ValueError):
         oracle.aggregate_backward("max", rp, ci, np.ones((2, 2), np.float32), 2, np.ones((2, 2), np.float32))
+
+
+def test_attention_layer_chain_matches_end_to_end_autograd():
+    """A whole locally trained attention layer, composed from the oracle's pieces the way the GPU path
+    composes its entry points — transform, edge-softmax aggregation, dense layer + temporary classifier
+    + loss, and back: input gradient, aggregation backward, transform backward — against torch autograd
+    of the same network written densely in float64.  (The pieces hand float32 tables to each other,
+    hence the 1e-5 tolerance.)"""
+    n, d_in, F, heads, Hd, C, slope = 30, 7, 12, 3, 6, 4, 0.2
+    src, dst = wl.random_pairs(n, 80, 6, skew=1.0)
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    A = np.zeros((n, n), bool)
+    A[np.repeat(np.arange(n), np.diff(rp)), ci] = True
+    rng = np.random.Generator(np.random.Philox(key=12))
+    Q = wl.random_matrix(n, d_in, 1)
+    Wg = (rng.standard_normal((d_in, F)) * 0.4).astype(np.float32)
+    bg = (rng.standard_normal(F) * 0.1).astype(np.float32)
+    a_s = (rng.standard_normal((heads, F // heads)) * 0.5).astype(np.float32)
+    a_d = (rng.standard_normal((heads, F // heads)) * 0.5).astype(np.float32)
+    W1 = (rng.standard_normal((F, Hd)) * 0.4).astype(np.float32)
+    b1 = (rng.standard_normal(Hd) * 0.1).astype(np.float32)
+    Wc = (rng.standard_normal((Hd, C)) * 0.4).astype(np.float32)
+    bc = (rng.standard_normal(C) * 0.1).astype(np.float32)
+    y = rng.integers(0, C, n).astype(np.int32)
+    y[rng.random(n) > 0.7] = -1
+    # the oracle's chain
+    Z = oracle.transform(Q, d_in, Wg, bg).astype(np.float32)
+    X = oracle.aggregate("gat_softmax", rp, ci, Z, F, heads=heads, a_src=a_s, a_dst=a_d, slope=slope).astype(np.float32)
+    loss, gW1, gb1, gWc, gbc, gX = oracle.layer_grad(X, F, y, W1, b1, Wc, bc, input_grad=True)
+    dZ, das, dad = oracle.aggregate_backward("gat_softmax", rp, ci, Z, F, gX.astype(np.float32), heads=heads,
+                                             a_src=a_s, a_dst=a_d, slope=slope)
+    gWg, gbg = oracle.transform_backward(Q, d_in, dZ.astype(np.float32), F)
+    # the same network, dense, float64, differentiated by torch
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64)).requires_grad_(True)
+    tWg, tbg, tas, tad, tW1, tb1, tWc, tbc = (t(a) for a in (Wg, bg, a_s, a_d, W1, b1, Wc, bc))
+    tZ = torch.from_numpy(Q.astype(np.float64)) @ tWg + tbg
+    tX = dense_forward_torch("gat_softmax", A, tZ, tas, tad, heads, slope, False)
+    logits = torch.relu(tX @ tW1 + tb1) @ tWc + tbc
+    lab = torch.from_numpy(y >= 0)
+    tl = torch.nn.functional.cross_entropy(logits[lab], torch.from_numpy(y.astype(np.int64))[lab])
+    tl.backward()
+    assert abs(loss - float(tl.detach())) < 1e-6
+    for got, ref, name in ((gWg, tWg, "W_g"), (gbg, tbg, "b_g"), (das, tas, "a_src"), (dad, tad, "a_dst"),
+                           (gW1, tW1, "W1"), (gb1, tb1, "b1"), (gWc, tWc, "Wc"), (gbc, tbc, "bc")):
+        ref = ref.grad.numpy()
+        assert np.abs(ref).max() > 1e-4, name
+        assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max(), name

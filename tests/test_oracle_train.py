@@ -124,3 +124,54 @@ def test_structure_of_the_gradients():
     lr = 0.1
     new = oracle.layer_loss(X, d_in, y, W1 - lr * gW1, b1 - lr * gb1, Wc - lr * gWc, bc - lr * gbc)
     assert new < loss
+
+
+@pytest.mark.parametrize("h", [0, 5])
+def test_input_gradient_matches_dense_algebra_and_differences(h):
+    """dL/dX, the gradient that flows back into an aggregation in front of the layer."""
+    n, d_in, c = 40, 6, 4
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, 6)
+    out = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, input_grad=True)
+    gX = out[5]
+    assert out[:1] == oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc)[:1]
+    Xd = X[:, :d_in].astype(np.float64)
+    lab = y >= 0
+    Y = np.zeros((n, c))
+    Y[lab, y[lab]] = 1
+    pre = Xd @ W1 + b1
+    Z = (np.maximum(pre, 0) @ Wc + bc) if h else pre
+    Z = Z - Z.max(1, keepdims=True)
+    P = np.exp(Z) / np.exp(Z).sum(1, keepdims=True)
+    dZ = (P - Y) * lab[:, None] / lab.sum()
+    want = ((dZ @ Wc.astype(np.float64).T) * (pre > 0)) @ W1.astype(np.float64).T if h else dZ @ W1.astype(np.float64).T
+    assert np.allclose(gX, want, atol=1e-14)
+    assert np.all(gX[~lab] == 0) and np.abs(gX[lab]).min() > 0
+    # central differences of the loss in perturbations that are exact in float32
+    grid = np.float32(2.0 ** -12)
+    Xq = X.copy()
+    Xq[:, :d_in] = np.round(X[:, :d_in] / grid) * grid
+    gXq = oracle.layer_grad(Xq, d_in, y, W1, b1, Wc, bc, input_grad=True)[5]
+    f = lambda Xp: oracle.layer_loss(Xp, d_in, y, W1, b1, Wc, bc) if h else oracle.layer_loss(Xp, d_in, y, W1, b1)
+    t = np.float32(2.0 ** -9)
+    rng = np.random.Generator(np.random.Philox(key=4))
+    for _ in range(4):
+        D = np.zeros_like(Xq)
+        D[:, :d_in] = rng.integers(-1, 2, (n, d_in))
+        num = (f(Xq + t * D) - f(Xq - t * D)) / (2 * float(t))
+        assert abs(num - (gXq * D[:, :d_in]).sum()) < 1e-6 * max(1.0, abs(num))
+
+
+def test_transform_backward_is_the_transposed_product():
+    n, d_in, d_out = 70, 9, 5
+    H = wl.random_matrix(n, d_in, 1, ld=d_in + 2)
+    dZ = wl.random_matrix(n, d_out, 2, ld=d_out + 3)
+    H[:, d_in:] = 1e30
+    dZ[:, d_out:] = 1e30
+    gW, gb = oracle.transform_backward(H, d_in, dZ, d_out)
+    assert np.allclose(gW, H[:, :d_in].astype(np.float64).T @ dZ[:, :d_out].astype(np.float64), rtol=1e-13, atol=1e-13)
+    assert np.allclose(gb, dZ[:, :d_out].astype(np.float64).sum(0), rtol=1e-13, atol=1e-13)
+    # adjoint of the oracle's own forward: <dZ, H W + b> = <gW, W> + <gb, b>
+    W = wl.random_matrix(d_in, d_out, 3)
+    b = wl.random_matrix(1, d_out, 4)[0]
+    Z = oracle.transform(H, d_in, W, b)
+    assert np.isclose((Z * dZ[:, :d_out]).sum(), (gW * W).sum() + (gb * b).sum(), rtol=1e-12)
