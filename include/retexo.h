@@ -245,6 +245,30 @@ int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
                       void* d_workspace, int64_t workspace_bytes, void* stream);
 int retexo_sgd_update(int64_t n, float* d_param, const float* d_grad, float lr, void* stream);
 
+/* retexo_layer_grad that also returns the gradient with respect to the layer's input,
+ * d_gX [N, ldgx] (first D_in columns; zero rows for nodes that are not training nodes), when
+ * d_gX is not NULL.  This is what flows back into an aggregation with trainable parameters
+ * that produced X: d_gX is the d_G of retexo_aggregate_backward.  d_gX must not overlap d_X.
+ * Same workspace as retexo_layer_grad. */
+int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                        const float* d_X, int64_t ldx, const int32_t* d_labels,
+                        const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                        float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                        float* d_gX, int64_t ldgx,
+                        void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* Parameter gradients of the dense transform Z = H W + b (the transform in front of an
+ * aggregation, trained through retexo_aggregate_backward, which supplies d_dZ = dL/dZ):
+ *     gW[k, j] = sum_v H[v, k] dZ[v, j]   (d_gW [D_in, D_out], dense)
+ *     gb[j]    = sum_v dZ[v, j]           (d_gb [D_out], or NULL to skip)
+ * Summed over node chunks in a fixed order (no atomics).  d_workspace:
+ * retexo_transform_backward_workspace_bytes(N, D_in, D_out) bytes, 256-aligned.  Enqueues on `stream`. */
+int64_t retexo_transform_backward_workspace_bytes(int64_t N, int64_t D_in, int64_t D_out);
+int retexo_transform_backward(int64_t N, int64_t D_in, int64_t D_out,
+                              const float* d_H, int64_t ldh, const float* d_dZ, int64_t lddz,
+                              float* d_gW, float* d_gb,
+                              void* d_workspace, int64_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------
  * One worker's share of an edge-partitioned graph (section "Edge-partitioned
  * Distributed Setup": worker i holds its inner nodes V_i, the edges touching

@@ -32,6 +32,7 @@ EXPORTS = (
     "retexo_partition_workspace_bytes", "retexo_partition_share", "retexo_halo_pack", "retexo_halo_unpack",
     "retexo_plan_set_degrees",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
+    "retexo_layer_grad_x", "retexo_transform_backward_workspace_bytes", "retexo_transform_backward",
 )
 
 _lib = None
@@ -108,6 +109,13 @@ def load():
     lib.retexo_layer_grad.restype = i32
     lib.retexo_layer_grad.argtypes = [i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                       vp, i64, vp]
+    lib.retexo_layer_grad_x.restype = i32
+    lib.retexo_layer_grad_x.argtypes = [i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                        vp, i64, vp, i64, vp]
+    lib.retexo_transform_backward_workspace_bytes.restype = i64
+    lib.retexo_transform_backward_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.retexo_transform_backward.restype = i32
+    lib.retexo_transform_backward.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.retexo_sgd_update.restype = i32
     lib.retexo_sgd_update.argtypes = [i64, vp, vp, f32, vp]
     lib.retexo_set_option.restype = i32
@@ -253,6 +261,24 @@ def retexo_layer_grad(n, d_in, h, c, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc,
                                         _vp(d_Wc), _vp(d_bc), _vp(d_gW1), _vp(d_gb1), _vp(d_gWc),
                                         _vp(d_gbc), _vp(d_loss), _vp(d_workspace), workspace_bytes,
                                         _vp(stream)))
+
+
+def retexo_layer_grad_x(n, d_in, h, c, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc, d_gW1, d_gb1, d_gWc, d_gbc,
+                        d_loss, d_gX, ldgx, d_workspace, workspace_bytes, stream=0) -> int:
+    return int(load().retexo_layer_grad_x(n, d_in, h, c, _vp(d_X), ldx, _vp(d_labels), _vp(d_W1), _vp(d_b1),
+                                          _vp(d_Wc), _vp(d_bc), _vp(d_gW1), _vp(d_gb1), _vp(d_gWc), _vp(d_gbc),
+                                          _vp(d_loss), _vp(d_gX), ldgx, _vp(d_workspace), workspace_bytes,
+                                          _vp(stream)))
+
+
+def retexo_transform_backward_workspace_bytes(n, d_in, d_out) -> int:
+    return int(load().retexo_transform_backward_workspace_bytes(n, d_in, d_out))
+
+
+def retexo_transform_backward(n, d_in, d_out, d_H, ldh, d_dZ, lddz, d_gW, d_gb, d_workspace, workspace_bytes,
+                              stream=0) -> int:
+    return int(load().retexo_transform_backward(n, d_in, d_out, _vp(d_H), ldh, _vp(d_dZ), lddz, _vp(d_gW),
+                                                _vp(d_gb), _vp(d_workspace), workspace_bytes, _vp(stream)))
 
 
 def retexo_sgd_update(n, d_param, d_grad, lr, stream=0) -> int:

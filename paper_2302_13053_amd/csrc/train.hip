@@ -370,7 +370,7 @@ void colsum(int64_t N, int64_t C, const float* D, int64_t ld, float* part, float
 
 struct TrainLayout {
     int64_t ldh, ldc;
-    int64_t hdr, A, L, dA, WcT, part, colpart, losspart, total;
+    int64_t hdr, A, L, dA, WcT, W1T, part, colpart, losspart, total;
 };
 
 int64_t partial_floats(int64_t K, int64_t M, int64_t Nq)
@@ -392,6 +392,7 @@ TrainLayout make_layout(int64_t N, int64_t D_in, int64_t H, int64_t C)
     t.L = take(n1 * t.ldc);
     t.dA = take(H > 0 ? n1 * t.ldh : 0);
     t.WcT = take(H > 0 ? t.ldc * H : 0);
+    t.W1T = take((H > 0 ? H : t.ldc) * D_in);            // transposed first-layer weights (input gradient)
     int64_t pf = 0;
     if (H > 0) {
         pf = partial_floats(N, D_in, t.ldh);
@@ -423,14 +424,20 @@ extern "C" int64_t retexo_train_workspace_bytes(int64_t N, int64_t D_in, int64_t
     return make_layout(N, D_in, H, C).total;
 }
 
-extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
-                                 const float* d_X, int64_t ldx, const int32_t* d_labels,
-                                 const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
-                                 float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
-                                 void* d_workspace, int64_t workspace_bytes, void* stream_)
+extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                                   const float* d_X, int64_t ldx, const int32_t* d_labels,
+                                   const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                                   float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                                   float* d_gX, int64_t ldgx,
+                                   void* d_workspace, int64_t workspace_bytes, void* stream_)
 {
     if (int s = check_sizes(N, D_in, H, C)) return s;
     if (ldx < D_in) return RETEXO_E_LD;
+    if (d_gX && ldgx < D_in) return RETEXO_E_LD;
+    if (d_gX && N > 0 && d_X &&
+        !((const char*)d_gX + (size_t)((N - 1) * ldgx + D_in) * 4 <= (const char*)d_X ||
+          (const char*)d_X + (size_t)((N - 1) * ldx + D_in) * 4 <= (const char*)d_gX))
+        return RETEXO_E_ALIAS;
     if (!d_W1 || !d_b1 || !d_gW1 || !d_gb1 || !d_loss) return RETEXO_E_NULL;
     if (N > 0 && (!d_X || !d_labels)) return RETEXO_E_NULL;
     if (H > 0 && (!d_Wc || !d_bc || !d_gWc || !d_gbc)) return RETEXO_E_NULL;
@@ -444,6 +451,7 @@ extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
     float* L = (float*)(ws + t.L);
     float* dA = (float*)(ws + t.dA);
     float* WcT = (float*)(ws + t.WcT);
+    float* W1T = (float*)(ws + t.W1T);
     float* part = (float*)(ws + t.part);
     float* colpart = (float*)(ws + t.colpart);
     float* losspart = (float*)(ws + t.losspart);
@@ -497,7 +505,75 @@ extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
         // (padding columns of dA only produce partial columns that reduce_partials never reads)
         wgrad(N, D_in, t.ldh, H, d_X, ldx, dA, t.ldh, part, d_gW1, stream);
         colsum(N, H, dA, t.ldh, colpart, d_gb1, stream);
+        if (d_gX) {
+            // dL/dX = dA W1^T, contracted over exactly H columns (dA's padding columns are not written)
+            const int64_t tot1 = H * D_in;
+            transpose_kernel<<<dim3((unsigned)((tot1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+                (int)D_in, (int)H, (int)H, d_W1, W1T);
+            if (int e = launch_transform(N, H, D_in, dA, t.ldh, W1T, nullptr, false, d_gX, ldgx, stream)) return e;
+        }
+    } else if (d_gX) {
+        // dL/dX = dL W1^T over the padded width of dL (its padding columns and the padding rows of W1^T are zero)
+        const int64_t tot1 = t.ldc * D_in;
+        transpose_kernel<<<dim3((unsigned)((tot1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            (int)D_in, (int)C, (int)t.ldc, d_W1, W1T);
+        if (int e = launch_transform(N, t.ldc, D_in, L, t.ldc, W1T, nullptr, false, d_gX, ldgx, stream)) return e;
     }
+    if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
+    return RETEXO_OK;
+}
+
+extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                                 const float* d_X, int64_t ldx, const int32_t* d_labels,
+                                 const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                                 float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                                 void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    return retexo_layer_grad_x(N, D_in, H, C, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc, d_gW1, d_gb1, d_gWc,
+                               d_gbc, d_loss, nullptr, 0, d_workspace, workspace_bytes, stream);
+}
+
+namespace {
+struct TbLayout { int64_t part, colpart, total; };
+TbLayout tb_layout(int64_t N, int64_t D_in, int64_t D_out)
+{
+    TbLayout t;
+    const int64_t n1 = N > 0 ? N : 1;
+    int64_t off = 0;
+    auto take = [&](int64_t floats) { const int64_t at = off; off += align_up(floats * 4, 256); return at; };
+    t.part = take(partial_floats(n1, D_in, D_out));
+    t.colpart = take(((n1 + kColRows - 1) / kColRows) * D_out);
+    t.total = off;
+    return t;
+}
+}  // namespace
+
+extern "C" int64_t retexo_transform_backward_workspace_bytes(int64_t N, int64_t D_in, int64_t D_out)
+{
+    if (int s = check_sizes(N, D_in, 0, D_out)) return s;
+    return tb_layout(N, D_in, D_out).total;
+}
+
+extern "C" int retexo_transform_backward(int64_t N, int64_t D_in, int64_t D_out,
+                                         const float* d_H, int64_t ldh, const float* d_dZ, int64_t lddz,
+                                         float* d_gW, float* d_gb,
+                                         void* d_workspace, int64_t workspace_bytes, void* stream_)
+{
+    if (int s = check_sizes(N, D_in, 0, D_out)) return s;
+    if (ldh < D_in || lddz < D_out) return RETEXO_E_LD;
+    if (!d_gW) return RETEXO_E_NULL;
+    if (N > 0 && (!d_H || !d_dZ)) return RETEXO_E_NULL;
+    const TbLayout t = tb_layout(N, D_in, D_out);
+    if (!d_workspace || workspace_bytes < t.total || ((uintptr_t)d_workspace & 255)) return RETEXO_E_WORKSPACE;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (N == 0) {
+        RETEXO_HIP_TRY(hipMemsetAsync(d_gW, 0, (size_t)(D_in * D_out) * 4, stream));
+        if (d_gb) RETEXO_HIP_TRY(hipMemsetAsync(d_gb, 0, (size_t)D_out * 4, stream));
+        return RETEXO_OK;
+    }
+    char* ws = (char*)d_workspace;
+    wgrad(N, D_in, D_out, D_out, d_H, ldh, d_dZ, lddz, (float*)(ws + t.part), d_gW, stream);
+    if (d_gb) colsum(N, D_out, d_dZ, lddz, (float*)(ws + t.colpart), d_gb, stream);
     if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
     return RETEXO_OK;
 }

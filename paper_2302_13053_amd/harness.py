@@ -218,9 +218,27 @@ def round_(g: DeviceGraph, st: Stage, H: torch.Tensor, W, b, a_src, a_dst, out: 
     B.check(rc, "retexo_round")
 
 
+def transform_backward(H: torch.Tensor, d_in: int, dZ: torch.Tensor, d_out: int,
+                       workspace: Optional[torch.Tensor] = None):
+    """-> (gW [d_in, d_out], gb [d_out]) of Z = H W + b given dZ = dL/dZ."""
+    n = int(H.shape[0])
+    need = B.retexo_transform_backward_workspace_bytes(n, d_in, d_out)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_transform_backward_workspace_bytes")
+    if workspace is None:
+        workspace = ws_tensor(need)
+    gW = torch.empty((d_in, d_out), dtype=torch.float32, device="cuda")
+    gb = torch.empty(d_out, dtype=torch.float32, device="cuda")
+    B.check(B.retexo_transform_backward(n, d_in, d_out, H.data_ptr(), H.stride(0), dZ.data_ptr(), dZ.stride(0),
+                                        gW.data_ptr(), gb.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                        _stream_ptr()), "retexo_transform_backward")
+    return gW, gb
+
+
 def layer_grad(X: torch.Tensor, d_in: int, labels: torch.Tensor, W1, b1, Wc=None, bc=None,
-               workspace: Optional[torch.Tensor] = None):
-    """Loss and gradients of one locally trained layer -> (loss [1], gW1, gb1, gWc, gbc) device tensors."""
+               workspace: Optional[torch.Tensor] = None, gX: Optional[torch.Tensor] = None):
+    """Loss and gradients of one locally trained layer -> (loss [1], gW1, gb1, gWc, gbc) device tensors;
+    with ``gX`` given, dL/dX is written into it as well."""
     n = int(labels.numel())
     h = 0 if Wc is None else int(W1.shape[1])
     c = int(W1.shape[1]) if Wc is None else int(Wc.shape[1])
@@ -234,9 +252,14 @@ def layer_grad(X: torch.Tensor, d_in: int, labels: torch.Tensor, W1, b1, Wc=None
     gbc = torch.empty_like(bc) if Wc is not None else None
     loss = torch.empty(1, dtype=torch.float32, device="cuda")
     p = lambda t: t.data_ptr() if t is not None else 0
-    st = B.retexo_layer_grad(n, d_in, h, c, X.data_ptr(), X.stride(0), labels.data_ptr(), p(W1), p(b1), p(Wc),
-                             p(bc), p(gW1), p(gb1), p(gWc), p(gbc), loss.data_ptr(), workspace.data_ptr(),
-                             workspace.numel(), _stream_ptr())
+    if gX is None:
+        st = B.retexo_layer_grad(n, d_in, h, c, X.data_ptr(), X.stride(0), labels.data_ptr(), p(W1), p(b1), p(Wc),
+                                 p(bc), p(gW1), p(gb1), p(gWc), p(gbc), loss.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel(), _stream_ptr())
+    else:
+        st = B.retexo_layer_grad_x(n, d_in, h, c, X.data_ptr(), X.stride(0), labels.data_ptr(), p(W1), p(b1), p(Wc),
+                                   p(bc), p(gW1), p(gb1), p(gWc), p(gbc), loss.data_ptr(), gX.data_ptr(),
+                                   gX.stride(0), workspace.data_ptr(), workspace.numel(), _stream_ptr())
     B.check(st, "retexo_layer_grad")
     return loss, gW1, gb1, gWc, gbc
 

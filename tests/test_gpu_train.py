@@ -131,3 +131,43 @@ def test_large_sage_layer_full_size_sampled_labels():
     got = run_gpu(X, d_in, y, W1, b1, Wc, bc)
     want = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc)
     compare(got, want, "full-size SAGE layer")
+
+
+@pytest.mark.parametrize("n,d_in,h,c,ld", [
+    (1000, 37, 5, 3, 37), (4099, 128, 64, 8, 128), (3000, 128, 0, 7, 128), (2500, 256, 256, 47, 256), (130, 16, 300, 5, 16),
+])
+def test_input_gradient_matches_oracle(n, d_in, h, c, ld):
+    """retexo_layer_grad_x: the same loss and parameter gradients, plus dL/dX."""
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, seed=n + h + 1, ld=ld)
+    d = lambda a: None if a is None else Hn.dev(a)
+    gX = torch.full((n, d_in + 5), 3.0, dtype=torch.float32, device="cuda")
+    out = Hn.layer_grad(d(X), d_in, d(y), d(W1), d(b1), d(Wc), d(bc), gX=gX)
+    torch.cuda.synchronize()
+    got = [None if t is None else t.cpu().numpy() for t in out]
+    want = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, input_grad=True)
+    compare(got, want[:5], "layer_grad_x %d x %d -> %d -> %d" % (n, d_in, h, c))
+    g = gX.cpu().numpy()
+    assert np.all(g[:, d_in:] == 3.0)
+    assert_close(g[:, :d_in], want[5], what="dL/dX")
+    assert np.all(g[y < 0, :d_in] == 0.0)
+    # same bits as the entry point without the input gradient
+    plain = run_gpu(X, d_in, y, W1, b1, Wc, bc)
+    assert all(np.array_equal(p, q) for p, q in zip(plain, got) if p is not None)
+    # the output may not lie over the input
+    Xd = d(X)
+    ws = Hn.ws_tensor(B.retexo_train_workspace_bytes(n, d_in, h, c))
+    with pytest.raises(B.RetexoError):
+        Hn.layer_grad(Xd, d_in, d(y), d(W1), d(b1), d(Wc), d(bc), workspace=ws, gX=Xd)
+
+
+@pytest.mark.parametrize("n,d_in,d_out,ldh,ldz", [(1000, 37, 5, 37, 5), (4099, 100, 256, 128, 256), (70000, 256, 188, 256, 192),
+                                                   (3, 1, 1, 1, 1), (513, 300, 700, 304, 704)])
+def test_transform_backward_matches_oracle(n, d_in, d_out, ldh, ldz):
+    H = wl.random_matrix(n, d_in, n, ld=ldh)
+    dZ = wl.random_matrix(n, d_out, n + 1, ld=ldz)
+    gW, gb = Hn.transform_backward(Hn.dev(H), d_in, Hn.dev(dZ), d_out)
+    torch.cuda.synchronize()
+    wW, wb = oracle.transform_backward(H, d_in, dZ, d_out)
+    assert_close(gW.cpu().numpy(), wW, what="transform backward gW")
+    assert_close(gb.cpu().numpy()[None, :], wb[None, :], what="transform backward gb")
+    assert B.retexo_transform_backward(n, d_in, d_out, 1, ldh, 1, d_out - 1, 1, 1, 1, 1 << 30) == -3
