@@ -1,0 +1,123 @@
+"""Lazy message passing as a whole on one GPU (section "Lazy Message Passing", the two-layer
+walk-through): aggregate the raw features once, train layer 1 alone with its temporary classifier,
+freeze it, compute its output for every node, aggregate once more, train the final classifier on the
+fixed aggregated inputs — no message passing inside either training loop.  The GPU run (library entry
+points only) is followed step by step by the same loop made of oracle pieces; a planted-community graph
+gives labels that the aggregations make easier to predict, so the accuracy has to rise layer by layer."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2302_13053_amd import binding as B
+from paper_2302_13053_amd import harness as Hn
+from paper_2302_13053_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def planted_graph(n, n_cls, pairs, f0, seed):
+    """Nodes in n_cls communities; 70 % of the pairs stay inside a community; features = a weak class
+    signal under unit noise, so a node alone is hard to classify and a neighbourhood mean is not."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    cls = rng.integers(0, n_cls, n).astype(np.int32)
+    members = [np.flatnonzero(cls == c) for c in range(n_cls)]
+    u = rng.integers(0, n, pairs)
+    same = rng.random(pairs) < 0.7
+    v = rng.integers(0, n, pairs)
+    pick = rng.random(pairs)
+    for c in range(n_cls):
+        sel = same & (cls[u] == c)
+        v[sel] = members[c][(pick[sel] * members[c].size).astype(np.int64)]
+    centres = rng.standard_normal((n_cls, f0)).astype(np.float32) * np.float32(0.15)
+    X = centres[cls] + rng.standard_normal((n, f0)).astype(np.float32)
+    train = rng.random(n) < 0.5
+    return u.astype(np.int32), v.astype(np.int32), cls, np.ascontiguousarray(X), train
+
+
+def accuracy(logits, cls, mask):
+    return float((np.argmax(logits[mask], axis=1) == cls[mask]).mean())
+
+
+def test_two_layer_lazy_message_passing_trains_and_matches_the_oracle_loop():
+    n, C, F0, Hd, steps, lr = 6000, 4, 32, 48, 40, 0.5
+    src, dst, cls, X0, train = planted_graph(n, C, 30000, F0, 5)
+    y = np.where(train, cls, -1).astype(np.int32)
+    test = ~train
+    rng = np.random.Generator(np.random.Philox(key=77))
+    W1, b1 = wl.glorot(rng, 2 * F0, Hd, (2 * F0, Hd)), np.zeros(Hd, np.float32)
+    Wc, bc = wl.glorot(rng, Hd, C, (Hd, C)), np.zeros(C, np.float32)
+    W2, b2 = wl.glorot(rng, 2 * Hd, C, (2 * Hd, C)), np.zeros(C, np.float32)
+
+    # ---- oracle loop: float64 gradients, float32 parameters and tables ----
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    oX1 = oracle.aggregate("mean", rp, ci, X0, F0, self_concat=True).astype(np.float32)
+    oW1, ob1, oWc, obc = W1.copy(), b1.copy(), Wc.copy(), bc.copy()
+    o_losses1 = []
+    for _ in range(steps):
+        loss, g1, g2, g3, g4 = oracle.layer_grad(oX1, 2 * F0, y, oW1, ob1, oWc, obc)
+        o_losses1.append(loss)
+        for p, g in ((oW1, g1), (ob1, g2), (oWc, g3), (obc, g4)):
+            p -= (lr * g).astype(np.float32)
+    oQ1 = oracle.transform(oX1, 2 * F0, oW1, ob1, relu=True).astype(np.float32)
+    o_acc1 = accuracy(oracle.transform(oQ1, Hd, oWc, obc), cls, test)
+    oX2 = oracle.aggregate("mean", rp, ci, oQ1, Hd, self_concat=True).astype(np.float32)
+    oW2, ob2 = W2.copy(), b2.copy()
+    o_losses2 = []
+    for _ in range(steps):
+        loss, g1, g2, _, _ = oracle.layer_grad(oX2, 2 * Hd, y, oW2, ob2)
+        o_losses2.append(loss)
+        oW2 -= (lr * g1).astype(np.float32)
+        ob2 -= (lr * g2).astype(np.float32)
+    o_acc2 = accuracy(oracle.transform(oX2, 2 * Hd, oW2, ob2), cls, test)
+    o_acc0 = accuracy(oracle.transform(X0, F0, *fit_raw(X0, F0, y, C, steps, lr)), cls, test)
+
+    # ---- GPU loop: library entry points only ----
+    d = Hn.dev
+    g = Hn.make_plan(Hn.csr_from_coo(d(src), d(dst), n, False))
+    dy = d(y)
+    X1 = Hn.aggregate(g, "mean", d(X0), F0, concat=True)                       # round 1: raw features
+    P1 = [d(W1), d(b1), d(Wc), d(bc)]
+    losses1 = train_layer(X1, 2 * F0, dy, P1, steps, lr)
+    Q1 = Hn.transform(X1, 2 * F0, P1[0], P1[1], True)                          # frozen layer 1, every node
+    acc1 = accuracy(Hn.transform(Q1, Hd, P1[2], P1[3], False).cpu().numpy()[:, :C], cls, test)
+    X2 = Hn.aggregate(g, "mean", Q1, Hd, concat=True)                          # round 2
+    P2 = [d(W2), d(b2)]
+    losses2 = train_layer(X2, 2 * Hd, dy, P2, steps, lr)
+    acc2 = accuracy(Hn.transform(X2, 2 * Hd, P2[0], P2[1], False).cpu().numpy()[:, :C], cls, test)
+    torch.cuda.synchronize()
+
+    # the two loops walk the same path
+    assert np.allclose(losses1, o_losses1, rtol=2e-4) and np.allclose(losses2, o_losses2, rtol=2e-4)
+    assert abs(acc1 - o_acc1) <= 0.01 and abs(acc2 - o_acc2) <= 0.01
+    # and the method does what it is for: each aggregation round makes the labels easier
+    assert losses1[-1] < 0.8 * losses1[0] and losses2[-1] < 0.8 * losses2[0]
+    assert acc2 > acc1 + 0.05 and acc1 > o_acc0 + 0.1 and acc2 > 0.75, (o_acc0, acc1, acc2)
+    g.destroy()
+
+
+def train_layer(X, d_in, dy, params, steps, lr):
+    """Full-batch SGD on one layer with the aggregated inputs fixed; -> loss per step."""
+    n = int(dy.numel())
+    hidden = len(params) == 4
+    h = int(params[0].shape[1]) if hidden else 0
+    c = int(params[2].shape[1]) if hidden else int(params[0].shape[1])
+    ws = Hn.ws_tensor(B.retexo_train_workspace_bytes(n, d_in, h, c))
+    out = []
+    for _ in range(steps):
+        loss, *grads = Hn.layer_grad(X, d_in, dy, *params, workspace=ws)
+        for p_, g_ in zip(params, grads):
+            B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), lr, Hn._stream_ptr()), "sgd")
+        out.append(float(loss.cpu()[0]))
+    return out
+
+
+def fit_raw(X0, F0, y, C, steps, lr):
+    """Baseline without any message passing: a linear classifier on the raw features (oracle pieces)."""
+    rng = np.random.Generator(np.random.Philox(key=3))
+    W, b = wl.glorot(rng, F0, C, (F0, C)), np.zeros(C, np.float32)
+    for _ in range(steps):
+        _, gW, gb, _, _ = oracle.layer_grad(X0, F0, y, W, b)
+        W -= (lr * gW).astype(np.float32)
+        b -= (lr * gb).astype(np.float32)
+    return W, b
