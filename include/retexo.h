@@ -324,6 +324,21 @@ int retexo_halo_unpack(int64_t n, const int32_t* d_ids, int64_t table_rows, int6
 int retexo_plan_set_degrees(retexo_plan* plan, const int32_t* d_deg, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * The communication-efficiency analysis as host arithmetic (no GPU involved): the network data
+ * volumes of the appendix "Communication-efficiency Analysis" and their ratio gamma, Eq. 2.
+ * n workers, B boundary nodes per worker (retexo_partition_share reports a worker's n_halo),
+ * R training rounds, H0 feature size, sum_H = H_1 + .. + H_{K-1}, sum_C = C_1 + .. + C_{K-1}
+ * (added classifier layers), M model size; sizes in one common unit.
+ * retexo_data_volumes writes out4 = { standard local training, lazy local training,
+ * standard gradient aggregation, lazy gradient aggregation }; RETEXO_E_SIZE unless
+ * n, B, H0, sum_H, sum_C >= 0 and R, M > 0.  retexo_gamma returns (out4[0] + out4[2]) /
+ * (out4[1] + out4[3]), which is Eq. 2, or -1 for invalid arguments.
+ */
+int retexo_data_volumes(double n, double B, double R, double H0, double sum_H, double sum_C, double M,
+                        double* out4);
+double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, double M);
+
+/* ---------------------------------------------------------------------------
  * Tuning knobs (process-wide, for experiments; defaults are chosen per shape).
  * name: "agg_slab_cols" (0 = auto), "agg_slab_major" (-1 auto / 0 / 1),
  *       "agg_heavy_degree" (rows at least this long get a whole workgroup),

@@ -30,7 +30,7 @@ EXPORTS = (
     "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
     "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward",
     "retexo_partition_workspace_bytes", "retexo_partition_share", "retexo_halo_pack", "retexo_halo_unpack",
-    "retexo_plan_set_degrees",
+    "retexo_plan_set_degrees", "retexo_data_volumes", "retexo_gamma",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
     "retexo_layer_grad_x", "retexo_transform_backward_workspace_bytes", "retexo_transform_backward",
 )
@@ -101,6 +101,10 @@ def load():
     lib.retexo_halo_unpack.argtypes = [i64, vp, i64, i64, vp, i64, vp, i64, vp]
     lib.retexo_plan_set_degrees.restype = i32
     lib.retexo_plan_set_degrees.argtypes = [vp, vp, vp]
+    lib.retexo_data_volumes.restype = i32
+    lib.retexo_data_volumes.argtypes = [C.c_double] * 7 + [C.POINTER(C.c_double)]
+    lib.retexo_gamma.restype = C.c_double
+    lib.retexo_gamma.argtypes = [C.c_double] * 6
     lib.retexo_round.restype = i32
     lib.retexo_round.argtypes = [vp, i32, i64, i64, i32, vp, i64, vp, vp, vp, vp, f32, u32, vp, i64,
                                  vp, i64, vp]
@@ -242,6 +246,17 @@ def retexo_halo_unpack(n, d_ids, table_rows, F, d_buf, ldb, d_H, ldh, stream=0) 
 
 def retexo_plan_set_degrees(plan, d_deg, stream=0) -> int:
     return int(load().retexo_plan_set_degrees(_vp(plan), _vp(d_deg), _vp(stream)))
+
+
+def retexo_data_volumes(n, B, R, H0, sum_H, sum_C, M):
+    """-> (status, [standard_lt, lazy_lt, standard_reduce, lazy_reduce])"""
+    out = (C.c_double * 4)()
+    st = load().retexo_data_volumes(n, B, R, H0, sum_H, sum_C, M, out)
+    return int(st), list(out)
+
+
+def retexo_gamma(B, R, H0, sum_H, sum_C, M) -> float:
+    return float(load().retexo_gamma(B, R, H0, sum_H, sum_C, M))
 
 
 def retexo_round(plan, mode, d_in, d_out, heads, d_H, ldh, d_W, d_b, d_attn_src, d_attn_dst,

@@ -142,6 +142,31 @@ extern "C" int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, in
     return launch_aggregate(c, (hipStream_t)stream);
 }
 
+// Network data volumes of the communication-efficiency analysis (host arithmetic only).
+// Appendix "Communication-efficiency Analysis": n workers, B boundary nodes per worker, R training
+// rounds, feature size H0, intermediate sizes summing to sum_H, added classifier sizes summing to
+// sum_C, model size M (all sizes in one unit, e.g. bytes).
+extern "C" int retexo_data_volumes(double n, double B, double R, double H0, double sum_H, double sum_C, double M,
+                                   double* out4)
+{
+    if (!out4) return RETEXO_E_NULL;
+    if (!(n >= 0.0) || !(B >= 0.0) || !(R > 0.0) || !(H0 >= 0.0) || !(sum_H >= 0.0) || !(sum_C >= 0.0) || !(M > 0.0))
+        return RETEXO_E_SIZE;
+    out4[0] = 2.0 * n * R * B * (sum_H + sum_H) + 2.0 * n * B * H0;     // standard, local training
+    out4[1] = 2.0 * n * B * sum_H + 2.0 * n * B * H0;                   // lazy, local training
+    out4[2] = n * R * M + n * R * M;                                    // standard, gradient aggregation
+    out4[3] = 2.0 * n * R * M + 2.0 * n * R * sum_C;                    // lazy, gradient aggregation
+    return RETEXO_OK;
+}
+
+// gamma of Eq. 2: total standard volume over total lazy volume (independent of n)
+extern "C" double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, double M)
+{
+    double v[4];
+    if (retexo_data_volumes(1.0, B, R, H0, sum_H, sum_C, M, v) != RETEXO_OK) return -1.0;
+    return (v[0] + v[2]) / (v[1] + v[3]);
+}
+
 extern "C" int64_t retexo_aggregate_backward_workspace_bytes(const retexo_plan* plan, int mode, int64_t F, int heads)
 {
     if (!plan) return RETEXO_E_NULL;
