@@ -324,6 +324,35 @@ def main():
         gbs = 2.0 * nnz * Fz * 4 / bms / 1e6              # two gather passes, one row of F floats per entry each
         out["aggregate_backward"] = {"shape": "%s F=%d heads=%d ld=%d" % (st.mode, Fz, st.heads, width), "ms": bms,
                                      "GB/s_algorithmic": gbs, "frac_hbm": gbs / 8000.0}
+    # the partition-shaped run: one worker's share of this graph (seeded random ownership over 4 workers for
+    # the dense graph, 2 for the large sparse one, as the paper distributes them) and the pack / unpack of all
+    # its boundary rows at the first round's width
+    if w.index in (3, 4):
+        n_workers = 4 if w.index == 3 else 2
+        owner = torch.from_numpy(np.random.Generator(np.random.Philox(key=70 + w.index))
+                                 .integers(0, n_workers, n).astype(np.int32)).cuda()
+        share = Hn.partition_share(pipe.graph, owner, n_workers, 0)             # size query + real call
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            share = Hn.partition_share(pipe.graph, owner, n_workers, 0)
+        torch.cuda.synchronize()
+        share_ms = (time.perf_counter() - t0) / reps * 1e3
+        Fp = w.stages[0].d_out
+        table = pipe.outs[0][:share.n_inner + share.n_halo]                      # any resident table of that width
+        buf = Hn.halo_pack(share.recv_ids, table, Fp)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            Hn.halo_pack(share.recv_ids, table, Fp, buf=buf)
+            Hn.halo_unpack(share.recv_ids, buf, table, Fp)
+        e1.record()
+        torch.cuda.synchronize()
+        pu_ms = e0.elapsed_time(e1) / reps
+        out["partition"] = {"workers": n_workers, "inner": share.n_inner, "boundary": share.n_halo,
+                            "local_entries": share.graph.nnz, "share_ms_incl_size_query_and_allocation": share_ms,
+                            "pack_plus_unpack_ms": pu_ms, "rows": share.n_halo, "width": Fp,
+                            "GB/s_read_plus_write": 4.0 * share.n_halo * Fp * 4 / pu_ms / 1e6}
     pipe.close()
     if not args.no_cpu:
         default_rows = w.n_nodes      # the oracle is fast enough to run every row of every stage in 10-30 s
