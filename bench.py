@@ -324,6 +324,32 @@ def main():
         gbs = 2.0 * nnz * Fz * 4 / bms / 1e6              # two gather passes, one row of F floats per entry each
         out["aggregate_backward"] = {"shape": "%s F=%d heads=%d ld=%d" % (st.mode, Fz, st.heads, width), "ms": bms,
                                      "GB/s_algorithmic": gbs, "frac_hbm": gbs / 8000.0}
+        # in a training loop: the forward in save mode, then the backward that reuses what it kept (one gather pass)
+        try:
+            sws = Hn.ws_tensor(B.retexo_workspace_bytes(pipe.graph.plan, Fz, B.MODES[st.mode], st.heads, B.F_SAVE))
+            fout = torch.empty_like(Zb)
+
+            def forward_save():
+                Hn.aggregate(pipe.graph, st.mode, Zb, Fz, heads=st.heads, a_src=a_s, a_dst=a_d, out=fout,
+                             workspace=sws, save=True)
+
+            def backward_saved():
+                Hn.aggregate_backward(pipe.graph, st.mode, Fz, Gb, Z=Zb, heads=st.heads, a_src=a_s, a_dst=a_d,
+                                      dZ=dZb, workspace=bws, saved=sws)
+            times = []
+            for fn in (forward_save, backward_saved):
+                fn()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) / reps)
+            out["aggregate_backward"].update({"forward_save_mode_ms": times[0], "backward_after_save_ms": times[1],
+                                              "GB/s_algorithmic_after_save": nnz * Fz * 4 / times[1] / 1e6})
+        except B.RetexoError:
+            pass                                           # layout without save mode: the plain backward stands
     # the partition-shaped run: one worker's share of this graph (seeded random ownership over 4 workers for
     # the dense graph, 2 for the large sparse one, as the paper distributes them) and the pack / unpack of all
     # its boundary rows at the first round's width

@@ -57,6 +57,8 @@ enum {
     RETEXO_F_RELU = 1,         /* transform: act = ReLU (Eq. 1's f)                   */
     RETEXO_F_SELF_CONCAT = 2,  /* aggregate: out row = [ z_v | aggregate ], 2F wide   */
     RETEXO_F_VALIDATE = 4,     /* plan_create: check the CSR on the device first      */
+    RETEXO_F_SAVE = 16,        /* aggregate (GAT_SOFTMAX): keep what the backward pass can
+                                  reuse in the workspace (retexo_aggregate_backward_saved) */
     RETEXO_F_SPLIT_ROWS = 8    /* plan_create: always build the per-row source-range split
                                   (by default only for dense graphs too large for L2)  */
 };
@@ -193,6 +195,27 @@ int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, int heads,
  * allocation, no synchronisation, no atomics (bitwise reproducible).
  */
 int64_t retexo_aggregate_backward_workspace_bytes(const retexo_plan* plan, int mode, int64_t F, int heads);
+
+/* The edge-softmax backward after a forward pass in save mode, one gather pass instead of two.
+ * In a training loop the forward runs anyway: retexo_aggregate(..., flags | RETEXO_F_SAVE, ...)
+ * with a workspace of retexo_workspace_bytes(plan, F, RETEXO_GAT_SOFTMAX, heads, flags |
+ * RETEXO_F_SAVE) bytes additionally leaves there the attention scores, each row's softmax
+ * statistics and the aggregate split into the parts that come from entries with a positive
+ * and with a non-positive score (the forward output is their sum, so in save mode it can
+ * differ from the plain forward's in the last bit).
+ * Pass that untouched workspace as d_saved (saved_bytes = its size); everything else as in
+ * retexo_aggregate_backward, same results within the same bound.  d_Z, the attention vectors
+ * and negative_slope must be those of the forward call.
+ * Save mode needs 16-byte aligned rows of d_Z (ldz % 4 == 0, aligned base) and a table below
+ * 4 GiB; otherwise retexo_aggregate returns RETEXO_E_FLAGS and the caller uses the plain
+ * backward. */
+int retexo_aggregate_backward_saved(const retexo_plan* plan, int mode, int64_t F, int heads,
+                                    const float* d_Z, int64_t ldz,
+                                    const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                                    unsigned flags, const float* d_G, int64_t ldg,
+                                    const void* d_saved, int64_t saved_bytes,
+                                    float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
+                                    void* d_workspace, int64_t workspace_bytes, void* stream);
 int retexo_aggregate_backward(const retexo_plan* plan, int mode, int64_t F, int heads,
                               const float* d_Z, int64_t ldz,
                               const float* d_attn_src, const float* d_attn_dst, float negative_slope,

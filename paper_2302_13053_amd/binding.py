@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libretexo.so")
 
 MEAN, SUM, GCN_SYM, GAT_SOFTMAX, MAX = 0, 1, 2, 3, 4
 MODES = {"mean": MEAN, "sum": SUM, "gcn_sym": GCN_SYM, "gat_softmax": GAT_SOFTMAX, "max": MAX}
-F_RELU, F_SELF_CONCAT, F_VALIDATE, F_SPLIT_ROWS = 1, 2, 4, 8
+F_RELU, F_SELF_CONCAT, F_VALIDATE, F_SPLIT_ROWS, F_SAVE = 1, 2, 4, 8, 16
 
 OK = 0
 E_NULL, E_SIZE, E_LD, E_MODE, E_FLAGS, E_HEADS = -1, -2, -3, -4, -5, -6
@@ -28,7 +28,7 @@ EXPORTS = (
     "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
     "retexo_workspace_bytes",
     "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
-    "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward",
+    "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward", "retexo_aggregate_backward_saved",
     "retexo_partition_workspace_bytes", "retexo_partition_share", "retexo_halo_pack", "retexo_halo_unpack",
     "retexo_plan_set_degrees", "retexo_data_volumes", "retexo_gamma",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
@@ -90,6 +90,9 @@ def load():
     lib.retexo_aggregate_backward.restype = i32
     lib.retexo_aggregate_backward.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64,
                                               vp, i64, vp, vp, vp, i64, vp]
+    lib.retexo_aggregate_backward_saved.restype = i32
+    lib.retexo_aggregate_backward_saved.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64,
+                                                    vp, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.retexo_partition_workspace_bytes.restype = i64
     lib.retexo_partition_workspace_bytes.argtypes = [i64, i32, i64]
     lib.retexo_partition_share.restype = i32
@@ -215,6 +218,16 @@ def retexo_aggregate_backward(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn
                                                 _vp(d_attn_dst), negative_slope, flags, _vp(d_G), ldg,
                                                 _vp(d_dZ), lddz, _vp(d_dattn_src), _vp(d_dattn_dst),
                                                 _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+def retexo_aggregate_backward_saved(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, negative_slope, flags,
+                                    d_G, ldg, d_saved, saved_bytes, d_dZ, lddz, d_dattn_src,
+                                    d_dattn_dst, d_workspace, workspace_bytes, stream=0) -> int:
+    return int(load().retexo_aggregate_backward_saved(_vp(plan), mode, F, heads, _vp(d_Z), ldz, _vp(d_attn_src),
+                                                      _vp(d_attn_dst), negative_slope, flags, _vp(d_G), ldg,
+                                                      _vp(d_saved), saved_bytes, _vp(d_dZ), lddz,
+                                                      _vp(d_dattn_src), _vp(d_dattn_dst), _vp(d_workspace),
+                                                      workspace_bytes, _vp(stream)))
 
 
 def retexo_partition_workspace_bytes(n_nodes, n_parts, send_capacity) -> int:

@@ -65,6 +65,11 @@ struct AggArgs {
     int part_lo, part_hi;
     int first;             // first range of the walk: start from zero, write the self copy
     int last;              // last range: apply the mean / gcn scaling
+    // edge softmax, kept for the backward pass (TRAIN kernels only):
+    f32x4* save_stats;     // [N, HP] {row maximum, 1/sum, share of the sum with p > 0, share with p <= 0}
+    float* save_pos;       // [N, ld_pos] the part of the aggregate that comes from entries with p > 0
+    float* save_neg;       // [N, ld_pos] ... and from entries with p <= 0 (the aggregate is their sum)
+    int64_t ld_pos;
 };
 
 // ---------------------------------------------------------------------------
@@ -739,12 +744,16 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_ker
 // the end of a tile carry the tile's first neighbour with weight zero, so every
 // gather address is valid and nothing in the loop branches per lane.
 // ---------------------------------------------------------------------------
-template <int NC, int NW, int HP, bool HU>
+template <int NC, int NW, int HP, bool HU, bool TRAIN>
 __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fast_kernel(AggArgs a)
 {
     constexpr int WAVES = NW == 1 ? kLightWaves : NW;
     constexpr int U = 4;
-    __shared__ float wl[WAVES][HP][64];
+    // TRAIN: the aggregate is accumulated in two parts, entries with a non-positive score (acc) and
+    // with a positive score (accp), each with its own weight per edge (zero for the other kind); the
+    // backward pass needs the two parts separately, each accurate relative to its own size
+    constexpr int WSETS = TRAIN ? 2 : 1;
+    __shared__ float wl[WAVES][WSETS][HP][64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t items = a.row_count * a.nslab;
@@ -762,7 +771,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
     bool act[NC];
     uint32_t colbytes[NC];
     int hc[NC][HU ? 1 : 4];
-    float acc[NC][4];
+    float acc[NC][4], accp[TRAIN ? NC : 1][4];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = col0 + c * 256;
@@ -772,17 +781,24 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
 #pragma unroll
         for (int k = 0; k < (HU ? 1 : 4); ++k) hc[c][k] = min((int)((col + k) / a.Dh), a.heads - 1);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc[c][k] = 0.0f;
+        for (int k = 0; k < 4; ++k) {
+            acc[c][k] = 0.0f;
+            if constexpr (TRAIN) accp[c][k] = 0.0f;
+        }
     }
     const char* zbase = reinterpret_cast<const char*>(a.Z);
     const uint32_t rowbytes = (uint32_t)(a.ldz * 4);
-    float* myw = &wl[wave][0][0];
+    float* myw = &wl[wave][0][0][0];
+    float* mywp = &wl[wave][WSETS - 1][0][0];
 
-    float m[HP], s[HP], erv[HP];
+    // sp, sn: the parts of s from entries with a positive / non-positive score (kept apart so that a
+    // share that is structurally zero comes out as an exact zero)
+    float m[HP], s[HP], sp[TRAIN ? HP : 1], sn[TRAIN ? HP : 1], erv[HP];
 #pragma unroll
     for (int h = 0; h < HP; ++h) {
         m[h] = -INFINITY;
         s[h] = 0.0f;
+        if constexpr (TRAIN) { sp[h] = 0.0f; sn[h] = 0.0f; }
         erv[h] = a.er[(int64_t)v * HP + h];
     }
 
@@ -823,7 +839,15 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
             const float pe = valid ? expf(sc - mn) : 0.0f;
             s[h] = s[h] * scale[h] + wave_sum(pe);
             m[h] = mn;
-            myw[h * 64 + lane] = pe;
+            if constexpr (TRAIN) {
+                const float pp = x > 0.0f ? pe : 0.0f, pn = x > 0.0f ? 0.0f : pe;
+                sp[h] = sp[h] * scale[h] + wave_sum(pp);
+                sn[h] = sn[h] * scale[h] + wave_sum(pn);
+                myw[h * 64 + lane] = pn;
+                mywp[h * 64 + lane] = pp;
+            } else {
+                myw[h * 64 + lane] = pe;
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -832,7 +856,11 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
 #pragma unroll
             for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int k = 0; k < 4; ++k) acc[c][k] *= select_head<HP>(scale, hc[c][HU ? 0 : k]);
+                for (int k = 0; k < 4; ++k) {
+                    const float f = select_head<HP>(scale, hc[c][HU ? 0 : k]);
+                    acc[c][k] *= f;
+                    if constexpr (TRAIN) accp[c][k] *= f;
+                }
         }
 
         for (int j = 0; j < cnt; j += U) {
@@ -858,11 +886,24 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
                         acc[c][1] = fmaf(w, zq[t][c].y, acc[c][1]);
                         acc[c][2] = fmaf(w, zq[t][c].z, acc[c][2]);
                         acc[c][3] = fmaf(w, zq[t][c].w, acc[c][3]);
+                        if constexpr (TRAIN) {
+                            const float wq = mywp[hc[c][0] * 64 + j + t];
+                            accp[c][0] = fmaf(wq, zq[t][c].x, accp[c][0]);
+                            accp[c][1] = fmaf(wq, zq[t][c].y, accp[c][1]);
+                            accp[c][2] = fmaf(wq, zq[t][c].z, accp[c][2]);
+                            accp[c][3] = fmaf(wq, zq[t][c].w, accp[c][3]);
+                        }
                     } else {
                         acc[c][0] = fmaf(myw[hc[c][0] * 64 + j + t], zq[t][c].x, acc[c][0]);
                         acc[c][1] = fmaf(myw[hc[c][1] * 64 + j + t], zq[t][c].y, acc[c][1]);
                         acc[c][2] = fmaf(myw[hc[c][2] * 64 + j + t], zq[t][c].z, acc[c][2]);
                         acc[c][3] = fmaf(myw[hc[c][3] * 64 + j + t], zq[t][c].w, acc[c][3]);
+                        if constexpr (TRAIN) {
+                            accp[c][0] = fmaf(mywp[hc[c][0] * 64 + j + t], zq[t][c].x, accp[c][0]);
+                            accp[c][1] = fmaf(mywp[hc[c][1] * 64 + j + t], zq[t][c].y, accp[c][1]);
+                            accp[c][2] = fmaf(mywp[hc[c][2] * 64 + j + t], zq[t][c].z, accp[c][2]);
+                            accp[c][3] = fmaf(mywp[hc[c][3] * 64 + j + t], zq[t][c].w, accp[c][3]);
+                        }
                     }
                 }
             }
@@ -876,15 +917,22 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
     }
 
     if constexpr (NW > 1) {
-        __shared__ float red[NW][NC * 4][64];
-        __shared__ float mred[NW][HP], sred[NW][HP];
+        __shared__ float red[NW][NC * 4 * WSETS][64];
+        __shared__ float mred[NW][HP], sred[NW][HP], spred[NW][HP], snred[NW][HP];
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
-            for (int k = 0; k < 4; ++k) red[wave][c * 4 + k][lane] = acc[c][k];
+            for (int k = 0; k < 4; ++k) {
+                red[wave][c * 4 + k][lane] = acc[c][k];
+                if constexpr (TRAIN) red[wave][NC * 4 + c * 4 + k][lane] = accp[c][k];
+            }
         if (lane == 0) {
 #pragma unroll
-            for (int h = 0; h < HP; ++h) { mred[wave][h] = m[h]; sred[wave][h] = s[h]; }
+            for (int h = 0; h < HP; ++h) {
+                mred[wave][h] = m[h];
+                sred[wave][h] = s[h];
+                if constexpr (TRAIN) { spred[wave][h] = sp[h]; snred[wave][h] = sn[h]; }
+            }
         }
         __syncthreads();
         if (wave != 0) return;
@@ -894,23 +942,30 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
             float mm = mred[0][h];
 #pragma unroll
             for (int w = 1; w < NW; ++w) mm = fmaxf(mm, mred[w][h]);
-            float ss = 0.0f;
+            float ss = 0.0f, pp = 0.0f, nn = 0.0f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 f[w][h] = (mred[w][h] == -INFINITY) ? 0.0f : expf(mred[w][h] - mm);
                 ss += sred[w][h] * f[w][h];
+                if constexpr (TRAIN) { pp += spred[w][h] * f[w][h]; nn += snred[w][h] * f[w][h]; }
             }
             s[h] = ss;
+            m[h] = mm;
+            if constexpr (TRAIN) { sp[h] = pp; sn[h] = nn; }
         }
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                float t = 0.0f;
+                float t = 0.0f, tp = 0.0f;
 #pragma unroll
-                for (int w = 0; w < NW; ++w)
-                    t += red[w][c * 4 + k][lane] * select_head<HP>(f[w], hc[c][HU ? 0 : k]);
+                for (int w = 0; w < NW; ++w) {
+                    const float fw = select_head<HP>(f[w], hc[c][HU ? 0 : k]);
+                    t += red[w][c * 4 + k][lane] * fw;
+                    if constexpr (TRAIN) tp += red[w][NC * 4 + c * 4 + k][lane] * fw;
+                }
                 acc[c][k] = t;
+                if constexpr (TRAIN) accp[c][k] = tp;
             }
     }
 
@@ -921,16 +976,40 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
         const int64_t col = col0 + c * 256;
         const int valid = (int)min((int64_t)4, a.F - col);
         float r[4];
+        if constexpr (TRAIN) {
+            float rp[4], rn[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float den = select_head<HP>(s, hc[c][HU ? 0 : k]);
-            r[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
+            for (int k = 0; k < 4; ++k) {
+                const float den = select_head<HP>(s, hc[c][HU ? 0 : k]);
+                r[k] = den > 0.0f ? (acc[c][k] + accp[c][k]) / den : 0.0f;
+                rp[k] = den > 0.0f ? accp[c][k] / den : 0.0f;
+                rn[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
+            }
+            store_row<4>(a.save_pos + (int64_t)v * a.ld_pos + col, rp, valid, true);
+            store_row<4>(a.save_neg + (int64_t)v * a.ld_pos + col, rn, valid, true);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float den = select_head<HP>(s, hc[c][HU ? 0 : k]);
+                r[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
+            }
         }
         store_row<4>(orow + a.ocol + col, r, valid, a.out_vec != 0);
         if (a.copy_self) {
             float zs[4];
             load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
             store_row<4>(orow + col, zs, valid, a.self_vec != 0);
+        }
+    }
+    if constexpr (TRAIN) {
+        if (lane == 0 && slab == 0) {
+#pragma unroll
+            for (int h = 0; h < HP; ++h) {
+                const bool any = s[h] > 0.0f;
+                const float rs = any ? 1.0f / s[h] : 0.0f;
+                const f32x4 t = {any ? m[h] : 0.0f, rs, sp[h] * rs, sn[h] * rs};
+                a.save_stats[(int64_t)v * HP + h] = t;
+            }
         }
     }
 }
@@ -1010,7 +1089,7 @@ void launch_gat_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_
     }
 }
 
-template <int NC, int HP, bool HU>
+template <int NC, int HP, bool HU, bool TRAIN>
 void launch_gat_fast_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
 {
     if (n_heavy > 0) {
@@ -1018,22 +1097,27 @@ void launch_gat_fast_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipSt
         a.row_begin = 0;
         a.row_count = n_heavy;
         const int64_t blocks = n_heavy * a.nslab;
-        agg_gat_fast_kernel<NC, kHeavyWaves, HP, HU><<<dim3((unsigned)blocks), dim3(64 * kHeavyWaves), 0, stream>>>(a);
+        agg_gat_fast_kernel<NC, kHeavyWaves, HP, HU, TRAIN><<<dim3((unsigned)blocks), dim3(64 * kHeavyWaves), 0, stream>>>(a);
     }
     if (N > n_heavy) {
         AggArgs a = base;
         a.row_begin = n_heavy;
         a.row_count = N - n_heavy;
         const int64_t blocks = (a.row_count * a.nslab + kLightWaves - 1) / kLightWaves;
-        agg_gat_fast_kernel<NC, 1, HP, HU><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+        agg_gat_fast_kernel<NC, 1, HP, HU, TRAIN><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
     }
 }
 
 template <int HP, bool HU>
-void dispatch_gat_fast(int nc, const AggArgs& a, int64_t nh, int64_t N, hipStream_t s)
+void dispatch_gat_fast(int nc, bool train, const AggArgs& a, int64_t nh, int64_t N, hipStream_t s)
 {
-    if (nc == 1) launch_gat_fast_pair<1, HP, HU>(a, nh, N, s);
-    else launch_gat_fast_pair<2, HP, HU>(a, nh, N, s);
+    if (train) {
+        if (nc == 1) launch_gat_fast_pair<1, HP, HU, true>(a, nh, N, s);
+        else launch_gat_fast_pair<2, HP, HU, true>(a, nh, N, s);
+    } else {
+        if (nc == 1) launch_gat_fast_pair<1, HP, HU, false>(a, nh, N, s);
+        else launch_gat_fast_pair<2, HP, HU, false>(a, nh, N, s);
+    }
 }
 
 template <int VEC, bool MAXOP>
@@ -1071,10 +1155,25 @@ AggOptions& agg_options()
     return o;
 }
 
-int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads)
+GatWorkspace gat_workspace(int64_t N, int64_t F, int heads, bool save)
+{
+    const int64_t n = N > 0 ? N : 1, hp = heads_padded(heads);
+    GatWorkspace w;
+    int64_t off = 0;
+    w.el = off; off += align_up(n * hp * (int64_t)sizeof(float), 256);
+    w.er = off; off += align_up(n * hp * (int64_t)sizeof(float), 256);
+    w.ld_pos = align_up(F > 0 ? F : 1, 32);
+    w.stats = off; if (save) off += align_up(n * hp * 16, 256);
+    w.pos = off;   if (save) off += align_up(n * w.ld_pos * (int64_t)sizeof(float), 256);
+    w.neg = off;   if (save) off += align_up(n * w.ld_pos * (int64_t)sizeof(float), 256);
+    w.total = off;
+    return w;
+}
+
+int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads, int64_t F, bool save)
 {
     if (mode != RETEXO_GAT_SOFTMAX) return 0;
-    return 2 * align_up((N > 0 ? N : 1) * heads_padded(heads) * (int64_t)sizeof(float), 256);
+    return gat_workspace(N, F, heads, save).total;
 }
 
 void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
@@ -1142,6 +1241,10 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.part_hi = 0;
     a.first = 1;
     a.last = 1;
+    a.save_stats = nullptr;
+    a.save_pos = nullptr;
+    a.save_neg = nullptr;
+    a.ld_pos = 0;
 
     // rows at or above the heavy threshold (rounded up to a tabulated one)
     int64_t n_heavy = 0;
@@ -1194,15 +1297,24 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     } else {
         const int hp = heads_padded(c.heads);
         float* el = (float*)c.workspace;
-        float* er = (float*)((char*)c.workspace + align_up(N * heads_padded(c.heads) * (int64_t)sizeof(float), 256));
+        float* er = (float*)((char*)c.workspace + gat_workspace(N, c.F, c.heads, false).er);
         a.el = el;
         a.er = er;
         launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream);
         const bool hu = (a.Dh % vec) == 0;
         const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
+        if (c.save) {
+            // only the pipelined kernel keeps the backward's statistics
+            if (!(vec == 4 && off32 && opt.gat_fast)) return RETEXO_E_FLAGS;
+            const GatWorkspace w = gat_workspace(N, c.F, c.heads, true);
+            a.save_stats = (f32x4*)((char*)c.workspace + w.stats);
+            a.save_pos = (float*)((char*)c.workspace + w.pos);
+            a.save_neg = (float*)((char*)c.workspace + w.neg);
+            a.ld_pos = w.ld_pos;
+        }
         if (vec == 4 && off32 && opt.gat_fast) {
-            if (hp == 4) { if (hu) dispatch_gat_fast<4, true>(nc, a, n_heavy, N, stream); else dispatch_gat_fast<4, false>(nc, a, n_heavy, N, stream); }
-            else         { if (hu) dispatch_gat_fast<8, true>(nc, a, n_heavy, N, stream); else dispatch_gat_fast<8, false>(nc, a, n_heavy, N, stream); }
+            if (hp == 4) { if (hu) dispatch_gat_fast<4, true>(nc, c.save, a, n_heavy, N, stream); else dispatch_gat_fast<4, false>(nc, c.save, a, n_heavy, N, stream); }
+            else         { if (hu) dispatch_gat_fast<8, true>(nc, c.save, a, n_heavy, N, stream); else dispatch_gat_fast<8, false>(nc, c.save, a, n_heavy, N, stream); }
         } else if (vec == 4) {
             if (hp == 4) { if (hu) dispatch_gat_nc<4, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat_nc<4, 4, false>(nc, a, n_heavy, N, stream); }
             else         { if (hu) dispatch_gat_nc<4, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat_nc<4, 8, false>(nc, a, n_heavy, N, stream); }

@@ -456,6 +456,47 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void gat_bwd_src
 }
 
 // ---------------------------------------------------------------------------
+// What the "dst" pass produces, from what a forward pass in save mode left behind instead of a
+// second gather over Z:  A+- = <G_v, out+-_v> (out+, out-: the parts of the aggregate from entries
+// with a positive / non-positive score),  c_v = A+ + A-,  P+-: the saved shares of the softmax sum.
+// One wave per node.
+// ---------------------------------------------------------------------------
+template <int HP>
+__global__ __launch_bounds__(256) void gat_bwd_from_saved_kernel(
+    int64_t N, int64_t F, int heads, int Dh, float slope, const float* __restrict__ G, int64_t ldg,
+    const float* __restrict__ pos, const float* __restrict__ neg, int64_t ldp,
+    const f32x4* __restrict__ stats, const float* __restrict__ er, f32x4* __restrict__ nbr,
+    float* __restrict__ ddst)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= N) return;
+    float pp[HP], pn[HP];
+#pragma unroll
+    for (int h = 0; h < HP; ++h) { pp[h] = 0.0f; pn[h] = 0.0f; }
+    for (int64_t c = lane; c < F; c += 64) {
+        const float g = G[v * ldg + c];
+        const int h = (int)(c / Dh);
+        const float x = g * pos[v * ldp + c], y = g * neg[v * ldp + c];
+#pragma unroll
+        for (int i = 0; i < HP; ++i) {
+            pp[i] += (h == i) ? x : 0.0f;
+            pn[i] += (h == i) ? y : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < HP; ++h) {
+        const float ap = wave_sum(pp[h]), an = wave_sum(pn[h]);
+        if (lane == 0) {
+            const f32x4 st = stats[v * HP + h];           // {max, 1/sum, P+, P-}
+            const f32x4 t = {er[v * HP + h], st.x, st.y, ap + an};
+            nbr[v * HP + h] = t;
+            ddst[v * HP + h] = h < heads ? (1.0f - slope) * (ap * st.w - an * st.z) : 0.0f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // da_src[c] = sum_u dsrc[u, head(c)] Z[u, c],  da_dst[c] = sum_v ddst[v, head(c)] Z[v, c]
 // stage 1: each workgroup sums a contiguous range of rows, one thread per column
 // stage 2: the partial rows are added in index order
@@ -524,10 +565,11 @@ __global__ __launch_bounds__(256) void add_rows_kernel(int64_t N, int64_t F, con
 
 bool aligned4(const void* p, int64_t ld) { return ((uintptr_t)p % 16) == 0 && ld % 4 == 0; }
 
+// first_pass 0: the "dst" pass then the "src" pass; 1: the "src" pass alone (statistics already in place)
 template <int VEC, int NC, int HP, bool HU>
-void launch_passes(const BwdArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
+void launch_passes(const BwdArgs& base, int first_pass, int64_t n_heavy, int64_t N, hipStream_t stream)
 {
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = first_pass; pass < 2; ++pass) {
         if (n_heavy > 0) {
             BwdArgs a = base;
             a.row_begin = 0;
@@ -551,20 +593,20 @@ void launch_passes(const BwdArgs& base, int64_t n_heavy, int64_t N, hipStream_t 
 }
 
 template <int VEC, int HP, bool HU>
-void dispatch_nc(int nc, const BwdArgs& a, int64_t nh, int64_t N, hipStream_t s)
+void dispatch_nc(int nc, const BwdArgs& a, int fp, int64_t nh, int64_t N, hipStream_t s)
 {
-    if (nc == 1) launch_passes<VEC, 1, HP, HU>(a, nh, N, s);
-    else if (nc == 2) launch_passes<VEC, 2, HP, HU>(a, nh, N, s);
-    else launch_passes<VEC, 4, HP, HU>(a, nh, N, s);
+    if (nc == 1) launch_passes<VEC, 1, HP, HU>(a, fp, nh, N, s);
+    else if (nc == 2) launch_passes<VEC, 2, HP, HU>(a, fp, nh, N, s);
+    else launch_passes<VEC, 4, HP, HU>(a, fp, nh, N, s);
 }
 
 template <int HP>
-void dispatch_wide(int nc, const BwdArgs& a, int64_t nh, int64_t N, hipStream_t s)
+void dispatch_wide(int nc, const BwdArgs& a, int fp, int64_t nh, int64_t N, hipStream_t s)
 {
     // unaligned tables: scalar gathers, up to 16 chunks of 64 columns
-    if (nc <= 4) launch_passes<1, 4, HP, true>(a, nh, N, s);
-    else if (nc <= 8) launch_passes<1, 8, HP, true>(a, nh, N, s);
-    else launch_passes<1, 16, HP, true>(a, nh, N, s);
+    if (nc <= 4) launch_passes<1, 4, HP, true>(a, fp, nh, N, s);
+    else if (nc <= 8) launch_passes<1, 8, HP, true>(a, fp, nh, N, s);
+    else launch_passes<1, 16, HP, true>(a, fp, nh, N, s);
 }
 
 constexpr int64_t kParamBlocks = 2048;
@@ -670,7 +712,26 @@ int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream)
     a.Dh = (int)(F / c.heads);
     a.slope = c.slope;
 
-    launch_gat_scores(N, F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, (float*)(ws + w.el), (float*)(ws + w.er), stream);
+    int first_pass = 0;
+    if (c.saved) {
+        // the forward pass left scores, softmax statistics and the positive-score part of the aggregate
+        const GatWorkspace fw = gat_workspace(N, F, c.heads, true);
+        const char* sv = (const char*)c.saved;
+        a.el = (const float*)(sv + fw.el);
+        a.er = (const float*)(sv + fw.er);
+        const unsigned gb = (unsigned)((N + 3) / 4);
+        if (hp == 4)
+            gat_bwd_from_saved_kernel<4><<<dim3(gb), dim3(256), 0, stream>>>(
+                N, F, c.heads, a.Dh, c.slope, Ga, c.ldg, (const float*)(sv + fw.pos), (const float*)(sv + fw.neg),
+                fw.ld_pos, (const f32x4*)(sv + fw.stats), a.er, a.nbr, a.ddst);
+        else
+            gat_bwd_from_saved_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(
+                N, F, c.heads, a.Dh, c.slope, Ga, c.ldg, (const float*)(sv + fw.pos), (const float*)(sv + fw.neg),
+                fw.ld_pos, (const f32x4*)(sv + fw.stats), a.er, a.nbr, a.ddst);
+        first_pass = 1;
+    } else {
+        launch_gat_scores(N, F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, (float*)(ws + w.el), (float*)(ws + w.er), stream);
+    }
 
     int64_t n_heavy = 0;
     const AggOptions& opt = agg_options();
@@ -685,12 +746,12 @@ int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream)
     if (v4) {
         const int nc = (int)((F + 255) / 256);
         const bool hu = a.Dh % 4 == 0;
-        if (hp == 4) { if (hu) dispatch_nc<4, 4, true>(nc, a, n_heavy, N, stream); else dispatch_nc<4, 4, false>(nc, a, n_heavy, N, stream); }
-        else         { if (hu) dispatch_nc<4, 8, true>(nc, a, n_heavy, N, stream); else dispatch_nc<4, 8, false>(nc, a, n_heavy, N, stream); }
+        if (hp == 4) { if (hu) dispatch_nc<4, 4, true>(nc, a, first_pass, n_heavy, N, stream); else dispatch_nc<4, 4, false>(nc, a, first_pass, n_heavy, N, stream); }
+        else         { if (hu) dispatch_nc<4, 8, true>(nc, a, first_pass, n_heavy, N, stream); else dispatch_nc<4, 8, false>(nc, a, first_pass, n_heavy, N, stream); }
     } else {
         const int nc = (int)((F + 63) / 64);
-        if (hp == 4) dispatch_wide<4>(nc, a, n_heavy, N, stream);
-        else dispatch_wide<8>(nc, a, n_heavy, N, stream);
+        if (hp == 4) dispatch_wide<4>(nc, a, first_pass, n_heavy, N, stream);
+        else dispatch_wide<8>(nc, a, first_pass, n_heavy, N, stream);
     }
 
     const int64_t nblk = param_blocks(N);

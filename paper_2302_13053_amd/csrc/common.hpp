@@ -73,9 +73,13 @@ struct AggCall {
     float* out;
     int64_t ldo;
     void* workspace;
+    bool save = false;    // edge softmax: keep the backward's statistics in the workspace
 };
 int launch_aggregate(const AggCall& c, hipStream_t stream);
-int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads);
+// edge-softmax workspace: scores, then (save) the row statistics and the aggregate split by the sign of the score
+struct GatWorkspace { int64_t el, er, stats, pos, neg, total, ld_pos; };
+GatWorkspace gat_workspace(int64_t N, int64_t F, int heads, bool save);
+int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads, int64_t F = 0, bool save = false);
 // el[v,h] = <a_src[h], z_v,h>, er[v,h] = <a_dst[h], z_v,h>, both [N, heads_padded(heads)]
 void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
                        const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream);
@@ -99,6 +103,8 @@ struct AggBackwardCall {
     float* d_attn_src;
     float* d_attn_dst;
     void* workspace;
+    // edge softmax after a forward pass in save mode: that pass's workspace (else NULL)
+    const void* saved = nullptr;
 };
 int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream);
 int64_t aggregate_backward_workspace_bytes(int64_t N, int mode, int64_t F, int heads);

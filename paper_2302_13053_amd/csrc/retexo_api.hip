@@ -93,7 +93,11 @@ extern "C" int64_t retexo_workspace_bytes(const retexo_plan* plan, int64_t D_out
     if (!plan) return RETEXO_E_NULL;
     if (D_out < 0) return RETEXO_E_SIZE;
     if (int s = check_mode(mode, D_out, heads)) return s;
-    if (flags & ~(unsigned)(RETEXO_F_RELU | RETEXO_F_SELF_CONCAT)) return RETEXO_E_FLAGS;
+    if (flags & ~(unsigned)(RETEXO_F_RELU | RETEXO_F_SELF_CONCAT | RETEXO_F_SAVE)) return RETEXO_E_FLAGS;
+    const bool save = (flags & RETEXO_F_SAVE) != 0;
+    if (save && mode != RETEXO_GAT_SOFTMAX) return RETEXO_E_FLAGS;
+    // retexo_aggregate in save mode: exactly its own layout (the backward call looks into it)
+    if (save) return aggregate_workspace_bytes(plan->N, mode, heads, D_out, true);
     // sized for retexo_round with a weight matrix; retexo_aggregate needs only the second term
     return round_z_bytes(plan->N, D_out, true, (flags & RETEXO_F_SELF_CONCAT) != 0, nullptr) +
            aggregate_workspace_bytes(plan->N, mode, heads);
@@ -120,8 +124,10 @@ extern "C" int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, in
     if (!plan) return RETEXO_E_NULL;
     if (F < 0 || F >= (1ll << 30)) return RETEXO_E_SIZE;
     if (int s = check_mode(mode, F, heads)) return s;
-    if (flags & ~(unsigned)RETEXO_F_SELF_CONCAT) return RETEXO_E_FLAGS;
+    if (flags & ~(unsigned)(RETEXO_F_SELF_CONCAT | RETEXO_F_SAVE)) return RETEXO_E_FLAGS;
     const bool concat = (flags & RETEXO_F_SELF_CONCAT) != 0;
+    const bool save = (flags & RETEXO_F_SAVE) != 0;
+    if (save && mode != RETEXO_GAT_SOFTMAX) return RETEXO_E_FLAGS;
     const int64_t N = plan->N, ow = concat ? 2 * F : F;
     if (N > 0 && F > 0 && (!d_Z || !d_out)) return RETEXO_E_NULL;
     if (mode == RETEXO_GAT_SOFTMAX && N > 0 && F > 0 && (!d_attn_src || !d_attn_dst)) return RETEXO_E_NULL;
@@ -130,7 +136,7 @@ extern "C" int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, in
     if (!in_place && N > 0 && F > 0 &&
         overlaps(d_Z, extent_bytes(N, ldz, F), d_out, extent_bytes(N, ldo, ow)))
         return RETEXO_E_ALIAS;
-    const int64_t need = aggregate_workspace_bytes(N, mode, heads);
+    const int64_t need = aggregate_workspace_bytes(N, mode, heads, F, save);
     if (need > 0 && (!d_workspace || workspace_bytes < need || ((uintptr_t)d_workspace & 255)))
         return RETEXO_E_WORKSPACE;
 
@@ -139,6 +145,7 @@ extern "C" int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, in
     c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
     c.self_concat = concat; c.copy_self = !in_place; c.out = d_out; c.ldo = ldo;
     c.workspace = d_workspace;
+    c.save = save;
     return launch_aggregate(c, (hipStream_t)stream);
 }
 
@@ -177,12 +184,14 @@ extern "C" int64_t retexo_aggregate_backward_workspace_bytes(const retexo_plan* 
     return aggregate_backward_workspace_bytes(plan->N, mode, F, heads);
 }
 
-extern "C" int retexo_aggregate_backward(const retexo_plan* plan, int mode, int64_t F, int heads,
-                                         const float* d_Z, int64_t ldz,
-                                         const float* d_attn_src, const float* d_attn_dst, float negative_slope,
-                                         unsigned flags, const float* d_G, int64_t ldg,
-                                         float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
-                                         void* d_workspace, int64_t workspace_bytes, void* stream)
+namespace {
+int aggregate_backward_checked(const retexo_plan* plan, int mode, int64_t F, int heads,
+                               const float* d_Z, int64_t ldz,
+                               const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                               unsigned flags, const float* d_G, int64_t ldg,
+                               const void* d_saved, int64_t saved_bytes,
+                               float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
+                               void* d_workspace, int64_t workspace_bytes, void* stream)
 {
     if (!plan) return RETEXO_E_NULL;
     if (F < 0 || F >= (1ll << 30)) return RETEXO_E_SIZE;
@@ -217,7 +226,40 @@ extern "C" int retexo_aggregate_backward(const retexo_plan* plan, int mode, int6
     c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
     c.self_concat = concat; c.G = d_G; c.ldg = ldg; c.dZ = d_dZ; c.lddz = lddz;
     c.d_attn_src = d_dattn_src; c.d_attn_dst = d_dattn_dst; c.workspace = d_workspace;
+    if (d_saved) {
+        if (!gat) return RETEXO_E_MODE;
+        if (saved_bytes < aggregate_workspace_bytes(N, mode, heads, F, true) || ((uintptr_t)d_saved & 255))
+            return RETEXO_E_WORKSPACE;
+        c.saved = d_saved;
+    }
     return launch_aggregate_backward(c, (hipStream_t)stream);
+}
+}  // namespace
+
+extern "C" int retexo_aggregate_backward(const retexo_plan* plan, int mode, int64_t F, int heads,
+                                         const float* d_Z, int64_t ldz,
+                                         const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                                         unsigned flags, const float* d_G, int64_t ldg,
+                                         float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
+                                         void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    return aggregate_backward_checked(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, negative_slope, flags,
+                                      d_G, ldg, nullptr, 0, d_dZ, lddz, d_dattn_src, d_dattn_dst,
+                                      d_workspace, workspace_bytes, stream);
+}
+
+extern "C" int retexo_aggregate_backward_saved(const retexo_plan* plan, int mode, int64_t F, int heads,
+                                               const float* d_Z, int64_t ldz,
+                                               const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                                               unsigned flags, const float* d_G, int64_t ldg,
+                                               const void* d_saved, int64_t saved_bytes,
+                                               float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
+                                               void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    if (!d_saved) return RETEXO_E_NULL;
+    return aggregate_backward_checked(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, negative_slope, flags,
+                                      d_G, ldg, d_saved, saved_bytes, d_dZ, lddz, d_dattn_src,
+                                      d_dattn_dst, d_workspace, workspace_bytes, stream);
 }
 
 extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out, int heads,

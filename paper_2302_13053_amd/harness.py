@@ -162,11 +162,13 @@ def transform(H: torch.Tensor, d_in: int, W: torch.Tensor, b: Optional[torch.Ten
 def aggregate(g: DeviceGraph, mode: str, Z: torch.Tensor, F: int, *, heads: int = 1,
               a_src: Optional[torch.Tensor] = None, a_dst: Optional[torch.Tensor] = None,
               slope: float = 0.2, concat: bool = False, out: Optional[torch.Tensor] = None,
-              ld_out: Optional[int] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+              ld_out: Optional[int] = None, workspace: Optional[torch.Tensor] = None,
+              save: bool = False) -> torch.Tensor:
+    """``save``: edge softmax in save mode; pass ``workspace`` (sized for it) and keep it for the backward."""
     ow = 2 * F if concat else F
     if out is None:
         out = torch.empty((g.n_nodes, ld_out or pad_ld(ow)), dtype=torch.float32, device="cuda")
-    flags = B.F_SELF_CONCAT if concat else 0
+    flags = (B.F_SELF_CONCAT if concat else 0) | (B.F_SAVE if save else 0)
     need = B.retexo_workspace_bytes(g.plan, F, B.MODES[mode], heads, flags)
     if need < 0:
         raise B.RetexoError(need, "retexo_workspace_bytes")
@@ -184,8 +186,9 @@ def aggregate(g: DeviceGraph, mode: str, Z: torch.Tensor, F: int, *, heads: int 
 def aggregate_backward(g: DeviceGraph, mode: str, F: int, G: torch.Tensor, *, Z: Optional[torch.Tensor] = None,
                        heads: int = 1, a_src: Optional[torch.Tensor] = None, a_dst: Optional[torch.Tensor] = None,
                        slope: float = 0.2, concat: bool = False, dZ: Optional[torch.Tensor] = None,
-                       workspace: Optional[torch.Tensor] = None):
-    """-> (dZ, da_src, da_dst) device tensors (da_* None unless mode is gat_softmax)."""
+                       workspace: Optional[torch.Tensor] = None, saved: Optional[torch.Tensor] = None):
+    """-> (dZ, da_src, da_dst) device tensors (da_* None unless mode is gat_softmax).
+    ``saved``: the workspace of a forward pass in save mode (one gather pass instead of two)."""
     if dZ is None:
         dZ = torch.empty((g.n_nodes, pad_ld(F)), dtype=torch.float32, device="cuda")
     need = B.retexo_aggregate_backward_workspace_bytes(g.plan, B.MODES[mode], F, heads)
@@ -198,6 +201,14 @@ def aggregate_backward(g: DeviceGraph, mode: str, F: int, G: torch.Tensor, *, Z:
         das = torch.empty((heads, F // heads), dtype=torch.float32, device="cuda")
         dad = torch.empty_like(das)
     p = lambda t: t.data_ptr() if t is not None else 0
+    if saved is not None:
+        st = B.retexo_aggregate_backward_saved(g.plan, B.MODES[mode], F, heads, p(Z), Z.stride(0), p(a_src), p(a_dst),
+                                               slope, B.F_SELF_CONCAT if concat else 0, G.data_ptr(), G.stride(0),
+                                               saved.data_ptr(), saved.numel(),
+                                               dZ.data_ptr(), dZ.stride(0), p(das), p(dad),
+                                               workspace.data_ptr(), workspace.numel(), _stream_ptr())
+        B.check(st, "retexo_aggregate_backward_saved")
+        return dZ, das, dad
     st = B.retexo_aggregate_backward(g.plan, B.MODES[mode], F, heads, p(Z), Z.stride(0) if Z is not None else 0,
                                      p(a_src), p(a_dst), slope, B.F_SELF_CONCAT if concat else 0,
                                      G.data_ptr(), G.stride(0), dZ.data_ptr(), dZ.stride(0), p(das), p(dad),

@@ -74,11 +74,14 @@ def test_attention_layer_training_step(n, pairs, d_in, F, heads, Hd, C):
     # a few SGD steps on every parameter lower the loss
     params = [dWg, dbg, das_in, dad_in, d(W1), d(b1), d(Wc), d(bc)]
     first = None
+    saved = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, F, B.MODES["gat_softmax"], heads, B.F_SAVE))
     for step in range(6):
         Zd = Hn.transform(dQ, d_in, params[0], params[1], False)
-        Xd = Hn.aggregate(g, "gat_softmax", Zd, F, heads=heads, a_src=params[2], a_dst=params[3])
+        # the forward keeps what the backward can reuse (one gather pass instead of two)
+        Xd = Hn.aggregate(g, "gat_softmax", Zd, F, heads=heads, a_src=params[2], a_dst=params[3], workspace=saved, save=True)
         lossd, g1, g2, g3, g4 = Hn.layer_grad(Xd, F, d(y), params[4], params[5], params[6], params[7], gX=gXd)
-        dZd, ga, gb_ = Hn.aggregate_backward(g, "gat_softmax", F, gXd, Z=Zd, heads=heads, a_src=params[2], a_dst=params[3])
+        dZd, ga, gb_ = Hn.aggregate_backward(g, "gat_softmax", F, gXd, Z=Zd, heads=heads, a_src=params[2], a_dst=params[3],
+                                             saved=saved)
         gw, gbias = Hn.transform_backward(dQ, d_in, dZd, F)
         for p_, g_ in zip(params, (gw, gbias, ga, gb_, g1, g2, g3, g4)):
             B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), 0.2, Hn._stream_ptr()), "sgd")

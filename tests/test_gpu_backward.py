@@ -245,3 +245,47 @@ def test_full_size_products_shape_sampled_rows():
     torch.cuda.synchronize()
     assert np.abs(dad1.cpu().numpy()).max() <= 1e-4 * np.abs(das1.cpu().numpy()).max()
     g.destroy()
+
+
+@pytest.mark.parametrize("F,ld,heads,concat", [(256, 256, 4, False), (256, 256, 4, True), (188, 192, 4, False),
+                                               (512, 512, 8, False), (1024, 1024, 8, True), (96, 96, 3, False)])
+def test_backward_after_a_forward_in_save_mode(graphs, F, ld, heads, concat):
+    """retexo_aggregate with RETEXO_F_SAVE leaves the statistics behind (its output stays within the forward's
+    bound), and retexo_aggregate_backward_saved reaches the oracle's gradients with one gather pass."""
+    for name in ("skewed", "flat"):
+        g, rp, ci = graphs[(name, False)]
+        n = g.n_nodes
+        Zh = wl.random_matrix(n, F, F + 21, ld=ld)
+        Gh = wl.random_matrix(n, 2 * F if concat else F, F + 22)
+        scale = np.float32(min(0.3, 2.4 / np.sqrt(F // heads)))
+        a_s = wl.random_matrix(heads, F // heads, F + 23) * scale
+        a_d = wl.random_matrix(heads, F // heads, F + 24) * scale
+        Z, G, As, Ad = Hn.dev(Zh), Hn.dev(Gh), Hn.dev(a_s), Hn.dev(a_d)
+        fwd = oracle.aggregate("gat_softmax", rp, ci, Zh, F, heads=heads, a_src=a_s, a_dst=a_d, self_concat=concat)
+        flags = (B.F_SELF_CONCAT if concat else 0) | B.F_SAVE
+        saved = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, F, B.MODES["gat_softmax"], heads, flags))
+        out = Hn.aggregate(g, "gat_softmax", Z, F, heads=heads, a_src=As, a_dst=Ad, concat=concat, workspace=saved, save=True)
+        ow = 2 * F if concat else F
+        assert_close(out.cpu().numpy()[:, :ow], fwd, what="forward in save mode %s F=%d" % (name, F))
+        dZ, das, dad = Hn.aggregate_backward(g, "gat_softmax", F, G, Z=Z, heads=heads, a_src=As, a_dst=Ad, concat=concat,
+                                             saved=saved)
+        torch.cuda.synchronize()
+        want = oracle.aggregate_backward("gat_softmax", rp, ci, Zh, F, Gh, heads=heads, a_src=a_s, a_dst=a_d, self_concat=concat)
+        what = "saved backward %s F=%d" % (name, F)
+        assert_close(dZ.cpu().numpy()[:, :F], want[0], what=what)
+        check_params(das, dad, want, what)
+        again = Hn.aggregate_backward(g, "gat_softmax", F, G, Z=Z, heads=heads, a_src=As, a_dst=Ad, concat=concat,
+                                      saved=saved)
+        assert torch.equal(dZ[:, :F], again[0][:, :F]) and torch.equal(das, again[1]) and torch.equal(dad, again[2])
+
+
+def test_save_mode_needs_aligned_rows(graphs):
+    g, _, _ = graphs[("flat", False)]
+    n, F, heads = g.n_nodes, 94, 2
+    Z = Hn.dev(wl.random_matrix(n, F, 1, ld=94))                 # rows not a multiple of 16 bytes
+    a = Hn.dev(wl.random_matrix(heads, F // heads, 2))
+    ws = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, F, B.MODES["gat_softmax"], heads, B.F_SAVE))
+    with pytest.raises(B.RetexoError) as e:
+        Hn.aggregate(g, "gat_softmax", Z, F, heads=heads, a_src=a, a_dst=a, workspace=ws, save=True)
+    assert e.value.status == -5
+    assert B.retexo_workspace_bytes(g.plan, F, B.MODES["mean"], 1, B.F_SAVE) == -5      # only the edge softmax saves
