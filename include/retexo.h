@@ -293,6 +293,31 @@ int retexo_transform_backward(int64_t N, int64_t D_in, int64_t D_out,
                               void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Variant: the gathered table kept in 16-bit storage.  The aggregation is bound by the bytes it
+ * gathers, so a table in bfloat16 or IEEE half moves half of them.  Outside the fp32 results:
+ * the stored value is the float32 value rounded to nearest even in the target format; sums are
+ * still accumulated in float32, the output is float32.
+ *   retexo_store_rows: d_dst[i, j] = round(d_src[i, j]) for j < F; d_dst is [N, ldd] 16-bit
+ *     elements (ldd in elements).  NaN stays NaN, overflow rounds to infinity, fp16 keeps subnormals.
+ *   retexo_aggregate_stored: retexo_aggregate with d_Z a stored table ([N, ldz] elements, ldz in
+ *     elements); all five modes; under RETEXO_F_SELF_CONCAT the self half is the stored value
+ *     widened to float32 (there is no in-place form).  16-byte aligned rows with
+ *     ldz >= F rounded up to 8 take 16-byte gathers, anything else two-byte gathers.
+ *     Workspace: retexo_workspace_bytes(plan, F, mode, heads, flags).
+ */
+typedef enum {
+    RETEXO_STORE_BF16 = 1,
+    RETEXO_STORE_FP16 = 2
+} retexo_storage;
+int retexo_store_rows(int storage, int64_t N, int64_t F, const float* d_src, int64_t lds,
+                      void* d_dst, int64_t ldd, void* stream);
+int retexo_aggregate_stored(const retexo_plan* plan, int mode, int storage, int64_t F, int heads,
+                            const void* d_Z, int64_t ldz,
+                            const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                            unsigned flags, float* d_out, int64_t ldo,
+                            void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
  * One worker's share of an edge-partitioned graph (section "Edge-partitioned
  * Distributed Setup": worker i holds its inner nodes V_i, the edges touching
  * an inner node and, as boundary nodes, their other endpoints) and the pack /

@@ -84,6 +84,28 @@ int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads, int64_t F = 0,
 void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
                        const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream);
 
+// Aggregation over a table in 16-bit storage (see retexo_aggregate_stored)
+struct StoredCall {
+    const retexo_plan* plan;
+    int mode;
+    int storage;           // RETEXO_STORE_*
+    int64_t F;
+    int heads;
+    const void* Z;         // [N, ldz] 16-bit elements
+    int64_t ldz;           // in elements
+    const float* attn_src;
+    const float* attn_dst;
+    float slope;
+    bool self_concat;
+    bool copy_self;
+    float* out;
+    int64_t ldo;
+    void* workspace;
+};
+int launch_aggregate_stored(const StoredCall& c, hipStream_t stream);
+int launch_store_rows(int storage, int64_t N, int64_t F, const float* src, int64_t lds, void* dst, int64_t ldd,
+                      hipStream_t stream);
+
 // Backward of the aggregation (see retexo_aggregate_backward)
 struct AggBackwardCall {
     const retexo_plan* plan;

@@ -262,6 +262,46 @@ extern "C" int retexo_aggregate_backward_saved(const retexo_plan* plan, int mode
                                       d_dattn_dst, d_workspace, workspace_bytes, stream);
 }
 
+extern "C" int retexo_store_rows(int storage, int64_t N, int64_t F, const float* d_src, int64_t lds,
+                                 void* d_dst, int64_t ldd, void* stream)
+{
+    if (storage != RETEXO_STORE_BF16 && storage != RETEXO_STORE_FP16) return RETEXO_E_MODE;
+    if (N < 0 || F < 0) return RETEXO_E_SIZE;
+    if (N > 0 && F > 0 && (!d_src || !d_dst)) return RETEXO_E_NULL;
+    if (lds < F || ldd < F) return RETEXO_E_LD;
+    if (N > 0 && F > 0 && overlaps(d_src, extent_bytes(N, lds, F), d_dst, (size_t)((N - 1) * ldd + F) * 2))
+        return RETEXO_E_ALIAS;
+    return launch_store_rows(storage, N, F, d_src, lds, d_dst, ldd, (hipStream_t)stream);
+}
+
+extern "C" int retexo_aggregate_stored(const retexo_plan* plan, int mode, int storage, int64_t F, int heads,
+                                       const void* d_Z, int64_t ldz,
+                                       const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                                       unsigned flags, float* d_out, int64_t ldo,
+                                       void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    if (!plan) return RETEXO_E_NULL;
+    if (storage != RETEXO_STORE_BF16 && storage != RETEXO_STORE_FP16) return RETEXO_E_MODE;
+    if (F < 0 || F >= (1ll << 30)) return RETEXO_E_SIZE;
+    if (int s = check_mode(mode, F, heads)) return s;
+    if (flags & ~(unsigned)RETEXO_F_SELF_CONCAT) return RETEXO_E_FLAGS;
+    const bool concat = (flags & RETEXO_F_SELF_CONCAT) != 0;
+    const int64_t N = plan->N, ow = concat ? 2 * F : F;
+    if (N > 0 && F > 0 && (!d_Z || !d_out)) return RETEXO_E_NULL;
+    if (mode == RETEXO_GAT_SOFTMAX && N > 0 && F > 0 && (!d_attn_src || !d_attn_dst)) return RETEXO_E_NULL;
+    if (ldz < F || ldo < ow) return RETEXO_E_LD;
+    if (N > 0 && F > 0 && overlaps(d_Z, (size_t)((N - 1) * ldz + F) * 2, d_out, extent_bytes(N, ldo, ow)))
+        return RETEXO_E_ALIAS;
+    const int64_t need = aggregate_workspace_bytes(N, mode, heads);
+    if (need > 0 && (!d_workspace || workspace_bytes < need || ((uintptr_t)d_workspace & 255)))
+        return RETEXO_E_WORKSPACE;
+    StoredCall c;
+    c.plan = plan; c.mode = mode; c.storage = storage; c.F = F; c.heads = heads; c.Z = d_Z; c.ldz = ldz;
+    c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
+    c.self_concat = concat; c.copy_self = true; c.out = d_out; c.ldo = ldo; c.workspace = d_workspace;
+    return launch_aggregate_stored(c, (hipStream_t)stream);
+}
+
 extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out, int heads,
                             const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
                             const float* d_attn_src, const float* d_attn_dst, float negative_slope,

@@ -183,6 +183,38 @@ def aggregate(g: DeviceGraph, mode: str, Z: torch.Tensor, F: int, *, heads: int 
     return out
 
 
+def store_rows(X: torch.Tensor, F: int, fmt: str, ld: Optional[int] = None) -> torch.Tensor:
+    """float32 table -> int16 tensor of bf16 / fp16 patterns, row pitch ``ld`` elements (default: F rounded up to 64)."""
+    n = int(X.shape[0])
+    ld = ld or (F + 63) // 64 * 64
+    out = torch.zeros((n, ld), dtype=torch.int16, device="cuda")
+    B.check(B.retexo_store_rows(B.STORAGE[fmt], n, F, X.data_ptr(), X.stride(0), out.data_ptr(), out.stride(0),
+                                _stream_ptr()), "retexo_store_rows")
+    return out
+
+
+def aggregate_stored(g: DeviceGraph, mode: str, Z16: torch.Tensor, F: int, fmt: str, *, heads: int = 1,
+                     a_src: Optional[torch.Tensor] = None, a_dst: Optional[torch.Tensor] = None,
+                     slope: float = 0.2, concat: bool = False, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    ow = 2 * F if concat else F
+    if out is None:
+        out = torch.empty((g.n_nodes, pad_ld(ow)), dtype=torch.float32, device="cuda")
+    flags = B.F_SELF_CONCAT if concat else 0
+    need = B.retexo_workspace_bytes(g.plan, F, B.MODES[mode], heads, flags)
+    if need < 0:
+        raise B.RetexoError(need, "retexo_workspace_bytes")
+    if workspace is None:
+        workspace = ws_tensor(need)
+    st = B.retexo_aggregate_stored(g.plan, B.MODES[mode], B.STORAGE[fmt], F, heads, Z16.data_ptr(), Z16.stride(0),
+                                   a_src.data_ptr() if a_src is not None else 0,
+                                   a_dst.data_ptr() if a_dst is not None else 0, slope, flags,
+                                   out.data_ptr(), out.stride(0), workspace.data_ptr(), workspace.numel(),
+                                   _stream_ptr())
+    B.check(st, "retexo_aggregate_stored")
+    return out
+
+
 def aggregate_backward(g: DeviceGraph, mode: str, F: int, G: torch.Tensor, *, Z: Optional[torch.Tensor] = None,
                        heads: int = 1, a_src: Optional[torch.Tensor] = None, a_dst: Optional[torch.Tensor] = None,
                        slope: float = 0.2, concat: bool = False, dZ: Optional[torch.Tensor] = None,
