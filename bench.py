@@ -350,6 +350,27 @@ def main():
                                               "GB/s_algorithmic_after_save": nnz * Fz * 4 / times[1] / 1e6})
         except B.RetexoError:
             pass                                           # layout without save mode: the plain backward stands
+    # variant: the dominant aggregation over a table in 16-bit storage (half the gathered bytes; the stored value
+    # is the float32 value rounded to nearest even, sums stay in float32)
+    try:
+        Z16 = Hn.store_rows(Zin, F, "bf16")               # the table the roofline figure above was measured on
+        kw16 = dict(heads=dst_stage.heads, a_src=pipe.params[di][2], a_dst=pipe.params[di][3]) if gat else {}
+        run16 = lambda: Hn.aggregate_stored(pipe.graph, dst_stage.mode, Z16, F, "bf16", concat=dst_stage.concat,
+                                            out=agg_out, workspace=ws, **kw16)
+        run16()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            run16()
+        e1.record()
+        torch.cuda.synchronize()
+        ms16 = e0.elapsed_time(e1) / reps
+        out["stored_aggregation"] = {"storage": "bf16", "stage": roofline["stage"], "ms": ms16,
+                                     "fp32_ms": roofline["ms_per_launch"],
+                                     "GB/s_algorithmic": nnz * F * 2 / ms16 / 1e6}
+        del Z16
+    except B.RetexoError:
+        pass
     # the partition-shaped run: one worker's share of this graph (seeded random ownership over 4 workers for
     # the dense graph, 2 for the large sparse one, as the paper distributes them) and the pack / unpack of all
     # its boundary rows at the first round's width

@@ -74,13 +74,26 @@ __global__ __launch_bounds__(256) void store_rows_kernel(int64_t N, int64_t F, c
     dst[r * ldd + c] = encode1<FMT>(src[r * lds + c]);
 }
 
-// row loads of E stored elements per lane (E = 8: one 16-byte load; E = 1: one 2-byte load)
+// row loads of E stored elements per lane (E = 8: one 16-byte load; 4: one 8-byte load; 1: one 2-byte load)
 template <int FMT, int E>
 __device__ __forceinline__ void load_stored(const uint16_t* p, float (&v)[E])
 {
     if constexpr (E == 8) {
         const f32x4 raw = *reinterpret_cast<const f32x4*>(p);
         decode8<FMT>(raw, v);
+    } else if constexpr (E == 4) {
+        const f32x2 raw = *reinterpret_cast<const f32x2*>(p);
+        const uint32_t w[2] = {__float_as_uint(raw.x), __float_as_uint(raw.y)};
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if constexpr (FMT == FMT_BF16) {
+                v[2 * i] = __uint_as_float(w[i] << 16);
+                v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            } else {
+                v[2 * i] = decode1<FMT>((uint16_t)(w[i] & 0xffffu));
+                v[2 * i + 1] = decode1<FMT>((uint16_t)(w[i] >> 16));
+            }
+        }
     } else {
         v[0] = decode1<FMT>(*p);
     }
@@ -93,6 +106,9 @@ __device__ __forceinline__ void store_floats(float* p, const float (&v)[E], int 
         const f32x4 a = {v[0], v[1], v[2], v[3]}, b = {v[E > 4 ? 4 : 0], v[E > 5 ? 5 : 0], v[E > 6 ? 6 : 0], v[E > 7 ? 7 : 0]};
         *reinterpret_cast<f32x4*>(p) = a;
         *reinterpret_cast<f32x4*>(p + 4) = b;
+    } else if (E == 4 && vec_ok && valid >= 4) {
+        const f32x4 a = {v[0], v[E > 1 ? 1 : 0], v[E > 2 ? 2 : 0], v[E > 3 ? 3 : 0]};
+        *reinterpret_cast<f32x4*>(p) = a;
     } else {
 #pragma unroll
         for (int k = 0; k < E; ++k)
@@ -243,7 +259,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void stored_line
 template <int FMT, bool WEIGHTED>
 __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(StoredArgs a)
 {
-    constexpr int LPG = 8, G = 64 / LPG, U = 4;
+    constexpr int LPG = 8, G = 64 / LPG, U = 8;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t bundles = (a.row_count + G - 1) / G;
@@ -303,11 +319,25 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
     }
 
     const int gaddr = (lane - li) * 4;          // ds_bpermute byte address of this group's lane 0
+    // this lane's entry of the next chunk is fetched while the current chunk is consumed
+    int nxt_u = 0;
+    float nxt_w = 0.0f;
+    if (li < len) {
+        nxt_u = a.col_idx[lo + li];
+        nxt_w = WEIGHTED ? a.wsrc[nxt_u] : 1.0f;
+    }
     for (int c0 = 0; c0 < maxlen; c0 += LPG) {
-        const int idx = c0 + li;
-        const bool ok = idx < len;
-        const int my_u = ok ? a.col_idx[lo + idx] : 0;
-        const float my_w = ok ? (WEIGHTED ? a.wsrc[my_u] : 1.0f) : 0.0f;
+        const int my_u = nxt_u;
+        const float my_w = nxt_w;
+        {
+            const int nb = c0 + LPG + li;
+            nxt_u = 0;
+            nxt_w = 0.0f;
+            if (nb < len) {
+                nxt_u = a.col_idx[lo + nb];
+                nxt_w = WEIGHTED ? a.wsrc[nxt_u] : 1.0f;
+            }
+        }
         const uint32_t my_off = (uint32_t)my_u * rowbytes;
         const bool full = c0 + LPG <= minlen;        // every group still has LPG entries: nothing to mask
 #pragma unroll
@@ -348,6 +378,110 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
     for (int k = 0; k < 8; ++k) {
         float x = acc[k];
         if (a.last) {
+            if (a.scale == 1) x = d > 0 ? x / (float)d : 0.0f;
+            else if (a.scale == 2) x = x * a.dinv[v];
+        }
+        r[k] = x;
+    }
+    store_floats<8>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+    if (a.copy_self && a.first) {
+        float zs[8];
+        load_stored<FMT, 8>(a.Z + (int64_t)v * a.ldz + col, zs);
+        store_floats<8>(orow + col, zs, valid, a.self_vec != 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The same slabs for long rows: a workgroup of eight waves per (row, slab).  A wave reads 64
+// consecutive entries of the row at a time; each of its eight 8-lane groups gathers the eight entries
+// its own lanes hold.  Partial sums are combined across the groups of a wave by shuffles and across
+// waves through LDS, in a fixed order.
+// ---------------------------------------------------------------------------
+template <int FMT, bool WEIGHTED>
+__global__ __launch_bounds__(64 * kHeavyWaves) void stored_grouped_kernel(StoredArgs a)
+{
+    constexpr int LPG = 8, U = 8;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t item = blockIdx.x;                        // slab-major
+    const int slab = (int)(item / a.row_count);
+    const int64_t slot = item % a.row_count;
+    const int v = a.order[a.row_begin + slot];
+    int lo, hi;
+    if (a.part_ptr) {
+        lo = a.part_ptr[(int64_t)a.part_lo * a.n_rows + a.row_begin + slot];
+        hi = a.part_ptr[(int64_t)a.part_hi * a.n_rows + a.row_begin + slot];
+    } else {
+        lo = (int)a.row_ptr[v];
+        hi = (int)a.row_ptr[v + 1];
+    }
+    const int li = lane % LPG;
+    const int64_t col = (int64_t)slab * 64 + li * 8;
+    const bool act = col < a.F;
+    const int valid = (int)min((int64_t)8, a.F - col);
+    const char* zbase = reinterpret_cast<const char*>(a.Z);
+    const uint32_t colbytes = (uint32_t)((act ? col : 0) * 2);
+    const uint32_t rowbytes = (uint32_t)(a.ldz * 2);
+    const int gaddr = (lane - li) * 4;
+
+    float acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = 0.0f;
+    for (int base = lo + 64 * wave; base < hi; base += 64 * kHeavyWaves) {
+        const int e = base + lane;
+        const bool ok = e < hi;
+        const int my_u = ok ? a.col_idx[e] : 0;
+        const float my_w = ok ? (WEIGHTED ? a.wsrc[my_u] : 1.0f) : 0.0f;
+        const uint32_t my_off = (uint32_t)my_u * rowbytes;
+        const bool full = base + 64 <= hi;
+        f32x4 raw[U];
+        float w[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            const uint32_t off = (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * t, (int)my_off) + colbytes;
+            raw[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+            w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * t, __float_as_int(my_w)));
+        }
+        if (!full) {
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                const uint32_t keep = base + (lane - li) + t < hi ? 0xffffffffu : 0u;
+                raw[t].x = __uint_as_float(__float_as_uint(raw[t].x) & keep);
+                raw[t].y = __uint_as_float(__float_as_uint(raw[t].y) & keep);
+                raw[t].z = __uint_as_float(__float_as_uint(raw[t].z) & keep);
+                raw[t].w = __uint_as_float(__float_as_uint(raw[t].w) & keep);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < U; ++t) {
+            float z[8];
+            decode8<FMT>(raw[t], z);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[k] = fmaf(w[t], z[k], acc[k]);
+        }
+    }
+    // the eight groups of a wave, then the eight waves
+#pragma unroll
+    for (int m = LPG; m < 64; m <<= 1)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] += __shfl_xor(acc[k], m, 64);
+    __shared__ float red[kHeavyWaves][LPG][8];
+    if (lane < LPG) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) red[wave][lane][k] = acc[k];
+    }
+    __syncthreads();
+    if (wave != 0 || lane >= LPG || !act) return;
+    float* orow = a.out + (int64_t)v * a.ldo;
+    float r[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float x = red[0][lane][k];
+#pragma unroll
+        for (int w = 1; w < kHeavyWaves; ++w) x += red[w][lane][k];
+        if (!a.first && k < valid) x += orow[a.ocol + col + k];
+        if (a.last) {
+            const int d = a.deg[v];
             if (a.scale == 1) x = d > 0 ? x / (float)d : 0.0f;
             else if (a.scale == 2) x = x * a.dinv[v];
         }
@@ -628,9 +762,10 @@ int launch_stored(const StoredCall& c, hipStream_t stream)
     const bool gat = c.mode == RETEXO_GAT_SOFTMAX;
     const uint16_t* Z = (const uint16_t*)c.Z;
 
-    // 16-byte loads of eight elements need aligned rows padded to whole vectors
+    // 16-byte loads of eight elements need aligned rows padded to whole vectors; rows of at most 256
+    // columns use 8-byte loads of four elements so that all 64 lanes of a wave carry a share of the row
     const bool wide = aligned_rows(Z, c.ldz, 2) && align_up(F, 8) <= c.ldz && opt.max_vec >= 4;
-    const int E = wide ? 8 : 1;
+    const int E = wide ? (F <= 256 ? 4 : 8) : 1;
 
     StoredArgs a;
     a.row_ptr = p->row_ptr;
@@ -688,22 +823,39 @@ int launch_stored(const StoredCall& c, hipStream_t stream)
         }
         if (!p->part_ptr || (parts != 2 && parts != 4 && parts != 8 && parts != 16)) parts = 1;
         if (parts > 1) a.part_ptr = p->part_ptr;
-        a.row_begin = 0;
-        a.row_count = N;
-        const int64_t bundles = (N + 7) / 8;
+        // rows whose share of one range is long get a workgroup each
+        int64_t n_long = 0;
+        for (int i = 0; i < 8; ++i)
+            if (kPlanThresholds[i] >= opt.narrow_heavy * parts || kPlanThresholds[i] >= 16384) {
+                n_long = p->rows_at_least[i];
+                break;
+            }
+        const int64_t bundles = (N - n_long + 7) / 8;
         const int64_t blocks = (bundles * a.nslab + kLightWaves - 1) / kLightWaves;
         for (int k = 0; k < parts; ++k) {
             a.part_lo = k * (kMaxParts / parts);
             a.part_hi = (k + 1) * (kMaxParts / parts);
             a.first = k == 0;
             a.last = k == parts - 1;
-            if (a.wsrc) stored_rowgroup_kernel<FMT, true><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
-            else stored_rowgroup_kernel<FMT, false><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+            if (n_long > 0) {
+                a.row_begin = 0;
+                a.row_count = n_long;
+                const dim3 grid((unsigned)(n_long * a.nslab));
+                if (a.wsrc) stored_grouped_kernel<FMT, true><<<grid, dim3(64 * kHeavyWaves), 0, stream>>>(a);
+                else stored_grouped_kernel<FMT, false><<<grid, dim3(64 * kHeavyWaves), 0, stream>>>(a);
+            }
+            if (N > n_long) {
+                a.row_begin = n_long;
+                a.row_count = N - n_long;
+                if (a.wsrc) stored_rowgroup_kernel<FMT, true><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+                else stored_rowgroup_kernel<FMT, false><<<dim3((unsigned)blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
+            }
         }
     } else if (!gat) {
         const bool maxop = c.mode == RETEXO_MAX;
-        if (E == 8) { if (maxop) dispatch_linear<FMT, 8, true>(nc, a, n_heavy, N, stream); else dispatch_linear<FMT, 8, false>(nc, a, n_heavy, N, stream); }
-        else        { if (maxop) dispatch_linear<FMT, 1, true>(nc, a, n_heavy, N, stream); else dispatch_linear<FMT, 1, false>(nc, a, n_heavy, N, stream); }
+        if (E == 8)      { if (maxop) dispatch_linear<FMT, 8, true>(nc, a, n_heavy, N, stream); else dispatch_linear<FMT, 8, false>(nc, a, n_heavy, N, stream); }
+        else if (E == 4) { if (maxop) dispatch_linear<FMT, 4, true>(nc, a, n_heavy, N, stream); else dispatch_linear<FMT, 4, false>(nc, a, n_heavy, N, stream); }
+        else             { if (maxop) dispatch_linear<FMT, 1, true>(nc, a, n_heavy, N, stream); else dispatch_linear<FMT, 1, false>(nc, a, n_heavy, N, stream); }
     } else {
         const int hp = heads_padded(c.heads);
         const GatWorkspace w = gat_workspace(N, F, c.heads, false);
@@ -718,6 +870,9 @@ int launch_stored(const StoredCall& c, hipStream_t stream)
         if (E == 8) {
             if (hp == 4) { if (hu) dispatch_gat<FMT, 8, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 8, 4, false>(nc, a, n_heavy, N, stream); }
             else         { if (hu) dispatch_gat<FMT, 8, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 8, 8, false>(nc, a, n_heavy, N, stream); }
+        } else if (E == 4) {
+            if (hp == 4) { if (hu) dispatch_gat<FMT, 4, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 4, 4, false>(nc, a, n_heavy, N, stream); }
+            else         { if (hu) dispatch_gat<FMT, 4, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 4, 8, false>(nc, a, n_heavy, N, stream); }
         } else {
             if (hp == 4) dispatch_gat<FMT, 1, 4, true>(nc, a, n_heavy, N, stream);
             else dispatch_gat<FMT, 1, 8, true>(nc, a, n_heavy, N, stream);

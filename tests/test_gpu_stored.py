@@ -185,5 +185,8 @@ def test_full_size_stored_first_round(idx):
         return e0.elapsed_time(e1) / reps
     t32 = t(lambda: Hn.aggregate(g, st.mode, Zd, F, concat=st.concat, out=o32, workspace=ws, **kw))
     t16 = t(lambda: Hn.aggregate_stored(g, st.mode, Z16, F, "bf16", concat=st.concat, out=out, workspace=ws, **kw))
-    print("workload %d first-round aggregation: fp32 table %.2f ms, bf16 table %.2f ms" % (idx, t32, t16), flush=True)
+    Zh16 = Hn.store_rows(Zd, F, "fp16")
+    th = t(lambda: Hn.aggregate_stored(g, st.mode, Zh16, F, "fp16", concat=st.concat, out=out, workspace=ws, **kw))
+    print("workload %d first-round aggregation: fp32 table %.2f ms, bf16 table %.2f ms, fp16 table %.2f ms"
+          % (idx, t32, t16, th), flush=True)
     g.destroy()
