@@ -325,7 +325,7 @@ int retexo_aggregate_stored(const retexo_plan* plan, int mode, int storage, int6
  * of the implementation section; the transport itself is not part of this
  * library).  Input: the global CSR (as retexo_csr_from_coo builds it: columns
  * ascending) and d_part [N], the worker that owns each node, values in
- * [0, n_parts), n_parts <= 64.  Output for worker `part`:
+ * [0, n_parts), n_parts <= 64, N * (n_parts - 1) < 2^31.  Output for worker `part`:
  *   local numbering [ inner nodes, ascending global id | boundary nodes, ascending global id ]
  *   d_local_ids      [n_local]     global id of each local node, n_local = n_inner + n_halo
  *   d_local_row_ptr  [n_local + 1] int64; an inner node's row is its global row renumbered,

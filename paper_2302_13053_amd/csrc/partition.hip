@@ -317,6 +317,7 @@ extern "C" int64_t retexo_partition_workspace_bytes(int64_t N, int n_parts, int6
 {
     if (N < 0 || N >= (1ll << 31) || send_capacity < 0 || send_capacity >= (1ll << 31)) return RETEXO_E_SIZE;
     if (n_parts < 1 || n_parts > kMaxWorkers) return RETEXO_E_SIZE;
+    if (N * (int64_t)(n_parts - 1) >= (1ll << 31)) return RETEXO_E_SIZE;     // 32-bit offsets of the send keys
     Layout L;
     if (int s = make_layout(N, send_capacity, L)) return s;
     return L.total;
@@ -332,6 +333,7 @@ extern "C" int retexo_partition_share(int64_t N, const int64_t* d_row_ptr, const
 {
     if (N < 0 || N >= (1ll << 31)) return RETEXO_E_SIZE;
     if (n_parts < 1 || n_parts > kMaxWorkers || part < 0 || part >= n_parts) return RETEXO_E_SIZE;
+    if (N * (int64_t)(n_parts - 1) >= (1ll << 31)) return RETEXO_E_SIZE;     // 32-bit offsets of the send keys
     if (local_capacity < 0 || col_capacity < 0 || send_capacity < 0 || send_capacity >= (1ll << 31)) return RETEXO_E_SIZE;
     if (!h_sizes) return RETEXO_E_NULL;
     if (N > 0 && (!d_row_ptr || !d_part)) return RETEXO_E_NULL;
