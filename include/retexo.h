@@ -223,6 +223,13 @@ int retexo_aggregate_backward(const retexo_plan* plan, int mode, int64_t F, int 
                               float* d_dZ, int64_t lddz, float* d_dattn_src, float* d_dattn_dst,
                               void* d_workspace, int64_t workspace_bytes, void* stream);
 
+/* Mean over attention heads: d_out[v, c] = (1 / heads) * sum_h d_in[v, h * C + c] for c < C.
+ * The last attention round of a classifier has width heads * classes and its heads are averaged,
+ * not concatenated (the standard form of the cited attention network; the paper does not say).
+ * d_in [N, ldi] with ldi >= heads * C, d_out [N, ldo]; must not overlap.  Enqueues on `stream`. */
+int retexo_head_mean(int64_t N, int heads, int64_t C, const float* d_in, int64_t ldi,
+                     float* d_out, int64_t ldo, void* stream);
+
 /* ---------------------------------------------------------------------------
  * One whole round: retexo_transform followed by retexo_aggregate on the same
  * stream, Z being kept in the workspace (or directly in out's first D_out

@@ -31,7 +31,7 @@ EXPORTS = (
     "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward", "retexo_aggregate_backward_saved",
     "retexo_partition_workspace_bytes", "retexo_partition_share", "retexo_halo_pack", "retexo_halo_unpack",
     "retexo_plan_set_degrees", "retexo_data_volumes", "retexo_gamma",
-    "retexo_store_rows", "retexo_aggregate_stored",
+    "retexo_store_rows", "retexo_aggregate_stored", "retexo_head_mean",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
     "retexo_layer_grad_x", "retexo_transform_backward_workspace_bytes", "retexo_transform_backward",
 )
@@ -94,6 +94,8 @@ def load():
     lib.retexo_aggregate_backward_saved.restype = i32
     lib.retexo_aggregate_backward_saved.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64,
                                                     vp, i64, vp, i64, vp, vp, vp, i64, vp]
+    lib.retexo_head_mean.restype = i32
+    lib.retexo_head_mean.argtypes = [i64, i32, i64, vp, i64, vp, i64, vp]
     lib.retexo_store_rows.restype = i32
     lib.retexo_store_rows.argtypes = [i32, i64, i64, vp, i64, vp, i64, vp]
     lib.retexo_aggregate_stored.restype = i32
@@ -233,6 +235,10 @@ def retexo_aggregate_backward_saved(plan, mode, F, heads, d_Z, ldz, d_attn_src, 
                                                       _vp(d_saved), saved_bytes, _vp(d_dZ), lddz,
                                                       _vp(d_dattn_src), _vp(d_dattn_dst), _vp(d_workspace),
                                                       workspace_bytes, _vp(stream)))
+
+
+def retexo_head_mean(n, heads, C_, d_in, ldi, d_out, ldo, stream=0) -> int:
+    return int(load().retexo_head_mean(n, heads, C_, _vp(d_in), ldi, _vp(d_out), ldo, _vp(stream)))
 
 
 STORAGE = {"bf16": 1, "fp16": 2}

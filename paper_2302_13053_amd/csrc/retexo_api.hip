@@ -302,6 +302,35 @@ extern "C" int retexo_aggregate_stored(const retexo_plan* plan, int mode, int st
     return launch_aggregate_stored(c, (hipStream_t)stream);
 }
 
+namespace {
+// out[v, c] = (1 / heads) * sum_h in[v, h * C + c]; heads added in index order
+__global__ __launch_bounds__(256) void head_mean_kernel(int64_t N, int heads, int64_t C, const float* __restrict__ in,
+                                                         int64_t ldi, float* __restrict__ out, int64_t ldo)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * C) return;
+    const int64_t v = i / C, c = i % C;
+    float s = 0.0f;
+    for (int h = 0; h < heads; ++h) s += in[v * ldi + h * C + c];
+    out[v * ldo + c] = s / (float)heads;
+}
+}  // namespace
+
+extern "C" int retexo_head_mean(int64_t N, int heads, int64_t C, const float* d_in, int64_t ldi,
+                                float* d_out, int64_t ldo, void* stream)
+{
+    if (N < 0 || C < 0 || N * C >= (1ll << 40)) return RETEXO_E_SIZE;
+    if (heads < 1 || heads > kMaxHeads) return RETEXO_E_HEADS;
+    if (ldi < heads * C || ldo < C) return RETEXO_E_LD;
+    if (N == 0 || C == 0) return RETEXO_OK;
+    if (!d_in || !d_out) return RETEXO_E_NULL;
+    if (overlaps(d_in, extent_bytes(N, ldi, heads * C), d_out, extent_bytes(N, ldo, C))) return RETEXO_E_ALIAS;
+    head_mean_kernel<<<dim3((unsigned)((N * C + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        N, heads, C, d_in, ldi, d_out, ldo);
+    if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
+    return RETEXO_OK;
+}
+
 extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int64_t D_out, int heads,
                             const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
                             const float* d_attn_src, const float* d_attn_dst, float negative_slope,

@@ -320,3 +320,20 @@ def test_in_place_concat_and_argument_errors(graphs):
     assert args(flags=B.F_RELU) == B.E_FLAGS
     assert args(out=Z.data_ptr() + 64, ldo=F) == B.E_ALIAS
     assert args(Z=0) == B.E_NULL
+
+
+@pytest.mark.parametrize("n,heads,C,ldi,ldo", [(1000, 4, 47, 188, 47), (513, 8, 7, 64, 9), (3, 1, 5, 5, 5), (0, 2, 3, 6, 3)])
+def test_head_mean(n, heads, C, ldi, ldo):
+    """The last attention round's heads are averaged: plain definition (float64 mean over the head axis)."""
+    X = wl.random_matrix(max(n, 1), heads * C, 5, ld=ldi)[:n]
+    out = torch.full((max(n, 1), ldo + 2), 9.0, dtype=torch.float32, device="cuda")
+    Xd = Hn.dev(np.ascontiguousarray(X)) if n else torch.zeros((1, ldi), dtype=torch.float32, device="cuda")
+    B.check(B.retexo_head_mean(n, heads, C, Xd.data_ptr(), ldi, out.data_ptr(), out.stride(0)), "retexo_head_mean")
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = X[:, :heads * C].astype(np.float64).reshape(n, heads, C).mean(axis=1)
+    if n:
+        assert_close(got[:n, :C], want, what="head mean")
+    assert np.all(got[:, C:] == 9.0) and np.all(got[n:] == 9.0)
+    assert B.retexo_head_mean(5, 9, C, Xd.data_ptr(), ldi, out.data_ptr(), ldo) == -6
+    assert B.retexo_head_mean(5, heads, C, Xd.data_ptr(), heads * C - 1, out.data_ptr(), ldo) == -3
