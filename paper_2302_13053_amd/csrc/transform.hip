@@ -122,18 +122,28 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nk) { load_a(kt + 1); load_b(kt + 1); }
+        // operand fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued
+        // before the MFMAs of k-step s, so their latency hides behind matrix work
+        float af[2][TM], bf[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[0][i] = As[buf][lk][wm * TM * 32 + i * 32 + lrow];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bf[0][j] = Bs[buf][lk][wn * TN * 32 + j * 32 + lrow];
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            float af[TM], bf[TN];
+            const int cur = (kk >> 1) & 1;
+            if (kk + 2 < BK) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = As[buf][kk + lk][wm * TM * 32 + i * 32 + lrow];
+                for (int i = 0; i < TM; ++i) af[cur ^ 1][i] = As[buf][kk + 2 + lk][wm * TM * 32 + i * 32 + lrow];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = Bs[buf][kk + lk][wn * TN * 32 + j * 32 + lrow];
+                for (int j = 0; j < TN; ++j) bf[cur ^ 1][j] = Bs[buf][kk + 2 + lk][wn * TN * 32 + j * 32 + lrow];
+            }
+            __builtin_amdgcn_sched_barrier(0);       // keep those reads ahead of this step's MFMAs
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) store_tiles(buf ^ 1);
         __syncthreads();
