@@ -21,6 +21,11 @@
  *     they do not allocate, free or synchronise.  retexo_csr_from_coo and
  *     retexo_plan_create synchronise the stream once; retexo_plan_create also
  *     allocates the plan's own small arrays.
+ *   - Every entry point documented as "Enqueues on `stream`" only launches kernels there: no
+ *     allocation, no host synchronisation, no memset or copy nodes.  A caller may therefore record
+ *     a sequence of them (a round, a training step) into a HIP graph by stream capture and
+ *     replay it; retexo_csr_from_coo, retexo_plan_create and retexo_partition_share synchronise
+ *     and cannot be captured.
  *   - Return value 0 (RETEXO_OK) or a negative retexo_status.  Argument errors
  *     are detected before any kernel is launched, so no output byte has been
  *     written when one is returned.

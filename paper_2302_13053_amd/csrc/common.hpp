@@ -53,6 +53,10 @@ struct AggOptions {
 };
 AggOptions& agg_options();
 
+// Zero `bytes` (a multiple of 4) at `p` with a small kernel.  The stream-ordered entry points use this
+// instead of memset nodes so that a caller can record them into a HIP graph.
+int launch_zero(void* p, size_t bytes, hipStream_t stream);
+
 // internal launchers (no argument validation; the C entry points did it)
 int launch_transform(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
                      const float* W, const float* b, bool relu, float* Z, int64_t ldz,

@@ -215,8 +215,8 @@ int aggregate_backward_checked(const retexo_plan* plan, int mode, int64_t F, int
         return RETEXO_E_WORKSPACE;
     if (gat && !work && d_dattn_src && d_dattn_dst && F > 0) {
         // no nodes: the parameter gradients are zero
-        if (hipMemsetAsync(d_dattn_src, 0, (size_t)F * sizeof(float), (hipStream_t)stream) != hipSuccess ||
-            hipMemsetAsync(d_dattn_dst, 0, (size_t)F * sizeof(float), (hipStream_t)stream) != hipSuccess)
+        if (launch_zero(d_dattn_src, (size_t)F * sizeof(float), (hipStream_t)stream) != RETEXO_OK ||
+            launch_zero(d_dattn_dst, (size_t)F * sizeof(float), (hipStream_t)stream) != RETEXO_OK)
             return RETEXO_E_HIP;
         return RETEXO_OK;
     }
@@ -300,6 +300,22 @@ extern "C" int retexo_aggregate_stored(const retexo_plan* plan, int mode, int st
     c.attn_src = d_attn_src; c.attn_dst = d_attn_dst; c.slope = negative_slope;
     c.self_concat = concat; c.copy_self = true; c.out = d_out; c.ldo = ldo; c.workspace = d_workspace;
     return launch_aggregate_stored(c, (hipStream_t)stream);
+}
+
+namespace {
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* __restrict__ p, size_t words)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
+}  // namespace
+
+int launch_zero(void* p, size_t bytes, hipStream_t stream)
+{
+    const size_t words = bytes / 4;
+    if (words == 0) return RETEXO_OK;
+    zero_words_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream>>>((uint32_t*)p, words);
+    return hipGetLastError() == hipSuccess ? RETEXO_OK : RETEXO_E_HIP;
 }
 
 namespace {

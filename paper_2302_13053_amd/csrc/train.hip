@@ -459,17 +459,17 @@ extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C
 
     if (N == 0) {
         // nothing to learn from: zero loss and gradients
-        RETEXO_HIP_TRY(hipMemsetAsync(d_gW1, 0, (size_t)(D_in * W1cols) * 4, stream));
-        RETEXO_HIP_TRY(hipMemsetAsync(d_gb1, 0, (size_t)W1cols * 4, stream));
+        if (launch_zero(d_gW1, (size_t)(D_in * W1cols) * 4, stream)) return RETEXO_E_HIP;
+        if (launch_zero(d_gb1, (size_t)W1cols * 4, stream)) return RETEXO_E_HIP;
         if (H > 0) {
-            RETEXO_HIP_TRY(hipMemsetAsync(d_gWc, 0, (size_t)(H * C) * 4, stream));
-            RETEXO_HIP_TRY(hipMemsetAsync(d_gbc, 0, (size_t)C * 4, stream));
+            if (launch_zero(d_gWc, (size_t)(H * C) * 4, stream)) return RETEXO_E_HIP;
+            if (launch_zero(d_gbc, (size_t)C * 4, stream)) return RETEXO_E_HIP;
         }
-        RETEXO_HIP_TRY(hipMemsetAsync(d_loss, 0, 4, stream));
+        if (launch_zero(d_loss, 4, stream)) return RETEXO_E_HIP;
         return RETEXO_OK;
     }
 
-    RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(TrainHeader), stream));
+    if (launch_zero(hdr, sizeof(TrainHeader), stream)) return RETEXO_E_HIP;
     count_labelled<<<dim3((unsigned)min((int64_t)1024, (N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(N, d_labels, hdr);
 
     // forward
@@ -567,8 +567,8 @@ extern "C" int retexo_transform_backward(int64_t N, int64_t D_in, int64_t D_out,
     if (!d_workspace || workspace_bytes < t.total || ((uintptr_t)d_workspace & 255)) return RETEXO_E_WORKSPACE;
     hipStream_t stream = (hipStream_t)stream_;
     if (N == 0) {
-        RETEXO_HIP_TRY(hipMemsetAsync(d_gW, 0, (size_t)(D_in * D_out) * 4, stream));
-        if (d_gb) RETEXO_HIP_TRY(hipMemsetAsync(d_gb, 0, (size_t)D_out * 4, stream));
+        if (launch_zero(d_gW, (size_t)(D_in * D_out) * 4, stream)) return RETEXO_E_HIP;
+        if (d_gb) if (launch_zero(d_gb, (size_t)D_out * 4, stream)) return RETEXO_E_HIP;
         return RETEXO_OK;
     }
     char* ws = (char*)d_workspace;
