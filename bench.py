@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (0-4)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = per-workload default)")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a tuning knob of the library (retexo_set_option) before running, for experiments")
     ap.add_argument("--probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one pass, then one 1 GiB device copy (the known-size "
                          "reference for the byte counters) and one launch of the dominant aggregation; no JSON")
@@ -123,6 +125,9 @@ def main():
     from paper_2302_13053_amd import workloads as wl
 
     B.load()
+    for item in args.option:
+        name, _, value = item.partition("=")
+        B.check(B.retexo_set_option(name, int(value)), "retexo_set_option(%s)" % item)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
