@@ -20,6 +20,9 @@ namespace {
 
 enum { FMT_BF16 = RETEXO_STORE_BF16, FMT_FP16 = RETEXO_STORE_FP16 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));    // sixteen bytes of stored elements, kept as integers
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 template <int FMT>
 __device__ __forceinline__ float decode1(uint16_t x)
 {
@@ -34,9 +37,9 @@ __device__ __forceinline__ float decode1(uint16_t x)
 
 // eight stored elements (16 bytes) -> floats
 template <int FMT>
-__device__ __forceinline__ void decode8(const f32x4& raw, float (&v)[8])
+__device__ __forceinline__ void decode8(const u32x4& raw, float (&v)[8])
 {
-    const uint32_t w[4] = {__float_as_uint(raw.x), __float_as_uint(raw.y), __float_as_uint(raw.z), __float_as_uint(raw.w)};
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if constexpr (FMT == FMT_BF16) {
@@ -79,11 +82,11 @@ template <int FMT, int E>
 __device__ __forceinline__ void load_stored(const uint16_t* p, float (&v)[E])
 {
     if constexpr (E == 8) {
-        const f32x4 raw = *reinterpret_cast<const f32x4*>(p);
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(p);
         decode8<FMT>(raw, v);
     } else if constexpr (E == 4) {
-        const f32x2 raw = *reinterpret_cast<const f32x2*>(p);
-        const uint32_t w[2] = {__float_as_uint(raw.x), __float_as_uint(raw.y)};
+        const u32x2 raw = *reinterpret_cast<const u32x2*>(p);
+        const uint32_t w[2] = {raw.x, raw.y};
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             if constexpr (FMT == FMT_BF16) {
@@ -342,12 +345,12 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
         const bool full = c0 + LPG <= minlen;        // every group still has LPG entries: nothing to mask
 #pragma unroll
         for (int i0 = 0; i0 < LPG; i0 += U) {
-            f32x4 raw[U];
+            u32x4 raw[U];
             float w[U];
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 const uint32_t off = (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (i0 + t), (int)my_off) + colbytes;
-                raw[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+                raw[t] = *reinterpret_cast<const u32x4*>(zbase + off);
                 w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (i0 + t), __float_as_int(my_w)));
             }
             if (!full) {
@@ -355,11 +358,11 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
                 // decode zero bits to +0), so that nothing of an unrelated row can reach the sum
 #pragma unroll
                 for (int t = 0; t < U; ++t) {
-                    const float keep = c0 + i0 + t < len ? __uint_as_float(0xffffffffu) : 0.0f;
-                    raw[t].x = __uint_as_float(__float_as_uint(raw[t].x) & __float_as_uint(keep));
-                    raw[t].y = __uint_as_float(__float_as_uint(raw[t].y) & __float_as_uint(keep));
-                    raw[t].z = __uint_as_float(__float_as_uint(raw[t].z) & __float_as_uint(keep));
-                    raw[t].w = __uint_as_float(__float_as_uint(raw[t].w) & __float_as_uint(keep));
+                    const uint32_t keep = c0 + i0 + t < len ? 0xffffffffu : 0u;
+                    raw[t].x &= keep;
+                    raw[t].y &= keep;
+                    raw[t].z &= keep;
+                    raw[t].w &= keep;
                 }
             }
 #pragma unroll
@@ -434,22 +437,22 @@ __global__ __launch_bounds__(64 * kHeavyWaves) void stored_grouped_kernel(Stored
         const float my_w = ok ? (WEIGHTED ? a.wsrc[my_u] : 1.0f) : 0.0f;
         const uint32_t my_off = (uint32_t)my_u * rowbytes;
         const bool full = base + 64 <= hi;
-        f32x4 raw[U];
+        u32x4 raw[U];
         float w[U];
 #pragma unroll
         for (int t = 0; t < U; ++t) {
             const uint32_t off = (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * t, (int)my_off) + colbytes;
-            raw[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+            raw[t] = *reinterpret_cast<const u32x4*>(zbase + off);
             w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * t, __float_as_int(my_w)));
         }
         if (!full) {
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 const uint32_t keep = base + (lane - li) + t < hi ? 0xffffffffu : 0u;
-                raw[t].x = __uint_as_float(__float_as_uint(raw[t].x) & keep);
-                raw[t].y = __uint_as_float(__float_as_uint(raw[t].y) & keep);
-                raw[t].z = __uint_as_float(__float_as_uint(raw[t].z) & keep);
-                raw[t].w = __uint_as_float(__float_as_uint(raw[t].w) & keep);
+                raw[t].x &= keep;
+                raw[t].y &= keep;
+                raw[t].z &= keep;
+                raw[t].w &= keep;
             }
         }
 #pragma unroll
