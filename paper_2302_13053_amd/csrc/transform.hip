@@ -10,19 +10,267 @@
 // whenever D_out <= 256, so H — by far the larger operand — is read from HBM
 // exactly once.  The K loop moves BK = 16 columns of H and rows of W per step
 // through LDS, both stored k-major so that the MFMA operand of lane l
-// (row l%32, k = l/32) is a conflict-free consecutive read.  The next step's
-// global loads are issued into registers before the current step's MFMAs and
-// written to the other LDS buffer afterwards (one barrier per step).
-// Bias and ReLU are applied to the accumulators before the store.
+// (row l%32, k = l/32) is a conflict-free consecutive read.
+//
+// Schedule.  One wave keeps a matrix core busy only if nothing else in its
+// instruction stream takes longer than one MFMA (64 cycles), so all staging
+// work is cut into pieces of that size and placed between the MFMAs of the
+// wave that does it: the operand reads of the next k-step after the first MFMA
+// of a step, then one slice per step of "write the next tile to the other LDS
+// buffer" and "fetch the tile after that into registers".  Global loads
+// therefore have a whole K step of MFMAs (4096 cycles) to arrive, and the one
+// barrier per K step sits between the last two k-steps, whose operands are
+// already in registers.  Sources are clamped instead of checked (rows past the
+// end repeat the last row, columns past D_out repeat the last four), so the
+// loop carries no selects; only a partial last K tile takes a checked form.
+// Bias and ReLU are applied to the accumulators on the way out, through one
+// pointer per 32x32 tile that walks down the rows.
+//
+// Shapes whose rows cannot be fetched as aligned 16-byte pieces take the
+// simple kernel below it (same arithmetic, same order, checked scalar loads).
 #include "common.hpp"
 #include "tiles.hpp"
+
+#include <type_traits>
 
 namespace {
 
 constexpr int BK = kTileK;
 
-template <int BM, int BN, int WGM, int WGN, bool HV, bool WV>
+#define FENCE() __builtin_amdgcn_sched_barrier(0)      // nothing is scheduled across this point
+
+// Bias, ReLU, optional mask and store of the accumulators of one wave.
+// Accumulator element r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile.
+// Only the last row block of the matrix checks rows.
+template <int TM, int TN, bool MASKED>
+__device__ __forceinline__ void write_out(const f32x16 (&acc)[TM][TN], const float (&bv)[TN], int64_t N, int D_out,
+                                          int64_t row_base, int col_base, int lane, int relu,
+                                          float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm,
+                                          bool whole_block)
+{
+    const int lrow = lane & 31, lk = lane >> 5;
+    auto run = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = col_base + j * 32 + lrow;
+            if (col >= D_out) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int64_t row0 = row_base + i * 32 + 4 * lk;
+                float* p = Z + row0 * ldz + col;
+                float mv[16];
+                if constexpr (MASKED) {
+                    // backward of a ReLU layer: the value passes only where the forward activation was positive
+                    const float* pm = mask + row0 * ldm + col;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int ro = 8 * (r / 4) + (r % 4);
+                        mv[r] = (FULL || row0 + ro < N) ? pm[ro * ldm] : 0.0f;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ro = 8 * (r / 4) + (r % 4);
+                    float x = acc[i][j][r] + bv[j];
+                    if (relu) x = fmaxf(x, 0.0f);
+                    if constexpr (MASKED) x = mv[r] > 0.0f ? x : 0.0f;
+                    if (FULL || row0 + ro < N) p[ro * ldz] = x;
+                }
+            }
+        }
+    };
+    if (whole_block) run(std::true_type{});
+    else run(std::false_type{});
+}
+
+// Aligned shapes: H rows and W rows are multiples of 16 bytes at 16-byte aligned addresses, D_out >= 4.
+template <int BM, int BN, int WGM, int WGN, bool MASKED>
 __global__ __launch_bounds__(256, 2) void transform_kernel(
+    int64_t N, int D_in, int D_out, const float* __restrict__ H, int64_t ldh,
+    const float* __restrict__ W, const float* __restrict__ bias, int relu,
+    float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    constexpr int TM = BM / (32 * WGM);
+    constexpr int TN = BN / (32 * WGN);
+    constexpr int LDA = BM + 2;
+    constexpr int LDB = BN + 4;
+    constexpr int A_F4 = BM * BK / 4 / 256;
+    constexpr int B_F4 = (BN * BK / 4 + 255) / 256;
+    constexpr bool B_PART = BN * BK / 4 % 256 != 0;
+    constexpr int NSTEP = BK / 2;
+    static_assert(A_F4 >= 1 && NSTEP == 8, "tile shape");
+
+    __shared__ float As[2][BK][LDA];
+    __shared__ float Bs[2][BK][LDB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // per-thread source pointers; rows past the end and columns past D_out are clamped to the
+    // last valid ones (their products land in outputs that are never stored)
+    const float* pa[A_F4];
+    const float* pb[B_F4];
+    int ka[A_F4], kb[B_F4];                   // k offset of the thread's element inside a tile
+#pragma unroll
+    for (int i = 0; i < A_F4; ++i) {
+        const int id = tid + i * 256;
+        const int r = id / 4, k4 = id % 4;
+        int64_t row = m0 + r;
+        row = row < N ? row : N - 1;
+        pa[i] = H + row * ldh + k4 * 4;
+        ka[i] = k4 * 4;
+    }
+#pragma unroll
+    for (int i = 0; i < B_F4; ++i) {
+        const int id = tid + i * 256;
+        const int kk = (id / (BN / 4)) % BK, n4 = id % (BN / 4);
+        int n = n0 + n4 * 4;
+        n = n < D_out - 4 ? n : D_out - 4;
+        pb[i] = W + (int64_t)kk * D_out + n;
+        kb[i] = kk;
+    }
+    const int64_t step_b = (int64_t)BK * D_out;
+
+    f32x4 ra[A_F4], rb[B_F4];
+    const int nk = (D_in + BK - 1) / BK;
+    const int k_tail = D_in % BK;             // > 0: the last tile is partly outside the matrix
+
+    // fetch tile kt into the staging registers; the partial last tile takes the checked form
+    auto fetch_a = [&](int kt) {
+        if (k_tail && kt == nk - 1) {
+#pragma unroll
+            for (int i = 0; i < A_F4; ++i) {
+                const bool in = ka[i] < k_tail;
+                const f32x4 t = *reinterpret_cast<const f32x4*>(in ? pa[i] : H);
+                ra[i] = in ? t : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_F4; ++i) ra[i] = *reinterpret_cast<const f32x4*>(pa[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) pa[i] += BK;
+    };
+    auto fetch_b = [&](int kt) {
+        if (k_tail && kt == nk - 1) {
+#pragma unroll
+            for (int i = 0; i < B_F4; ++i) {
+                const bool in = kb[i] < k_tail;
+                const f32x4 t = *reinterpret_cast<const f32x4*>(in ? pb[i] : W);
+                rb[i] = in ? t : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < B_F4; ++i) rb[i] = *reinterpret_cast<const f32x4*>(pb[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < B_F4; ++i) pb[i] += step_b;
+    };
+    auto put_a = [&](int buf, int i) {
+        const int id = tid + i * 256;
+        const int r = id / 4, k4 = id % 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) As[buf][k4 * 4 + q][r] = ra[i][q];
+    };
+    auto put_b = [&](int buf, int i) {
+        const int id = tid + i * 256;
+        if (B_PART && id >= BN * BK / 4) return;
+        const int kk = id / (BN / 4), n4 = id % (BN / 4);
+        *reinterpret_cast<f32x4*>(&Bs[buf][kk][n4 * 4]) = rb[i];
+    };
+
+    float bv[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * TN * 32 + j * 32 + lrow;
+        bv[j] = (bias && col < D_out) ? bias[col] : 0.0f;
+    }
+
+    float af[2][TM], bf[2][TN];
+    auto frag = [&](int buf, int s, int slot) {       // operands of k-step s -> register set slot
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[slot][i] = As[buf][2 * s + lk][wm * TM * 32 + i * 32 + lrow];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bf[slot][j] = Bs[buf][2 * s + lk][wn * TN * 32 + j * 32 + lrow];
+    };
+
+    // prologue: tile 0 -> LDS, tile 1 -> staging registers, first operands -> registers
+    fetch_a(0);
+    fetch_b(0);
+#pragma unroll
+    for (int i = 0; i < A_F4; ++i) put_a(0, i);
+#pragma unroll
+    for (int i = 0; i < B_F4; ++i) put_b(0, i);
+    if (nk > 1) { fetch_a(1); fetch_b(1); }
+    __syncthreads();
+    frag(0, 0, 0);
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        const bool more = kt + 1 < nk;        // staging registers hold tile kt + 1
+        const bool more2 = kt + 2 < nk;
+#pragma unroll
+        for (int s = 0; s < NSTEP; ++s) {
+            const int cur = s & 1;
+            int q = 0;                        // MFMAs issued in this step
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
+                    FENCE();
+                    if (q == 0) {
+                        // operands of the next k-step (the last step's successor is read after the barrier)
+                        if (s + 1 < NSTEP) frag(buf, s + 1, cur ^ 1);
+                        FENCE();
+                    }
+                    if (q == (TM * TN > 1 ? 1 : 0)) {
+                        // one slice of the staging work per step
+                        if (s == 0 && more) { put_a(buf ^ 1, 0); if (A_F4 > 1) put_a(buf ^ 1, 1); }
+                        if (s == 1 && more) { _Pragma("unroll") for (int x = 2; x < A_F4; ++x) put_a(buf ^ 1, x); put_b(buf ^ 1, 0); }
+                        if (s == 2 && more) { _Pragma("unroll") for (int x = 1; x < B_F4; ++x) put_b(buf ^ 1, x); }
+                        if (s == 3 && more2) fetch_a(kt + 2);
+                        if (s == 4 && more2) fetch_b(kt + 2);
+                        FENCE();
+                    }
+                    ++q;
+                }
+            }
+            if (s == NSTEP - 2) {
+                // every wave has read its last operands of this tile and written its share of the next
+                __syncthreads();                       // waits for LDS traffic only: the global loads stay in flight
+                FENCE();
+                if (more) frag(buf ^ 1, 0, 0);
+                FENCE();
+            }
+        }
+    }
+
+
+    write_out<TM, TN, MASKED>(acc, bv, N, D_out, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, relu, Z, ldz, mask, ldm,
+                              m0 + BM <= N);
+}
+
+// Any shape: every element is fetched under its own check (HV / WV: the rows of H / W still allow 16-byte
+// loads), the next K step's loads are issued before this step's MFMAs and written to the other LDS
+// buffer after them.
+template <int BM, int BN, int WGM, int WGN, bool HV, bool WV, bool MASKED>
+__global__ __launch_bounds__(256, 2) void transform_generic_kernel(
     int64_t N, int D_in, int D_out, const float* __restrict__ H, int64_t ldh,
     const float* __restrict__ W, const float* __restrict__ bias, int relu,
     float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm)
@@ -123,7 +371,7 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
         const int buf = kt & 1;
         if (kt + 1 < nk) { load_a(kt + 1); load_b(kt + 1); }
         // operand fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued
-        // before the MFMAs of k-step s, so their latency hides behind matrix work
+        // before the MFMAs of k-step s
         float af[2][TM], bf[2][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[0][i] = As[buf][lk][wm * TM * 32 + i * 32 + lrow];
@@ -138,7 +386,7 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
 #pragma unroll
                 for (int j = 0; j < TN; ++j) bf[cur ^ 1][j] = Bs[buf][kk + 2 + lk][wn * TN * 32 + j * 32 + lrow];
             }
-            __builtin_amdgcn_sched_barrier(0);       // keep those reads ahead of this step's MFMAs
+            FENCE();                                 // keep those reads ahead of this step's MFMAs
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -149,29 +397,26 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
         __syncthreads();
     }
 
-    // accumulator element r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * TN * 32 + j * 32 + lrow;
-        if (col >= D_out) continue;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (row < N) {
-                    float x = acc[i][j][r] + bv[j];
-                    if (relu) x = fmaxf(x, 0.0f);
-                    // backward of a ReLU layer: pass the value only where the forward activation was positive
-                    if (mask) x = mask[row * ldm + col] > 0.0f ? x : 0.0f;
-                    Z[row * ldz + col] = x;
-                }
-            }
-        }
+    write_out<TM, TN, MASKED>(acc, bv, N, D_out, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, relu, Z, ldz, mask, ldm,
+                              m0 + BM <= N);
+}
+
+// D_in == 0: the product is empty and every row is act(b); H and W are not touched (they may be NULL)
+__global__ void bias_rows_kernel(int64_t N, int D_out, const float* __restrict__ bias, int relu,
+                                 float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm)
+{
+    const int64_t total = N * D_out;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / D_out;
+        const int col = (int)(e % D_out);
+        float x = bias ? bias[col] : 0.0f;
+        if (relu) x = fmaxf(x, 0.0f);
+        if (mask) x = mask[row * ldm + col] > 0.0f ? x : 0.0f;
+        Z[row * ldz + col] = x;
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, bool MASKED>
 void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh, const float* W,
             const float* b, bool relu, float* Z, int64_t ldz, const float* mask, int64_t ldm,
             hipStream_t stream)
@@ -182,13 +427,24 @@ void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
     dim3 grid((unsigned)((N + BM - 1) / BM), (unsigned)((D_out + BN - 1) / BN));
     const int r = relu ? 1 : 0;
     if (hv && wv)
-        transform_kernel<BM, BN, WGM, WGN, true, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        transform_kernel<BM, BN, WGM, WGN, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else if (hv)
-        transform_kernel<BM, BN, WGM, WGN, true, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        transform_generic_kernel<BM, BN, WGM, WGN, true, false, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else if (wv)
-        transform_kernel<BM, BN, WGM, WGN, false, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        transform_generic_kernel<BM, BN, WGM, WGN, false, true, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else
-        transform_kernel<BM, BN, WGM, WGN, false, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        transform_generic_kernel<BM, BN, WGM, WGN, false, false, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+}
+
+template <bool MASKED>
+void launch_by_width(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh, const float* W,
+                     const float* b, bool relu, float* Z, int64_t ldz, const float* mask, int64_t ldm,
+                     hipStream_t stream)
+{
+    if (D_out <= 32)       launch<128, 32, 4, 1, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else if (D_out <= 64)  launch<128, 64, 4, 1, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else if (D_out <= 128) launch<128, 128, 2, 2, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else                   launch<128, 256, 2, 2, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
 }
 
 }  // namespace
@@ -198,10 +454,14 @@ int launch_transform(int64_t N, int64_t D_in, int64_t D_out, const float* H, int
                      hipStream_t stream, const float* mask, int64_t ldm)
 {
     if (N == 0 || D_out == 0) return RETEXO_OK;
-    if (D_out <= 32)       launch<128, 32, 4, 1>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
-    else if (D_out <= 64)  launch<128, 64, 4, 1>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
-    else if (D_out <= 128) launch<128, 128, 2, 2>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
-    else                   launch<128, 256, 2, 2>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    if (D_in == 0) {
+        const int64_t blocks = (N * D_out + 255) / 256;
+        bias_rows_kernel<<<dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, stream>>>(
+            N, (int)D_out, b, relu ? 1 : 0, Z, ldz, mask, ldm);
+        return hipGetLastError() != hipSuccess ? RETEXO_E_HIP : RETEXO_OK;
+    }
+    if (mask) launch_by_width<true>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else      launch_by_width<false>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
     return RETEXO_OK;
 }

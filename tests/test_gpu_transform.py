@@ -35,11 +35,31 @@ def run(n, d_in, d_out, ldh, ldz, relu, bias, seed):
     (64, 16, 32, 16, 32, True, False),          # exactly one tile, one K step
     (1, 3, 300, 3, 300, False, True),           # single row, more than one column tile
     (2049, 128, 7, 128, 32, False, True),
+    # aligned shapes (the software-pipelined kernel): one, two, three and many K steps, with and without a K tail
+    (130, 16, 256, 16, 256, False, True),
+    (1500, 32, 256, 32, 256, True, True),
+    (1500, 48, 200, 64, 256, True, True),
+    (4000, 20, 128, 32, 128, False, True),
+    (300, 36, 4, 48, 16, False, False),
+    (777, 260, 96, 272, 96, True, True),
+    (5000, 52, 64, 64, 64, False, True),
+    (3001, 200, 32, 208, 32, True, False),
 ])
 def test_transform_matches_oracle(n, d_in, d_out, ldh, ldz, relu, bias):
     H, W, b, Z = run(n, d_in, d_out, ldh, ldz, relu, bias, seed=n + d_in)
     want = oracle.transform(H, d_in, W, b, relu)
     assert_close(Z, want, what="transform %dx%d->%d" % (n, d_in, d_out))
+
+
+def test_transform_with_no_input_columns_is_the_bias():
+    # an empty product: every row is act(b), and neither H nor W is read (both may be NULL)
+    n, d_out = 300, 40
+    b = Hn.dev(wl.random_matrix(1, d_out, 3)[0])
+    Z = torch.full((n, 48), 777.0, dtype=torch.float32, device="cuda")
+    for flags, want in ((0, b), (B.F_RELU, torch.clamp(b, min=0))):
+        B.check(B.retexo_transform(n, 0, d_out, 0, 0, 0, b.data_ptr(), flags, Z.data_ptr(), 48, Hn._stream_ptr()), "transform")
+        torch.cuda.synchronize()
+        assert torch.equal(Z[:, :d_out], want.expand(n, d_out)) and bool((Z[:, d_out:] == 777.0).all())
 
 
 def test_transform_identity_weight_is_exact_and_relu_clamps():
