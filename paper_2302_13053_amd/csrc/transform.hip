@@ -444,6 +444,7 @@ void launch_by_width(int64_t N, int64_t D_in, int64_t D_out, const float* H, int
     if (D_out <= 32)       launch<128, 32, 4, 1, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     else if (D_out <= 64)  launch<128, 64, 4, 1, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     else if (D_out <= 128) launch<128, 128, 2, 2, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+    else if (D_out <= 192) launch<128, 192, 2, 2, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     else                   launch<128, 256, 2, 2, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
 }
 

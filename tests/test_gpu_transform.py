@@ -44,6 +44,8 @@ def run(n, d_in, d_out, ldh, ldz, relu, bias, seed):
     (777, 260, 96, 272, 96, True, True),
     (5000, 52, 64, 64, 64, False, True),
     (3001, 200, 32, 208, 32, True, False),
+    (1000, 64, 192, 64, 192, True, True),        # the 192-column tile, full and partly used
+    (1000, 40, 132, 48, 144, False, True),
 ])
 def test_transform_matches_oracle(n, d_in, d_out, ldh, ldz, relu, bias):
     H, W, b, Z = run(n, d_in, d_out, ldh, ldz, relu, bias, seed=n + d_in)
