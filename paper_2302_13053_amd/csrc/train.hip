@@ -30,6 +30,169 @@ constexpr int kThreads = 256;
 // ---------------------------------------------------------------------------
 // part[z][m][n] = sum over k in chunk z of P[k][m] * Q[k][n]
 // ---------------------------------------------------------------------------
+
+// Partial tile of one wave -> part[z]: accumulator element r of lane l is row 8*(r/4) + 4*(l/32) + r%4,
+// column l%32 of its 32 x 32 tile.
+template <int TM, int TN>
+__device__ __forceinline__ void write_partial(const f32x16 (&acc)[TM][TN], int M, int Nq, int row_base, int col_base,
+                                              int lane, float* __restrict__ out)
+{
+    const int lrow = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = col_base + j * 32 + lrow;
+        if (col >= Nq) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = row_base + i * 32 + 4 * lk;
+            float* p = out + (int64_t)row0 * Nq + col;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ro = 8 * (r / 4) + (r % 4);
+                if (row0 + ro < M) p[(int64_t)ro * Nq] = acc[i][j][r];
+            }
+        }
+    }
+}
+
+// Aligned operands (rows of P and Q are 16-byte multiples at 16-byte aligned addresses, M >= 4, Nq >= 4):
+// the software-pipelined K loop shared with the dense transform.  Columns past M / Nq are clamped to the
+// last four (their products land in partials that are never stored); only a partial last K tile of a
+// chunk takes a checked, zero-filling fetch.
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256, 2) void wgrad_pipe_kernel(
+    int64_t K, int M, int Nq, const float* __restrict__ P, int64_t ldp,
+    const float* __restrict__ Q, int64_t ldq, int64_t k_chunk, float* __restrict__ part)
+{
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    constexpr int TM = BM / (32 * WGM);
+    constexpr int TN = BN / (32 * WGN);
+    constexpr int LDA = BM + 4;
+    constexpr int LDB = BN + 4;
+    constexpr int A_F4 = BM * BK / 4 / 256;
+    constexpr int B_F4 = (BN * BK / 4 + 255) / 256;
+    constexpr bool B_PART = BN * BK / 4 % 256 != 0;
+    static_assert(A_F4 >= 1 && BM * BK / 4 % 256 == 0, "tile shape");
+
+    __shared__ float As[2][BK][LDA];
+    __shared__ float Bs[2][BK][LDB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int m0 = blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int64_t k_begin = (int64_t)blockIdx.z * k_chunk;
+    const int64_t k_end = min(K, k_begin + k_chunk);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = k_end > k_begin ? (int)((k_end - k_begin + BK - 1) / BK) : 0;
+    if (nk > 0) {
+        const int k_tail = (int)((k_end - k_begin) % BK);      // > 0: the chunk's last tile is partial
+        const float* pa[A_F4];
+        const float* pb[B_F4];
+        int ka[A_F4], kb[B_F4];                                // row of the thread's piece inside a tile
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) {
+            const int id = tid + i * 256;
+            const int kk = id / (BM / 4), m4 = id % (BM / 4);
+            int m = m0 + m4 * 4;
+            m = m < M - 4 ? m : M - 4;
+            pa[i] = P + (k_begin + kk) * ldp + m;
+            ka[i] = kk;
+        }
+#pragma unroll
+        for (int i = 0; i < B_F4; ++i) {
+            const int id = tid + i * 256;
+            const int kk = (id / (BN / 4)) % BK, n4 = id % (BN / 4);
+            int n = n0 + n4 * 4;
+            n = n < Nq - 4 ? n : Nq - 4;
+            pb[i] = Q + (k_begin + kk) * ldq + n;
+            kb[i] = kk;
+        }
+        const int64_t step_a = (int64_t)BK * ldp, step_b = (int64_t)BK * ldq;
+        f32x4 ra[A_F4], rb[B_F4];
+
+        auto fetch_a = [&](int kt) {
+            if (k_tail && kt == nk - 1) {
+#pragma unroll
+                for (int i = 0; i < A_F4; ++i) {
+                    const bool in = ka[i] < k_tail;
+                    const f32x4 t = *reinterpret_cast<const f32x4*>(in ? pa[i] : P);
+                    ra[i] = in ? t : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < A_F4; ++i) ra[i] = *reinterpret_cast<const f32x4*>(pa[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < A_F4; ++i) pa[i] += step_a;
+        };
+        auto fetch_b = [&](int kt) {
+            if (k_tail && kt == nk - 1) {
+#pragma unroll
+                for (int i = 0; i < B_F4; ++i) {
+                    const bool in = kb[i] < k_tail;
+                    const f32x4 t = *reinterpret_cast<const f32x4*>(in ? pb[i] : Q);
+                    rb[i] = in ? t : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < B_F4; ++i) rb[i] = *reinterpret_cast<const f32x4*>(pb[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < B_F4; ++i) pb[i] += step_b;
+        };
+        auto put_a = [&](int buf, int i) {
+            const int id = tid + i * 256;
+            const int kk = id / (BM / 4), m4 = id % (BM / 4);
+            *reinterpret_cast<f32x4*>(&As[buf][kk][m4 * 4]) = ra[i];
+        };
+        auto put_b = [&](int buf, int i) {
+            const int id = tid + i * 256;
+            if (B_PART && id >= BN * BK / 4) return;
+            const int kk = id / (BN / 4), n4 = id % (BN / 4);
+            *reinterpret_cast<f32x4*>(&Bs[buf][kk][n4 * 4]) = rb[i];
+        };
+
+        fetch_a(0);
+        fetch_b(0);
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) put_a(0, i);
+#pragma unroll
+        for (int i = 0; i < B_F4; ++i) put_b(0, i);
+        if (nk > 1) { fetch_a(1); fetch_b(1); }
+        __syncthreads();
+
+        auto put = [&](int buf, int third) {
+            if (third == 0) {
+#pragma unroll
+                for (int x = 0; x < A_F4; ++x) put_a(buf, x);
+            } else if (third == 1) {
+                put_b(buf, 0);
+            } else {
+#pragma unroll
+                for (int x = 1; x < B_F4; ++x) put_b(buf, x);
+            }
+        };
+        auto fetch = [&](int kt, int half) {
+            if (half == 0) fetch_a(kt);
+            else fetch_b(kt);
+        };
+        mfma_k_loop<TM, TN, LDA, LDB>(acc, As, Bs, nk, wm * TM * 32, wn * TN * 32, lane, put, fetch);
+    }
+    write_partial<TM, TN>(acc, M, Nq, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, part + (int64_t)blockIdx.z * M * Nq);
+}
+
+// Any shape: every element fetched under its own check.
 template <int BM, int BN, int WGM, int WGN, bool PV, bool QV>
 __global__ __launch_bounds__(256, 2) void wgrad_kernel(
     int64_t K, int M, int Nq, const float* __restrict__ P, int64_t ldp,
@@ -136,19 +299,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(
         __syncthreads();
     }
 
-    float* out = part + (int64_t)blockIdx.z * M * Nq;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * TN * 32 + j * 32 + lrow;
-        if (col >= Nq) continue;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (row < M) out[(int64_t)row * Nq + col] = acc[i][j][r];
-            }
-    }
+    write_partial<TM, TN>(acc, M, Nq, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, part + (int64_t)blockIdx.z * M * Nq);
 }
 
 // out[m][n] = sum_z part[z][m][n] for n < n_keep (partials are Nq wide), in z order
@@ -316,7 +467,9 @@ struct Split { int S; int64_t k_chunk; };
 Split choose_split(int64_t K, int64_t M, int64_t Nq, int bn)
 {
     const int64_t tiles = ((M + 127) / 128) * ((Nq + bn - 1) / bn);
-    int64_t S = (1024 + tiles - 1) / tiles;                 // about four workgroups per CU in total
+    // the widest tile runs two workgroups per CU: at most 1024 workgroups are exactly two rounds of the 512
+    // slots (one more workgroup would add a third round for it alone)
+    int64_t S = 1024 / tiles;
     const int64_t max_s = (K + 255) / 256;                  // at least 256 nodes per chunk
     if (S > max_s) S = max_s;
     if (S < 1) S = 1;
@@ -336,7 +489,9 @@ void launch_wgrad_bn(int64_t K, int64_t M, int64_t Nq, const float* P, int64_t l
     const bool pv = (uintptr_t)P % 16 == 0 && ldp % 4 == 0 && M % 4 == 0;
     const bool qv = (uintptr_t)Q % 16 == 0 && ldq % 4 == 0 && Nq % 4 == 0;
     dim3 grid((unsigned)((M + 127) / 128), (unsigned)((Nq + BN - 1) / BN), (unsigned)sp.S);
-    if (pv && qv)
+    if (pv && qv && M >= 4 && Nq >= 4)
+        wgrad_pipe_kernel<128, BN, WGM, WGN><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);
+    else if (pv && qv)
         wgrad_kernel<128, BN, WGM, WGN, true, true><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);
     else if (pv)
         wgrad_kernel<128, BN, WGM, WGN, true, false><<<grid, dim3(256), 0, stream>>>(K, (int)M, (int)Nq, P, ldp, Q, ldq, sp.k_chunk, part);

@@ -37,8 +37,6 @@ namespace {
 
 constexpr int BK = kTileK;
 
-#define FENCE() __builtin_amdgcn_sched_barrier(0)      // nothing is scheduled across this point
-
 // Bias, ReLU, optional mask and store of the accumulators of one wave.
 // Accumulator element r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile.
 // Only the last row block of the matrix checks rows.
@@ -99,8 +97,7 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
     constexpr int A_F4 = BM * BK / 4 / 256;
     constexpr int B_F4 = (BN * BK / 4 + 255) / 256;
     constexpr bool B_PART = BN * BK / 4 % 256 != 0;
-    constexpr int NSTEP = BK / 2;
-    static_assert(A_F4 >= 1 && NSTEP == 8, "tile shape");
+    static_assert(A_F4 >= 1, "tile shape");
 
     __shared__ float As[2][BK][LDA];
     __shared__ float Bs[2][BK][LDB];
@@ -111,7 +108,7 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
     const int wm = wave / WGN, wn = wave % WGN;
     const int64_t m0 = (int64_t)blockIdx.x * BM;
     const int n0 = blockIdx.y * BN;
-    const int lrow = lane & 31, lk = lane >> 5;
+    const int lrow = lane & 31;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -201,15 +198,7 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
         bv[j] = (bias && col < D_out) ? bias[col] : 0.0f;
     }
 
-    float af[2][TM], bf[2][TN];
-    auto frag = [&](int buf, int s, int slot) {       // operands of k-step s -> register set slot
-#pragma unroll
-        for (int i = 0; i < TM; ++i) af[slot][i] = As[buf][2 * s + lk][wm * TM * 32 + i * 32 + lrow];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bf[slot][j] = Bs[buf][2 * s + lk][wn * TN * 32 + j * 32 + lrow];
-    };
-
-    // prologue: tile 0 -> LDS, tile 1 -> staging registers, first operands -> registers
+    // prologue: tile 0 -> LDS, tile 1 -> staging registers
     fetch_a(0);
     fetch_b(0);
 #pragma unroll
@@ -218,49 +207,26 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
     for (int i = 0; i < B_F4; ++i) put_b(0, i);
     if (nk > 1) { fetch_a(1); fetch_b(1); }
     __syncthreads();
-    frag(0, 0, 0);
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < nk;        // staging registers hold tile kt + 1
-        const bool more2 = kt + 2 < nk;
+    // thirds of "staged tile -> LDS": the A pieces, the first B piece, the other B pieces
+    auto put = [&](int buf, int third) {
+        if (third == 0) {
+            put_a(buf, 0);
+            if (A_F4 > 1) put_a(buf, 1);
+        } else if (third == 1) {
 #pragma unroll
-        for (int s = 0; s < NSTEP; ++s) {
-            const int cur = s & 1;
-            int q = 0;                        // MFMAs issued in this step
+            for (int x = 2; x < A_F4; ++x) put_a(buf, x);
+            put_b(buf, 0);
+        } else {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
-                    FENCE();
-                    if (q == 0) {
-                        // operands of the next k-step (the last step's successor is read after the barrier)
-                        if (s + 1 < NSTEP) frag(buf, s + 1, cur ^ 1);
-                        FENCE();
-                    }
-                    if (q == (TM * TN > 1 ? 1 : 0)) {
-                        // one slice of the staging work per step
-                        if (s == 0 && more) { put_a(buf ^ 1, 0); if (A_F4 > 1) put_a(buf ^ 1, 1); }
-                        if (s == 1 && more) { _Pragma("unroll") for (int x = 2; x < A_F4; ++x) put_a(buf ^ 1, x); put_b(buf ^ 1, 0); }
-                        if (s == 2 && more) { _Pragma("unroll") for (int x = 1; x < B_F4; ++x) put_b(buf ^ 1, x); }
-                        if (s == 3 && more2) fetch_a(kt + 2);
-                        if (s == 4 && more2) fetch_b(kt + 2);
-                        FENCE();
-                    }
-                    ++q;
-                }
-            }
-            if (s == NSTEP - 2) {
-                // every wave has read its last operands of this tile and written its share of the next
-                __syncthreads();                       // waits for LDS traffic only: the global loads stay in flight
-                FENCE();
-                if (more) frag(buf ^ 1, 0, 0);
-                FENCE();
-            }
+            for (int x = 1; x < B_F4; ++x) put_b(buf, x);
         }
-    }
-
+    };
+    auto fetch = [&](int kt, int half) {
+        if (half == 0) fetch_a(kt);
+        else fetch_b(kt);
+    };
+    mfma_k_loop<TM, TN, LDA, LDB>(acc, As, Bs, nk, wm * TM * 32, wn * TN * 32, lane, put, fetch);
 
     write_out<TM, TN, MASKED>(acc, bv, N, D_out, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, relu, Z, ldz, mask, ldm,
                               m0 + BM <= N);
@@ -386,7 +352,7 @@ __global__ __launch_bounds__(256, 2) void transform_generic_kernel(
 #pragma unroll
                 for (int j = 0; j < TN; ++j) bf[cur ^ 1][j] = Bs[buf][kk + 2 + lk][wn * TN * 32 + j * 32 + lrow];
             }
-            FENCE();                                 // keep those reads ahead of this step's MFMAs
+            RETEXO_SCHED_FENCE();                    // keep those reads ahead of this step's MFMAs
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -91,3 +91,21 @@ def test_transform_is_deterministic_and_rejects_alias():
     b = Hn.transform(H, d_in, W, None, True)
     assert torch.equal(a, b)
     assert B.retexo_transform(n, d_in, d_in, H.data_ptr(), d_in, W.data_ptr(), 0, 0, H.data_ptr(), d_in) == B.E_ALIAS
+
+
+def test_transform_aligned_and_unaligned_operands_give_the_same_bits():
+    # the software-pipelined kernel (16-byte aligned rows) and the checked-load kernel (here: H and W moved
+    # by one float) do the same arithmetic in the same order
+    n, d_in, d_out = 1111, 212, 256
+    H = wl.random_matrix(n, d_in, 21)
+    W = wl.random_matrix(d_in, d_out, 22)
+    b = Hn.dev(wl.random_matrix(1, d_out, 23)[0])
+    Ha, Wa = Hn.dev(H), Hn.dev(W)
+    Hu = torch.empty(n * d_in + 1, dtype=torch.float32, device="cuda")[1:].view(n, d_in)
+    Wu = torch.empty(d_in * d_out + 1, dtype=torch.float32, device="cuda")[1:].view(d_in, d_out)
+    Hu.copy_(Ha)
+    Wu.copy_(Wa)
+    assert Hu.data_ptr() % 16 != 0 and Wu.data_ptr() % 16 != 0
+    za = Hn.transform(Ha, d_in, Wa, b, True)
+    zu = Hn.transform(Hu, d_in, Wu, b, True)
+    assert torch.equal(za, zu)
