@@ -146,7 +146,8 @@ int64_t retexo_workspace_bytes(const retexo_plan* plan, int64_t D_out, int mode,
  *   d_H [N, ldh], first D_in columns used;  d_W [D_in, D_out] row-major, dense;
  *   d_b [D_out] or NULL;  d_Z [N, ldz], first D_out columns written.
  * fp32 inputs, fp32 matrix-core accumulation.  flags: RETEXO_F_RELU only.
- * Z must not overlap H.  N == 0 is a no-op.
+ * Z must not overlap H.  N == 0 is a no-op; D_in == 0 gives Z[i, j] = act(b[j]) and reads neither H nor W
+ * (both may then be NULL).
  */
 int retexo_transform(int64_t N, int64_t D_in, int64_t D_out,
                      const float* d_H, int64_t ldh, const float* d_W, const float* d_b,
