@@ -134,6 +134,16 @@ const float* retexo_plan_dinv(const retexo_plan* plan);    /* device, [N] */
  * equal lengths in ascending id order).  Enqueued on `stream`. */
 int retexo_plan_export(const retexo_plan* plan, int32_t* d_deg, float* d_dinv, int32_t* d_order,
                        void* stream);
+/* The row split by source-id range that plans of dense graphs carry (built when the feature table of the
+ * graph cannot stay in L2 but a range of it can, or on request with RETEXO_F_SPLIT_ROWS): the entries of
+ * row order[s] whose column lies in [k*span, (k+1)*span) are col_idx[pos[k*N + s] .. pos[(k+1)*N + s]),
+ * k < RETEXO_SPLIT_PARTS, s = position in the schedule order.  Returns the span (> 0), 0 when the plan
+ * has no split, < 0 on error; with d_pos != NULL the int32 [(RETEXO_SPLIT_PARTS + 1) * N] positions are
+ * copied there (enqueued on `stream`).  Columns of a row are expected in ascending order, as
+ * retexo_csr_from_coo writes them; for any other order the positions still cut every row into
+ * consecutive pieces, so aggregation results stay correct and only the locality is lost. */
+#define RETEXO_SPLIT_PARTS 16
+int64_t retexo_plan_export_split(const retexo_plan* plan, int32_t* d_pos, void* stream);
 
 /* Bytes of workspace retexo_aggregate (D_in == 0) or retexo_round needs for
  * rows of width D_out; < 0 is a retexo_status. */

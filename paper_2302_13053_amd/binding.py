@@ -26,6 +26,7 @@ EXPORTS = (
     "retexo_status_string", "retexo_csr_workspace_bytes", "retexo_csr_from_coo",
     "retexo_plan_create", "retexo_plan_destroy", "retexo_plan_num_nodes", "retexo_plan_nnz",
     "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
+    "retexo_plan_export_split",
     "retexo_workspace_bytes",
     "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
     "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward", "retexo_aggregate_backward_saved",
@@ -80,6 +81,8 @@ def load():
     lib.retexo_plan_dinv.argtypes = [vp]
     lib.retexo_plan_export.restype = i32
     lib.retexo_plan_export.argtypes = [vp, vp, vp, vp, vp]
+    lib.retexo_plan_export_split.restype = i64
+    lib.retexo_plan_export_split.argtypes = [vp, vp, vp]
     lib.retexo_workspace_bytes.restype = i64
     lib.retexo_workspace_bytes.argtypes = [vp, i64, i32, i32, u32]
     lib.retexo_transform.restype = i32
@@ -196,6 +199,13 @@ def retexo_plan_dinv(plan) -> int:
 
 def retexo_plan_export(plan, d_deg, d_dinv, d_order, stream=0) -> int:
     return int(load().retexo_plan_export(_vp(plan), _vp(d_deg), _vp(d_dinv), _vp(d_order), _vp(stream)))
+
+
+SPLIT_PARTS = 16
+
+
+def retexo_plan_export_split(plan, d_pos, stream=0) -> int:
+    return int(load().retexo_plan_export_split(_vp(plan), _vp(d_pos), _vp(stream)))
 
 
 def retexo_workspace_bytes(plan, d_out, mode, heads=1, flags=0) -> int:

@@ -36,6 +36,7 @@ struct retexo_plan {
     int32_t max_degree = 0;
     // number of rows with deg >= threshold[i], thresholds fixed in plan.hip
     int64_t rows_at_least[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    void* block = nullptr;          // the one device allocation behind deg, dinv, order, part_ptr
     void* build_scratch = nullptr;
 };
 

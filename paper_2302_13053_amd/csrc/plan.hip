@@ -48,27 +48,47 @@ __global__ __launch_bounds__(kThreads) void check_columns(
     if (c < 0 || c >= N) atomicOr(bad, 1u);
 }
 
-// part_ptr[k][s] = first position in row order[s] whose column is >= k * span (columns ascend in a row)
+// part_ptr[k][s] = first position in row order[s] whose column is >= k * span (columns ascend in a row).
+// One wave per row walks its columns once, 64 at a time: position e is such a first position for every k
+// in (part of column e-1, part of column e], part = column / span (the row start counts as part -1);
+// the positions after the last column's part are the row end.  "Part" is taken as the running maximum
+// along the row, which changes nothing for ascending columns and keeps the positions a monotone chain
+// from row start to row end (every entry in exactly one range) for any other order.
 __global__ __launch_bounds__(kThreads) void split_rows_kernel(
-    int64_t N, int64_t span, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+    int64_t N, int64_t nnz, int64_t span, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
     const int32_t* __restrict__ order, int32_t* __restrict__ part_ptr)
 {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= N * (kMaxParts + 1)) return;
-    const int k = (int)(i / N);
-    const int64_t s = i % N;
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (s >= N) return;                       // whole waves leave together
     const int64_t v = order[s];
-    int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
-    if (k < kMaxParts) {
-        const int64_t want = (int64_t)k * span;
-        while (lo < hi) {
-            const int64_t mid = lo + ((hi - lo) >> 1);
-            if (col_idx[mid] < want) lo = mid + 1; else hi = mid;
+    const int64_t begin = row_ptr[v], end = row_ptr[v + 1];
+    // this runs before the host has seen the verdict on row_ptr: a row that does not lie inside
+    // col_idx is left alone (such a CSR is rejected and the plan never used)
+    if (begin < 0 || end > nnz || begin > end) return;
+    const uint32_t sp = (uint32_t)span;
+    int carry = -1;                           // running maximum over the chunks already walked
+    for (int64_t base = begin; base < end; base += 64) {
+        const int64_t e = base + lane;
+        int inc = -1;
+        if (e < end) {
+            const uint32_t part = (uint32_t)col_idx[e] / sp;
+            inc = part > (uint32_t)kMaxParts ? kMaxParts : (int)part;
         }
-    } else {
-        lo = hi;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {    // inclusive prefix maximum over the lanes
+            const int o = __shfl_up(inc, d);
+            if (lane >= d) inc = max(inc, o);
+        }
+        int exc = __shfl_up(inc, 1);
+        if (lane == 0) exc = -1;
+        const int here = max(carry, inc), before = max(carry, exc);
+        if (e < end)
+            for (int k = before + 1; k <= here; ++k) part_ptr[(int64_t)k * N + s] = (int32_t)e;
+        carry = max(carry, __shfl(inc, 63));
     }
-    part_ptr[i] = (int32_t)lo;
+    if (lane == 0)
+        for (int k = carry + 1; k <= kMaxParts; ++k) part_ptr[(int64_t)k * N + s] = (int32_t)end;
 }
 
 // counts[i] = number of rows with degree >= thresholds[i]; keys are sorted descending
@@ -116,10 +136,28 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
 
     auto fail = [&](int code) { retexo_plan_destroy(p); return code; };
 
+    // The entry count decides whether the row split is built, so it is fetched first; everything the plan
+    // keeps then comes from one allocation (device allocations cost tens of microseconds each).
     const int64_t n1 = N > 0 ? N : 1;
-    if (hipMalloc(&p->deg, n1 * sizeof(int32_t)) != hipSuccess) return fail(RETEXO_E_HIP);
-    if (hipMalloc(&p->dinv, n1 * sizeof(float)) != hipSuccess) return fail(RETEXO_E_HIP);
-    if (hipMalloc(&p->order, n1 * sizeof(int32_t)) != hipSuccess) return fail(RETEXO_E_HIP);
+    int64_t nnz = 0;
+    if (hipMemcpyAsync(&nnz, d_row_ptr + N, sizeof(int64_t), hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return fail(RETEXO_E_HIP);
+    if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (nnz < 0) return fail(RETEXO_E_CSR);
+    if (nnz >= (1ll << 31)) return fail(RETEXO_E_SIZE);
+    if (nnz > 0 && !d_col_idx) return fail(RETEXO_E_NULL);
+    p->nnz = nnz;
+    // Dense-enough graphs whose feature table cannot stay in L2 get the row split that lets
+    // the aggregation walk one source-id range at a time.
+    const bool split = N > 0 && nnz > 0 &&
+        ((flags & RETEXO_F_SPLIT_ROWS) ||
+         (nnz >= 64 * N && N * 128 > (4ll << 20) && N * 128 <= kMaxParts * (8ll << 20)));
+    const int64_t o_deg = 0, o_dinv = align_up(4 * n1, 256), o_order = 2 * o_dinv, o_part = 3 * o_dinv;
+    const int64_t keep_bytes = o_part + (split ? align_up(4 * N * (kMaxParts + 1), 256) : 0);
+    if (hipMalloc(&p->block, (size_t)keep_bytes) != hipSuccess) return fail(RETEXO_E_HIP);
+    p->deg = (int32_t*)((char*)p->block + o_deg);
+    p->dinv = (float*)((char*)p->block + o_dinv);
+    p->order = (int32_t*)((char*)p->block + o_order);
 
     size_t sort_bytes = 0;
     if (N > 0 &&
@@ -149,14 +187,18 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
         for (int i = 0; i < 8; ++i) th.t[i] = kPlanThresholds[i];
         count_at_least<<<dim3(1), dim3(64), 0, stream>>>(N, kout, th, rb->counts);
     }
-    if (hipMemcpyAsync(&rb->nnz, d_row_ptr + N, sizeof(int64_t), hipMemcpyDeviceToDevice, stream) != hipSuccess)
-        return fail(RETEXO_E_HIP);
+    if (split) {
+        // needs only the schedule order, so it runs before the host looks at the counts
+        p->part_ptr = (int32_t*)((char*)p->block + o_part);
+        p->part_span = (N + kMaxParts - 1) / kMaxParts;
+        const int64_t rows_per_block = kThreads / 64;
+        split_rows_kernel<<<dim3((unsigned)((N + rows_per_block - 1) / rows_per_block)), dim3(kThreads), 0, stream>>>(
+            N, nnz, p->part_span, d_row_ptr, d_col_idx, p->order, p->part_ptr);
+    }
     Readback h;
     if (hipMemcpyAsync(&h, rb, sizeof(h), hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(RETEXO_E_HIP);
     if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
-    if (h.bad || h.nnz < 0 || h.nnz >= (1ll << 31)) return fail(h.bad || h.nnz < 0 ? RETEXO_E_CSR : RETEXO_E_SIZE);
-    p->nnz = h.nnz;
-    if (p->nnz > 0 && !d_col_idx) return fail(RETEXO_E_NULL);
+    if (h.bad) return fail(RETEXO_E_CSR);
     for (int i = 0; i < 8; ++i) p->rows_at_least[i] = h.counts[i];
     p->max_degree = (int32_t)h.counts[8];
 
@@ -169,17 +211,6 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
         if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
         if (bad) return fail(RETEXO_E_CSR);
     }
-    // Dense-enough graphs whose feature table cannot stay in L2 get the row split that lets
-    // the aggregation walk one source-id range at a time.
-    if (N > 0 && p->nnz > 0 && ((flags & RETEXO_F_SPLIT_ROWS) || (p->nnz >= 64 * N && N * 128 > (4ll << 20) && N * 128 <= kMaxParts * (8ll << 20)))) {
-        if (hipMalloc(&p->part_ptr, (size_t)N * (kMaxParts + 1) * sizeof(int32_t)) != hipSuccess)
-            return fail(RETEXO_E_HIP);
-        p->part_span = (N + kMaxParts - 1) / kMaxParts;
-        const int64_t work = N * (kMaxParts + 1);
-        split_rows_kernel<<<dim3((unsigned)((work + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            N, p->part_span, d_row_ptr, d_col_idx, p->order, p->part_ptr);
-        if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
-    }
     (void)hipFree(p->build_scratch);
     p->build_scratch = nullptr;
     *out = p;
@@ -189,10 +220,7 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
 extern "C" int retexo_plan_destroy(retexo_plan* p)
 {
     if (!p) return RETEXO_OK;
-    if (p->deg) (void)hipFree(p->deg);
-    if (p->dinv) (void)hipFree(p->dinv);
-    if (p->order) (void)hipFree(p->order);
-    if (p->part_ptr) (void)hipFree(p->part_ptr);
+    if (p->block) (void)hipFree(p->block);       // deg, dinv, order and part_ptr live in it
     if (p->build_scratch) (void)hipFree(p->build_scratch);
     delete p;
     return RETEXO_OK;
@@ -215,4 +243,16 @@ extern "C" int retexo_plan_export(const retexo_plan* p, int32_t* d_deg, float* d
     if (d_dinv) RETEXO_HIP_TRY(hipMemcpyAsync(d_dinv, p->dinv, n * 4, hipMemcpyDeviceToDevice, stream));
     if (d_order) RETEXO_HIP_TRY(hipMemcpyAsync(d_order, p->order, n * 4, hipMemcpyDeviceToDevice, stream));
     return RETEXO_OK;
+}
+
+static_assert(kMaxParts == RETEXO_SPLIT_PARTS, "the header states the number of source-id ranges");
+
+extern "C" int64_t retexo_plan_export_split(const retexo_plan* p, int32_t* d_pos, void* stream_)
+{
+    if (!p) return RETEXO_E_NULL;
+    if (!p->part_ptr) return 0;
+    if (d_pos)
+        RETEXO_HIP_TRY(hipMemcpyAsync(d_pos, p->part_ptr, (size_t)p->N * (kMaxParts + 1) * sizeof(int32_t),
+                                      hipMemcpyDeviceToDevice, (hipStream_t)stream_));
+    return p->part_span;
 }

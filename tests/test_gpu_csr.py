@@ -108,3 +108,58 @@ def test_plan_validation_catches_malformed_csr():
     st, plan = B.retexo_plan_create(3, rp.data_ptr(), ci.data_ptr(), B.F_VALIDATE)
     assert st == B.OK and plan
     B.retexo_plan_destroy(plan)
+
+
+def _split_positions(g):
+    n = g.n_nodes
+    pos = torch.empty((B.SPLIT_PARTS + 1) * n, dtype=torch.int32, device="cuda")
+    span = B.retexo_plan_export_split(g.plan, pos.data_ptr(), Hn._stream_ptr())
+    torch.cuda.synchronize()
+    return span, pos.cpu().numpy().reshape(B.SPLIT_PARTS + 1, n)
+
+
+@pytest.mark.parametrize("n,pairs,skew,seed", [(3000, 60000, 1.2, 1), (1000, 90000, 0.0, 2), (70, 40, 0.0, 3)])
+def test_plan_row_split_is_the_first_position_per_source_range(n, pairs, skew, seed):
+    # every row cut at the first entry whose column reaches k * span: integer work, compared exactly with
+    # a search over the (ascending) columns of the row
+    src, dst = wl.graph_power_law(n, pairs, 2.0 + skew, 20.0, 400.0, seed) if skew else wl.graph_er(n, pairs, seed)
+    g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False), validate=True, split_rows=True)
+    rp = g.row_ptr.cpu().numpy()
+    ci = g.col_idx.cpu().numpy()[: g.nnz]
+    _, _, order = Hn.plan_arrays(g)
+    span, pos = _split_positions(g)
+    assert span == (n + B.SPLIT_PARTS - 1) // B.SPLIT_PARTS
+    for s in range(n):
+        v = int(order[s])
+        row = ci[rp[v]:rp[v + 1]]
+        want = rp[v] + np.searchsorted(row, np.arange(B.SPLIT_PARTS + 1) * span, side="left")
+        want[-1] = rp[v + 1]
+        assert np.array_equal(pos[:, s], want), (s, v)
+    g.destroy()
+    # a plan without the split says so
+    g2 = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False))
+    assert B.retexo_plan_export_split(g2.plan, 0) == 0
+    g2.destroy()
+
+
+def test_row_split_of_unsorted_columns_still_cuts_every_row_into_consecutive_pieces():
+    # columns shuffled inside each row (a caller's own CSR): the positions stay a monotone chain from row
+    # start to row end, so sums over the pieces are sums over the row
+    n = 800
+    src, dst = wl.graph_er(n, 30000, 5)
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    rng = np.random.Generator(np.random.Philox(key=9))
+    ci = ci.copy()
+    for v in range(n):
+        rng.shuffle(ci[rp[v]:rp[v + 1]])
+    g = Hn.DeviceGraph(n, int(rp[-1]), Hn.dev(rp.astype(np.int64)), Hn.dev(ci.astype(np.int32)))
+    Hn.make_plan(g, validate=True, split_rows=True)
+    _, _, order = Hn.plan_arrays(g)
+    span, pos = _split_positions(g)
+    assert span > 0
+    assert np.array_equal(pos[0], rp[order]) and np.array_equal(pos[-1], rp[order + 1])
+    assert bool((np.diff(pos.astype(np.int64), axis=0) >= 0).all())
+    Z = wl.random_matrix(n, 40, 6, kind="smallint")
+    out = Hn.aggregate(g, "sum", Hn.dev(Z), 40)
+    assert np.array_equal(out.cpu().numpy()[:, :40].astype(np.float64), oracle.aggregate("sum", rp, ci, Z, 40))
+    g.destroy()
