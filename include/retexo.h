@@ -415,8 +415,10 @@ double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, d
  *       "agg_heavy_degree" (rows at least this long get a whole workgroup),
  *       "agg_parts" (source-id ranges walked one after the other: -1 auto, 1 off, 2/4/8/16),
  *       "agg_max_vec" (cap on floats per lane per gather),
- *       "agg_gat_fast" (0: plain edge-softmax kernel), "agg_wide_offsets" (1: 64-bit row offsets
- *       even for tables below 4 GiB; both exist so that tests reach every code path).
+ *       "agg_gat_fast" (0: plain edge-softmax kernel), "agg_gat_flash" (0: ordinary rows read the
+ *       source scores from the table instead of computing them from the gathered rows),
+ *       "agg_wide_offsets" (1: 64-bit row offsets even for tables below 4 GiB; these three exist
+ *       so that tests reach every code path).
  * Returns RETEXO_E_FLAGS for an unknown name.
  */
 int retexo_set_option(const char* name, int64_t value);

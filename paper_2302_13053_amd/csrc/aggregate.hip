@@ -1116,6 +1116,139 @@ void dispatch_grouped(const AggArgs& a, int64_t n_heavy, int64_t N, bool weighte
     }
 }
 
+// ---------------------------------------------------------------------------
+// gat_softmax for rows of ordinary length when the whole row fits one wave
+// (F <= 256, four floats per lane) and a head is a power-of-two group of lanes:
+// the score of an entry is computed from the gathered source row itself.
+//
+// The kernels above fetch el[u] = <a_src, z_u> from a table, one 16-byte read
+// per entry, which on a graph whose table misses L2 costs a whole extra cache
+// line per entry next to the eight lines of the row.  Here every lane
+// multiplies its four floats of z_u with its four floats of a_src, the lanes of
+// a head add up over the group with DPP moves, and the softmax runs online over
+// batches of four entries (running maximum m, sum s and weighted row acc per
+// lane, all three rescaled when the maximum moves).  Scores are kept in units
+// of log2(e) (LeakyReLU commutes with a positive factor) so that every
+// exponential is one v_exp_f32.  er[v] still comes from the score kernel.
+// ---------------------------------------------------------------------------
+template <int G>
+__device__ __forceinline__ float group_sum(float x)
+{
+    // butterfly over the G lanes of a head; every lane ends with the group's sum
+    if constexpr (G >= 2) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    if constexpr (G >= 4) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    if constexpr (G >= 8) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    if constexpr (G >= 16) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, true)); // row_mirror
+    if constexpr (G >= 32) x += __shfl_xor(x, 16, 64);
+    if constexpr (G >= 64) x += __shfl_xor(x, 32, 64);
+    return x;
+}
+
+template <int G>
+__global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs a, const float* __restrict__ attn_src,
+                                                                         int er_stride)
+{
+    constexpr int U = 4;      // entries per batch of the online softmax (2 and 8 measure the same: the kernel waits for memory)
+    constexpr float kLog2e = 1.4426950408889634f;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t slot = (int64_t)blockIdx.x * kLightWaves + wave;
+    if (slot >= a.row_count) return;
+    const int v = __builtin_amdgcn_readfirstlane(a.order[a.row_begin + slot]);
+    const int lo = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v]);
+    const int hi = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v + 1]);
+
+    const int64_t col = lane * 4;
+    const bool act = col < a.F;
+    // lanes past the row width gather the last valid vector instead (never stored, weight vector zero)
+    const uint32_t colbytes = (uint32_t)((act ? col : ((a.F - 1) / 4) * 4) * 4);
+    const int h = min((int)(col / a.Dh), a.heads - 1);
+    f32x4 as = {0.0f, 0.0f, 0.0f, 0.0f};
+    float erv = 0.0f;
+    if (act) {
+        as = *reinterpret_cast<const f32x4*>(attn_src + col);        // [heads, Dh] is F contiguous floats
+        as.x *= kLog2e; as.y *= kLog2e; as.z *= kLog2e; as.w *= kLog2e;
+        erv = a.er[(int64_t)v * er_stride + h] * kLog2e;
+    }
+    const char* zbase = reinterpret_cast<const char*>(a.Z);
+    const uint32_t rowbytes = (uint32_t)(a.ldz * 4);
+
+    float m = -INFINITY, s = 0.0f;
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int base = lo; base < hi; base += 64) {
+        const int e = base + lane;
+        const bool valid = e < hi;
+        const int cnt = min(64, hi - base);
+        int my_u = valid ? a.col_idx[e] : 0;
+        my_u = valid ? my_u : bcast_i(my_u, 0);          // lane 0 is always valid
+        const int my_off = (int)((uint32_t)my_u * rowbytes);
+
+        f32x4 zq[U];
+#pragma unroll
+        for (int t = 0; t < U; ++t)
+            zq[t] = *reinterpret_cast<const f32x4*>(zbase + (uint32_t)bcast_i(my_off, t) + colbytes);
+
+        for (int j = 0; j < cnt; j += U) {
+            // request the next batch, then consume the current one
+            f32x4 zn[U];
+            const bool more = j + U < cnt;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t)
+                    zn[t] = *reinterpret_cast<const f32x4*>(zbase + (uint32_t)bcast_i(my_off, (j + U + t) & 63) + colbytes);
+            }
+            float sc[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                float d = as.x * zq[t].x;
+                d = fmaf(as.y, zq[t].y, d);
+                d = fmaf(as.z, zq[t].z, d);
+                d = fmaf(as.w, zq[t].w, d);
+                const float x = group_sum<G>(d) + erv;
+                sc[t] = (j + t < cnt) ? (x > 0.0f ? x : a.slope * x) : -INFINITY;   // entries past the tile weigh nothing
+            }
+            float mn = m;
+#pragma unroll
+            for (int t = 0; t < U; ++t) mn = fmaxf(mn, sc[t]);                           // finite: entry j of the tile is real
+            const float scale = __builtin_amdgcn_exp2f(m - mn);
+            float pw[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) pw[t] = __builtin_amdgcn_exp2f(sc[t] - mn);
+            float ps = 0.0f;
+#pragma unroll
+            for (int t = 0; t < U; ++t) ps += pw[t];
+            s = s * scale + ps;
+            acc.x *= scale; acc.y *= scale; acc.z *= scale; acc.w *= scale;
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                acc.x = fmaf(pw[t], zq[t].x, acc.x);
+                acc.y = fmaf(pw[t], zq[t].y, acc.y);
+                acc.z = fmaf(pw[t], zq[t].z, acc.z);
+                acc.w = fmaf(pw[t], zq[t].w, acc.w);
+            }
+            m = mn;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t) zq[t] = zn[t];
+            }
+        }
+    }
+
+    if (!act) return;
+    float* orow = a.out + (int64_t)v * a.ldo;
+    float r[4];
+    r[0] = s > 0.0f ? acc.x / s : 0.0f;
+    r[1] = s > 0.0f ? acc.y / s : 0.0f;
+    r[2] = s > 0.0f ? acc.z / s : 0.0f;
+    r[3] = s > 0.0f ? acc.w / s : 0.0f;
+    store_row<4>(orow + a.ocol + col, r, 4, a.out_vec != 0);
+    if (a.copy_self) {
+        float zs[4];
+        load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
+        store_row<4>(orow + col, zs, 4, a.self_vec != 0);
+    }
+}
+
 template <int VEC, int NC, int HP, bool HU>
 void launch_gat_pair(const AggArgs& base, int64_t n_heavy, int64_t N, hipStream_t stream)
 {
@@ -1366,9 +1499,34 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             a.save_neg = (float*)((char*)c.workspace + w.neg);
             a.ld_pos = w.ld_pos;
         }
-        if (vec == 4 && off32 && opt.gat_fast) {
-            if (hp == 4) { if (hu) dispatch_gat_fast<4, true>(nc, c.save, a, n_heavy, N, stream); else dispatch_gat_fast<4, false>(nc, c.save, a, n_heavy, N, stream); }
-            else         { if (hu) dispatch_gat_fast<8, true>(nc, c.save, a, n_heavy, N, stream); else dispatch_gat_fast<8, false>(nc, c.save, a, n_heavy, N, stream); }
+        // rows of ordinary length compute the source scores from the gathered rows themselves when a head is
+        // a power-of-two group of four-float lanes; the long rows keep the table of scores
+        const int g = a.Dh / 4;
+        const bool flash = vec == 4 && off32 && opt.gat_fast && opt.gat_flash && !c.save && c.F <= 256 &&
+                           a.Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 && aligned_for(c.attn_src, 4, 4);
+        int64_t n_table = N;          // rows [0, n_table) of the schedule go through the table kernels
+        if (flash && N > n_heavy) {
+            AggArgs f = a;
+            f.nslab = 1;
+            f.row_begin = n_heavy;
+            f.row_count = N - n_heavy;
+            const dim3 grid((unsigned)((f.row_count + kLightWaves - 1) / kLightWaves)), block(64 * kLightWaves);
+            switch (g) {
+                case 1:  agg_gat_flash_kernel<1><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 2:  agg_gat_flash_kernel<2><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 4:  agg_gat_flash_kernel<4><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 8:  agg_gat_flash_kernel<8><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 16: agg_gat_flash_kernel<16><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 32: agg_gat_flash_kernel<32><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                default: agg_gat_flash_kernel<64><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+            }
+            n_table = n_heavy;
+        }
+        if (n_table == 0) {
+            // nothing left for the table kernels
+        } else if (vec == 4 && off32 && opt.gat_fast) {
+            if (hp == 4) { if (hu) dispatch_gat_fast<4, true>(nc, c.save, a, n_heavy, n_table, stream); else dispatch_gat_fast<4, false>(nc, c.save, a, n_heavy, n_table, stream); }
+            else         { if (hu) dispatch_gat_fast<8, true>(nc, c.save, a, n_heavy, n_table, stream); else dispatch_gat_fast<8, false>(nc, c.save, a, n_heavy, n_table, stream); }
         } else if (vec == 4) {
             if (hp == 4) { if (hu) dispatch_gat_nc<4, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat_nc<4, 4, false>(nc, a, n_heavy, N, stream); }
             else         { if (hu) dispatch_gat_nc<4, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat_nc<4, 8, false>(nc, a, n_heavy, N, stream); }

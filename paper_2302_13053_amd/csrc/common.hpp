@@ -48,6 +48,7 @@ struct AggOptions {
     int64_t heavy_degree = 2048;
     int64_t max_vec = 4;        // cap on floats per lane per gather (experiments)
     int64_t gat_fast = 1;       // pipelined edge-softmax kernel (0: the plain one)
+    int64_t gat_flash = 1;      // ordinary rows: source scores from the gathered rows (0: from the table)
     int64_t wide_offsets = 0;   // 1: use the 64-bit row-offset code paths even when 32 bits would do (tests)
     int64_t narrow_heavy = 512;  // narrow slabs: rows whose share of one source range is at least this long get a workgroup
     int64_t parts = -1;         // source-id ranges per aggregation: -1 auto, 1 = off, 2/4/8/16

@@ -82,6 +82,7 @@ extern "C" int retexo_set_option(const char* name, int64_t value)
     if (!strcmp(name, "agg_max_vec")) { o.max_vec = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_parts")) { o.parts = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_fast")) { o.gat_fast = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_gat_flash")) { o.gat_flash = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_wide_offsets")) { o.wide_offsets = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_narrow_heavy")) { o.narrow_heavy = value; return RETEXO_OK; }
     return RETEXO_E_FLAGS;

@@ -337,3 +337,33 @@ def test_head_mean(n, heads, C, ldi, ldo):
     assert np.all(got[:, C:] == 9.0) and np.all(got[n:] == 9.0)
     assert B.retexo_head_mean(5, 9, C, Xd.data_ptr(), ldi, out.data_ptr(), ldo) == -6
     assert B.retexo_head_mean(5, heads, C, Xd.data_ptr(), heads * C - 1, out.data_ptr(), ldo) == -3
+
+
+@pytest.mark.parametrize("F,heads", [
+    (256, 1),     # one head over the whole wave
+    (256, 2),     # 32 lanes per head
+    (256, 4),     # 16
+    (192, 3),     # 16, last quarter of the lanes idle
+    (96, 3),      # 8
+    (96, 6),      # 4
+    (64, 8),      # 2
+    (32, 8),      # one lane per head
+    (24, 2),      # heads of three lanes: not a power of two, stays on the score table
+])
+@pytest.mark.parametrize("concat", [False, True])
+def test_edge_softmax_with_scores_from_gathered_rows(graphs, F, heads, concat):
+    # ordinary rows compute <a_src, z_u> from the row they gather anyway; long rows and odd head widths read
+    # the score table.  Both must match the oracle, and each other to rounding.
+    kind = "normal" if F >= 64 else "absnormal"
+    results = {}
+    try:
+        for flash in (1, 0):
+            B.retexo_set_option("agg_gat_flash", flash)
+            for name in ("skewed", "flat", "tiny"):
+                got, want = run_case(graphs, name, "gat_softmax", F, F, heads, concat, seed=F + heads, kind=kind)
+                assert_close(got, want, what="gat F=%d heads=%d flash=%d %s" % (F, heads, flash, name))
+                results[(flash, name)] = got
+    finally:
+        B.retexo_set_option("agg_gat_flash", 1)
+    for name in ("skewed", "flat", "tiny"):
+        assert_close(results[(1, name)], results[(0, name)].astype(np.float64), what="flash vs table " + name)
