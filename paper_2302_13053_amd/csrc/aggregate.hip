@@ -1132,19 +1132,6 @@ void dispatch_grouped(const AggArgs& a, int64_t n_heavy, int64_t N, bool weighte
 // exponential is one v_exp_f32.  er[v] still comes from the score kernel.
 // ---------------------------------------------------------------------------
 template <int G>
-__device__ __forceinline__ float group_sum(float x)
-{
-    // butterfly over the G lanes of a head; every lane ends with the group's sum
-    if constexpr (G >= 2) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-    if constexpr (G >= 4) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-    if constexpr (G >= 8) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, true));  // row_half_mirror
-    if constexpr (G >= 16) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, true)); // row_mirror
-    if constexpr (G >= 32) x += __shfl_xor(x, 16, 64);
-    if constexpr (G >= 64) x += __shfl_xor(x, 32, 64);
-    return x;
-}
-
-template <int G>
 __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs a, const float* __restrict__ attn_src,
                                                                          int er_stride)
 {

@@ -717,6 +717,108 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void stored_gat_
 }
 
 // ---------------------------------------------------------------------------
+// gat_softmax over a stored table for rows of ordinary length when the row fits one wave at four
+// elements per lane (F <= 256) and a head is a power-of-two group of lanes: the source score of an
+// entry is computed from the gathered (decoded) row itself instead of being read from the score
+// table, which costs a cache line per entry — a fifth of the traffic when a row is only 512 bytes.
+// Same scheme as the fp32 kernel of that name: per-lane dot product with a_src, sum over the head's
+// lanes, online softmax over batches of four entries, scores in units of log2(e).
+// ---------------------------------------------------------------------------
+template <int FMT, int G>
+__global__ __launch_bounds__(64 * kLightWaves) void stored_gat_flash_kernel(StoredArgs a, const float* __restrict__ attn_src,
+                                                                            int er_stride)
+{
+    constexpr int U = 4, E = 4;
+    constexpr float kLog2e = 1.4426950408889634f;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t slot = (int64_t)blockIdx.x * kLightWaves + wave;
+    if (slot >= a.row_count) return;
+    const int v = __builtin_amdgcn_readfirstlane(a.order[a.row_begin + slot]);
+    const int lo = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v]);
+    const int hi = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v + 1]);
+
+    const int64_t col = lane * E;
+    const bool act = col < a.F;
+    const int64_t colsafe = act ? col : 0;            // idle lanes read the row start (weight vector zero, never stored)
+    const int h = min((int)(col / a.Dh), a.heads - 1);
+    float as[E] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float erv = 0.0f;
+    if (act) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(attn_src + col);
+        as[0] = t.x * kLog2e; as[1] = t.y * kLog2e; as[2] = t.z * kLog2e; as[3] = t.w * kLog2e;
+        erv = a.er[(int64_t)v * er_stride + h] * kLog2e;
+    }
+
+    float m = -INFINITY, s = 0.0f;
+    float acc[E] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int base = lo; base < hi; base += 64) {
+        const int e = base + lane;
+        const bool valid = e < hi;
+        const int cnt = min(64, hi - base);
+        int my_u = valid ? a.col_idx[e] : 0;
+        my_u = valid ? my_u : bcast_i(my_u, 0);
+
+        float zq[U][E];
+#pragma unroll
+        for (int t = 0; t < U; ++t) load_stored<FMT, E>(a.Z + (int64_t)bcast_i(my_u, t) * a.ldz + colsafe, zq[t]);
+
+        for (int j = 0; j < cnt; j += U) {
+            float zn[U][E];
+            const bool more = j + U < cnt;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t)
+                    load_stored<FMT, E>(a.Z + (int64_t)bcast_i(my_u, (j + U + t) & 63) * a.ldz + colsafe, zn[t]);
+            }
+            float sc[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                float d = as[0] * zq[t][0];
+                d = fmaf(as[1], zq[t][1], d);
+                d = fmaf(as[2], zq[t][2], d);
+                d = fmaf(as[3], zq[t][3], d);
+                const float x = group_sum<G>(d) + erv;
+                sc[t] = (j + t < cnt) ? (x > 0.0f ? x : a.slope * x) : -INFINITY;
+            }
+            float mn = m;
+#pragma unroll
+            for (int t = 0; t < U; ++t) mn = fmaxf(mn, sc[t]);      // finite: entry j of the tile is real
+            const float scale = __builtin_amdgcn_exp2f(m - mn);
+            float pw[U], ps = 0.0f;
+#pragma unroll
+            for (int t = 0; t < U; ++t) { pw[t] = __builtin_amdgcn_exp2f(sc[t] - mn); ps += pw[t]; }
+            s = s * scale + ps;
+#pragma unroll
+            for (int k = 0; k < E; ++k) acc[k] *= scale;
+#pragma unroll
+            for (int t = 0; t < U; ++t)
+#pragma unroll
+                for (int k = 0; k < E; ++k) acc[k] = fmaf(pw[t], zq[t][k], acc[k]);
+            m = mn;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t)
+#pragma unroll
+                    for (int k = 0; k < E; ++k) zq[t][k] = zn[t][k];
+            }
+        }
+    }
+
+    if (!act) return;
+    float* orow = a.out + (int64_t)v * a.ldo;
+    float r[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) r[k] = s > 0.0f ? acc[k] / s : 0.0f;
+    store_floats<E>(orow + a.ocol + col, r, E, a.out_vec != 0);
+    if (a.copy_self) {
+        float zs[E];
+        load_stored<FMT, E>(a.Z + (int64_t)v * a.ldz + col, zs);
+        store_floats<E>(orow + col, zs, E, a.self_vec != 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 template <typename K, typename KH>
@@ -870,12 +972,36 @@ int launch_stored(const StoredCall& c, hipStream_t stream)
         if (hp == 4) stored_scores_kernel<FMT, 4><<<dim3(gb), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
         else stored_scores_kernel<FMT, 8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
         const bool hu = (a.Dh % E) == 0;
-        if (E == 8) {
+        // rows of ordinary length compute the source scores from the gathered rows (see the kernel)
+        const int g = a.Dh / 4;
+        const bool flash = E == 4 && opt.gat_flash && a.Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 &&
+                           (uintptr_t)c.attn_src % 16 == 0;
+        int64_t n_table = N;          // rows [0, n_table) of the schedule go through the table kernels
+        if (flash && N > n_heavy) {
+            StoredArgs f = a;
+            f.nslab = 1;
+            f.row_begin = n_heavy;
+            f.row_count = N - n_heavy;
+            const dim3 grid((unsigned)((f.row_count + kLightWaves - 1) / kLightWaves)), block(64 * kLightWaves);
+            switch (g) {
+                case 1:  stored_gat_flash_kernel<FMT, 1><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 2:  stored_gat_flash_kernel<FMT, 2><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 4:  stored_gat_flash_kernel<FMT, 4><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 8:  stored_gat_flash_kernel<FMT, 8><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 16: stored_gat_flash_kernel<FMT, 16><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 32: stored_gat_flash_kernel<FMT, 32><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                default: stored_gat_flash_kernel<FMT, 64><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+            }
+            n_table = n_heavy;
+        }
+        if (n_table == 0) {
+            // nothing left for the table kernels
+        } else if (E == 8) {
             if (hp == 4) { if (hu) dispatch_gat<FMT, 8, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 8, 4, false>(nc, a, n_heavy, N, stream); }
             else         { if (hu) dispatch_gat<FMT, 8, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 8, 8, false>(nc, a, n_heavy, N, stream); }
         } else if (E == 4) {
-            if (hp == 4) { if (hu) dispatch_gat<FMT, 4, 4, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 4, 4, false>(nc, a, n_heavy, N, stream); }
-            else         { if (hu) dispatch_gat<FMT, 4, 8, true>(nc, a, n_heavy, N, stream); else dispatch_gat<FMT, 4, 8, false>(nc, a, n_heavy, N, stream); }
+            if (hp == 4) { if (hu) dispatch_gat<FMT, 4, 4, true>(nc, a, n_heavy, n_table, stream); else dispatch_gat<FMT, 4, 4, false>(nc, a, n_heavy, n_table, stream); }
+            else         { if (hu) dispatch_gat<FMT, 4, 8, true>(nc, a, n_heavy, n_table, stream); else dispatch_gat<FMT, 4, 8, false>(nc, a, n_heavy, n_table, stream); }
         } else {
             if (hp == 4) dispatch_gat<FMT, 1, 4, true>(nc, a, n_heavy, N, stream);
             else dispatch_gat<FMT, 1, 8, true>(nc, a, n_heavy, N, stream);

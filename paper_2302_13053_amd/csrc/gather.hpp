@@ -72,6 +72,21 @@ __device__ __forceinline__ float bcast_f(float x, int lane)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
 }
 
+// sum over aligned groups of G neighbouring lanes (G a power of two): up to 16 lanes with DPP moves inside
+// a row of 16, beyond that with cross-row shuffles
+template <int G>
+__device__ __forceinline__ float group_sum(float x)
+{
+    // butterfly over the G lanes of a head; every lane ends with the group's sum
+    if constexpr (G >= 2) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    if constexpr (G >= 4) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    if constexpr (G >= 8) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    if constexpr (G >= 16) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, true)); // row_mirror
+    if constexpr (G >= 32) x += __shfl_xor(x, 16, 64);
+    if constexpr (G >= 64) x += __shfl_xor(x, 32, 64);
+    return x;
+}
+
 // pick s[h] for a per-lane head index from per-head wave-uniform values
 template <int HP>
 __device__ __forceinline__ float select_head(const float (&s)[HP], int h)

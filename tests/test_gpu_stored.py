@@ -190,3 +190,24 @@ def test_full_size_stored_first_round(idx):
     print("workload %d first-round aggregation: fp32 table %.2f ms, bf16 table %.2f ms, fp16 table %.2f ms"
           % (idx, t32, t16, th), flush=True)
     g.destroy()
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+@pytest.mark.parametrize("F,heads", [(256, 1), (256, 2), (256, 4), (192, 3), (96, 3), (96, 6), (64, 8), (32, 8), (24, 2)])
+@pytest.mark.parametrize("concat", [False, True])
+def test_stored_edge_softmax_with_scores_from_gathered_rows(graphs, fmt, F, heads, concat):
+    # ordinary rows compute <a_src, z_u> from the stored row they gather; long rows and head widths that are
+    # not a power-of-two number of lanes read the score table: both against the oracle, and each other
+    kind = "normal" if F >= 64 else "absnormal"
+    results = {}
+    try:
+        for flash in (1, 0):
+            B.retexo_set_option("agg_gat_flash", flash)
+            for name in ("skewed", "flat", "tiny"):
+                got, want = run_case(graphs, name, "gat_softmax", fmt, F, F, heads, concat, seed=F + heads, kind=kind)
+                assert_close(got, want, what="%s gat F=%d heads=%d flash=%d %s" % (fmt, F, heads, flash, name))
+                results[(flash, name)] = got
+    finally:
+        B.retexo_set_option("agg_gat_flash", 1)
+    for name in ("skewed", "flat", "tiny"):
+        assert_close(results[(1, name)], results[(0, name)].astype(np.float64), what="flash vs table " + name)
