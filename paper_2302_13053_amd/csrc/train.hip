@@ -302,16 +302,36 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(
     write_partial<TM, TN>(acc, M, Nq, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, part + (int64_t)blockIdx.z * M * Nq);
 }
 
-// out[m][n] = sum_z part[z][m][n] for n < n_keep (partials are Nq wide), in z order
+// out[m][n] = sum_z part[z][m][n] for n < n_keep (partials are Nq wide).  A workgroup owns 64 outputs; its four
+// waves each add a quarter of the z range with four running sums (z mod 4), and the sixteen sums of an output
+// are combined in a fixed order: the result does not depend on the launch, and with few outputs and hundreds of
+// partials (a classifier's gradient) the additions no longer wait for one load at a time.
 __global__ __launch_bounds__(kThreads) void reduce_partials(
     int S, int M, int Nq, int n_keep, const float* __restrict__ part, float* __restrict__ out)
 {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= (int64_t)M * n_keep) return;
-    const int m = (int)(i / n_keep), n = (int)(i % n_keep);
+    __shared__ float sh[kThreads / 64][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+    const bool live = i < (int64_t)M * n_keep;
     float s = 0.0f;
-    for (int z = 0; z < S; ++z) s += part[((int64_t)z * M + m) * Nq + n];
-    out[i] = s;
+    if (live) {
+        const int m = (int)(i / n_keep), n = (int)(i % n_keep);
+        const int per = (S + 3) / 4;
+        const int z0 = wave * per, z1 = min(S, z0 + per);
+        const float* p = part + (int64_t)m * Nq + n;
+        const int64_t pitch = (int64_t)M * Nq;
+        float q[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        int z = z0;
+        for (; z + 4 <= z1; z += 4) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) q[k] += p[(int64_t)(z + k) * pitch];
+        }
+        for (int k = 0; z < z1; ++z, ++k) q[k] += p[(int64_t)z * pitch];
+        s = (q[0] + q[1]) + (q[2] + q[3]);
+    }
+    sh[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && live) out[i] = (sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane]);
 }
 
 struct TrainHeader {
@@ -512,7 +532,7 @@ void wgrad(int64_t K, int64_t M, int64_t Nq, int64_t n_keep, const float* P, int
     else if (bn == 128) launch_wgrad_bn<128, 2, 2>(K, M, Nq, P, ldp, Q, ldq, sp, part, stream);
     else launch_wgrad_bn<256, 2, 2>(K, M, Nq, P, ldp, Q, ldq, sp, part, stream);
     const int64_t total = M * n_keep;
-    reduce_partials<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+    reduce_partials<<<dim3((unsigned)((total + 63) / 64)), dim3(kThreads), 0, stream>>>(
         sp.S, (int)M, (int)Nq, (int)n_keep, part, out);
 }
 
