@@ -424,9 +424,10 @@ __global__ __launch_bounds__(kThreads) void loss_reduce_kernel(int64_t n_part, c
 }
 
 // Column sums in two deterministic stages.  Stage 1: a workgroup takes kColRows rows; its four
-// waves stride the rows, lanes stride the columns, and the waves are added in order through LDS.
+// waves stride the rows, lanes stride the columns, every wave keeps four running sums (four loads in
+// flight) that are combined in a fixed order, and the waves are added in order through LDS.
 // Stage 2: one workgroup per column adds the stage-1 results with a fixed tree.
-constexpr int kColRows = 512;
+constexpr int kColRows = 128;
 
 __global__ __launch_bounds__(kThreads) void colsum_stage1(int64_t N, int C, const float* __restrict__ D, int64_t ld,
                                                           float* __restrict__ part)
@@ -437,8 +438,16 @@ __global__ __launch_bounds__(kThreads) void colsum_stage1(int64_t N, int C, cons
     for (int c0 = 0; c0 < C; c0 += 64) {
         const int c = c0 + lane;
         float s = 0.0f;
-        if (c < C)
-            for (int64_t r = r0 + wave; r < r1; r += 4) s += D[r * ld + c];
+        if (c < C) {
+            float q[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            int64_t r = r0 + wave;
+            for (; r + 12 < r1; r += 16) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) q[k] += D[(r + 4 * k) * ld + c];
+            }
+            for (int k = 0; r < r1; r += 4, ++k) q[k] += D[r * ld + c];
+            s = (q[0] + q[1]) + (q[2] + q[3]);
+        }
         sh[wave][lane] = s;
         __syncthreads();
         if (wave == 0 && c < C)
