@@ -521,19 +521,45 @@ __global__ __launch_bounds__(256) void gat_bwd_param_partial_kernel(
     }
 }
 
-__global__ __launch_bounds__(256) void gat_bwd_param_final_kernel(
+// A workgroup of 16 waves owns 64 columns: every wave adds a sixteenth of the blocks' partial sums with four
+// running sums (four loads in flight), and the 64 sums of a column are combined in a fixed order.
+__global__ __launch_bounds__(1024) void gat_bwd_param_final_kernel(
     int64_t nblk, int64_t F, const float* __restrict__ partial, float* __restrict__ da_src,
     float* __restrict__ da_dst)
 {
-    const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (col >= F) return;
+    __shared__ float sh[2][16][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col = (int64_t)blockIdx.x * 64 + lane;
     float ss = 0.0f, sd = 0.0f;
-    for (int64_t b = 0; b < nblk; ++b) {
-        ss += partial[(b * 2 + 0) * F + col];
-        sd += partial[(b * 2 + 1) * F + col];
+    if (col < F) {
+        const int64_t per = (nblk + 15) / 16;
+        const int64_t b0 = wave * per, b1 = min(nblk, b0 + per);
+        float qs[4] = {0.0f, 0.0f, 0.0f, 0.0f}, qd[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        int64_t b = b0;
+        for (; b + 4 <= b1; b += 4) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                qs[k] += partial[((b + k) * 2 + 0) * F + col];
+                qd[k] += partial[((b + k) * 2 + 1) * F + col];
+            }
+        }
+        for (int k = 0; b < b1; ++b, ++k) {
+            qs[k] += partial[(b * 2 + 0) * F + col];
+            qd[k] += partial[(b * 2 + 1) * F + col];
+        }
+        ss = (qs[0] + qs[1]) + (qs[2] + qs[3]);
+        sd = (qd[0] + qd[1]) + (qd[2] + qd[3]);
     }
-    da_src[col] = ss;
-    da_dst[col] = sd;
+    sh[0][wave][lane] = ss;
+    sh[1][wave][lane] = sd;
+    __syncthreads();
+    if (wave == 0 && col < F) {
+        float ts = 0.0f, td = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { ts += sh[0][w][lane]; td += sh[1][w][lane]; }
+        da_src[col] = ts;
+        da_dst[col] = td;
+    }
 }
 
 // S[v, :] = G[v, :] / deg v (zero for an empty row): the mean's backward sums these rows.
@@ -759,7 +785,7 @@ int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream)
     float* partial = (float*)(ws + w.partial);
     gat_bwd_param_partial_kernel<<<dim3((unsigned)nblk), dim3(256), 0, stream>>>(
         N, F, a.Dh, c.heads, hp, c.Z, c.ldz, a.dsrc, a.ddst, rows_per_block, partial);
-    gat_bwd_param_final_kernel<<<dim3((unsigned)((F + 255) / 256)), dim3(256), 0, stream>>>(
+    gat_bwd_param_final_kernel<<<dim3((unsigned)((F + 63) / 64)), dim3(1024), 0, stream>>>(
         nblk, F, partial, c.d_attn_src, c.d_attn_dst);
     if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
     return RETEXO_OK;
