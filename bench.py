@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (0-4)")
+    ap.add_argument("--config", type=int, default=3, help="workload index (0-4; 3 = Reddit-shaped, 4 = ogbn-products-shaped)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = per-workload default)")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
