@@ -16,6 +16,7 @@
 // self-loops are requested and never flagged otherwise, so no sentinel value
 // and no extra key bit is needed: the sort covers exactly 2*cbits bits.
 #include <cstring>
+#include <iterator>
 
 #include <rocprim/device/device_radix_sort.hpp>
 #include <rocprim/device/device_scan.hpp>
@@ -96,6 +97,95 @@ __global__ __launch_bounds__(kThreads) void row_offsets(
         if (keys[mid] < want) lo = mid + 1; else hi = mid;
     }
     row_ptr[r] = (lo < M) ? (int64_t)pos[lo] : hdr->nnz;
+}
+
+// ---------------------------------------------------------------------------
+// One-pass finish (used when col_idx can hold every key, so nothing can overflow): the exclusive scan
+// writes through an iterator whose assignment is the rest of the construction.  For key i with scan
+// value pos: a kept key stores its column at col_idx[pos]; the first key of a row stores pos as that
+// row's offset; the last key stores the total.  Rows without keys are filled in afterwards.
+// Nothing is written when an id was out of range.
+// ---------------------------------------------------------------------------
+struct EmitCtx {
+    const uint64_t* keys;
+    int cbits;
+    int keep_diagonal;
+    int64_t M;
+    int32_t* col_idx;
+    int64_t* row_ptr;
+    CsrHeader* hdr;
+};
+
+struct EmitProxy {
+    EmitCtx c;
+    int64_t i;
+    __device__ const EmitProxy& operator=(uint32_t pos) const
+    {
+        if (c.hdr->bad_id) return *this;
+        const uint64_t mask = (1ull << c.cbits) - 1;
+        const uint64_t k = c.keys[i];
+        const bool first = i == 0;
+        const uint64_t prev = first ? 0 : c.keys[i - 1];
+        const uint64_t row = k >> c.cbits, col = k & mask;
+        const bool kept = (c.keep_diagonal || row != col) && (first || prev != k);
+        if (kept) c.col_idx[pos] = (int32_t)col;
+        if (first || (prev >> c.cbits) != row) c.row_ptr[row] = (int64_t)pos;
+        if (i == c.M - 1) c.hdr->nnz = (int64_t)pos + (kept ? 1 : 0);
+        return *this;
+    }
+};
+
+class EmitIterator {
+public:
+    using iterator_category = std::random_access_iterator_tag;
+    using value_type = uint32_t;
+    using difference_type = std::ptrdiff_t;
+    using pointer = void;
+    using reference = EmitProxy;
+
+    __host__ __device__ EmitIterator(const EmitCtx& c, int64_t i = 0) : c_(c), i_(i) {}
+    __host__ __device__ EmitProxy operator*() const { return EmitProxy{c_, i_}; }
+    __host__ __device__ EmitProxy operator[](difference_type d) const { return EmitProxy{c_, i_ + d}; }
+    __host__ __device__ EmitIterator operator+(difference_type d) const { return EmitIterator(c_, i_ + d); }
+    __host__ __device__ EmitIterator operator-(difference_type d) const { return EmitIterator(c_, i_ - d); }
+    __host__ __device__ difference_type operator-(const EmitIterator& o) const { return i_ - o.i_; }
+    __host__ __device__ EmitIterator& operator+=(difference_type d) { i_ += d; return *this; }
+    __host__ __device__ EmitIterator& operator-=(difference_type d) { i_ -= d; return *this; }
+    __host__ __device__ EmitIterator& operator++() { ++i_; return *this; }
+    __host__ __device__ EmitIterator operator++(int) { EmitIterator t = *this; ++i_; return t; }
+    __host__ __device__ bool operator==(const EmitIterator& o) const { return i_ == o.i_; }
+    __host__ __device__ bool operator!=(const EmitIterator& o) const { return i_ != o.i_; }
+    __host__ __device__ bool operator<(const EmitIterator& o) const { return i_ < o.i_; }
+
+private:
+    EmitCtx c_;
+    int64_t i_;
+};
+
+// every row offset starts as "not set"
+__global__ __launch_bounds__(kThreads) void unset_rows(int64_t N, const CsrHeader* hdr, int64_t* __restrict__ row_ptr)
+{
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (r > N || hdr->bad_id) return;
+    row_ptr[r] = -1;
+}
+
+// rows without keys take the offset of the next row that has some (or nnz); row_ptr[N] = nnz
+__global__ __launch_bounds__(kThreads) void fill_rows(int64_t N, int64_t M, const uint64_t* __restrict__ keys, int cbits,
+                                                      const CsrHeader* hdr, int64_t* row_ptr)
+{
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (r > N || hdr->bad_id) return;
+    if (r == N) { row_ptr[N] = hdr->nnz; return; }
+    if (row_ptr[r] != -1) return;
+    const uint64_t want = (uint64_t)r << cbits;
+    int64_t lo = 0, hi = M;                       // first index with keys[idx] >= want: a later row's first key
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (keys[mid] < want) lo = mid + 1; else hi = mid;
+    }
+    // that row has keys, so its offset was set by the scan and is not touched here
+    row_ptr[r] = lo < M ? row_ptr[(int64_t)(keys[lo] >> cbits)] : hdr->nnz;
 }
 
 int column_bits(int64_t N)
@@ -182,6 +272,8 @@ extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const 
     const int64_t M = L.M;
 
     const FirstOfRun flag{keys_b, cbits, add_self_loops ? 1 : 0};
+    // col_idx can hold every key: no count is needed before the columns are written
+    const bool one_pass = M > 0 && col_capacity >= M;
     RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(CsrHeader), stream));
     if (M > 0) {
         const int64_t work = n_pairs + (add_self_loops ? N : 0);
@@ -192,15 +284,26 @@ extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const 
                                                 (unsigned)(2 * cbits), stream));
         size_t cb = L.scan_bytes;
         auto flags_it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), flag);
-        RETEXO_HIP_TRY(rocprim::exclusive_scan(ws + L.scan_tmp, cb, flags_it, pos, 0u, (size_t)M,
-                                               rocprim::plus<uint32_t>(), stream));
-        total_kept<<<dim3(1), dim3(64), 0, stream>>>(M, flag, pos, hdr);
+        if (one_pass) {
+            const unsigned gr = (unsigned)((N + 1 + kThreads - 1) / kThreads);
+            unset_rows<<<dim3(gr), dim3(kThreads), 0, stream>>>(N, hdr, d_row_ptr);
+            const EmitCtx ctx{keys_b, cbits, add_self_loops ? 1 : 0, M, d_col_idx, d_row_ptr, hdr};
+            RETEXO_HIP_TRY(rocprim::exclusive_scan(ws + L.scan_tmp, cb, flags_it, EmitIterator(ctx), 0u, (size_t)M,
+                                                   rocprim::plus<uint32_t>(), stream));
+            fill_rows<<<dim3(gr), dim3(kThreads), 0, stream>>>(N, M, keys_b, cbits, hdr, d_row_ptr);
+        } else {
+            RETEXO_HIP_TRY(rocprim::exclusive_scan(ws + L.scan_tmp, cb, flags_it, pos, 0u, (size_t)M,
+                                                   rocprim::plus<uint32_t>(), stream));
+            total_kept<<<dim3(1), dim3(64), 0, stream>>>(M, flag, pos, hdr);
+        }
     }
+    RETEXO_HIP_TRY(hipGetLastError());
     CsrHeader h;
     RETEXO_HIP_TRY(hipMemcpyAsync(&h, hdr, sizeof(h), hipMemcpyDeviceToHost, stream));
     RETEXO_HIP_TRY(hipStreamSynchronize(stream));
     if (h.bad_id) return RETEXO_E_CSR;
     if (h_nnz) *h_nnz = h.nnz;
+    if (one_pass) return RETEXO_OK;                 // everything is written, and the stream is idle
     if (h.nnz > col_capacity) return RETEXO_E_CAPACITY;
 
     if (M > 0) {

@@ -163,3 +163,27 @@ def test_row_split_of_unsorted_columns_still_cuts_every_row_into_consecutive_pie
     out = Hn.aggregate(g, "sum", Hn.dev(Z), 40)
     assert np.array_equal(out.cpu().numpy()[:, :40].astype(np.float64), oracle.aggregate("sum", rp, ci, Z, 40))
     g.destroy()
+
+
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_csr_with_exactly_sized_columns_gives_the_same_arrays(self_loops):
+    # a column array that can hold every key lets the builder write columns and row offsets in the scan
+    # itself; a smaller one (here: exactly nnz, after a size query) makes it count first.  Same result.
+    n = 3000
+    src, dst = wl.random_pairs(n, 40000, 11, skew=2.0)
+    rp_o, ci_o = oracle.csr_from_coo(src, dst, n, self_loops)
+    d_src, d_dst = Hn.dev(src), Hn.dev(dst)
+    ws = Hn.ws_tensor(B.retexo_csr_workspace_bytes(src.size, n, self_loops))
+    rp = torch.full((n + 1,), -7, dtype=torch.int64, device="cuda")
+    st, nnz = B.retexo_csr_from_coo(src.size, d_src.data_ptr(), d_dst.data_ptr(), n, self_loops,
+                                    rp.data_ptr(), 0, 0, ws.data_ptr(), ws.numel())
+    assert st == B.E_CAPACITY and nnz == rp_o[-1] and bool((rp == -7).all())
+    ci = torch.full((nnz + 5,), -7, dtype=torch.int32, device="cuda")
+    st, nnz2 = B.retexo_csr_from_coo(src.size, d_src.data_ptr(), d_dst.data_ptr(), n, self_loops,
+                                     rp.data_ptr(), ci.data_ptr(), nnz, ws.data_ptr(), ws.numel())
+    torch.cuda.synchronize()
+    assert st == B.OK and nnz2 == nnz
+    assert np.array_equal(rp.cpu().numpy(), rp_o) and np.array_equal(ci.cpu().numpy()[:nnz], ci_o)
+    assert bool((ci[nnz:] == -7).all())
+    big = Hn.csr_from_coo(d_src, d_dst, n, self_loops)            # roomy column array: the one-pass path
+    assert np.array_equal(big.row_ptr.cpu().numpy(), rp_o) and np.array_equal(big.col_idx.cpu().numpy()[:nnz], ci_o)
