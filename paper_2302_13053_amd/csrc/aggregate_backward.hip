@@ -272,6 +272,124 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void gat_bwd_dst
 }
 
 // ---------------------------------------------------------------------------
+// "dst" pass for rows of ordinary length when the row fits one wave at four floats per lane
+// (F <= 256) and a head is a power-of-two group of G lanes: the source score of an entry is
+// computed from the gathered row z_u itself (dot product with a_src over the head's lanes)
+// instead of being read from the score table, which costs a cache line per entry.  Same
+// quantities as gat_bwd_dst_kernel, kept per lane (equal over the lanes of a head) and updated
+// online over batches of four entries: running maximum m, sums of exp over entries with a
+// positive score (s) and the others (sn), and the lane's share of sum exp * <g_v, z_u>, again
+// split by the sign of the score (qp, qn).
+// ---------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(64 * kLightWaves) void gat_bwd_dst_flash_kernel(BwdArgs a, int hp)
+{
+    constexpr int U = 4;
+    constexpr float kLog2e = 1.4426950408889634f;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t item = (int64_t)blockIdx.x * kLightWaves + wave;
+    if (item >= a.row_count) return;
+    const int v = __builtin_amdgcn_readfirstlane(a.order[a.row_begin + item]);
+    const int lo = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v]);
+    const int hi = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v + 1]);
+
+    const int64_t col = (int64_t)lane * 4;
+    const bool act = col < a.F;
+    const int64_t colsafe = act ? col : 0;    // lanes past the row width gather column 0 with zero multipliers
+    const int h = min((int)(col / a.Dh), a.heads - 1);
+    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f}, as[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float erv = 0.0f;
+    if (act) {
+        load_row<4>(a.G + (int64_t)v * a.ldg + col, g);
+        load_row<4>(a.a_src + col, as);
+        erv = a.er[(int64_t)v * hp + h];
+    }
+
+    float m = -INFINITY, s = 0.0f, sn = 0.0f, qp = 0.0f, qn = 0.0f;
+    for (int base = lo; base < hi; base += 64) {
+        const int e = base + lane;
+        const bool valid = e < hi;
+        const int cnt = min(64, hi - base);
+        int my_u = valid ? a.col_idx[e] : 0;
+        my_u = valid ? my_u : bcast_i(my_u, 0);          // lane 0 is always valid
+
+        float zq[U][4];
+#pragma unroll
+        for (int t = 0; t < U; ++t) load_row<4>(a.Z + (int64_t)bcast_i(my_u, t) * a.ldz + colsafe, zq[t]);
+
+        for (int j = 0; j < cnt; j += U) {
+            float zn[U][4];
+            const bool more = j + U < cnt;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t)
+                    load_row<4>(a.Z + (int64_t)bcast_i(my_u, (j + U + t) & 63) * a.ldz + colsafe, zn[t]);
+            }
+            float x[U], sc[U], pd[U];
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                float d = as[0] * zq[t][0];
+                d = fmaf(as[1], zq[t][1], d);
+                d = fmaf(as[2], zq[t][2], d);
+                d = fmaf(as[3], zq[t][3], d);
+                x[t] = group_sum<G>(d) + erv;
+                sc[t] = (j + t < cnt) ? (x[t] > 0.0f ? x[t] : a.slope * x[t]) : -INFINITY;
+                float q = g[0] * zq[t][0];
+                q = fmaf(g[1], zq[t][1], q);
+                q = fmaf(g[2], zq[t][2], q);
+                q = fmaf(g[3], zq[t][3], q);
+                pd[t] = q;
+            }
+            float mn = m;
+#pragma unroll
+            for (int t = 0; t < U; ++t) mn = fmaxf(mn, sc[t]);      // finite: entry j of the tile is real
+            const float scale = __builtin_amdgcn_exp2f((m - mn) * kLog2e);   // 0 on the first batch
+            float sp_b = 0.0f, sn_b = 0.0f, qp_b = 0.0f, qn_b = 0.0f;
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                const float pe = __builtin_amdgcn_exp2f((sc[t] - mn) * kLog2e);   // 0 past the tile
+                const float pp = x[t] > 0.0f ? pe : 0.0f;
+                const float pn = x[t] > 0.0f ? 0.0f : pe;
+                sp_b += pp;
+                sn_b += pn;
+                qp_b = fmaf(pp, pd[t], qp_b);
+                qn_b = fmaf(pn, pd[t], qn_b);
+            }
+            s = s * scale + sp_b;
+            sn = sn * scale + sn_b;
+            qp = qp * scale + qp_b;
+            qn = qn * scale + qn_b;
+            m = mn;
+            if (more) {
+#pragma unroll
+                for (int t = 0; t < U; ++t)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) zq[t][k] = zn[t][k];
+            }
+        }
+    }
+
+    const float QP = group_sum<G>(qp), QN = group_sum<G>(qn);
+    if (act && (lane % G) == 0 && col < (int64_t)a.heads * a.Dh) {
+        const float sum = s + sn;
+        const bool any = sum > 0.0f;
+        const float rs = any ? 1.0f / sum : 0.0f;
+        const float ap = QP * rs, an = QN * rs;              // A+, A-
+        const f32x4 t = {erv, any ? m : 0.0f, rs, ap + an};
+        a.nbr[(int64_t)v * hp + h] = t;
+        a.ddst[(int64_t)v * hp + h] = (1.0f - a.slope) * (ap * (sn * rs) - an * (s * rs));
+    }
+    if (lane == 0) {
+        // padded heads carry no columns: neutral entries
+        for (int k = a.heads; k < hp; ++k) {
+            a.nbr[(int64_t)v * hp + k] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            a.ddst[(int64_t)v * hp + k] = 0.0f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // "src" pass: row u, gathers G_v for v in N(u) (the entries (v,u) by symmetry).
 // Writes dZ[u,:] and dsrc[u,h].
 // ---------------------------------------------------------------------------
@@ -591,9 +709,17 @@ __global__ __launch_bounds__(256) void add_rows_kernel(int64_t N, int64_t F, con
 
 bool aligned4(const void* p, int64_t ld) { return ((uintptr_t)p % 16) == 0 && ld % 4 == 0; }
 
-// first_pass 0: the "dst" pass then the "src" pass; 1: the "src" pass alone (statistics already in place)
+template <int G>
+void launch_dst_flash(const BwdArgs& a, int hp, unsigned blocks, hipStream_t stream)
+{
+    gat_bwd_dst_flash_kernel<G><<<dim3(blocks), dim3(64 * kLightWaves), 0, stream>>>(a, hp);
+}
+
+// first_pass 0: the "dst" pass then the "src" pass; 1: the "src" pass alone (statistics already in place).
+// flash_g > 0: ordinary rows of the "dst" pass compute the source scores from the gathered rows, flash_g
+// lanes per head.
 template <int VEC, int NC, int HP, bool HU>
-void launch_passes(const BwdArgs& base, int first_pass, int64_t n_heavy, int64_t N, hipStream_t stream)
+void launch_passes(const BwdArgs& base, int first_pass, int64_t n_heavy, int64_t N, hipStream_t stream, int flash_g = 0)
 {
     for (int pass = first_pass; pass < 2; ++pass) {
         if (n_heavy > 0) {
@@ -610,7 +736,17 @@ void launch_passes(const BwdArgs& base, int first_pass, int64_t n_heavy, int64_t
             a.row_begin = n_heavy;
             a.row_count = N - n_heavy;
             const unsigned blocks = (unsigned)((a.row_count + kLightWaves - 1) / kLightWaves);
-            if (pass == 0)
+            if (pass == 0 && flash_g > 0) {
+                switch (flash_g) {
+                    case 1:  launch_dst_flash<1>(a, HP, blocks, stream); break;
+                    case 2:  launch_dst_flash<2>(a, HP, blocks, stream); break;
+                    case 4:  launch_dst_flash<4>(a, HP, blocks, stream); break;
+                    case 8:  launch_dst_flash<8>(a, HP, blocks, stream); break;
+                    case 16: launch_dst_flash<16>(a, HP, blocks, stream); break;
+                    case 32: launch_dst_flash<32>(a, HP, blocks, stream); break;
+                    default: launch_dst_flash<64>(a, HP, blocks, stream); break;
+                }
+            } else if (pass == 0)
                 gat_bwd_dst_kernel<VEC, NC, 1, HP, HU><<<dim3(blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
             else
                 gat_bwd_src_kernel<VEC, NC, 1, HP, HU><<<dim3(blocks), dim3(64 * kLightWaves), 0, stream>>>(a);
@@ -619,9 +755,9 @@ void launch_passes(const BwdArgs& base, int first_pass, int64_t n_heavy, int64_t
 }
 
 template <int VEC, int HP, bool HU>
-void dispatch_nc(int nc, const BwdArgs& a, int fp, int64_t nh, int64_t N, hipStream_t s)
+void dispatch_nc(int nc, const BwdArgs& a, int fp, int64_t nh, int64_t N, hipStream_t s, int flash_g = 0)
 {
-    if (nc == 1) launch_passes<VEC, 1, HP, HU>(a, fp, nh, N, s);
+    if (nc == 1) launch_passes<VEC, 1, HP, HU>(a, fp, nh, N, s, flash_g);
     else if (nc == 2) launch_passes<VEC, 2, HP, HU>(a, fp, nh, N, s);
     else launch_passes<VEC, 4, HP, HU>(a, fp, nh, N, s);
 }
@@ -772,8 +908,12 @@ int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream)
     if (v4) {
         const int nc = (int)((F + 255) / 256);
         const bool hu = a.Dh % 4 == 0;
-        if (hp == 4) { if (hu) dispatch_nc<4, 4, true>(nc, a, first_pass, n_heavy, N, stream); else dispatch_nc<4, 4, false>(nc, a, first_pass, n_heavy, N, stream); }
-        else         { if (hu) dispatch_nc<4, 8, true>(nc, a, first_pass, n_heavy, N, stream); else dispatch_nc<4, 8, false>(nc, a, first_pass, n_heavy, N, stream); }
+        // ordinary rows of the "dst" pass: source scores from the gathered rows when a head is a power-of-two
+        // group of four-float lanes (see the kernel)
+        const int g = a.Dh / 4;
+        const int flash_g = (opt.gat_flash && nc == 1 && hu && g <= 64 && (g & (g - 1)) == 0) ? g : 0;
+        if (hp == 4) { if (hu) dispatch_nc<4, 4, true>(nc, a, first_pass, n_heavy, N, stream, flash_g); else dispatch_nc<4, 4, false>(nc, a, first_pass, n_heavy, N, stream); }
+        else         { if (hu) dispatch_nc<4, 8, true>(nc, a, first_pass, n_heavy, N, stream, flash_g); else dispatch_nc<4, 8, false>(nc, a, first_pass, n_heavy, N, stream); }
     } else {
         const int nc = (int)((F + 63) / 64);
         if (hp == 4) dispatch_wide<4>(nc, a, first_pass, n_heavy, N, stream);

@@ -289,3 +289,26 @@ def test_save_mode_needs_aligned_rows(graphs):
         Hn.aggregate(g, "gat_softmax", Z, F, heads=heads, a_src=a, a_dst=a, workspace=ws, save=True)
     assert e.value.status == -5
     assert B.retexo_workspace_bytes(g.plan, F, B.MODES["mean"], 1, B.F_SAVE) == -5      # only the edge softmax saves
+
+
+@pytest.mark.parametrize("F,heads", [(256, 1), (256, 2), (256, 4), (192, 3), (96, 3), (96, 6), (64, 8), (32, 8), (24, 2)])
+@pytest.mark.parametrize("concat", [False, True])
+def test_edge_softmax_backward_with_scores_from_gathered_rows(graphs, F, heads, concat):
+    # ordinary rows of the first gather pass compute <a_src, z_u> from the row they gather (1 to 64 lanes per
+    # head); long rows and head widths that are not a power-of-two number of lanes read the score table.
+    # Both against the oracle, and each other to rounding.
+    res = {}
+    try:
+        for flash in (1, 0):
+            B.retexo_set_option("agg_gat_flash", flash)
+            for name in ("skewed", "flat", "tiny"):
+                got, das, dad, want = run_case(graphs, name, "gat_softmax", F, F, heads, concat, seed=F + heads)
+                what = "gat backward F=%d heads=%d flash=%d %s" % (F, heads, flash, name)
+                assert_close(got, want[0], tol=1e-5 if F >= 64 else 5e-4, what=what)
+                check_params(das, dad, want, what)
+                res[(flash, name)] = got
+    finally:
+        B.retexo_set_option("agg_gat_flash", 1)
+    for name in ("skewed", "flat", "tiny"):
+        assert_close(res[(1, name)], res[(0, name)].astype(np.float64), tol=1e-5 if F >= 64 else 5e-4,
+                     what="flash vs table " + name)
