@@ -24,6 +24,8 @@
 //    running (max, sum, accumulator) triple is rescaled once per tile (online
 //    softmax at tile granularity) — one exp per edge and head instead of one
 //    per edge and lane.
+#include <type_traits>
+
 #include "common.hpp"
 #include "gather.hpp"
 
@@ -1131,12 +1133,17 @@ void dispatch_grouped(const AggArgs& a, int64_t n_heavy, int64_t N, bool weighte
 // of log2(e) (LeakyReLU commutes with a positive factor) so that every
 // exponential is one v_exp_f32.  er[v] still comes from the score kernel.
 // ---------------------------------------------------------------------------
-template <int G>
+// TRAIN (save mode): the aggregate is accumulated in two parts, entries with a positive score (accp) and the
+// others (acc), with the sums of their weights (sp, sn), and the row statistics are kept for the backward
+// pass; scores then stay in natural units, because the stored row maximum is used as such.
+template <int G, bool TRAIN>
 __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs a, const float* __restrict__ attn_src,
                                                                          int er_stride)
 {
     constexpr int U = 4;      // entries per batch of the online softmax (2 and 8 measure the same: the kernel waits for memory)
     constexpr float kLog2e = 1.4426950408889634f;
+    constexpr float kIn = TRAIN ? 1.0f : kLog2e;       // factor on the scores as they are formed
+    constexpr float kEx = TRAIN ? kLog2e : 1.0f;       // factor inside the exponentials
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t slot = (int64_t)blockIdx.x * kLightWaves + wave;
@@ -1154,14 +1161,14 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs
     float erv = 0.0f;
     if (act) {
         as = *reinterpret_cast<const f32x4*>(attn_src + col);        // [heads, Dh] is F contiguous floats
-        as.x *= kLog2e; as.y *= kLog2e; as.z *= kLog2e; as.w *= kLog2e;
-        erv = a.er[(int64_t)v * er_stride + h] * kLog2e;
+        as.x *= kIn; as.y *= kIn; as.z *= kIn; as.w *= kIn;
+        erv = a.er[(int64_t)v * er_stride + h] * kIn;
     }
     const char* zbase = reinterpret_cast<const char*>(a.Z);
     const uint32_t rowbytes = (uint32_t)(a.ldz * 4);
 
-    float m = -INFINITY, s = 0.0f;
-    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    float m = -INFINITY, s = 0.0f, sp = 0.0f, sn = 0.0f;
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f}, accp = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int base = lo; base < hi; base += 64) {
         const int e = base + lane;
         const bool valid = e < hi;
@@ -1184,34 +1191,55 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs
                 for (int t = 0; t < U; ++t)
                     zn[t] = *reinterpret_cast<const f32x4*>(zbase + (uint32_t)bcast_i(my_off, (j + U + t) & 63) + colbytes);
             }
-            float sc[U];
+            float x[U], sc[U];
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 float d = as.x * zq[t].x;
                 d = fmaf(as.y, zq[t].y, d);
                 d = fmaf(as.z, zq[t].z, d);
                 d = fmaf(as.w, zq[t].w, d);
-                const float x = group_sum<G>(d) + erv;
-                sc[t] = (j + t < cnt) ? (x > 0.0f ? x : a.slope * x) : -INFINITY;   // entries past the tile weigh nothing
+                x[t] = group_sum<G>(d) + erv;
+                sc[t] = (j + t < cnt) ? (x[t] > 0.0f ? x[t] : a.slope * x[t]) : -INFINITY;   // entries past the tile weigh nothing
             }
             float mn = m;
 #pragma unroll
             for (int t = 0; t < U; ++t) mn = fmaxf(mn, sc[t]);                           // finite: entry j of the tile is real
-            const float scale = __builtin_amdgcn_exp2f(m - mn);
+            const float scale = __builtin_amdgcn_exp2f((m - mn) * kEx);
             float pw[U];
 #pragma unroll
-            for (int t = 0; t < U; ++t) pw[t] = __builtin_amdgcn_exp2f(sc[t] - mn);
+            for (int t = 0; t < U; ++t) pw[t] = __builtin_amdgcn_exp2f((sc[t] - mn) * kEx);
             float ps = 0.0f;
 #pragma unroll
             for (int t = 0; t < U; ++t) ps += pw[t];
             s = s * scale + ps;
             acc.x *= scale; acc.y *= scale; acc.z *= scale; acc.w *= scale;
+            if constexpr (TRAIN) {
+                float pps = 0.0f, pns = 0.0f;
+                accp.x *= scale; accp.y *= scale; accp.z *= scale; accp.w *= scale;
 #pragma unroll
-            for (int t = 0; t < U; ++t) {
-                acc.x = fmaf(pw[t], zq[t].x, acc.x);
-                acc.y = fmaf(pw[t], zq[t].y, acc.y);
-                acc.z = fmaf(pw[t], zq[t].z, acc.z);
-                acc.w = fmaf(pw[t], zq[t].w, acc.w);
+                for (int t = 0; t < U; ++t) {
+                    const float pp = x[t] > 0.0f ? pw[t] : 0.0f, pn = x[t] > 0.0f ? 0.0f : pw[t];
+                    pps += pp;
+                    pns += pn;
+                    accp.x = fmaf(pp, zq[t].x, accp.x);
+                    accp.y = fmaf(pp, zq[t].y, accp.y);
+                    accp.z = fmaf(pp, zq[t].z, accp.z);
+                    accp.w = fmaf(pp, zq[t].w, accp.w);
+                    acc.x = fmaf(pn, zq[t].x, acc.x);
+                    acc.y = fmaf(pn, zq[t].y, acc.y);
+                    acc.z = fmaf(pn, zq[t].z, acc.z);
+                    acc.w = fmaf(pn, zq[t].w, acc.w);
+                }
+                sp = sp * scale + pps;
+                sn = sn * scale + pns;
+            } else {
+#pragma unroll
+                for (int t = 0; t < U; ++t) {
+                    acc.x = fmaf(pw[t], zq[t].x, acc.x);
+                    acc.y = fmaf(pw[t], zq[t].y, acc.y);
+                    acc.z = fmaf(pw[t], zq[t].z, acc.z);
+                    acc.w = fmaf(pw[t], zq[t].w, acc.w);
+                }
             }
             m = mn;
             if (more) {
@@ -1221,13 +1249,39 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs
         }
     }
 
+    if constexpr (TRAIN) {
+        // statistics: one lane per head; the padded heads carry no columns and look like a uniform softmax
+        if (act && (lane % G) == 0 && col < (int64_t)a.heads * a.Dh) {
+            const bool any = s > 0.0f;
+            const float rs = any ? 1.0f / s : 0.0f;
+            a.save_stats[(int64_t)v * er_stride + h] = f32x4{any ? m : 0.0f, rs, sp * rs, sn * rs};
+        }
+        if (lane == 0) {
+            const bool any = hi > lo;
+            const f32x4 t = {0.0f, any ? 1.0f / (float)(hi - lo) : 0.0f, 0.0f, any ? 1.0f : 0.0f};
+            for (int k = a.heads; k < er_stride; ++k) a.save_stats[(int64_t)v * er_stride + k] = t;
+        }
+    }
     if (!act) return;
     float* orow = a.out + (int64_t)v * a.ldo;
     float r[4];
-    r[0] = s > 0.0f ? acc.x / s : 0.0f;
-    r[1] = s > 0.0f ? acc.y / s : 0.0f;
-    r[2] = s > 0.0f ? acc.z / s : 0.0f;
-    r[3] = s > 0.0f ? acc.w / s : 0.0f;
+    if constexpr (TRAIN) {
+        float rp[4], rn[4];
+        const float ap[4] = {accp.x, accp.y, accp.z, accp.w}, an[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            r[k] = s > 0.0f ? (an[k] + ap[k]) / s : 0.0f;
+            rp[k] = s > 0.0f ? ap[k] / s : 0.0f;
+            rn[k] = s > 0.0f ? an[k] / s : 0.0f;
+        }
+        store_row<4>(a.save_pos + (int64_t)v * a.ld_pos + col, rp, 4, true);
+        store_row<4>(a.save_neg + (int64_t)v * a.ld_pos + col, rn, 4, true);
+    } else {
+        r[0] = s > 0.0f ? acc.x / s : 0.0f;
+        r[1] = s > 0.0f ? acc.y / s : 0.0f;
+        r[2] = s > 0.0f ? acc.z / s : 0.0f;
+        r[3] = s > 0.0f ? acc.w / s : 0.0f;
+    }
     store_row<4>(orow + a.ocol + col, r, 4, a.out_vec != 0);
     if (a.copy_self) {
         float zs[4];
@@ -1489,7 +1543,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         // rows of ordinary length compute the source scores from the gathered rows themselves when a head is
         // a power-of-two group of four-float lanes; the long rows keep the table of scores
         const int g = a.Dh / 4;
-        const bool flash = vec == 4 && off32 && opt.gat_fast && opt.gat_flash && !c.save && c.F <= 256 &&
+        const bool flash = vec == 4 && off32 && opt.gat_fast && opt.gat_flash && c.F <= 256 &&
                            a.Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 && aligned_for(c.attn_src, 4, 4);
         int64_t n_table = N;          // rows [0, n_table) of the schedule go through the table kernels
         if (flash && N > n_heavy) {
@@ -1498,14 +1552,19 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             f.row_begin = n_heavy;
             f.row_count = N - n_heavy;
             const dim3 grid((unsigned)((f.row_count + kLightWaves - 1) / kLightWaves)), block(64 * kLightWaves);
+            auto go = [&](auto gtag) {
+                constexpr int GG = decltype(gtag)::value;
+                if (c.save) agg_gat_flash_kernel<GG, true><<<grid, block, 0, stream>>>(f, c.attn_src, hp);
+                else agg_gat_flash_kernel<GG, false><<<grid, block, 0, stream>>>(f, c.attn_src, hp);
+            };
             switch (g) {
-                case 1:  agg_gat_flash_kernel<1><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
-                case 2:  agg_gat_flash_kernel<2><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
-                case 4:  agg_gat_flash_kernel<4><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
-                case 8:  agg_gat_flash_kernel<8><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
-                case 16: agg_gat_flash_kernel<16><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
-                case 32: agg_gat_flash_kernel<32><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
-                default: agg_gat_flash_kernel<64><<<grid, block, 0, stream>>>(f, c.attn_src, hp); break;
+                case 1:  go(std::integral_constant<int, 1>{}); break;
+                case 2:  go(std::integral_constant<int, 2>{}); break;
+                case 4:  go(std::integral_constant<int, 4>{}); break;
+                case 8:  go(std::integral_constant<int, 8>{}); break;
+                case 16: go(std::integral_constant<int, 16>{}); break;
+                case 32: go(std::integral_constant<int, 32>{}); break;
+                default: go(std::integral_constant<int, 64>{}); break;
             }
             n_table = n_heavy;
         }
