@@ -355,7 +355,7 @@ extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int
                             void* d_workspace, int64_t workspace_bytes, void* stream)
 {
     if (!plan) return RETEXO_E_NULL;
-    if (D_in < 0 || D_out < 0 || D_out >= (1ll << 30)) return RETEXO_E_SIZE;
+    if (D_in < 0 || D_in >= (1ll << 31) || D_out < 0 || D_out >= (1ll << 30)) return RETEXO_E_SIZE;
     if (int s = check_mode(mode, D_out, heads)) return s;
     if (flags & ~(unsigned)(RETEXO_F_RELU | RETEXO_F_SELF_CONCAT)) return RETEXO_E_FLAGS;
     const bool concat = (flags & RETEXO_F_SELF_CONCAT) != 0;

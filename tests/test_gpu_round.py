@@ -77,6 +77,48 @@ def test_round_separately_equals_fused_and_gcn_gat_modes():
         g.destroy()
 
 
+def test_round_argument_errors_leave_the_output_untouched():
+    n, d_in, d_out = 300, 40, 64
+    src, dst = wl.random_pairs(n, 2000, 31)
+    g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False))
+    H = Hn.dev(wl.random_matrix(n, d_in, 32, ld=64))
+    W = Hn.dev(wl.random_matrix(d_in, d_out, 33))
+    b = Hn.dev(wl.random_matrix(1, d_out, 34)[0])
+    out = torch.full((n, 128), -7.0, dtype=torch.float32, device="cuda")
+    ws = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, d_out, B.GAT_SOFTMAX, 4, 0))
+
+    def call(mode=B.MEAN, di=d_in, do=d_out, heads=1, h=H.data_ptr(), ldh=64, w=W.data_ptr(), bias=b.data_ptr(),
+             a=0, flags=0, o=out.data_ptr(), ldo=128, wsp=ws.data_ptr(), wsb=ws.numel()):
+        return B.retexo_round(g.plan, mode, di, do, heads, h, ldh, w, bias, a, a, 0.2, flags, o, ldo, wsp, wsb)
+
+    assert call(di=-1) == B.E_SIZE
+    assert call(di=1 << 31) == B.E_SIZE
+    assert call(do=1 << 30) == B.E_SIZE
+    assert call(mode=9) == B.E_MODE
+    assert call(heads=0) == B.E_HEADS
+    assert call(mode=B.GAT_SOFTMAX, heads=3, a=W.data_ptr()) == B.E_HEADS        # 64 columns, 3 heads
+    assert call(flags=64) == B.E_FLAGS
+    assert call(w=0, bias=0) == B.E_SIZE                                         # identity needs D_out == D_in
+    assert call(w=0, do=d_in) == B.E_FLAGS                                       # a bias without a weight matrix
+    assert call(w=0, bias=0, do=d_in, flags=B.F_RELU) == B.E_FLAGS
+    assert call(h=0) == B.E_NULL
+    assert call(o=0) == B.E_NULL
+    assert call(mode=B.GAT_SOFTMAX, heads=4) == B.E_NULL                         # attention vectors missing
+    assert call(ldh=d_in - 1) == B.E_LD
+    assert call(flags=B.F_SELF_CONCAT, ldo=2 * d_out - 1) == B.E_LD
+    assert call(o=H.data_ptr() + 128, ldo=64) == B.E_ALIAS
+    assert call(wsp=0) == B.E_WORKSPACE
+    assert call(wsp=ws.data_ptr() + 64) == B.E_WORKSPACE
+    assert call(wsb=1024) == B.E_WORKSPACE
+    assert call(wsp=out.data_ptr(), wsb=out.numel() * 4) == B.E_ALIAS             # Z staged on top of the output
+    torch.cuda.synchronize()
+    assert bool((out == -7.0).all())
+    assert call() == B.OK
+    torch.cuda.synchronize()
+    assert not bool((out[:, :d_out] == -7.0).any()) and bool((out[:, d_out:] == -7.0).all())
+    g.destroy()
+
+
 def test_one_partitions_share_matches_the_global_result():
     """The edge-partitioned set-up of the paper on one GPU: a worker holds its inner nodes, its
     boundary nodes and the edges touching an inner node, numbered [inner | boundary].  Running
