@@ -40,6 +40,7 @@ def _load():
         lib = C.CDLL(build())
         i64, i32p, i64p = C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int64)
         f32p, f64p = C.POINTER(C.c_float), C.POINTER(C.c_double)
+        u8p = C.POINTER(C.c_uint8)
         lib.oracle_threads.restype = C.c_int
         lib.oracle_csr_from_coo.restype = i64
         lib.oracle_csr_from_coo.argtypes = [i64, i32p, i32p, i64, C.c_int, i64p, i32p]
@@ -59,11 +60,15 @@ def _load():
                                                   f64p, f64p, f64p]
         lib.oracle_layer_grad.restype = C.c_double
         lib.oracle_layer_grad.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f32p, f32p, f32p, f32p,
-                                          f64p, f64p, f64p, f64p, f64p]
+                                          f64p, f64p, f64p, f64p, f64p, u8p, C.c_double]
+        lib.oracle_philox4x32_10.restype = None
+        lib.oracle_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        lib.oracle_dropout_keep.restype = None
+        lib.oracle_dropout_keep.argtypes = [i64, i64, C.c_float, C.c_uint64, C.c_uint64, u8p]
         lib.oracle_transform_backward.restype = None
         lib.oracle_transform_backward.argtypes = [i64, i64, i64, f32p, i64, f32p, i64, f64p, f64p]
         lib.oracle_layer_loss.restype = C.c_double
-        lib.oracle_layer_loss.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f64p, f64p, f64p, f64p]
+        lib.oracle_layer_loss.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f64p, f64p, f64p, f64p, u8p, C.c_double]
         _lib = lib
     return _lib
 
@@ -233,9 +238,37 @@ def round_(mode: str, row_ptr, col_idx, H, d_in: int, W, b, *, relu: bool = Fals
                      slope=slope, self_concat=self_concat, rows=rows)
 
 
-def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None, input_grad: bool = False):
+def philox4x32_10(counter, key):
+    """One block of the counter-based generator behind the dropout mask: four 32-bit words."""
+    c = (C.c_uint32 * 4)(*[int(x) for x in counter])
+    k = (C.c_uint32 * 2)(*[int(x) for x in key])
+    out = (C.c_uint32 * 4)()
+    _load().oracle_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def dropout_keep(n: int, h: int, p_drop: float, seed: int, draw: int) -> np.ndarray:
+    """-> uint8 [n, h]: 1 where unit j of node v survives dropout number ``draw`` of stream ``seed``."""
+    keep = np.empty((n, h), np.uint8)
+    _load().oracle_dropout_keep(n, h, np.float32(p_drop), seed, draw, _p(keep, C.c_uint8))
+    return keep
+
+
+def _dropout_args(dropout, n: int, h: int):
+    """dropout = None or (p_drop, seed, draw) -> (mask array or None, scale)"""
+    if dropout is None:
+        return None, 1.0
+    assert h > 0, "dropout acts on the hidden units"
+    p_drop, seed, draw = dropout
+    p32 = np.float32(p_drop)
+    assert 0.0 <= p32 < 1.0
+    return dropout_keep(n, h, p32, seed, draw), 1.0 / (1.0 - float(p32))
+
+
+def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None, input_grad: bool = False, dropout=None):
     """Loss and parameter gradients of one locally trained layer (see oracle_layer_grad).
     Wc None: the layer is the final classifier (logits = X W1 + b1).
+    dropout: None, or (p_drop, seed, draw) for dropout on the hidden units.
     -> (loss, gW1, gb1, gWc or None, gbc or None), float64; with ``input_grad`` a sixth item,
     dL/dX [n, d_in]."""
     X, ldx = _matrix(X)
@@ -256,10 +289,12 @@ def layer_grad(X, d_in: int, labels, W1, b1, Wc=None, bc=None, input_grad: bool 
     gW1 = np.empty(W1.shape, np.float64)
     gb1 = np.empty(W1.shape[1], np.float64)
     gX = np.empty((n, d_in), np.float64) if input_grad else None
+    keep, scale = _dropout_args(dropout, n, H)
     loss = _load().oracle_layer_grad(n, d_in, H, Cc, _p(X, C.c_float), ldx, _p(labels, C.c_int32),
                                      _p(W1, C.c_float), _p(b1, C.c_float), _p(Wc_, C.c_float),
                                      _p(bc_, C.c_float), _p(gW1, C.c_double), _p(gb1, C.c_double),
-                                     _p(gWc, C.c_double), _p(gbc, C.c_double), _p(gX, C.c_double))
+                                     _p(gWc, C.c_double), _p(gbc, C.c_double), _p(gX, C.c_double),
+                                     _p(keep, C.c_uint8), scale)
     if input_grad:
         return float(loss), gW1, gb1, gWc, gbc, gX
     return float(loss), gW1, gb1, gWc, gbc
@@ -277,7 +312,7 @@ def transform_backward(H, d_in: int, dZ, d_out: int):
     return gW, gb
 
 
-def layer_loss(X, d_in: int, labels, W1, b1, Wc=None, bc=None) -> float:
+def layer_loss(X, d_in: int, labels, W1, b1, Wc=None, bc=None, dropout=None) -> float:
     """The loss alone, with float64 parameters (for numerical differencing in tests)."""
     X, ldx = _matrix(X)
     labels = _c(labels, np.int32)
@@ -287,6 +322,8 @@ def layer_loss(X, d_in: int, labels, W1, b1, Wc=None, bc=None) -> float:
     else:
         Wc_, bc_ = _c(Wc, np.float64), _c(bc, np.float64)
         H, Cc = W1.shape[1], Wc_.shape[1]
+    keep, scale = _dropout_args(dropout, labels.size, H)
     return float(_load().oracle_layer_loss(labels.size, d_in, H, Cc, _p(X, C.c_float), ldx,
                                            _p(labels, C.c_int32), _p(W1, C.c_double), _p(b1, C.c_double),
-                                           _p(Wc_, C.c_double), _p(bc_, C.c_double)))
+                                           _p(Wc_, C.c_double), _p(bc_, C.c_double),
+                                           _p(keep, C.c_uint8), scale))

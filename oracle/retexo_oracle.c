@@ -431,6 +431,55 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
 }
 
 /* ---------------------------------------------------------------------------
+ * The random draws of dropout.  Both sides of a parity test must draw the same
+ * mask, so the mask is a pure function of (seed, draw, node, unit) through a
+ * counter-based generator: Philox-4x32 with 10 rounds (Salmon, Moraes, Dror,
+ * Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC 2011).  One block
+ * gives four 32-bit words:
+ *      counter = (node, unit / 4, low word of draw, high word of draw)
+ *      key     = (low word of seed, high word of seed)
+ * and unit j takes word j % 4.  The unit is dropped when its word is below
+ * floor(p * 2^32) (p is a float, so the product is exact in double) and kept
+ * otherwise: p = 0 keeps everything.
+ * A round multiplies counter words 0 and 2 by two fixed odd constants, swaps the
+ * halves of the products into place and mixes the other two words and the key in;
+ * the key grows by two fixed increments between rounds.
+ * ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t counter[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = counter[0], c1 = counter[1], c2 = counter[2], c3 = counter[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;      /* golden ratio */
+            k1 += 0xBB67AE85u;      /* sqrt(3) - 1 */
+        }
+        const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* keep[v * H + j] = 1 if unit j of node v survives the dropout of probability p_drop */
+void oracle_dropout_keep(int64_t N, int64_t H, float p_drop, uint64_t seed, uint64_t draw, uint8_t *keep)
+{
+    const uint32_t threshold = (uint32_t)((double)p_drop * 4294967296.0);
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (int64_t v = 0; v < N; ++v)
+        for (int64_t q = 0; 4 * q < H; ++q) {
+            const uint32_t counter[4] = {(uint32_t)v, (uint32_t)q, (uint32_t)draw, (uint32_t)(draw >> 32)};
+            uint32_t w[4];
+            oracle_philox4x32_10(counter, key, w);
+            for (int64_t k = 0; k < 4 && 4 * q + k < H; ++k) keep[v * H + 4 * q + k] = w[k] >= threshold;
+        }
+}
+
+/* ---------------------------------------------------------------------------
  * Local training of one layer (section "Lazy Message Passing": a layer is
  * trained by itself on its fixed aggregated inputs, with a temporary
  * classification layer C added on top, using stochastic gradient descent; the
@@ -447,11 +496,19 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
  * (zero rows for nodes that are not training nodes) — what flows back into an
  * aggregation with trainable parameters that produced X.
  * With no labelled node the loss and all gradients are zero.
+ *
+ * Dropout (the appendix on hyper-parameters trains with dropout 0.3 or 0.5; where it
+ * sits is not said, it is taken on the layer's output A, in front of the temporary
+ * classifier): with keep != NULL, keep[v * H + j] in {0, 1},
+ *      A_vj = keep_vj ? scale * ReLU(X W1 + b1)_vj : 0,      scale = 1 / (1 - p),
+ * and the gradients are those of the loss with this fixed mask.  keep == NULL is the
+ * step without dropout.  oracle_dropout_keep below draws the mask.
  */
 double oracle_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
                          const float *X, int64_t ldx, const int32_t *labels,
                          const float *W1, const float *b1, const float *Wc, const float *bc,
-                         double *gW1, double *gb1, double *gWc, double *gbc, double *gX)
+                         double *gW1, double *gb1, double *gWc, double *gbc, double *gX,
+                         const uint8_t *keep, double scale)
 {
     const int64_t W1cols = H > 0 ? H : C;
     if (gX) for (int64_t i = 0; i < N * D_in; ++i) gX[i] = 0.0;
@@ -478,6 +535,7 @@ double oracle_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
                 double s = (double)b1[j];
                 for (int64_t k = 0; k < D_in; ++k) s += (double)x[k] * (double)W1[k * H + j];
                 a[j] = s > 0.0 ? s : 0.0;
+                if (keep) a[j] = keep[v * H + j] ? scale * a[j] : 0.0;
             }
             for (int64_t c = 0; c < C; ++c) {
                 double s = (double)bc[c];
@@ -506,7 +564,8 @@ double oracle_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,
                     gWc[j * C + c] += a[j] * z[c];
                     s += z[c] * (double)Wc[j * C + c];
                 }
-                da[j] = a[j] > 0.0 ? s : 0.0;
+                /* a_j > 0 exactly when the unit is active and kept */
+                da[j] = a[j] > 0.0 ? (keep ? scale * s : s) : 0.0;
             }
             for (int64_t j = 0; j < H; ++j) gb1[j] += da[j];
             for (int64_t k = 0; k < D_in; ++k) {
@@ -561,7 +620,8 @@ void oracle_transform_backward(int64_t N, int64_t D_in, int64_t D_out, const flo
 /* The loss alone (same formula), used by the tests to difference numerically. */
 double oracle_layer_loss(int64_t N, int64_t D_in, int64_t H, int64_t C,
                          const float *X, int64_t ldx, const int32_t *labels,
-                         const double *W1, const double *b1, const double *Wc, const double *bc)
+                         const double *W1, const double *b1, const double *Wc, const double *bc,
+                         const uint8_t *keep, double scale)
 {
     int64_t n_lab = 0;
     double loss = 0.0;
@@ -577,6 +637,7 @@ double oracle_layer_loss(int64_t N, int64_t D_in, int64_t H, int64_t C,
                 double s = b1[j];
                 for (int64_t k = 0; k < D_in; ++k) s += (double)x[k] * W1[k * H + j];
                 a[j] = s > 0.0 ? s : 0.0;
+                if (keep) a[j] = keep[v * H + j] ? scale * a[j] : 0.0;
             }
             for (int64_t c = 0; c < C; ++c) {
                 double s = bc[c];

@@ -107,6 +107,109 @@ def test_gradient_is_the_derivative_of_the_loss(h):
             assert abs(num - g[idx]) < 2e-8, (pi, idx, num, g[idx])
 
 
+# ---------------------------------------------------------------------------
+# dropout on the hidden units
+# ---------------------------------------------------------------------------
+def test_generator_reproduces_the_published_known_answers():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_known_answers.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        assert oracle.philox4x32_10(w[0:4], w[4:6]) == w[6:10]
+
+
+def test_mask_is_a_function_of_seed_draw_node_and_unit():
+    n, h = 300, 37                                    # 37: the last block of a row is used in part
+    k = oracle.dropout_keep(n, h, 0.3, 1234, 5)
+    assert k.dtype == np.uint8 and set(np.unique(k)) <= {0, 1}
+    # definition, re-stated: word (j % 4) of block (v, j // 4, draw) under key seed, kept iff word >= floor(p 2^32)
+    thr = int(np.float64(np.float32(0.3)) * 4294967296.0)
+    for v, j in [(0, 0), (0, 3), (7, 4), (299, 36), (123, 18)]:
+        word = oracle.philox4x32_10([v, j // 4, 5, 0], [1234, 0])[j % 4]
+        assert k[v, j] == (word >= thr)
+    # high words of seed and draw are used
+    assert oracle.dropout_keep(4, 8, 0.5, (9 << 32) | 1234, 5)[0].tolist() == \
+        [int(w >= 2 ** 31) for q in (0, 1) for w in oracle.philox4x32_10([0, q, 5, 0], [1234, 9])]
+    assert oracle.dropout_keep(4, 8, 0.5, 1234, (3 << 32) | 5)[1].tolist() == \
+        [int(w >= 2 ** 31) for q in (0, 1) for w in oracle.philox4x32_10([1, q, 5, 3], [1234, 0])]
+    # a prefix of the nodes / another width leaves the shared blocks alone
+    assert np.array_equal(oracle.dropout_keep(100, h, 0.3, 1234, 5), k[:100])
+    assert np.array_equal(oracle.dropout_keep(n, 36, 0.3, 1234, 5), k[:, :36])
+    # other draw or seed: another mask; p = 0 keeps all; the kept share is 1 - p
+    assert not np.array_equal(oracle.dropout_keep(n, h, 0.3, 1234, 6), k)
+    assert not np.array_equal(oracle.dropout_keep(n, h, 0.3, 1235, 5), k)
+    assert oracle.dropout_keep(n, h, 0.0, 1234, 5).all()
+    big = oracle.dropout_keep(4000, 64, 0.3, 77, 0)
+    assert abs(big.mean() - 0.7) < 4 * math.sqrt(0.21 / big.size)
+    assert abs(big.mean(0) - 0.7).max() < 0.04 and abs(big.mean(1) - 0.7).max() < 0.35
+    # monotone in p: whoever survives p = 0.5 survives p = 0.3
+    assert np.all(oracle.dropout_keep(n, h, 0.5, 1234, 5) <= k)
+
+
+def test_dropout_matches_dense_matrix_algebra_with_the_same_mask():
+    n, d_in, h, c = 90, 7, 10, 4
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, 8)
+    p = 0.4
+    loss, gW1, gb1, gWc, gbc, gX = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, input_grad=True,
+                                                     dropout=(p, 42, 3))
+    keep = oracle.dropout_keep(n, h, p, 42, 3).astype(np.float64)
+    s = 1.0 / (1.0 - float(np.float32(p)))
+    Xd = X[:, :d_in].astype(np.float64)
+    lab = y >= 0
+    Y = np.zeros((n, c))
+    Y[lab, y[lab]] = 1
+    pre = Xd @ W1 + b1
+    A = np.maximum(pre, 0) * keep * s
+    Z = A @ Wc + bc
+    Z = Z - Z.max(1, keepdims=True)
+    P = np.exp(Z) / np.exp(Z).sum(1, keepdims=True)
+    nl = lab.sum()
+    assert abs(loss - (-(np.log(P[lab, y[lab]])).sum() / nl)) < 1e-13
+    dZ = (P - Y) * lab[:, None] / nl
+    assert np.allclose(gWc, A.T @ dZ, atol=1e-14) and np.allclose(gbc, dZ.sum(0), atol=1e-14)
+    dpre = (dZ @ Wc.astype(np.float64).T) * keep * s * (pre > 0)
+    assert np.allclose(gW1, Xd.T @ dpre, atol=1e-14) and np.allclose(gb1, dpre.sum(0), atol=1e-14)
+    assert np.allclose(gX, dpre @ W1.astype(np.float64).T, atol=1e-14)
+    # p = 0 is the step without dropout, bit for bit
+    plain = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc)
+    zero = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, dropout=(0.0, 42, 3))
+    assert plain[0] == zero[0] and all(np.array_equal(a, b) for a, b in zip(plain[1:], zero[1:]))
+    # ... and differs from it for p > 0
+    assert abs(loss - plain[0]) > 1e-4
+
+
+def test_dropout_gradient_is_the_derivative_of_the_loss_with_the_mask_held_fixed():
+    n, d_in, h, c = 30, 5, 6, 3
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, 9)
+    drop = (0.5, 7, 11)
+    _, gW1, gb1, gWc, gbc = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, dropout=drop)
+    params = [W1.astype(np.float64), b1.astype(np.float64), Wc.astype(np.float64), bc.astype(np.float64)]
+    grads = [gW1, gb1, gWc, gbc]
+    f = lambda ps: oracle.layer_loss(X, d_in, y, *ps, dropout=drop)
+    eps = 1e-6
+    for pi, (p, g) in enumerate(zip(params, grads)):
+        for idx in np.ndindex(p.shape):
+            hi = [q.copy() for q in params]
+            lo = [q.copy() for q in params]
+            hi[pi][idx] += eps
+            lo[pi][idx] -= eps
+            num = (f(hi) - f(lo)) / (2 * eps)
+            assert abs(num - g[idx]) < 2e-8, (pi, idx, num, g[idx])
+
+
+def test_dropout_keeps_the_expected_activation():
+    # E[A] over the draws is the plain activation: the mean loss gradient of the classifier bias over many
+    # draws approaches the one without dropout when the classifier is linear in A (zero Wc rows but one)
+    n, d_in, h, c = 40, 4, 8, 3
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, 10)
+    keep = np.stack([oracle.dropout_keep(n, h, 0.25, 5, d) for d in range(400)]).astype(np.float64)
+    s = 1.0 / (1.0 - 0.25)
+    assert abs((keep * s).mean() - 1.0) < 0.01
+    assert abs((keep * s).mean(0) - 1.0).max() < 0.15
+
+
 def test_structure_of_the_gradients():
     n, d_in, h, c = 120, 8, 6, 5
     X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, 4)
