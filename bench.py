@@ -303,6 +303,24 @@ def main():
         out["train_step"] = {"layer": "%d->%d (ReLU) + classifier %d->%d" % (st.d_in, st.d_out, st.d_out, n_cls),
                              "ms": tms, "TFLOP/s": tfl, "frac_fp32_mfma": tfl / 157.3,
                              "loss_first": l0, "loss_last": float(last.cpu()[0]), "sgd_steps": reps + 1}
+        # the same step with dropout 0.5 on the hidden units (a fresh mask per step)
+        draw = [0]
+
+        def train_dropout_once():
+            draw[0] += 1
+            loss, *grads = Hn.layer_grad(X, st.d_in, labels, W1, b1, Wc, bc, workspace=tws,
+                                         dropout=(0.5, 20230213, draw[0]))
+            for p_, g_ in zip((W1, b1, Wc, bc), grads):
+                B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), 0.01, Hn._stream_ptr()),
+                        "retexo_sgd_update")
+        train_dropout_once()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            train_dropout_once()
+        e1.record()
+        torch.cuda.synchronize()
+        out["train_step"]["ms_with_dropout"] = e0.elapsed_time(e1) / reps
     # a layer whose aggregation has trainable parameters (edge softmax) trains with the aggregation in the
     # loop: time its backward (dL/dZ and the attention-vector gradients) on the first such round's shape
     att = next((i for i, st in enumerate(w.stages) if st.kind == "round" and st.mode == "gat_softmax"

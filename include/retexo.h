@@ -303,6 +303,25 @@ int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C,
                         float* d_gX, int64_t ldgx,
                         void* d_workspace, int64_t workspace_bytes, void* stream);
 
+/* retexo_layer_grad_x with dropout on the hidden units (appendix on hyper-parameters: the layers are
+ * trained with dropout 0.3 or 0.5; the paper does not say where it sits, here it acts on the layer's
+ * output A in front of the temporary classifier):
+ *     A_vj = keep_vj ? ReLU(X W1 + b1)_vj / (1 - p_drop) : 0
+ * and the gradients are those of the loss under this mask.  The mask is not an argument: unit j of node v
+ * is dropped when word j % 4 of the Philox-4x32-10 block with
+ *     counter = (v, j / 4, low 32 bits of draw, high 32 bits of draw),  key = (low, high 32 bits of seed)
+ * is below floor(p_drop * 2^32), so a caller that needs the mask (or the other workers' masks) can draw
+ * it again.  `seed` names the stream, `draw` the training step; calls with the same pair use the same mask.
+ *   p_drop in [0, 1); 0 is exactly retexo_layer_grad_x.  RETEXO_E_SIZE if p_drop is outside that range
+ *   (or not a number), or positive with H == 0 (the last layer has no hidden units).
+ *   d_gX may be NULL.  Same workspace and behaviour as retexo_layer_grad otherwise. */
+int retexo_layer_grad_dropout(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                              const float* d_X, int64_t ldx, const int32_t* d_labels,
+                              const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                              float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                              float* d_gX, int64_t ldgx, float p_drop, uint64_t seed, uint64_t draw,
+                              void* d_workspace, int64_t workspace_bytes, void* stream);
+
 /* Parameter gradients of the dense transform Z = H W + b (the transform in front of an
  * aggregation, trained through retexo_aggregate_backward, which supplies d_dZ = dL/dZ):
  *     gW[k, j] = sum_v H[v, k] dZ[v, j]   (d_gW [D_in, D_out], dense)

@@ -34,7 +34,7 @@ EXPORTS = (
     "retexo_plan_set_degrees", "retexo_data_volumes", "retexo_gamma",
     "retexo_store_rows", "retexo_aggregate_stored", "retexo_head_mean",
     "retexo_train_workspace_bytes", "retexo_layer_grad", "retexo_sgd_update",
-    "retexo_layer_grad_x", "retexo_transform_backward_workspace_bytes", "retexo_transform_backward",
+    "retexo_layer_grad_x", "retexo_layer_grad_dropout", "retexo_transform_backward_workspace_bytes", "retexo_transform_backward",
 )
 
 _lib = None
@@ -129,6 +129,9 @@ def load():
     lib.retexo_layer_grad_x.restype = i32
     lib.retexo_layer_grad_x.argtypes = [i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                         vp, i64, vp, i64, vp]
+    lib.retexo_layer_grad_dropout.restype = i32
+    lib.retexo_layer_grad_dropout.argtypes = [i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                              vp, i64, C.c_float, C.c_uint64, C.c_uint64, vp, i64, vp]
     lib.retexo_transform_backward_workspace_bytes.restype = i64
     lib.retexo_transform_backward_workspace_bytes.argtypes = [i64, i64, i64]
     lib.retexo_transform_backward.restype = i32
@@ -332,6 +335,15 @@ def retexo_layer_grad_x(n, d_in, h, c, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_b
                                           _vp(d_Wc), _vp(d_bc), _vp(d_gW1), _vp(d_gb1), _vp(d_gWc), _vp(d_gbc),
                                           _vp(d_loss), _vp(d_gX), ldgx, _vp(d_workspace), workspace_bytes,
                                           _vp(stream)))
+
+
+def retexo_layer_grad_dropout(n, d_in, h, c, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc, d_gW1, d_gb1, d_gWc,
+                              d_gbc, d_loss, d_gX, ldgx, p_drop, seed, draw, d_workspace, workspace_bytes,
+                              stream=0) -> int:
+    return int(load().retexo_layer_grad_dropout(n, d_in, h, c, _vp(d_X), ldx, _vp(d_labels), _vp(d_W1), _vp(d_b1),
+                                                _vp(d_Wc), _vp(d_bc), _vp(d_gW1), _vp(d_gb1), _vp(d_gWc),
+                                                _vp(d_gbc), _vp(d_loss), _vp(d_gX), ldgx, p_drop, seed, draw,
+                                                _vp(d_workspace), workspace_bytes, _vp(stream)))
 
 
 def retexo_transform_backward_workspace_bytes(n, d_in, d_out) -> int:

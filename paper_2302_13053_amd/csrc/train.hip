@@ -392,13 +392,22 @@ __global__ __launch_bounds__(kThreads) void softmax_xent_kernel(
         float m = -INFINITY;
         for (int j = lane; j < C; j += 64) m = fmaxf(m, row[j]);
         m = wmax(m);
-        float s = 0.0f;
-        for (int j = lane; j < C; j += 64) s += expf(row[j] - m);
+        // s: the softmax denominator; so: its part from the classes other than the label.  The label's
+        // gradient p_y - 1 is formed as -so / s: for a confidently classified node p_y is close to one and
+        // the subtraction would leave only a few correct digits of what is then the whole gradient.
+        float s = 0.0f, so = 0.0f;
+        for (int j = lane; j < C; j += 64) {
+            const float e = expf(row[j] - m);
+            s += e;
+            so += j == y ? 0.0f : e;
+        }
         s = wsum(s);
-        if (y >= 0 && y < C) loss += -(row[y] - m - logf(s));
+        so = wsum(so);
+        const float rest = so / s;                 // 1 - p_y
+        if (y >= 0 && y < C) loss += rest <= 0.5f ? -log1pf(-rest) : -(row[y] - m - logf(s));
         for (int j = lane; j < ld; j += 64) {
             float g = 0.0f;
-            if (j < C) g = (expf(row[j] - m) / s - (j == y ? 1.0f : 0.0f)) * scale;
+            if (j < C) g = (j == y ? -rest : expf(row[j] - m) / s) * scale;
             row[j] = g;
         }
     }
@@ -471,14 +480,70 @@ __global__ __launch_bounds__(kThreads) void colsum_stage2(int B, int C, const fl
     if (threadIdx.x == 0) out[c] = sh[0];
 }
 
-// out [Cp, R] = transpose of in [R, Cn], rows Cn..Cp of out zero
+// out [Cp, R] = scale * transpose of in [R, Cn], rows Cn..Cp of out zero
 __global__ __launch_bounds__(kThreads) void transpose_kernel(int R, int Cn, int Cp, const float* __restrict__ in,
-                                                             float* __restrict__ out)
+                                                             float* __restrict__ out, float scale)
 {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= (int64_t)R * Cp) return;
     const int c = (int)(i / R), r = (int)(i % R);
-    out[i] = c < Cn ? in[(int64_t)r * Cn + c] : 0.0f;
+    out[i] = c < Cn ? scale * in[(int64_t)r * Cn + c] : 0.0f;
+}
+
+// ---------------------------------------------------------------------------
+// Dropout on the hidden units (the appendix on hyper-parameters trains with dropout; it is taken on the
+// layer's output, in front of the temporary classifier).  The mask is not stored: unit j of node v is
+// dropped in draw number `draw` of stream `seed` when word j % 4 of the Philox-4x32-10 block
+//      counter = (v, j / 4, draw low, draw high),  key = (seed low, seed high)
+// (Salmon, Moraes, Dror, Shaw, SC 2011) is below floor(p * 2^32), so any caller can re-draw it.
+// Kept units are scaled by 1 / (1 - p).  The backward pass needs no second draw: a unit of the stored
+// activations is positive exactly when it was active and kept.
+// ---------------------------------------------------------------------------
+struct PhiloxWords { uint32_t w0, w1, w2, w3; };
+
+__device__ __forceinline__ PhiloxWords philox_4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                      uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;      // multipliers of words 0 and 2
+    constexpr uint32_t kKeyA = 0x9E3779B9u, kKeyB = 0xBB67AE85u;      // key increments per round
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
+        const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
+        c0 = hiB ^ c1 ^ k0;
+        c2 = hiA ^ c3 ^ k1;
+        c1 = loB;
+        c3 = loA;
+        k0 += kKeyA;
+        k1 += kKeyB;
+    }
+    return {c0, c1, c2, c3};
+}
+
+__global__ __launch_bounds__(kThreads) void dropout_kernel(int64_t N, int H, float* __restrict__ A, int64_t ld,
+                                                           uint32_t threshold, float scale, uint32_t seed_lo,
+                                                           uint32_t seed_hi, uint32_t draw_lo, uint32_t draw_hi)
+{
+    const int Q = (H + 3) / 4;
+    const int64_t total = N * Q;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int64_t v = i / Q;
+        const int q = (int)(i % Q);
+        const PhiloxWords w = philox_4x32_10((uint32_t)v, (uint32_t)q, draw_lo, draw_hi, seed_lo, seed_hi);
+        float* p = A + v * ld + 4 * q;
+        if (4 * q + 3 < H) {
+            // rows of the workspace start on 128-byte lines
+            f32x4 x = *reinterpret_cast<const f32x4*>(p);
+            x.x = w.w0 >= threshold ? x.x * scale : 0.0f;
+            x.y = w.w1 >= threshold ? x.y * scale : 0.0f;
+            x.z = w.w2 >= threshold ? x.z * scale : 0.0f;
+            x.w = w.w3 >= threshold ? x.w * scale : 0.0f;
+            *reinterpret_cast<f32x4*>(p) = x;
+        } else {
+            const uint32_t ws[4] = {w.w0, w.w1, w.w2, w.w3};
+            for (int k = 0; k < 4 && 4 * q + k < H; ++k) p[k] = ws[k] >= threshold ? p[k] * scale : 0.0f;
+        }
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void sgd_kernel(int64_t n, float* __restrict__ p, const float* __restrict__ g,
@@ -608,14 +673,18 @@ extern "C" int64_t retexo_train_workspace_bytes(int64_t N, int64_t D_in, int64_t
     return make_layout(N, D_in, H, C).total;
 }
 
-extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C,
-                                   const float* d_X, int64_t ldx, const int32_t* d_labels,
-                                   const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
-                                   float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
-                                   float* d_gX, int64_t ldgx,
-                                   void* d_workspace, int64_t workspace_bytes, void* stream_)
+namespace {
+int layer_grad_impl(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                    const float* d_X, int64_t ldx, const int32_t* d_labels,
+                    const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                    float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                    float* d_gX, int64_t ldgx, float p_drop, uint64_t seed, uint64_t draw,
+                    void* d_workspace, int64_t workspace_bytes, void* stream_)
 {
     if (int s = check_sizes(N, D_in, H, C)) return s;
+    if (!(p_drop >= 0.0f && p_drop < 1.0f)) return RETEXO_E_SIZE;
+    if (p_drop > 0.0f && H == 0) return RETEXO_E_SIZE;        // there is no hidden unit to drop
+    const float keep_scale = p_drop > 0.0f ? 1.0f / (1.0f - p_drop) : 1.0f;
     if (ldx < D_in) return RETEXO_E_LD;
     if (d_gX && ldgx < D_in) return RETEXO_E_LD;
     if (d_gX && N > 0 && d_X &&
@@ -661,6 +730,14 @@ extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C
     int64_t ldfeat = ldx, dfeat = D_in;
     if (H > 0) {
         if (int e = launch_transform(N, D_in, H, d_X, ldx, d_W1, d_b1, true, A, t.ldh, stream)) return e;
+        if (p_drop > 0.0f) {
+            const uint32_t threshold = (uint32_t)((double)p_drop * 4294967296.0);
+            const int64_t quads = N * ((H + 3) / 4);
+            const int64_t blocks = (quads + kThreads - 1) / kThreads;
+            dropout_kernel<<<dim3((unsigned)(blocks < (1 << 20) ? blocks : (1 << 20))), dim3(kThreads), 0, stream>>>(
+                N, (int)H, A, t.ldh, threshold, keep_scale, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)draw,
+                (uint32_t)(draw >> 32));
+        }
         feat = A; ldfeat = t.ldh; dfeat = H;
     }
     if (int e = launch_transform(N, dfeat, C, feat, ldfeat, H > 0 ? d_Wc : d_W1, H > 0 ? d_bc : d_b1, false,
@@ -679,12 +756,13 @@ extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C
     colsum(N, C, L, t.ldc, colpart, gb_top, stream);
 
     if (H > 0) {
-        // back through the classifier and the ReLU, then the layer's own gradients
+        // back through the classifier, the dropout (its scale rides on the transposed classifier, its mask is
+        // part of "A > 0") and the ReLU, then the layer's own gradients
         // (the contraction runs over the padded width of dL: its padding columns and the padding rows
         // of the transposed classifier are zero, and a multiple of four keeps the loads 16 bytes wide)
         const int64_t tot = H * t.ldc;
         transpose_kernel<<<dim3((unsigned)((tot + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            (int)H, (int)C, (int)t.ldc, d_Wc, WcT);
+            (int)H, (int)C, (int)t.ldc, d_Wc, WcT, keep_scale);
         if (int e = launch_transform(N, t.ldc, H, L, t.ldc, WcT, nullptr, false, dA, t.ldh, stream, A, t.ldh)) return e;
         // (padding columns of dA only produce partial columns that reduce_partials never reads)
         wgrad(N, D_in, t.ldh, H, d_X, ldx, dA, t.ldh, part, d_gW1, stream);
@@ -693,18 +771,41 @@ extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C
             // dL/dX = dA W1^T, contracted over exactly H columns (dA's padding columns are not written)
             const int64_t tot1 = H * D_in;
             transpose_kernel<<<dim3((unsigned)((tot1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-                (int)D_in, (int)H, (int)H, d_W1, W1T);
+                (int)D_in, (int)H, (int)H, d_W1, W1T, 1.0f);
             if (int e = launch_transform(N, H, D_in, dA, t.ldh, W1T, nullptr, false, d_gX, ldgx, stream)) return e;
         }
     } else if (d_gX) {
         // dL/dX = dL W1^T over the padded width of dL (its padding columns and the padding rows of W1^T are zero)
         const int64_t tot1 = t.ldc * D_in;
         transpose_kernel<<<dim3((unsigned)((tot1 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            (int)D_in, (int)C, (int)t.ldc, d_W1, W1T);
+            (int)D_in, (int)C, (int)t.ldc, d_W1, W1T, 1.0f);
         if (int e = launch_transform(N, t.ldc, D_in, L, t.ldc, W1T, nullptr, false, d_gX, ldgx, stream)) return e;
     }
     if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
     return RETEXO_OK;
+}
+}  // namespace
+
+extern "C" int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                                   const float* d_X, int64_t ldx, const int32_t* d_labels,
+                                   const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                                   float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                                   float* d_gX, int64_t ldgx,
+                                   void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    return layer_grad_impl(N, D_in, H, C, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc, d_gW1, d_gb1, d_gWc, d_gbc,
+                           d_loss, d_gX, ldgx, 0.0f, 0, 0, d_workspace, workspace_bytes, stream);
+}
+
+extern "C" int retexo_layer_grad_dropout(int64_t N, int64_t D_in, int64_t H, int64_t C,
+                                         const float* d_X, int64_t ldx, const int32_t* d_labels,
+                                         const float* d_W1, const float* d_b1, const float* d_Wc, const float* d_bc,
+                                         float* d_gW1, float* d_gb1, float* d_gWc, float* d_gbc, float* d_loss,
+                                         float* d_gX, int64_t ldgx, float p_drop, uint64_t seed, uint64_t draw,
+                                         void* d_workspace, int64_t workspace_bytes, void* stream)
+{
+    return layer_grad_impl(N, D_in, H, C, d_X, ldx, d_labels, d_W1, d_b1, d_Wc, d_bc, d_gW1, d_gb1, d_gWc, d_gbc,
+                           d_loss, d_gX, ldgx, p_drop, seed, draw, d_workspace, workspace_bytes, stream);
 }
 
 extern "C" int retexo_layer_grad(int64_t N, int64_t D_in, int64_t H, int64_t C,

@@ -279,9 +279,10 @@ def transform_backward(H: torch.Tensor, d_in: int, dZ: torch.Tensor, d_out: int,
 
 
 def layer_grad(X: torch.Tensor, d_in: int, labels: torch.Tensor, W1, b1, Wc=None, bc=None,
-               workspace: Optional[torch.Tensor] = None, gX: Optional[torch.Tensor] = None):
+               workspace: Optional[torch.Tensor] = None, gX: Optional[torch.Tensor] = None, dropout=None):
     """Loss and gradients of one locally trained layer -> (loss [1], gW1, gb1, gWc, gbc) device tensors;
-    with ``gX`` given, dL/dX is written into it as well."""
+    with ``gX`` given, dL/dX is written into it as well.  ``dropout`` = (p_drop, seed, draw) trains with
+    dropout on the hidden units."""
     n = int(labels.numel())
     h = 0 if Wc is None else int(W1.shape[1])
     c = int(W1.shape[1]) if Wc is None else int(Wc.shape[1])
@@ -295,7 +296,13 @@ def layer_grad(X: torch.Tensor, d_in: int, labels: torch.Tensor, W1, b1, Wc=None
     gbc = torch.empty_like(bc) if Wc is not None else None
     loss = torch.empty(1, dtype=torch.float32, device="cuda")
     p = lambda t: t.data_ptr() if t is not None else 0
-    if gX is None:
+    if dropout is not None:
+        p_drop, seed, draw = dropout
+        st = B.retexo_layer_grad_dropout(n, d_in, h, c, X.data_ptr(), X.stride(0), labels.data_ptr(), p(W1), p(b1),
+                                         p(Wc), p(bc), p(gW1), p(gb1), p(gWc), p(gbc), loss.data_ptr(), p(gX),
+                                         gX.stride(0) if gX is not None else 0, float(p_drop), int(seed), int(draw),
+                                         workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    elif gX is None:
         st = B.retexo_layer_grad(n, d_in, h, c, X.data_ptr(), X.stride(0), labels.data_ptr(), p(W1), p(b1), p(Wc),
                                  p(bc), p(gW1), p(gb1), p(gWc), p(gbc), loss.data_ptr(), workspace.data_ptr(),
                                  workspace.numel(), _stream_ptr())

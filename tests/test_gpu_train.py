@@ -94,6 +94,83 @@ def test_sgd_update_and_a_few_steps_lower_the_loss():
     assert all(b < a for a, b in zip(losses, losses[1:])), losses
 
 
+def run_gpu_dropout(X, d_in, y, W1, b1, Wc, bc, dropout, input_grad=False):
+    d = lambda a: None if a is None else Hn.dev(a)
+    gX = torch.full((y.size, d_in + 5), -3.0, dtype=torch.float32, device="cuda") if input_grad else None
+    out = Hn.layer_grad(d(X), d_in, d(y), d(W1), d(b1), d(Wc), d(bc), gX=gX, dropout=dropout)
+    torch.cuda.synchronize()
+    res = [None if t is None else t.cpu().numpy() for t in out]
+    return res + [gX.cpu().numpy()] if input_grad else res
+
+
+@pytest.mark.parametrize("n,d_in,h,c,ld,p_drop", [
+    (1000, 37, 5, 3, 37, 0.5),           # nothing aligned, one partial block of units per node
+    (4099, 128, 64, 8, 128, 0.3),
+    (2708, 2866, 64, 7, 2880, 0.3),      # tiny-SAGE hidden layer
+    (5000, 512, 256, 41, 512, 0.5),      # large-SAGE widths, the paper's two dropout rates
+    (130, 16, 301, 5, 16, 0.9),          # hidden width above one column tile, not a multiple of four
+])
+def test_layer_grad_with_dropout_matches_oracle(n, d_in, h, c, ld, p_drop):
+    # the mask is drawn on both sides from (seed, draw, node, unit): one wrong bit in it moves a whole
+    # hidden unit of a node and shows as an error of order one
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, seed=n + h + 1, ld=ld)
+    drop = (p_drop, (0xABCD << 32) | 0x1234, (7 << 32) | 99)
+    got = run_gpu_dropout(X, d_in, y, W1, b1, Wc, bc, drop, input_grad=True)
+    want = oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, input_grad=True, dropout=drop)
+    compare(got[:5], want[:5], "dropout %.1f, %d x %d -> %d -> %d" % (p_drop, n, d_in, h, c))
+    assert np.all(got[5][:, d_in:] == -3.0)
+    # dL/dX of a node is a sum over its surviving units of (sum over classes of dL_c Wc_jc) W1_kj; with few
+    # survivors the inner sum can cancel to almost nothing, so the error is measured against the size of
+    # the terms (fp32 can promise no more), row by row
+    keep = oracle.dropout_keep(n, h, p_drop, drop[1], drop[2]).astype(np.float64)
+    sc = 1.0 / (1.0 - float(np.float32(p_drop)))
+    Xd = X[:, :d_in].astype(np.float64)
+    pre = Xd @ W1 + b1
+    Z = (np.maximum(pre, 0) * keep * sc) @ Wc + bc
+    Z = Z - Z.max(1, keepdims=True)
+    P = np.exp(Z) / np.exp(Z).sum(1, keepdims=True)
+    lab = y >= 0
+    P[lab, y[lab]] -= 1.0
+    dZ = P * lab[:, None] / lab.sum()
+    terms = ((np.abs(dZ) @ np.abs(Wc.astype(np.float64)).T) * keep * sc * (pre > 0)) @ np.abs(W1.astype(np.float64)).T
+    err = np.abs(got[5][:, :d_in] - want[5]).max(1)
+    size = terms.max(1)
+    assert np.all(err[size == 0] == 0)
+    assert (err[size > 0] / size[size > 0]).max() <= 1e-5
+    # ... and against the values themselves wherever the inner sums do not cancel badly
+    well = np.abs(want[5]).max(1) > 0.05 * size
+    assert_close(got[5][well, :d_in], want[5][well], what="dropout gX")
+
+
+def test_dropout_draws_and_special_cases():
+    n, d_in, h, c = 1500, 40, 48, 6
+    X, y, W1, b1, Wc, bc = problem(n, d_in, h, c, 12)
+    plain = run_gpu(X, d_in, y, W1, b1, Wc, bc)
+    # p = 0: the plain step, bit for bit
+    zero = run_gpu_dropout(X, d_in, y, W1, b1, Wc, bc, (0.0, 5, 6))
+    assert all(np.array_equal(a, b) for a, b in zip(plain, zero))
+    # same (seed, draw): same result; another draw or another seed: another mask
+    a = run_gpu_dropout(X, d_in, y, W1, b1, Wc, bc, (0.3, 5, 6))
+    b = run_gpu_dropout(X, d_in, y, W1, b1, Wc, bc, (0.3, 5, 6))
+    assert all(np.array_equal(p, q) for p, q in zip(a, b))
+    for other in [(0.3, 5, 7), (0.3, 6, 6), (0.3, 5, 6 + (1 << 32)), (0.3, 5 + (1 << 32), 6)]:
+        o = run_gpu_dropout(X, d_in, y, W1, b1, Wc, bc, other)
+        assert not np.array_equal(o[1], a[1])
+        compare(o, oracle.layer_grad(X, d_in, y, W1, b1, Wc, bc, dropout=other), "draw %r" % (other,))
+    # errors: p outside [0, 1), not a number, or the last layer (no hidden units)
+    ws = Hn.ws_tensor(B.retexo_train_workspace_bytes(n, d_in, h, c))
+    t = torch.full((4096,), -9.0, dtype=torch.float32, device="cuda")
+    dX, dy = Hn.dev(X), Hn.dev(y)
+    q = t.data_ptr()
+    call = lambda p_drop, hh=h: B.retexo_layer_grad_dropout(n, d_in, hh, c, dX.data_ptr(), dX.stride(0), dy.data_ptr(),
+                                                            q, q, q, q, q, q, q, q, q, 0, 0, p_drop, 1, 2,
+                                                            ws.data_ptr(), ws.numel())
+    assert call(1.0) == B.E_SIZE and call(-0.1) == B.E_SIZE and call(float("nan")) == B.E_SIZE
+    assert call(0.5, hh=0) == B.E_SIZE
+    torch.cuda.synchronize()
+    assert bool((t == -9.0).all())
+
+
 def test_argument_errors():
     ws = Hn.ws_tensor(1 << 20)
     t = torch.zeros(64, dtype=torch.float32, device="cuda")
