@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant aggregation measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "sage_large_powerlaw": 108157337163,     # profiles/bench_sage_large_powerlaw.md
+    "sage_large_powerlaw": 108037992371,     # profiles/bench_sage_large_powerlaw.md
     "gat_products_powerlaw": 134369875291,   # profiles/bench_gat_products_powerlaw.md
 }
 
