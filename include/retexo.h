@@ -436,7 +436,9 @@ double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, d
  *       "agg_max_vec" (cap on floats per lane per gather),
  *       "agg_gat_fast" (0: plain edge-softmax kernel), "agg_gat_flash" (0: ordinary rows read the
  *       source scores from the table instead of computing them from the gathered rows),
- *       "agg_wide_offsets" (1: 64-bit row offsets even for tables below 4 GiB; these three exist
+ *       "agg_gat_in_rows" (0: retexo_round keeps the source scores in the table even when the unused
+ *       columns of its own Z rows could hold them),
+ *       "agg_wide_offsets" (1: 64-bit row offsets even for tables below 4 GiB; these four exist
  *       so that tests reach every code path).
  * Returns RETEXO_E_FLAGS for an unknown name.
  */

@@ -46,7 +46,8 @@ struct AggArgs {
     float* out;
     int64_t ldo;
     int64_t ocol;          // first output column of the aggregate
-    const float* el;       // [N, HP]  <a_src, z_u>   (edge softmax only)
+    const float* el;       // <a_src, z_u> of node u, head h at el[u * el_stride + h]   (edge softmax only)
+    int64_t el_stride;     // HP for the table in the workspace; ldz when the scores sit in Z's padding columns
     const float* er;       // [N, HP]  <a_dst, z_v>
     int64_t row_begin;     // range of plan order handled by this launch
     int64_t row_count;
@@ -529,9 +530,9 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
 // ---------------------------------------------------------------------------
 template <int HP>
 __global__ __launch_bounds__(256) void gat_scores_kernel(
-    int64_t N, int64_t F, int heads, int Dh, const float* __restrict__ Z, int64_t ldz,
+    int64_t N, int64_t F, int heads, int Dh, const float* Z, int64_t ldz,
     const float* __restrict__ a_src, const float* __restrict__ a_dst,
-    float* __restrict__ el, float* __restrict__ er)
+    float* el, int64_t el_stride, float* __restrict__ er)
 {
     const int lane = threadIdx.x & 63;
     const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -552,7 +553,7 @@ __global__ __launch_bounds__(256) void gat_scores_kernel(
 #pragma unroll
     for (int h = 0; h < HP; ++h) {
         const float s = wave_sum(ps[h]), t = wave_sum(pd[h]);
-        if (lane == 0) { el[v * HP + h] = s; er[v * HP + h] = t; }
+        if (lane == 0) { el[v * el_stride + h] = s; er[v * HP + h] = t; }
     }
 }
 
@@ -561,9 +562,9 @@ __global__ __launch_bounds__(256) void gat_scores_kernel(
 // Needs 16-byte aligned rows and F % 4 == 0.
 template <int HP>
 __global__ __launch_bounds__(256) void gat_scores_vec_kernel(
-    int64_t N, int64_t F, int heads, int Dh, const float* __restrict__ Z, int64_t ldz,
+    int64_t N, int64_t F, int heads, int Dh, const float* Z, int64_t ldz,
     const float* __restrict__ a_src, const float* __restrict__ a_dst,
-    float* __restrict__ el, float* __restrict__ er)
+    float* el, int64_t el_stride, float* __restrict__ er)
 {
     const int li = threadIdx.x & 15;
     const int64_t v = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
@@ -598,7 +599,7 @@ __global__ __launch_bounds__(256) void gat_scores_vec_kernel(
     }
     if (have && li == 0) {
 #pragma unroll
-        for (int h = 0; h < HP; ++h) { el[v * HP + h] = ps[h]; er[v * HP + h] = pd[h]; }
+        for (int h = 0; h < HP; ++h) { el[v * el_stride + h] = ps[h]; er[v * HP + h] = pd[h]; }
     }
 }
 
@@ -653,11 +654,11 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_ker
         {
             float elu[HP];
             if constexpr (HP == 4) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(a.el + (int64_t)my_u * 4);
+                const f32x4 t = *reinterpret_cast<const f32x4*>(a.el + (int64_t)my_u * a.el_stride);
                 elu[0] = t.x; elu[1] = t.y; elu[2] = t.z; elu[3] = t.w;
             } else {
 #pragma unroll
-                for (int h = 0; h < HP; ++h) elu[h] = a.el[(int64_t)my_u * HP + h];
+                for (int h = 0; h < HP; ++h) elu[h] = a.el[(int64_t)my_u * a.el_stride + h];
             }
 #pragma unroll
             for (int h = 0; h < HP; ++h) {
@@ -870,11 +871,11 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
 
         float elu[HP];
         if constexpr (HP == 4) {
-            const f32x4 t = *reinterpret_cast<const f32x4*>(a.el + (int64_t)my_u * 4);
+            const f32x4 t = *reinterpret_cast<const f32x4*>(a.el + (int64_t)my_u * a.el_stride);
             elu[0] = t.x; elu[1] = t.y; elu[2] = t.z; elu[3] = t.w;
         } else {
 #pragma unroll
-            for (int h = 0; h < HP; ++h) elu[h] = a.el[(int64_t)my_u * HP + h];
+            for (int h = 0; h < HP; ++h) elu[h] = a.el[(int64_t)my_u * a.el_stride + h];
         }
         float scale[HP];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of wl are done
@@ -1397,22 +1398,24 @@ int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads, int64_t F, boo
 }
 
 void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
-                       const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream)
+                       const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream,
+                       int64_t el_stride)
 {
     const int Dh = (int)(F / heads);
+    if (el_stride == 0) el_stride = heads_padded(heads);
     if (F % 4 == 0 && aligned_for(Z, ldz, 4) && aligned_for(a_src, 4, 4) && aligned_for(a_dst, 4, 4) && agg_options().max_vec >= 4) {
         const unsigned gv = (unsigned)((N + 15) / 16);
         if (heads_padded(heads) == 4)
-            gat_scores_vec_kernel<4><<<dim3(gv), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, er);
+            gat_scores_vec_kernel<4><<<dim3(gv), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, el_stride, er);
         else
-            gat_scores_vec_kernel<8><<<dim3(gv), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, er);
+            gat_scores_vec_kernel<8><<<dim3(gv), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, el_stride, er);
         return;
     }
     const unsigned gb = (unsigned)((N + 3) / 4);
     if (heads_padded(heads) == 4)
-        gat_scores_kernel<4><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, er);
+        gat_scores_kernel<4><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, el_stride, er);
     else
-        gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, er);
+        gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, el_stride, er);
 }
 
 int launch_aggregate(const AggCall& c, hipStream_t stream)
@@ -1450,6 +1453,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.ldo = c.ldo;
     a.ocol = c.self_concat ? c.F : 0;
     a.el = nullptr;
+    a.el_stride = 0;
     a.er = nullptr;
     a.row_begin = 0;
     a.row_count = 0;
@@ -1526,11 +1530,23 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         const int hp = heads_padded(c.heads);
         float* el = (float*)c.workspace;
         float* er = (float*)((char*)c.workspace + gat_workspace(N, c.F, c.heads, false).er);
-        a.el = el;
-        a.er = er;
-        launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream);
         const bool hu = (a.Dh % vec) == 0;
         const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
+        const int g = a.Dh / 4;
+        // rows of ordinary length compute the source scores from the gathered rows themselves when a head is
+        // a power-of-two group of four-float lanes; the long rows keep the table of scores
+        const bool flash = vec == 4 && off32 && opt.gat_fast && opt.gat_flash && c.F <= 256 &&
+                           a.Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 && aligned_for(c.attn_src, 4, 4);
+        // Otherwise, when Z is the library's own buffer and its rows have unused columns behind F, the source
+        // scores of a node are kept there: the gather of a row then brings them along in the row's last cache
+        // line, instead of one more line per entry from a table elsewhere.
+        const bool in_rows = c.z_padding_free && !flash && vec == 4 && off32 && opt.gat_fast && opt.gat_in_rows &&
+                             c.F % 4 == 0 && c.ldz - c.F >= hp && c.F % 32 != 0 && (c.F % 32) + hp <= 32;
+        a.el_stride = in_rows ? c.ldz : hp;
+        if (in_rows) el = const_cast<float*>(c.Z) + c.F;
+        a.el = el;
+        a.er = er;
+        launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream, a.el_stride);
         if (c.save) {
             // only the pipelined kernel keeps the backward's statistics
             if (!(vec == 4 && off32 && opt.gat_fast)) return RETEXO_E_FLAGS;
@@ -1540,11 +1556,6 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             a.save_neg = (float*)((char*)c.workspace + w.neg);
             a.ld_pos = w.ld_pos;
         }
-        // rows of ordinary length compute the source scores from the gathered rows themselves when a head is
-        // a power-of-two group of four-float lanes; the long rows keep the table of scores
-        const int g = a.Dh / 4;
-        const bool flash = vec == 4 && off32 && opt.gat_fast && opt.gat_flash && c.F <= 256 &&
-                           a.Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 && aligned_for(c.attn_src, 4, 4);
         int64_t n_table = N;          // rows [0, n_table) of the schedule go through the table kernels
         if (flash && N > n_heavy) {
             AggArgs f = a;

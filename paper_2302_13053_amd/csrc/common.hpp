@@ -49,6 +49,7 @@ struct AggOptions {
     int64_t max_vec = 4;        // cap on floats per lane per gather (experiments)
     int64_t gat_fast = 1;       // pipelined edge-softmax kernel (0: the plain one)
     int64_t gat_flash = 1;      // ordinary rows: source scores from the gathered rows (0: from the table)
+    int64_t gat_in_rows = 1;    // retexo_round: source scores in the unused columns of its own Z rows (0: table)
     int64_t wide_offsets = 0;   // 1: use the 64-bit row-offset code paths even when 32 bits would do (tests)
     int64_t narrow_heavy = 512;  // narrow slabs: rows whose share of one source range is at least this long get a workgroup
     int64_t parts = -1;         // source-id ranges per aggregation: -1 auto, 1 = off, 2/4/8/16
@@ -80,6 +81,7 @@ struct AggCall {
     int64_t ldo;
     void* workspace;
     bool save = false;    // edge softmax: keep the backward's statistics in the workspace
+    bool z_padding_free = false;   // Z is the library's own buffer: columns [F, ldz) of its rows may be written
 };
 int launch_aggregate(const AggCall& c, hipStream_t stream);
 // edge-softmax workspace: scores, then (save) the row statistics and the aggregate split by the sign of the score
@@ -87,8 +89,10 @@ struct GatWorkspace { int64_t el, er, stats, pos, neg, total, ld_pos; };
 GatWorkspace gat_workspace(int64_t N, int64_t F, int heads, bool save);
 int64_t aggregate_workspace_bytes(int64_t N, int mode, int heads, int64_t F = 0, bool save = false);
 // el[v,h] = <a_src[h], z_v,h>, er[v,h] = <a_dst[h], z_v,h>, both [N, heads_padded(heads)]
+// (el_stride: floats between the el entries of consecutive nodes; 0 = heads_padded(heads), the dense table)
 void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t ldz,
-                       const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream);
+                       const float* a_src, const float* a_dst, float* el, float* er, hipStream_t stream,
+                       int64_t el_stride = 0);
 
 // Aggregation over a table in 16-bit storage (see retexo_aggregate_stored)
 struct StoredCall {

@@ -83,6 +83,7 @@ extern "C" int retexo_set_option(const char* name, int64_t value)
     if (!strcmp(name, "agg_parts")) { o.parts = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_fast")) { o.gat_fast = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_flash")) { o.gat_flash = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_gat_in_rows")) { o.gat_in_rows = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_wide_offsets")) { o.wide_offsets = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_narrow_heavy")) { o.narrow_heavy = value; return RETEXO_OK; }
     return RETEXO_E_FLAGS;
@@ -404,6 +405,7 @@ extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int
                                      Zws, ldz_ws, s))
             return e;
         c.Z = Zws; c.ldz = ldz_ws; c.copy_self = false;
+        c.z_padding_free = true;
     }
     return launch_aggregate(c, s);
 }

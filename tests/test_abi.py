@@ -84,6 +84,6 @@ def test_options():
     assert B.retexo_set_option("agg_slab_major", -1) == B.OK
     assert B.retexo_set_option("agg_heavy_degree", 2048) == B.OK
     for name, default in (("agg_parts", -1), ("agg_max_vec", 4), ("agg_gat_fast", 1), ("agg_gat_flash", 1),
-                          ("agg_wide_offsets", 0)):
+                          ("agg_gat_in_rows", 1), ("agg_wide_offsets", 0)):
         assert B.retexo_set_option(name, default) == B.OK
     assert B.retexo_set_option("no_such_option", 1) == B.E_FLAGS

@@ -77,6 +77,39 @@ def test_round_separately_equals_fused_and_gcn_gat_modes():
         g.destroy()
 
 
+@pytest.mark.parametrize("n,heads,dh,seed", [(5000, 4, 47, 1), (3000, 8, 27, 2), (2000, 2, 30, 3), (1500, 4, 7, 4)])
+def test_attention_round_with_the_source_scores_kept_in_the_rows_of_z(n, heads, dh, seed):
+    # head widths that are not a power-of-two number of four-float lanes: retexo_round keeps <a_src, z_u> in
+    # the unused columns of its own Z rows.  Same bits as with the score table, and parity with the oracle.
+    F = heads * dh
+    assert F % 4 == 0 and F % 32 != 0
+    src, dst = wl.graph_power_law(n, 12 * n, 2.2, 24.0, 3000.0, seed)
+    g = Hn.make_plan(Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False))
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    H = wl.random_matrix(n, 60, seed + 10, ld=64)
+    W = wl.glorot(np.random.Generator(np.random.Philox(key=seed + 20)), 60, F, (60, F))
+    b = wl.random_matrix(1, F, seed + 30)[0] * np.float32(0.1)
+    a_s = wl.random_matrix(heads, dh, seed + 40) * np.float32(0.3)
+    a_d = wl.random_matrix(heads, dh, seed + 50) * np.float32(0.3)
+    st = wl.Stage("round", 60, F, relu=False, mode="gat_softmax", concat=False, heads=heads)
+    ws = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, F, B.GAT_SOFTMAX, heads, 0))
+    outs = []
+    try:
+        for in_rows in (1, 0):
+            B.retexo_set_option("agg_gat_in_rows", in_rows)
+            out = torch.full((n, wl.pad_ld(F)), -5.0, dtype=torch.float32, device="cuda")
+            Hn.round_(g, st, Hn.dev(H), Hn.dev(W), Hn.dev(b), Hn.dev(a_s), Hn.dev(a_d), out, ws)
+            torch.cuda.synchronize()
+            outs.append(out)
+    finally:
+        B.retexo_set_option("agg_gat_in_rows", 1)
+    assert torch.equal(outs[0], outs[1])
+    assert bool((outs[0][:, F:] == -5.0).all())
+    want = oracle.round_("gat_softmax", rp, ci, H, 60, W, b, relu=False, heads=heads, a_src=a_s, a_dst=a_d)
+    assert_close(outs[0].cpu().numpy()[:, :F], want, what="attention round, scores in the rows")
+    g.destroy()
+
+
 def test_round_argument_errors_leave_the_output_untouched():
     n, d_in, d_out = 300, 40, 64
     src, dst = wl.random_pairs(n, 2000, 31)
