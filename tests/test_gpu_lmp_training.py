@@ -96,7 +96,46 @@ def test_two_layer_lazy_message_passing_trains_and_matches_the_oracle_loop():
     g.destroy()
 
 
-def train_layer(X, d_in, dy, params, steps, lr):
+def test_layer_training_with_dropout_follows_the_oracle_loop():
+    """Layer 1 trained with dropout 0.3 on its hidden units, a fresh mask per step (draw = step number):
+    both loops draw the same masks, so the losses agree step by step; the frozen layer is then evaluated
+    without dropout."""
+    n, C, F0, Hd, steps, lr, p_drop, seed = 5000, 4, 32, 48, 30, 0.5, 0.3, 2302
+    src, dst, cls, X0, train = planted_graph(n, C, 25000, F0, 6)
+    y = np.where(train, cls, -1).astype(np.int32)
+    rng = np.random.Generator(np.random.Philox(key=78))
+    W1, b1 = wl.glorot(rng, 2 * F0, Hd, (2 * F0, Hd)), np.zeros(Hd, np.float32)
+    Wc, bc = wl.glorot(rng, Hd, C, (Hd, C)), np.zeros(C, np.float32)
+
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    oX1 = oracle.aggregate("mean", rp, ci, X0, F0, self_concat=True).astype(np.float32)
+    oP = [W1.copy(), b1.copy(), Wc.copy(), bc.copy()]
+    o_losses = []
+    for step in range(steps):
+        loss, *grads = oracle.layer_grad(oX1, 2 * F0, y, *oP, dropout=(p_drop, seed, step))
+        o_losses.append(loss)
+        for p_, g_ in zip(oP, grads):
+            p_ -= (lr * g_).astype(np.float32)
+    o_eval = oracle.layer_grad(oX1, 2 * F0, y, *oP)[0]
+
+    d = Hn.dev
+    g = Hn.make_plan(Hn.csr_from_coo(d(src), d(dst), n, False))
+    dy = d(y)
+    X1 = Hn.aggregate(g, "mean", d(X0), F0, concat=True)
+    P = [d(W1), d(b1), d(Wc), d(bc)]
+    losses = train_layer(X1, 2 * F0, dy, P, steps, lr, dropout=lambda step: (p_drop, seed, step))
+    eval_loss = float(Hn.layer_grad(X1, 2 * F0, dy, *P)[0].cpu()[0])
+    assert np.allclose(losses, o_losses, rtol=2e-4), (losses[-3:], o_losses[-3:])
+    assert abs(eval_loss - o_eval) <= 2e-4 * o_eval
+    assert eval_loss < 0.8 * losses[0]
+    # the same stream of masks again gives the same parameters, bit for bit
+    P2 = [d(W1), d(b1), d(Wc), d(bc)]
+    train_layer(X1, 2 * F0, dy, P2, steps, lr, dropout=lambda step: (p_drop, seed, step))
+    assert all(torch.equal(a, b) for a, b in zip(P, P2))
+    g.destroy()
+
+
+def train_layer(X, d_in, dy, params, steps, lr, dropout=None):
     """Full-batch SGD on one layer with the aggregated inputs fixed; -> loss per step."""
     n = int(dy.numel())
     hidden = len(params) == 4
@@ -104,8 +143,9 @@ def train_layer(X, d_in, dy, params, steps, lr):
     c = int(params[2].shape[1]) if hidden else int(params[0].shape[1])
     ws = Hn.ws_tensor(B.retexo_train_workspace_bytes(n, d_in, h, c))
     out = []
-    for _ in range(steps):
-        loss, *grads = Hn.layer_grad(X, d_in, dy, *params, workspace=ws)
+    for step in range(steps):
+        loss, *grads = Hn.layer_grad(X, d_in, dy, *params, workspace=ws,
+                                     dropout=dropout(step) if dropout else None)
         for p_, g_ in zip(params, grads):
             B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), lr, Hn._stream_ptr()), "sgd")
         out.append(float(loss.cpu()[0]))
