@@ -311,7 +311,8 @@ int retexo_layer_grad_x(int64_t N, int64_t D_in, int64_t H, int64_t C,
  * is dropped when word j % 4 of the Philox-4x32-10 block with
  *     counter = (v, j / 4, low 32 bits of draw, high 32 bits of draw),  key = (low, high 32 bits of seed)
  * is below floor(p_drop * 2^32), so a caller that needs the mask (or the other workers' masks) can draw
- * it again.  `seed` names the stream, `draw` the training step; calls with the same pair use the same mask.
+ * it again.  `seed` names the stream, `draw` the training step; calls with the same pair use the same mask
+ * (both travel by value: a HIP graph that recorded this call replays the mask it recorded).
  *   p_drop in [0, 1); 0 is exactly retexo_layer_grad_x.  RETEXO_E_SIZE if p_drop is outside that range
  *   (or not a number), or positive with H == 0 (the last layer has no hidden units).
  *   d_gX may be NULL.  Same workspace and behaviour as retexo_layer_grad otherwise. */
