@@ -187,3 +187,20 @@ def test_csr_with_exactly_sized_columns_gives_the_same_arrays(self_loops):
     assert bool((ci[nnz:] == -7).all())
     big = Hn.csr_from_coo(d_src, d_dst, n, self_loops)            # roomy column array: the one-pass path
     assert np.array_equal(big.row_ptr.cpu().numpy(), rp_o) and np.array_equal(big.col_idx.cpu().numpy()[:nnz], ci_o)
+
+
+@pytest.mark.parametrize("n", [37, 1000, 70000])
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_csr_of_heavily_repeated_and_clustered_pairs(n, self_loops):
+    # neighbours within a window of 16 ids, one pair given thousands of times in both orders, one self
+    # pair given thousands of times: the clean-up (repeats, self pairs, both directions) is all there is
+    rng = np.random.Generator(np.random.Philox(key=n))
+    m = 20 * n
+    a = rng.integers(0, n, m)
+    b = (a + rng.integers(-8, 9, m)) % n
+    rep = np.full(3000, n // 3), np.full(3000, (n // 3 + 5) % n)
+    selfs = np.full(2000, n // 2)
+    src = np.concatenate([a, rep[0], rep[1], selfs, rng.integers(0, n, m // 4)]).astype(np.int32)
+    dst = np.concatenate([b, rep[1], rep[0], selfs, rng.integers(0, n, m // 4)]).astype(np.int32)
+    perm = rng.permutation(src.size)
+    check_against_oracle(src[perm], dst[perm], n, self_loops)
