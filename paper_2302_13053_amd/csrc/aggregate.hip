@@ -573,19 +573,44 @@ __global__ __launch_bounds__(256) void gat_scores_vec_kernel(
     float ps[HP], pd[HP];
 #pragma unroll
     for (int h = 0; h < HP; ++h) { ps[h] = 0.0f; pd[h] = 0.0f; }
-    for (int64_t c = li * 4; c < F; c += 64) {
-        const f32x4 z = *reinterpret_cast<const f32x4*>(Z + vv * ldz + c);
-        const f32x4 as = *reinterpret_cast<const f32x4*>(a_src + c);
-        const f32x4 ad = *reinterpret_cast<const f32x4*>(a_dst + c);
-        const float zs[4] = {z.x, z.y, z.z, z.w}, sa[4] = {as.x, as.y, as.z, as.w}, da[4] = {ad.x, ad.y, ad.z, ad.w};
+    const bool whole = Dh % 4 == 0;
+    // four row pieces are requested before the first is used (a row of up to 256 columns is one batch)
+    for (int64_t c0 = li * 4; c0 < F; c0 += 256) {
+        f32x4 zq[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int h = (int)((c + k) / Dh);
-            const float s = zs[k] * sa[k], t = zs[k] * da[k];
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = c0 + 64 * q;
+            zq[q] = c < F ? *reinterpret_cast<const f32x4*>(Z + vv * ldz + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll
-            for (int i = 0; i < HP; ++i) {
-                ps[i] += (h == i) ? s : 0.0f;
-                pd[i] += (h == i) ? t : 0.0f;
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = c0 + 64 * q;
+            if (c >= F) break;
+            const f32x4 z = zq[q];
+            const f32x4 as = *reinterpret_cast<const f32x4*>(a_src + c);
+            const f32x4 ad = *reinterpret_cast<const f32x4*>(a_dst + c);
+            const float zs[4] = {z.x, z.y, z.z, z.w}, sa[4] = {as.x, as.y, as.z, as.w}, da[4] = {ad.x, ad.y, ad.z, ad.w};
+            if (whole) {
+                // the four columns lie in one head: one head index and one add per head for the piece
+                const int h = (int)c / Dh;
+                const float s = ((zs[0] * sa[0] + zs[1] * sa[1]) + zs[2] * sa[2]) + zs[3] * sa[3];
+                const float t = ((zs[0] * da[0] + zs[1] * da[1]) + zs[2] * da[2]) + zs[3] * da[3];
+#pragma unroll
+                for (int i = 0; i < HP; ++i) {
+                    ps[i] += (h == i) ? s : 0.0f;
+                    pd[i] += (h == i) ? t : 0.0f;
+                }
+                continue;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int h = ((int)c + k) / Dh;
+                const float s = zs[k] * sa[k], t = zs[k] * da[k];
+#pragma unroll
+                for (int i = 0; i < HP; ++i) {
+                    ps[i] += (h == i) ? s : 0.0f;
+                    pd[i] += (h == i) ? t : 0.0f;
+                }
             }
         }
     }
