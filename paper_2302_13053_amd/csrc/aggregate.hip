@@ -1157,23 +1157,28 @@ void dispatch_grouped(const AggArgs& a, int64_t n_heavy, int64_t N, bool weighte
 // batches of four entries (running maximum m, sum s and weighted row acc per
 // lane, all three rescaled when the maximum moves).  Scores are kept in units
 // of log2(e) (LeakyReLU commutes with a positive factor) so that every
-// exponential is one v_exp_f32.  er[v] still comes from the score kernel.
+// exponential is one v_exp_f32.  The destination's own score <a_dst, z_v> is formed
+// the same way from row v when `attn_dst` is given (the plain forward: no score
+// kernel runs at all); with attn_dst == NULL it is read from the table (save mode).
+// NW > 1: the waves of a workgroup share one long row, take interleaved 64-entry
+// tiles and merge their (m, s, acc) triples through LDS in wave order.
 // ---------------------------------------------------------------------------
 // TRAIN (save mode): the aggregate is accumulated in two parts, entries with a positive score (accp) and the
 // others (acc), with the sums of their weights (sp, sn), and the row statistics are kept for the backward
 // pass; scores then stay in natural units, because the stored row maximum is used as such.
-template <int G, bool TRAIN>
-__global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs a, const float* __restrict__ attn_src,
-                                                                         int er_stride)
+template <int G, bool TRAIN, int NW>
+__global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_flash_kernel(
+    AggArgs a, const float* __restrict__ attn_src, const float* __restrict__ attn_dst, int er_stride)
 {
+    static_assert(!(TRAIN && NW > 1), "save mode keeps the long rows on the table kernel");
     constexpr int U = 4;      // entries per batch of the online softmax (2 and 8 measure the same: the kernel waits for memory)
     constexpr float kLog2e = 1.4426950408889634f;
     constexpr float kIn = TRAIN ? 1.0f : kLog2e;       // factor on the scores as they are formed
     constexpr float kEx = TRAIN ? kLog2e : 1.0f;       // factor inside the exponentials
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t slot = (int64_t)blockIdx.x * kLightWaves + wave;
-    if (slot >= a.row_count) return;
+    const int64_t slot = NW == 1 ? (int64_t)blockIdx.x * kLightWaves + wave : (int64_t)blockIdx.x;
+    if (slot >= a.row_count) return;          // NW > 1: uniform over the workgroup
     const int v = __builtin_amdgcn_readfirstlane(a.order[a.row_begin + slot]);
     const int lo = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v]);
     const int hi = __builtin_amdgcn_readfirstlane((int)a.row_ptr[v + 1]);
@@ -1185,17 +1190,28 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs
     const int h = min((int)(col / a.Dh), a.heads - 1);
     f32x4 as = {0.0f, 0.0f, 0.0f, 0.0f};
     float erv = 0.0f;
+    const char* zbase = reinterpret_cast<const char*>(a.Z);
+    const uint32_t rowbytes = (uint32_t)(a.ldz * 4);
     if (act) {
         as = *reinterpret_cast<const f32x4*>(attn_src + col);        // [heads, Dh] is F contiguous floats
         as.x *= kIn; as.y *= kIn; as.z *= kIn; as.w *= kIn;
-        erv = a.er[(int64_t)v * er_stride + h] * kIn;
+        if (!attn_dst) erv = a.er[(int64_t)v * er_stride + h] * kIn;
     }
-    const char* zbase = reinterpret_cast<const char*>(a.Z);
-    const uint32_t rowbytes = (uint32_t)(a.ldz * 4);
+    if (attn_dst) {
+        // (uniform branch) every lane takes part in the sums; lanes past the row width add zero
+        f32x4 ad = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (act) ad = *reinterpret_cast<const f32x4*>(attn_dst + col);
+        const f32x4 zv = *reinterpret_cast<const f32x4*>(zbase + (uint32_t)v * rowbytes + colbytes);
+        float d = (ad.x * kIn) * zv.x;
+        d = fmaf(ad.y * kIn, zv.y, d);
+        d = fmaf(ad.z * kIn, zv.z, d);
+        d = fmaf(ad.w * kIn, zv.w, d);
+        erv = group_sum<G>(d);
+    }
 
     float m = -INFINITY, s = 0.0f, sp = 0.0f, sn = 0.0f;
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f}, accp = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int base = lo; base < hi; base += 64) {
+    for (int base = lo + (NW == 1 ? 0 : 64 * wave); base < hi; base += 64 * NW) {
         const int e = base + lane;
         const bool valid = e < hi;
         const int cnt = min(64, hi - base);
@@ -1273,6 +1289,36 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_gat_flash_kernel(AggArgs
                 for (int t = 0; t < U; ++t) zq[t] = zn[t];
             }
         }
+    }
+
+    if constexpr (NW > 1) {
+        // merge the waves' running triples, in wave order
+        __shared__ float red[NW][6][64];
+        red[wave][0][lane] = m;
+        red[wave][1][lane] = s;
+        red[wave][2][lane] = acc.x;
+        red[wave][3][lane] = acc.y;
+        red[wave][4][lane] = acc.z;
+        red[wave][5][lane] = acc.w;
+        __syncthreads();
+        if (wave != 0) return;
+        float mm = red[0][0][lane];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) mm = fmaxf(mm, red[w][0][lane]);
+        s = 0.0f;
+        acc = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float mw = red[w][0][lane];
+            // a wave that saw no entry has m = -inf and weighs nothing
+            const float f = mw == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((mw - mm) * kEx);
+            s = fmaf(red[w][1][lane], f, s);
+            acc.x = fmaf(red[w][2][lane], f, acc.x);
+            acc.y = fmaf(red[w][3][lane], f, acc.y);
+            acc.z = fmaf(red[w][4][lane], f, acc.z);
+            acc.w = fmaf(red[w][5][lane], f, acc.w);
+        }
+        m = mm;
     }
 
     if constexpr (TRAIN) {
@@ -1571,7 +1617,10 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         if (in_rows) el = const_cast<float*>(c.Z) + c.F;
         a.el = el;
         a.er = er;
-        launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream, a.el_stride);
+        // the plain forward over rows whose scores all come from the gathered rows needs no table
+        const bool no_table = flash && !c.save && N > n_heavy && aligned_for(c.attn_dst, 4, 4);
+        if (!no_table)
+            launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream, a.el_stride);
         if (c.save) {
             // only the pipelined kernel keeps the backward's statistics
             if (!(vec == 4 && off32 && opt.gat_fast)) return RETEXO_E_FLAGS;
@@ -1590,8 +1639,20 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
             const dim3 grid((unsigned)((f.row_count + kLightWaves - 1) / kLightWaves)), block(64 * kLightWaves);
             auto go = [&](auto gtag) {
                 constexpr int GG = decltype(gtag)::value;
-                if (c.save) agg_gat_flash_kernel<GG, true><<<grid, block, 0, stream>>>(f, c.attn_src, hp);
-                else agg_gat_flash_kernel<GG, false><<<grid, block, 0, stream>>>(f, c.attn_src, hp);
+                if (c.save) {
+                    agg_gat_flash_kernel<GG, true, 1><<<grid, block, 0, stream>>>(f, c.attn_src, nullptr, hp);
+                } else if (no_table) {
+                    agg_gat_flash_kernel<GG, false, 1><<<grid, block, 0, stream>>>(f, c.attn_src, c.attn_dst, hp);
+                    if (n_heavy > 0) {
+                        AggArgs fh = f;
+                        fh.row_begin = 0;
+                        fh.row_count = n_heavy;
+                        agg_gat_flash_kernel<GG, false, kHeavyWaves>
+                            <<<dim3((unsigned)n_heavy), dim3(64 * kHeavyWaves), 0, stream>>>(fh, c.attn_src, c.attn_dst, hp);
+                    }
+                } else {
+                    agg_gat_flash_kernel<GG, false, 1><<<grid, block, 0, stream>>>(f, c.attn_src, nullptr, hp);
+                }
             };
             switch (g) {
                 case 1:  go(std::integral_constant<int, 1>{}); break;
@@ -1602,7 +1663,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
                 case 32: go(std::integral_constant<int, 32>{}); break;
                 default: go(std::integral_constant<int, 64>{}); break;
             }
-            n_table = n_heavy;
+            n_table = no_table ? 0 : n_heavy;
         }
         if (n_table == 0) {
             // nothing left for the table kernels

@@ -367,3 +367,13 @@ def test_edge_softmax_with_scores_from_gathered_rows(graphs, F, heads, concat):
         B.retexo_set_option("agg_gat_flash", 1)
     for name in ("skewed", "flat", "tiny"):
         assert_close(results[(1, name)], results[(0, name)].astype(np.float64), what="flash vs table " + name)
+    # long rows take the same kernel with eight waves per row: lower the threshold so that many rows do
+    try:
+        B.retexo_set_option("agg_heavy_degree", 64)
+        for name in ("skewed", "flat"):
+            got, want = run_case(graphs, name, "gat_softmax", F, F, heads, concat, seed=F + heads, kind=kind)
+            assert_close(got, want, what="gat F=%d heads=%d, eight waves per row, %s" % (F, heads, name))
+            again, _ = run_case(graphs, name, "gat_softmax", F, F, heads, concat, seed=F + heads, kind=kind)
+            assert np.array_equal(got, again)
+    finally:
+        B.retexo_set_option("agg_heavy_degree", 2048)
