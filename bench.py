@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
 MEASURED_TRAFFIC_BYTES = {
     "sage_large_powerlaw": 108037992371,     # profiles/bench_sage_large_powerlaw.md
-    "gat_products_powerlaw": 134369511482,   # profiles/bench_gat_products_powerlaw.md
+    "gat_products_powerlaw": 133628689160,   # profiles/bench_gat_products_powerlaw.md
 }
 
 
@@ -230,8 +230,8 @@ def main():
     achieved = gbytes / agg_ms / 1e6
     roofline = {
         "bound": "hbm",
-        "kernel": ("gat_scores_kernel + agg_gat_fast_kernel (long rows: workgroup per row, scores from the table) + "
-                   "agg_gat_flash_kernel (all other rows: wave per row, source scores from the gathered rows)"
+        "kernel": ("agg_gat_flash_kernel (wave per row, eight waves per long row; scores formed from the gathered "
+                   "rows; other head widths: gat_scores_kernel + agg_gat_fast_kernel with a score table)"
                    if gat else
                    "aggregation call = agg_rowgroup_kernel + agg_grouped_kernel per source range (narrow slabs) "
                    "or agg_linear_kernel (whole rows), chosen by the plan"),
