@@ -529,6 +529,74 @@ __global__ __launch_bounds__(256) void stored_scores_kernel(
     }
 }
 
+// The same scores with 8-byte loads: 16 lanes per node (four nodes per wave), each lane walks the row in steps
+// of 64 columns, four stored elements at a time, all pieces of a row of up to 256 columns requested before the
+// first is used; the per-head partial sums are reduced over the 16 lanes of a node.
+// Needs 8-byte aligned rows, 16-byte aligned attention vectors and F % 4 == 0.
+template <int FMT, int HP>
+__global__ __launch_bounds__(256) void stored_scores_vec_kernel(
+    int64_t N, int64_t F, int Dh, const uint16_t* __restrict__ Z, int64_t ldz,
+    const float* __restrict__ a_src, const float* __restrict__ a_dst, float* __restrict__ el, float* __restrict__ er)
+{
+    const int li = threadIdx.x & 15;
+    const int64_t v = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool have = v < N;
+    const int64_t vv = have ? v : N - 1;                 // idle groups repeat the last node (nothing stored)
+    const bool whole = Dh % 4 == 0;
+    float ps[HP], pd[HP];
+#pragma unroll
+    for (int h = 0; h < HP; ++h) { ps[h] = 0.0f; pd[h] = 0.0f; }
+    for (int64_t c0 = li * 4; c0 < F; c0 += 256) {
+        float zq[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = c0 + 64 * q;
+            if (c < F) load_stored<FMT, 4>(Z + vv * ldz + c, zq[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = c0 + 64 * q;
+            if (c >= F) break;
+            const f32x4 as = *reinterpret_cast<const f32x4*>(a_src + c);
+            const f32x4 ad = *reinterpret_cast<const f32x4*>(a_dst + c);
+            const float sa[4] = {as.x, as.y, as.z, as.w}, da[4] = {ad.x, ad.y, ad.z, ad.w};
+            if (whole) {
+                const int h = (int)c / Dh;
+                const float s = ((zq[q][0] * sa[0] + zq[q][1] * sa[1]) + zq[q][2] * sa[2]) + zq[q][3] * sa[3];
+                const float t = ((zq[q][0] * da[0] + zq[q][1] * da[1]) + zq[q][2] * da[2]) + zq[q][3] * da[3];
+#pragma unroll
+                for (int i = 0; i < HP; ++i) {
+                    ps[i] += (h == i) ? s : 0.0f;
+                    pd[i] += (h == i) ? t : 0.0f;
+                }
+                continue;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int h = ((int)c + k) / Dh;
+                const float s = zq[q][k] * sa[k], t = zq[q][k] * da[k];
+#pragma unroll
+                for (int i = 0; i < HP; ++i) {
+                    ps[i] += (h == i) ? s : 0.0f;
+                    pd[i] += (h == i) ? t : 0.0f;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < HP; ++h) {
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) {
+            ps[h] += __shfl_xor(ps[h], m, 64);
+            pd[h] += __shfl_xor(pd[h], m, 64);
+        }
+    }
+    if (have && li == 0) {
+#pragma unroll
+        for (int h = 0; h < HP; ++h) { el[v * HP + h] = ps[h]; er[v * HP + h] = pd[h]; }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // edge softmax over a stored table: whole rows per wave, online softmax at tile granularity, per-edge
 // weights through wave-private LDS, next batch of rows requested before the current one is consumed.
@@ -968,9 +1036,17 @@ int launch_stored(const StoredCall& c, hipStream_t stream)
         float* er = (float*)((char*)c.workspace + w.er);
         a.el = el;
         a.er = er;
-        const unsigned gb = (unsigned)((N + 3) / 4);
-        if (hp == 4) stored_scores_kernel<FMT, 4><<<dim3(gb), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
-        else stored_scores_kernel<FMT, 8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
+        const bool vec_scores = F % 4 == 0 && c.ldz % 4 == 0 && (uintptr_t)Z % 8 == 0 && F < (1ll << 30) &&
+                                (uintptr_t)c.attn_src % 16 == 0 && (uintptr_t)c.attn_dst % 16 == 0 && opt.max_vec >= 4;
+        if (vec_scores) {
+            const unsigned gv = (unsigned)((N + 15) / 16);
+            if (hp == 4) stored_scores_vec_kernel<FMT, 4><<<dim3(gv), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
+            else stored_scores_vec_kernel<FMT, 8><<<dim3(gv), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
+        } else {
+            const unsigned gb = (unsigned)((N + 3) / 4);
+            if (hp == 4) stored_scores_kernel<FMT, 4><<<dim3(gb), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
+            else stored_scores_kernel<FMT, 8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, a.Dh, Z, c.ldz, c.attn_src, c.attn_dst, el, er);
+        }
         const bool hu = (a.Dh % E) == 0;
         // rows of ordinary length compute the source scores from the gathered rows (see the kernel)
         const int g = a.Dh / 4;
