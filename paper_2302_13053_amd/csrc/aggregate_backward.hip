@@ -614,6 +614,84 @@ __global__ __launch_bounds__(256) void gat_bwd_from_saved_kernel(
     }
 }
 
+// The same with 16-byte loads: 16 lanes per node (four nodes per wave), the three rows of a node read in float4
+// steps of 64 columns, a row of up to 256 columns requested before any of it is used, per-head partial sums
+// reduced over the 16 lanes.  Needs 16-byte aligned rows of G and F % 4 == 0 (the kept rows are aligned).
+template <int HP>
+__global__ __launch_bounds__(256) void gat_bwd_from_saved_vec_kernel(
+    int64_t N, int64_t F, int heads, int Dh, float slope, const float* __restrict__ G, int64_t ldg,
+    const float* __restrict__ pos, const float* __restrict__ neg, int64_t ldp,
+    const f32x4* __restrict__ stats, const float* __restrict__ er, f32x4* __restrict__ nbr,
+    float* __restrict__ ddst)
+{
+    const int li = threadIdx.x & 15;
+    const int64_t v = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool have = v < N;
+    const int64_t vv = have ? v : N - 1;                 // idle groups repeat the last node (nothing stored)
+    const bool whole = Dh % 4 == 0;
+    float pp[HP], pn[HP];
+#pragma unroll
+    for (int h = 0; h < HP; ++h) { pp[h] = 0.0f; pn[h] = 0.0f; }
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t c0 = li * 4; c0 < F; c0 += 256) {
+        f32x4 gq[4], pq[4], nq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = c0 + 64 * q;
+            const bool in = c < F;
+            gq[q] = in ? *reinterpret_cast<const f32x4*>(G + vv * ldg + c) : zero;
+            pq[q] = in ? *reinterpret_cast<const f32x4*>(pos + vv * ldp + c) : zero;
+            nq[q] = in ? *reinterpret_cast<const f32x4*>(neg + vv * ldp + c) : zero;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t c = c0 + 64 * q;
+            if (c >= F) break;
+            const float g[4] = {gq[q].x, gq[q].y, gq[q].z, gq[q].w};
+            const float p[4] = {pq[q].x, pq[q].y, pq[q].z, pq[q].w};
+            const float n[4] = {nq[q].x, nq[q].y, nq[q].z, nq[q].w};
+            if (whole) {
+                const int h = (int)c / Dh;
+                const float x = ((g[0] * p[0] + g[1] * p[1]) + g[2] * p[2]) + g[3] * p[3];
+                const float y = ((g[0] * n[0] + g[1] * n[1]) + g[2] * n[2]) + g[3] * n[3];
+#pragma unroll
+                for (int i = 0; i < HP; ++i) {
+                    pp[i] += (h == i) ? x : 0.0f;
+                    pn[i] += (h == i) ? y : 0.0f;
+                }
+                continue;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int h = ((int)c + k) / Dh;
+                const float x = g[k] * p[k], y = g[k] * n[k];
+#pragma unroll
+                for (int i = 0; i < HP; ++i) {
+                    pp[i] += (h == i) ? x : 0.0f;
+                    pn[i] += (h == i) ? y : 0.0f;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < HP; ++h) {
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) {
+            pp[h] += __shfl_xor(pp[h], m, 64);
+            pn[h] += __shfl_xor(pn[h], m, 64);
+        }
+    }
+    if (have && li == 0) {
+#pragma unroll
+        for (int h = 0; h < HP; ++h) {
+            const f32x4 st = stats[v * HP + h];           // {max, 1/sum, P+, P-}
+            const f32x4 t = {er[v * HP + h], st.x, st.y, pp[h] + pn[h]};
+            nbr[v * HP + h] = t;
+            ddst[v * HP + h] = h < heads ? (1.0f - slope) * (pp[h] * st.w - pn[h] * st.z) : 0.0f;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // da_src[c] = sum_u dsrc[u, head(c)] Z[u, c],  da_dst[c] = sum_v ddst[v, head(c)] Z[v, c]
 // stage 1: each workgroup sums a contiguous range of rows, one thread per column
@@ -882,7 +960,17 @@ int launch_aggregate_backward(const AggBackwardCall& c, hipStream_t stream)
         a.el = (const float*)(sv + fw.el);
         a.er = (const float*)(sv + fw.er);
         const unsigned gb = (unsigned)((N + 3) / 4);
-        if (hp == 4)
+        const bool vec_rows = F % 4 == 0 && F < (1ll << 30) && c.ldg % 4 == 0 && (uintptr_t)Ga % 16 == 0 &&
+                              fw.ld_pos % 4 == 0 && (uintptr_t)sv % 16 == 0 && agg_options().max_vec >= 4;
+        if (vec_rows && hp == 4)
+            gat_bwd_from_saved_vec_kernel<4><<<dim3((unsigned)((N + 15) / 16)), dim3(256), 0, stream>>>(
+                N, F, c.heads, a.Dh, c.slope, Ga, c.ldg, (const float*)(sv + fw.pos), (const float*)(sv + fw.neg),
+                fw.ld_pos, (const f32x4*)(sv + fw.stats), a.er, a.nbr, a.ddst);
+        else if (vec_rows)
+            gat_bwd_from_saved_vec_kernel<8><<<dim3((unsigned)((N + 15) / 16)), dim3(256), 0, stream>>>(
+                N, F, c.heads, a.Dh, c.slope, Ga, c.ldg, (const float*)(sv + fw.pos), (const float*)(sv + fw.neg),
+                fw.ld_pos, (const f32x4*)(sv + fw.stats), a.er, a.nbr, a.ddst);
+        else if (hp == 4)
             gat_bwd_from_saved_kernel<4><<<dim3(gb), dim3(256), 0, stream>>>(
                 N, F, c.heads, a.Dh, c.slope, Ga, c.ldg, (const float*)(sv + fw.pos), (const float*)(sv + fw.neg),
                 fw.ld_pos, (const f32x4*)(sv + fw.stats), a.er, a.nbr, a.ddst);
