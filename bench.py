@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
 MEASURED_TRAFFIC_BYTES = {
     "sage_large_powerlaw": 108037992371,     # profiles/bench_sage_large_powerlaw.md
-    "gat_products_powerlaw": 133628689160,   # profiles/bench_gat_products_powerlaw.md
+    "gat_products_powerlaw": 133628371786,   # profiles/bench_gat_products_powerlaw.md
 }
 
 
