@@ -185,6 +185,31 @@ int retexo_aggregate(const retexo_plan* plan, int mode, int64_t F, int heads,
                      void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * retexo_aggregate for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as retexo_aggregate, except that there is no workspace argument: the
+ * aggregation's workspace (the per-node attention scores of RETEXO_GAT_SOFTMAX; the other
+ * modes need none) is a fixed device array of RETEXO_NOALLOC_SCRATCH_BYTES inside the
+ * library, which every GPU the library runs on holds until the process ends.
+ *   - RETEXO_E_WORKSPACE if retexo_workspace_bytes(plan, F, mode, heads, 0) for a bare
+ *     aggregation exceeds that size (RETEXO_GAT_SOFTMAX: more than 1,048,576 nodes with
+ *     up to 4 heads, or 524,288 with 5 to 8); nothing is written.
+ *   - RETEXO_F_SAVE is rejected (RETEXO_E_FLAGS): save mode hands its workspace to the
+ *     backward call and needs a buffer the caller owns.
+ *   - The call allocates nothing, frees nothing and does not synchronise; it only launches
+ *     kernels on `stream`.  The device that is current at the call must be the plan's.
+ *   - All calls on one GPU share the one array: two calls that overlap in time on the same
+ *     GPU (different streams or host threads) race on it.  Calls on one stream are ordered
+ *     and safe.  The array keeps the previous call's contents; nothing in it needs clearing,
+ *     every entry a call reads was written by that call first.
+ */
+#define RETEXO_NOALLOC_SCRATCH_BYTES 33554432
+int retexo_aggregate_noalloc(const retexo_plan* plan, int mode, int64_t F, int heads,
+                             const float* d_Z, int64_t ldz,
+                             const float* d_attn_src, const float* d_attn_dst, float negative_slope,
+                             unsigned flags, float* d_out, int64_t ldo, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Backward of retexo_aggregate: the gradient of a scalar loss with respect to
  * the aggregation's inputs, given d_G = dL/d(out).  This is what training a
  * layer needs when its AGGR has trainable parameters (the gloss under Eq. 1

@@ -28,7 +28,7 @@ EXPORTS = (
     "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
     "retexo_plan_export_split",
     "retexo_workspace_bytes",
-    "retexo_transform", "retexo_aggregate", "retexo_round", "retexo_set_option",
+    "retexo_transform", "retexo_aggregate", "retexo_aggregate_noalloc", "retexo_round", "retexo_set_option",
     "retexo_aggregate_backward_workspace_bytes", "retexo_aggregate_backward", "retexo_aggregate_backward_saved",
     "retexo_partition_workspace_bytes", "retexo_partition_share", "retexo_halo_pack", "retexo_halo_unpack",
     "retexo_plan_set_degrees", "retexo_data_volumes", "retexo_gamma",
@@ -89,6 +89,8 @@ def load():
     lib.retexo_transform.argtypes = [i64, i64, i64, vp, i64, vp, vp, u32, vp, i64, vp]
     lib.retexo_aggregate.restype = i32
     lib.retexo_aggregate.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64, vp, i64, vp]
+    lib.retexo_aggregate_noalloc.restype = i32
+    lib.retexo_aggregate_noalloc.argtypes = [vp, i32, i64, i32, vp, i64, vp, vp, f32, u32, vp, i64, vp]
     lib.retexo_aggregate_backward_workspace_bytes.restype = i64
     lib.retexo_aggregate_backward_workspace_bytes.argtypes = [vp, i32, i64, i32]
     lib.retexo_aggregate_backward.restype = i32
@@ -225,6 +227,16 @@ def retexo_aggregate(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, neg
     return int(load().retexo_aggregate(_vp(plan), mode, F, heads, _vp(d_Z), ldz, _vp(d_attn_src),
                                        _vp(d_attn_dst), negative_slope, flags, _vp(d_out), ldo,
                                        _vp(d_workspace), workspace_bytes, _vp(stream)))
+
+
+NOALLOC_SCRATCH_BYTES = 33554432
+
+
+def retexo_aggregate_noalloc(plan, mode, F, heads, d_Z, ldz, d_attn_src, d_attn_dst, negative_slope, flags,
+                             d_out, ldo, stream=0) -> int:
+    return int(load().retexo_aggregate_noalloc(_vp(plan), mode, F, heads, _vp(d_Z), ldz, _vp(d_attn_src),
+                                               _vp(d_attn_dst), negative_slope, flags, _vp(d_out), ldo,
+                                               _vp(stream)))
 
 
 def retexo_aggregate_backward_workspace_bytes(plan, mode, F, heads) -> int:

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libretexo.so")
 
-SOURCES = ["retexo_api.hip", "csr_build.hip", "plan.hip", "transform.hip", "aggregate.hip", "aggregate_backward.hip", "aggregate_stored.hip", "train.hip", "partition.hip"]
+SOURCES = ["retexo_api.hip", "csr_build.hip", "plan.hip", "transform.hip", "aggregate.hip", "aggregate_backward.hip", "aggregate_stored.hip", "train.hip", "partition.hip", "noalloc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -40,7 +40,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
