@@ -51,6 +51,8 @@ def _load():
         lib.oracle_aggregate.restype = None
         lib.oracle_aggregate.argtypes = [C.c_int, i64, i64p, i64p, i32p, f32p, i64, C.c_int,
                                          f32p, i64, f32p, f32p, C.c_double, C.c_int, f64p]
+        lib.oracle_aggregate_abs.restype = None
+        lib.oracle_aggregate_abs.argtypes = lib.oracle_aggregate.argtypes
         lib.oracle_gat_alpha.restype = None
         lib.oracle_gat_alpha.argtypes = [i64, C.c_int, i64p, i32p, i64, C.c_int, f32p, i64,
                                          f32p, f32p, C.c_double, f64p]
@@ -157,6 +159,30 @@ def aggregate(mode: str, row_ptr, col_idx, Z, F: int, *, heads: int = 1, a_src=N
     return out
 
 
+def aggregate_abs(mode: str, row_ptr, col_idx, Z, F: int, *, heads: int = 1, a_src=None, a_dst=None,
+                  slope: float = 0.2, self_concat: bool = False, rows=None) -> np.ndarray:
+    """Size of the terms behind every element of ``aggregate``: sum_u |c_vu z_uj| (same shape)."""
+    Z, ldz = _matrix(Z)
+    row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
+    n_nodes = row_ptr.size - 1
+    assert Z.shape[0] >= n_nodes and F <= Z.shape[1]
+    dinv = None
+    if mode == "gcn_sym":
+        _, dinv = degree(row_ptr)
+    if mode == "gat_softmax":
+        assert F % heads == 0
+        a_src, a_dst = _c(a_src, np.float32), _c(a_dst, np.float32)
+        assert a_src.size == F and a_dst.size == F
+    rows = None if rows is None else _c(rows, np.int64)
+    n = n_nodes if rows is None else rows.size
+    out = np.empty((n, 2 * F if self_concat else F), np.float64)
+    _load().oracle_aggregate_abs(MODES[mode], n, _p(rows, C.c_int64), _p(row_ptr, C.c_int64),
+                                 _p(col_idx, C.c_int32), _p(dinv, C.c_float), F, heads,
+                                 _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
+                                 float(slope), int(self_concat), _p(out, C.c_double))
+    return out
+
+
 def aggregate_backward(mode: str, row_ptr, col_idx, Z, F: int, G, *, heads: int = 1, a_src=None, a_dst=None,
                        slope: float = 0.2, self_concat: bool = False, rows=None):
     """Gradient of ``aggregate`` with respect to its inputs, given G = dL/d(out) ([N, F or 2F] float32).
@@ -236,6 +262,19 @@ def round_(mode: str, row_ptr, col_idx, H, d_in: int, W, b, *, relu: bool = Fals
             Z32[need] = transform(H, d_in, W, b, relu, rows=need).astype(np.float32)
     return aggregate(mode, row_ptr, col_idx, Z32, F, heads=heads, a_src=a_src, a_dst=a_dst,
                      slope=slope, self_concat=self_concat, rows=rows)
+
+
+def head_mean(X, heads: int, n_classes: int) -> np.ndarray:
+    """Average of the ``heads`` column blocks of X[:, :heads * n_classes], float64 [n, n_classes]:
+    out[v, c] = (1 / heads) * sum_h X[v, h * n_classes + c].  The last attention round of a classifier
+    keeps one block of class scores per head and averages them (the standard form of the attention
+    network the paper's evaluation set-up names; the paper itself does not print it)."""
+    X = np.asarray(X)
+    assert X.shape[1] >= heads * n_classes
+    out = np.zeros((X.shape[0], n_classes), np.float64)
+    for h in range(heads):
+        out += X[:, h * n_classes:(h + 1) * n_classes].astype(np.float64)
+    return out / float(heads)
 
 
 def philox4x32_10(counter, key):

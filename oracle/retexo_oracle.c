@@ -249,6 +249,64 @@ void oracle_aggregate(int mode, int64_t n_rows, const int64_t *rows,
     }
 }
 
+void oracle_gat_alpha(int64_t v, int h, const int64_t *row_ptr, const int32_t *col_idx,
+                      int64_t F, int heads, const float *Z, int64_t ldz,
+                      const float *a_src, const float *a_dst, double slope, double *alpha);
+
+/*
+ * The size of the terms behind every output element of oracle_aggregate: with
+ * out[v,j] = sum_u c_vu z_uj (c_vu = 1, 1/deg v, dinv_v dinv_u or alpha_vu), this returns
+ *     mag[v,j] = sum_u |c_vu z_uj|
+ * (the self half under self_concat and the max aggregator have a single term, |z|).
+ * It is the yardstick of the condition-aware error measure of the parity tests: a float32
+ * evaluation of a sum can only be expected to be accurate relative to the size of its terms,
+ * not relative to a result that cancels to nearly zero.  Same arguments and layout as
+ * oracle_aggregate.
+ */
+void oracle_aggregate_abs(int mode, int64_t n_rows, const int64_t *rows,
+                          const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
+                          int64_t F, int heads, const float *Z, int64_t ldz,
+                          const float *a_src, const float *a_dst, double slope,
+                          int self_concat, double *mag)
+{
+    const int64_t pitch = self_concat ? 2 * F : F;
+    const int64_t Dh = (mode == ORACLE_GAT_SOFTMAX) ? F / heads : F;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t v = rows ? rows[i] : i;
+        double *o = mag + i * pitch;
+        if (self_concat) {
+            for (int64_t j = 0; j < F; ++j) o[j] = fabs((double)Z[v * ldz + j]);
+            o += F;
+        }
+        const int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
+        const int64_t deg = hi - lo;
+        for (int64_t j = 0; j < F; ++j) o[j] = 0.0;
+        if (deg == 0) continue;
+        for (int64_t j = 0; j < F; ++j) {
+            const int h = (int)(j / Dh);
+            double s = 0.0, top = -INFINITY;
+            double *alpha = NULL;
+            if (mode == ORACLE_GAT_SOFTMAX) {
+                alpha = (double *)malloc((size_t)deg * sizeof(double));
+                oracle_gat_alpha(v, h, row_ptr, col_idx, F, heads, Z, ldz, a_src, a_dst, slope, alpha);
+            }
+            for (int64_t e = lo; e < hi; ++e) {
+                const int64_t u = col_idx[e];
+                const double z = (double)Z[u * ldz + j];
+                double c = 1.0;
+                if (mode == ORACLE_MEAN) c = 1.0 / (double)deg;
+                else if (mode == ORACLE_GCN_SYM) c = (double)dinv[v] * (double)dinv[u];
+                else if (mode == ORACLE_GAT_SOFTMAX) c = alpha[e - lo];
+                s += fabs(c * z);
+                if (z > top) top = z;
+            }
+            free(alpha);
+            o[j] = (mode == ORACLE_MAX) ? fabs(top) : s;
+        }
+    }
+}
+
 /*
  * Attention coefficients alpha_uv of one row and one head, in CSR entry
  * order (deg doubles).  Same formula as above, exposed so that a test can

@@ -361,6 +361,10 @@ class Pipeline:
         W, b, a_src, a_dst = self.params[i]
         if st.kind == "transform":
             transform(H, st.d_in, W, b, st.relu, out=self.outs[i])
+        elif st.kind == "head_mean":
+            B.check(B.retexo_head_mean(self.n, st.heads, st.d_out, H.data_ptr(), H.stride(0),
+                                       self.outs[i].data_ptr(), self.outs[i].stride(0), _stream_ptr()),
+                    "retexo_head_mean")
         else:
             round_(self.graph, st, H, W, b, a_src, a_dst, self.outs[i], self.round_ws)
         return self.outs[i]

@@ -36,6 +36,8 @@ class Stage:
 
     kind: "round"      -> transform (if d_in != 0) followed by aggregation
           "transform"  -> bare dense transform (the final classifier layer)
+          "head_mean"  -> mean over the ``heads`` column blocks of the last attention round
+                          (d_in = heads * d_out columns in, d_out out)
     For kind == "round", ``w`` False means the identity transform (the very
     first message-passing round is taken over the raw features).
     """
@@ -50,7 +52,7 @@ class Stage:
 
     @property
     def out_width(self) -> int:
-        if self.kind == "transform":
+        if self.kind in ("transform", "head_mean"):
             return self.d_out
         return 2 * self.d_out if self.concat else self.d_out
 
@@ -97,6 +99,8 @@ def _gat(f0: int, heads: int, dh: int, rounds: int, classes: int) -> Tuple[Stage
         out = heads * (dh if r < rounds - 1 else classes)
         st.append(Stage("round", width, out, mode="gat_softmax", heads=heads))
         width = out
+    # the last round's heads are averaged into the class scores
+    st.append(Stage("head_mean", width, classes, w=False, heads=heads))
     return tuple(st)
 
 

@@ -17,6 +17,8 @@ pytestmark = pytest.mark.gpu
 def oracle_stage(st, rp, ci, H, p, rows=None):
     if st.kind == "transform":
         return oracle.transform(H, st.d_in, p.W, p.b, st.relu, rows=rows)
+    if st.kind == "head_mean":
+        return oracle.head_mean(H if rows is None else H[rows], st.heads, st.d_out)
     return oracle.round_(st.mode, rp, ci, H, st.d_in, p.W, p.b, relu=st.relu, heads=st.heads,
                          a_src=p.a_src, a_dst=p.a_dst, self_concat=st.concat, rows=rows)
 

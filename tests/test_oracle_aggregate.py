@@ -76,7 +76,16 @@ def test_hand_computed_example():
             alpha = (int(tok[1]), np.array([float(t) for t in tok[2:]]))
         else:
             want.setdefault(tok[0], {})[int(tok[1])] = [float(tok[2]), float(tok[3])]
+    mags = {k[4:]: want.pop(k) for k in list(want) if k.startswith("abs_")}
     assert sorted(want) == sorted(MODES) and all(len(v) == 4 for v in want.values())
+    # the size of the terms behind each element (oracle.aggregate_abs), rows the file lists
+    assert sorted(mags) == sorted(MODES)
+    for mode, rows in mags.items():
+        rp, ci = oracle.csr_from_coo(src, dst, 4, mode == "gcn_sym")
+        got = oracle.aggregate_abs(mode, rp, ci, Z, 2, heads=1, a_src=a_src, a_dst=a_dst)
+        tol = 2e-7 if mode == "gcn_sym" else 1e-15
+        for v, ref in rows.items():
+            assert np.allclose(got[v], ref, rtol=tol, atol=tol), (mode, v)
     for mode in MODES:
         rp, ci = oracle.csr_from_coo(src, dst, 4, mode == "gcn_sym")
         got = oracle.aggregate(mode, rp, ci, Z, 2, heads=1, a_src=a_src, a_dst=a_dst)
@@ -308,3 +317,61 @@ def test_round_is_transform_rounded_to_float_then_aggregate():
     # identity round (first message-passing round is over the raw features)
     assert np.array_equal(oracle.round_("mean", rp, ci, H, 10, None, None),
                           oracle.aggregate("mean", rp, ci, H, 10))
+
+
+def test_head_mean_hand_example_and_single_head_identity():
+    # two nodes, heads = 3, two classes: columns are [h0c0 h0c1 | h1c0 h1c1 | h2c0 h2c1 | padding]
+    X = np.array([[1.0, 10.0, 2.0, 20.0, 6.0, 60.0, 99.0],
+                  [-3.0, 0.5, 3.0, 0.25, 0.0, 0.0, 99.0]], np.float32)
+    got = oracle.head_mean(X, 3, 2)
+    assert np.array_equal(got, np.array([[3.0, 30.0], [0.0, 0.25]]))
+    # one head: the class scores themselves; the padding column never enters
+    assert np.array_equal(oracle.head_mean(X, 1, 6), X[:, :6].astype(np.float64))
+    # averaging commutes with the layout: reshaping to [n, heads, classes] and taking the mean over heads
+    rng = np.random.Generator(np.random.Philox(key=77))
+    Y = rng.standard_normal((50, 4 * 47 + 4)).astype(np.float32)
+    want = Y[:, :188].astype(np.float64).reshape(50, 4, 47).mean(axis=1)
+    assert np.allclose(oracle.head_mean(Y, 4, 47), want, rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+@pytest.mark.parametrize("concat", [False, True])
+def test_term_magnitudes_against_dense_algebra_and_sign_flips(mode, concat):
+    """oracle.aggregate_abs is sum_u |c_vu z_uj|.  Pins: for non-negative Z it is the aggregate itself; for the
+    modes whose coefficients do not depend on Z it is the aggregate of |Z|; for the edge softmax it is the dense
+    alpha (masked softmax written with numpy) times |Z|; the maximum has a single term."""
+    n, F, heads = 31, 8, 2
+    rp, ci = small_graph(n, 150, 5, mode == "gcn_sym", skew=2.0)
+    Z = wl.random_matrix(n, F, 6, ld=F + 2)
+    a_src = wl.random_matrix(heads, F // heads, 7)
+    a_dst = wl.random_matrix(heads, F // heads, 8)
+    kw = dict(heads=heads, a_src=a_src, a_dst=a_dst, self_concat=concat)
+    mag = oracle.aggregate_abs(mode, rp, ci, Z, F, **kw)
+    val = oracle.aggregate(mode, rp, ci, Z, F, **kw)
+    assert mag.shape == val.shape and np.all(mag >= np.abs(val) - 1e-12)
+    Zp = np.abs(Z)
+    if mode != "gat_softmax":
+        # coefficients independent of Z
+        if mode == "max":
+            assert np.array_equal(mag, np.abs(val))
+        else:
+            assert np.allclose(mag, oracle.aggregate(mode, rp, ci, Zp, F, **kw), rtol=1e-13, atol=0)
+    else:
+        a = dense(rp, ci, n)
+        Zd = Z[:, :F].astype(np.float64)
+        dh = F // heads
+        ref = np.zeros((n, F))
+        for h in range(heads):
+            Zh = Zd[:, h * dh:(h + 1) * dh]
+            e = leaky((Zh @ a_dst[h].astype(np.float64))[:, None] + (Zh @ a_src[h].astype(np.float64))[None, :])
+            e = np.where(a > 0, e, -np.inf)
+            m = np.where(a.sum(1) > 0, e.max(1, initial=-np.inf), 0)
+            p = np.where(a > 0, np.exp(e - m[:, None]), 0)
+            ref[:, h * dh:(h + 1) * dh] = (p / np.maximum(p.sum(1), 1e-300)[:, None]) @ np.abs(Zh)
+        agg = mag[:, F:] if concat else mag
+        assert np.allclose(agg, ref, rtol=1e-12, atol=1e-14)
+    if concat:
+        assert np.array_equal(mag[:, :F], np.abs(Z[:, :F]).astype(np.float64))
+    # non-negative input: the magnitudes are the values
+    assert np.allclose(oracle.aggregate_abs(mode, rp, ci, Zp, F, **kw), oracle.aggregate(mode, rp, ci, Zp, F, **kw),
+                       rtol=1e-13, atol=0)
