@@ -4,19 +4,29 @@
 A step is one pass of the whole path over one synthetic workload whose inputs
 already sit in HBM: CSR construction from the raw pair list, plan creation,
 then every round (dense transform + neighbourhood aggregation) and the final
-classifier transform.  The headline value is the edge*feature arithmetic of
-all aggregations in the pass (2 flop per CSR entry and feature column) divided
-by the wall time of the whole step.
+classifier transform (or head mean).  The headline value is the edge*feature
+arithmetic of all aggregations in the pass (2 flop per CSR entry and feature
+column) divided by the wall time of the whole step.
+
+With no --config the headline workload is the Reddit-shaped one (index 3) and the
+ogbn-products-shaped one (index 4, the workload whose gathers really are HBM reads)
+runs in the same process and is reported under "also".
 
 Prints one JSON line.  Extra objects:
-  roofline      the dominant kernel (the widest aggregation) against the 8 TB/s HBM peak
-  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+  roofline      the dominant kernel (the widest aggregation) against the 8 TB/s HBM peak;
+                frac is measured-traffic bytes / time / peak and cannot exceed 1, the
+                gather-model and compulsory figures stand beside it
+  transforms    every dense transform timed alone against the fp32 matrix-core peak
+  cpu_baseline  the CPU oracle timed on the same workload
 """
 from __future__ import annotations
 
 import argparse
+import gc
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -27,13 +37,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-
-# HBM bytes per launch of the dominant aggregation measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    "sage_large_powerlaw": 108037992371,     # profiles/bench_sage_large_powerlaw.md
-    "gat_products_powerlaw": 133628371786,   # profiles/bench_gat_products_powerlaw.md
-}
+MFMA_F32_PEAK_TFLOPS = 157.3
 
 
 def parse():
@@ -41,8 +45,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="workload index (0-4; 3 = Reddit-shaped, 4 = ogbn-products-shaped)")
+    ap.add_argument("--config", type=int, default=None,
+                    help="workload index (0-4; 3 = Reddit-shaped, 4 = ogbn-products-shaped); "
+                         "default: 3 as the headline and 4 under 'also'")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the rows beyond the hot path (training step, backward, 16-bit table, partition)")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle sample (0 = per-workload default)")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="set a tuning knob of the library (retexo_set_option) before running, for experiments")
@@ -50,6 +58,34 @@ def parse():
                     help="for rocprofv3 --pmc runs: one pass, then one 1 GiB device copy (the known-size "
                          "reference for the byte counters) and one launch of the dominant aggregation; no JSON")
     return ap.parse_args()
+
+
+def library_source_hash():
+    """sha256 over the library's sources: ties a stored counter summary to the kernels it was taken from."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2302_13053_amd", "csrc")
+    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "retexo.h")]:
+        with open(path, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic(workload_name):
+    """HBM-side bytes per launch of the dominant aggregation from the committed rocprofv3 summary
+    (FETCH_SIZE + WRITE_SIZE runs): (bytes, source description, matches the current sources?)."""
+    path = os.path.join(ROOT, "profiles", "bench_%s.md" % workload_name)
+    if not os.path.exists(path):
+        return None, "no profiles/bench_%s.md" % workload_name, False
+    text = open(path).read()
+    m = re.search(r"total per aggregation:.*?=\s*(\d+) bytes", text)
+    if not m:
+        return None, "profiles/bench_%s.md has no traffic total" % workload_name, False
+    hm = re.search(r"library sources sha256:\s*([0-9a-f]+)", text)
+    same = bool(hm) and hm.group(1) == library_source_hash()
+    src = "profiles/bench_%s.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --probe`, not this run; " \
+          "taken from library sources %s, %s)" % (workload_name, hm.group(1) if hm else "unknown",
+                                                  "same as now" if same else "CHANGED since: re-profile")
+    return int(m.group(1)), src, same
 
 
 def algorithmic_bytes(n, nnz, F, concat, gat_heads=0):
@@ -61,6 +97,11 @@ def algorithmic_bytes(n, nnz, F, concat, gat_heads=0):
     if gat_heads:
         b += 4 * nnz * gat_heads + 8 * n * gat_heads
     return b
+
+
+def compulsory_bytes(n, nnz, F, concat):
+    """Bytes with a perfect cache: every feature row read once, the indices once, the output written once."""
+    return 4 * n * F + 4 * nnz + 8 * (n + 1) + 4 * n * (2 * F if concat else F)
 
 
 def cpu_baseline(w, src, dst, feats, params, n_rows):
@@ -85,6 +126,13 @@ def cpu_baseline(w, src, dst, feats, params, n_rows):
             H = feats
         else:
             H = wl.random_matrix(n, st.d_in, 100 + i, ld=wl.pad_ld(st.d_in))
+        if st.kind == "head_mean":
+            t0 = time.perf_counter()
+            oracle.head_mean(H[rows], st.heads, st.d_out)
+            dt = time.perf_counter() - t0
+            spent += dt
+            total += dt * n / rows.size
+            continue
         if st.w:
             t0 = time.perf_counter()
             oracle.transform(H, st.d_in, p.W, p.b, st.relu, rows=rows)
@@ -112,27 +160,51 @@ def cpu_baseline(w, src, dst, feats, params, n_rows):
     }
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+class Timer:
+    """HIP events on the stream the library launches on (torch's current stream)."""
 
+    def __init__(self, torch):
+        self.torch = torch
+        self.e0 = torch.cuda.Event(enable_timing=True)
+        self.e1 = torch.cuda.Event(enable_timing=True)
+
+    def ms(self, fn, reps):
+        fn()
+        self.torch.cuda.synchronize()
+        self.e0.record()
+        for _ in range(reps):
+            fn()
+        self.e1.record()
+        self.torch.cuda.synchronize()
+        return self.e0.elapsed_time(self.e1) / reps
+
+
+def run_probe(w, pipe, torch, Hn, wl):
+    pipe.run()
+    torch.cuda.synchronize()
+    ref_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    ref_dst = torch.empty_like(ref_src)
+    torch.cuda.synchronize()
+    ref_dst.copy_(ref_src)                       # 1 GiB read + 1 GiB written
+    torch.cuda.synchronize()
+    di = max((i for i, st in enumerate(w.stages) if st.kind == "round"), key=lambda i: w.stages[i].d_out)
+    st = w.stages[di]
+    Zin = pipe.H0 if not st.w else torch.empty((w.n_nodes, wl.pad_ld(st.d_out)), dtype=torch.float32,
+                                               device="cuda").normal_()
+    _, _, a_s, a_d = pipe.params[di]
+    Hn.aggregate(pipe.graph, st.mode, Zin, st.d_out, heads=st.heads, a_src=a_s, a_dst=a_d, concat=st.concat)
+    torch.cuda.synchronize()
+    print("probe done: copy of %d bytes each way, then stage %d aggregation (F=%d)"
+          % (ref_src.numel() * 4, di, st.d_out))
+
+
+def bench_workload(index, args):
     import torch
     from paper_2302_13053_amd import binding as B
     from paper_2302_13053_amd import harness as Hn
     from paper_2302_13053_amd import workloads as wl
 
-    B.load()
-    for item in args.option:
-        name, _, value = item.partition("=")
-        B.check(B.retexo_set_option(name, int(value)), "retexo_set_option(%s)" % item)
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-
-    w = wl.workload(args.config)
+    w = wl.workload(index)
     t0 = time.perf_counter()
     src, dst = wl.make_graph(w)
     feats = wl.make_features(w, ld=wl.pad_ld(w.feat_dim))
@@ -141,25 +213,9 @@ def main():
 
     pipe = Hn.Pipeline(w, src, dst, feats, params)
     if args.probe:
-        pipe.run()
-        torch.cuda.synchronize()
-        ref_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        ref_dst = torch.empty_like(ref_src)
-        torch.cuda.synchronize()
-        ref_dst.copy_(ref_src)                       # 1 GiB read + 1 GiB written
-        torch.cuda.synchronize()
-        di = max((i for i, st in enumerate(w.stages) if st.kind == "round"),
-                 key=lambda i: w.stages[i].d_out)
-        st = w.stages[di]
-        Zin = pipe.H0 if not st.w else torch.empty((w.n_nodes, wl.pad_ld(st.d_out)), dtype=torch.float32,
-                                                   device="cuda").normal_()
-        _, _, a_s, a_d = pipe.params[di]
-        Hn.aggregate(pipe.graph, st.mode, Zin, st.d_out, heads=st.heads, a_src=a_s, a_dst=a_d, concat=st.concat)
-        torch.cuda.synchronize()
-        print("probe done: copy of %d bytes each way, then stage %d aggregation (F=%d)"
-              % (ref_src.numel() * 4, di, st.d_out))
+        run_probe(w, pipe, torch, Hn, wl)
         pipe.close()
-        return
+        return None
     for _ in range(args.warmup):
         pipe.run()
     torch.cuda.synchronize()
@@ -173,6 +229,8 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     n, nnz = w.n_nodes, pipe.graph.nnz
+    timer = Timer(torch)
+    reps = max(3, args.steps)
     # per-step-kind mean over the timed steps, from events on the launch stream
     per = {}
     for label, a, b in events:
@@ -199,7 +257,7 @@ def main():
             rec["transform_gflop"] = 2.0 * n * st.d_in * st.d_out / 1e9
         stages.append(rec)
 
-    # roofline of the dominant aggregation: time it alone (aggregate call only) on the launch stream
+    # ---- roofline of the dominant aggregation: the aggregate call alone, on the launch stream
     di = dominant[0]
     dst_stage = w.stages[di]
     gat = dst_stage.mode == "gat_softmax"
@@ -213,21 +271,17 @@ def main():
     agg_out = torch.empty((n, wl.pad_ld(dst_stage.out_width)), dtype=torch.float32, device="cuda")
     ws = Hn.ws_tensor(B.retexo_workspace_bytes(pipe.graph.plan, F, B.MODES[dst_stage.mode], dst_stage.heads,
                                                B.F_SELF_CONCAT if dst_stage.concat else 0))
-    reps = max(3, args.steps)
-    Hn.aggregate(pipe.graph, dst_stage.mode, Zin, F, heads=dst_stage.heads, a_src=a_s, a_dst=a_d,
-                 concat=dst_stage.concat, out=agg_out, workspace=ws)
-    torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        Hn.aggregate(pipe.graph, dst_stage.mode, Zin, F, heads=dst_stage.heads, a_src=a_s, a_dst=a_d,
-                     concat=dst_stage.concat, out=agg_out, workspace=ws)
-    e1.record()
-    torch.cuda.synchronize()
-    agg_ms = e0.elapsed_time(e1) / reps
-    gbytes = algorithmic_bytes(n, nnz, F, dst_stage.concat, dst_stage.heads if gat else 0)
-    achieved = gbytes / agg_ms / 1e6
+    agg_ms = timer.ms(lambda: Hn.aggregate(pipe.graph, dst_stage.mode, Zin, F, heads=dst_stage.heads, a_src=a_s,
+                                           a_dst=a_d, concat=dst_stage.concat, out=agg_out, workspace=ws), reps)
+    g_bytes = algorithmic_bytes(n, nnz, F, dst_stage.concat, dst_stage.heads if gat else 0)
+    c_bytes = compulsory_bytes(n, nnz, F, dst_stage.concat)
+    traffic, traffic_src, traffic_current = profiled_traffic(w.name)
+
+    def rate(nbytes):
+        return None if nbytes is None else nbytes / agg_ms / 1e6          # GB/s
+
+    def frac(nbytes):
+        return None if nbytes is None else nbytes / agg_ms / 1e6 / HBM_PEAK_GBS
     roofline = {
         "bound": "hbm",
         "kernel": ("agg_gat_flash_kernel (wave per row, eight waves per long row; scores formed from the gathered "
@@ -236,41 +290,81 @@ def main():
                    "aggregation call = agg_rowgroup_kernel + agg_grouped_kernel per source range (narrow slabs) "
                    "or agg_linear_kernel (whole rows), chosen by the plan"),
         "stage": "round%d aggregation, F=%d" % (di, F),
-        "achieved": achieved,
+        # achieved / frac: bytes that crossed the L2 <-> fabric boundary (rocprofv3 counters of the same launch,
+        # an upper bound on HBM bytes) per second of this run's launch time; cannot exceed the peak
+        "achieved": rate(traffic),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-        "algorithmic_bytes": gbytes,
+        "frac": frac(traffic),
+        "traffic": traffic,
+        "traffic_source": traffic_src,
+        "traffic_matches_current_kernels": traffic_current,
         "ms_per_launch": agg_ms,
+        # the three figures: gather model (every entry reads one row: what the kernel delivers to its lanes;
+        # above 1 when most gathers are served by L2), measured traffic, and the perfect-cache bound
+        "effective_gather": {"bytes": g_bytes, "GB/s": rate(g_bytes), "frac": frac(g_bytes)},
+        "hbm_measured": {"bytes": traffic, "GB/s": rate(traffic), "frac": frac(traffic)},
+        "compulsory": {"bytes": c_bytes, "GB/s": rate(c_bytes), "frac": frac(c_bytes)},
         "edge_features_per_s": float(nnz) * F / (agg_ms * 1e-3),
     }
 
+    # ---- every dense transform alone, against the fp32 matrix-core peak (skinny outputs: against HBM)
+    transforms = []
+    for i, st in enumerate(w.stages):
+        if not st.w:
+            continue
+        Hin = pipe.H0 if i == 0 else pipe.outs[i - 1]
+        Wd, bd = pipe.params[i][0], pipe.params[i][1]
+        Zt = torch.empty((n, wl.pad_ld(st.d_out)), dtype=torch.float32, device="cuda")
+        tms = timer.ms(lambda: Hn.transform(Hin, st.d_in, Wd, bd, st.relu, out=Zt), reps)
+        fl = 2.0 * n * st.d_in * st.d_out
+        by = 4.0 * (n * st.d_in + n * st.d_out + st.d_in * st.d_out)
+        ai = fl / by
+        transforms.append({"stage": "%s%d" % (st.kind, i), "shape": "%d x %d -> %d" % (n, st.d_in, st.d_out),
+                           "ms_alone": tms, "TFLOP/s": fl / tms / 1e9, "frac_fp32_mfma": fl / tms / 1e9 / MFMA_F32_PEAK_TFLOPS,
+                           "GB/s": by / tms / 1e6, "frac_hbm": by / tms / 1e6 / HBM_PEAK_GBS,
+                           "flop_per_byte": ai, "bound": "mfma" if ai >= 20.0 else "hbm"})
+        del Zt
+
     out = {
-        "metric": "aggregated edge*feature GFLOP/s per lazy-MP pass (whole path: CSR build, plan, all rounds)",
-        "value": flops / (ms_per_step * 1e-3) / 1e9,
-        "unit": "GFLOP/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
         "data": "synthetic (seeded %s graph, %s)" % (w.graph, w.stands_in_for),
         "config": {"workload": w.name, "config_index": w.index, "family": w.family, "nodes": n,
                    "raw_pairs": int(src.size), "csr_entries": int(nnz),
                    "max_degree": B.retexo_plan_max_degree(pipe.graph.plan), "feat_dim": w.feat_dim,
-                   "stages": [st.kind + ":" + (st.mode if st.kind == "round" else "dense") +
-                              ":%d->%d" % (st.d_in, st.d_out) for st in w.stages]},
+                   "stages": [st.kind + ":" + (st.mode if st.kind == "round" else "dense" if st.kind == "transform"
+                                               else "heads") + ":%d->%d" % (st.d_in, st.d_out) for st in w.stages]},
         "csr_plan_ms": float(np.mean(per["csr+plan"])),
         "stages": stages,
         "input_generation_s": t_gen,
         "roofline": roofline,
+        "transforms": transforms,
     }
-    # the row after the hot path: one local training step (loss + gradients + SGD update) of the first
-    # trained layer with its temporary classifier, on the aggregated features that are already resident
+    if not args.no_extras:
+        extras(out, w, pipe, args, timer, reps, di, Zin, agg_out, ws, agg_ms)
+    pipe.close()
+    del pipe, Zin, agg_out, ws
+    gc.collect()
+    torch.cuda.empty_cache()
+    if not args.no_cpu:
+        default_rows = w.n_nodes      # the oracle is fast enough to run every row of every stage in 10-30 s
+        out["cpu_baseline"] = cpu_baseline(w, src, dst, feats, params, args.cpu_rows or default_rows)
+    return out
+
+
+def extras(out, w, pipe, args, timer, reps, di, Zin, agg_out, ws, agg_ms):
+    """Rows beyond the hot path, on the tensors that are already resident."""
+    import torch
+    from paper_2302_13053_amd import binding as B
+    from paper_2302_13053_amd import harness as Hn
+    from paper_2302_13053_amd import workloads as wl
+    n, nnz = w.n_nodes, pipe.graph.nnz
+    dst_stage = w.stages[di]
+    gat = dst_stage.mode == "gat_softmax"
+    F = dst_stage.d_out
+    # one local training step (loss + gradients + SGD update) of the first trained layer with its
+    # temporary classifier, on the aggregated features
     hidden = next((i for i, st in enumerate(w.stages) if st.kind == "round" and st.w and st.mode != "gat_softmax"),
                   None)
     if hidden is not None:
@@ -284,45 +378,28 @@ def main():
         Wc = torch.empty((st.d_out, n_cls), dtype=torch.float32, device="cuda").uniform_(-0.1, 0.1, generator=g)
         bc = torch.zeros(n_cls, dtype=torch.float32, device="cuda")
         tws = Hn.ws_tensor(B.retexo_train_workspace_bytes(n, st.d_in, st.d_out, n_cls))
+        losses = []
 
-        def train_once():
-            loss, *grads = Hn.layer_grad(X, st.d_in, labels, W1, b1, Wc, bc, workspace=tws)
+        def train_once(dropout=None):
+            loss, *grads = Hn.layer_grad(X, st.d_in, labels, W1, b1, Wc, bc, workspace=tws, dropout=dropout)
             for p_, g_ in zip((W1, b1, Wc, bc), grads):
                 B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), 0.01, Hn._stream_ptr()),
                         "retexo_sgd_update")
-            return loss
-        l0 = float(train_once().cpu()[0])
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            last = train_once()
-        e1.record()
-        torch.cuda.synchronize()
-        tms = e0.elapsed_time(e1) / reps
+            losses.append(loss)
+        tms = timer.ms(train_once, reps)
         tfl = (4.0 * n * st.d_in * st.d_out + 6.0 * n * st.d_out * n_cls) / tms / 1e9
         out["train_step"] = {"layer": "%d->%d (ReLU) + classifier %d->%d" % (st.d_in, st.d_out, st.d_out, n_cls),
-                             "ms": tms, "TFLOP/s": tfl, "frac_fp32_mfma": tfl / 157.3,
-                             "loss_first": l0, "loss_last": float(last.cpu()[0]), "sgd_steps": reps + 1}
-        # the same step with dropout 0.5 on the hidden units (a fresh mask per step)
+                             "ms": tms, "TFLOP/s": tfl, "frac_fp32_mfma": tfl / MFMA_F32_PEAK_TFLOPS,
+                             "loss_first": float(losses[0].cpu()[0]), "loss_last": float(losses[-1].cpu()[0]),
+                             "sgd_steps": reps + 1}
         draw = [0]
 
-        def train_dropout_once():
+        def train_dropout_once():       # the same step with dropout 0.5 on the hidden units (a fresh mask per step)
             draw[0] += 1
-            loss, *grads = Hn.layer_grad(X, st.d_in, labels, W1, b1, Wc, bc, workspace=tws,
-                                         dropout=(0.5, 20230213, draw[0]))
-            for p_, g_ in zip((W1, b1, Wc, bc), grads):
-                B.check(B.retexo_sgd_update(p_.numel(), p_.data_ptr(), g_.data_ptr(), 0.01, Hn._stream_ptr()),
-                        "retexo_sgd_update")
-        train_dropout_once()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            train_dropout_once()
-        e1.record()
-        torch.cuda.synchronize()
-        out["train_step"]["ms_with_dropout"] = e0.elapsed_time(e1) / reps
+            train_once(dropout=(0.5, 20230213, draw[0]))
+        out["train_step"]["ms_with_dropout"] = timer.ms(train_dropout_once, reps)
     # a layer whose aggregation has trainable parameters (edge softmax) trains with the aggregation in the
-    # loop: time its backward (dL/dZ and the attention-vector gradients) on the first such round's shape
+    # loop: its backward (dL/dZ and the attention-vector gradients) on the first such round's shape
     att = next((i for i, st in enumerate(w.stages) if st.kind == "round" and st.mode == "gat_softmax"
                 and st.d_out <= 1024), None)
     if att is not None:
@@ -333,71 +410,40 @@ def main():
         a_s, a_d = pipe.params[att][2], pipe.params[att][3]
         dZb = torch.empty_like(Zb)
         bws = Hn.ws_tensor(B.retexo_aggregate_backward_workspace_bytes(pipe.graph.plan, B.MODES[st.mode], Fz, st.heads))
-
-        def backward_once():
-            return Hn.aggregate_backward(pipe.graph, st.mode, Fz, Gb, Z=Zb, heads=st.heads, a_src=a_s, a_dst=a_d,
-                                         dZ=dZb, workspace=bws)
-        backward_once()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            backward_once()
-        e1.record()
-        torch.cuda.synchronize()
-        bms = e0.elapsed_time(e1) / reps
+        bms = timer.ms(lambda: Hn.aggregate_backward(pipe.graph, st.mode, Fz, Gb, Z=Zb, heads=st.heads, a_src=a_s,
+                                                     a_dst=a_d, dZ=dZb, workspace=bws), reps)
         gbs = 2.0 * nnz * Fz * 4 / bms / 1e6              # two gather passes, one row of F floats per entry each
         out["aggregate_backward"] = {"shape": "%s F=%d heads=%d ld=%d" % (st.mode, Fz, st.heads, width), "ms": bms,
-                                     "GB/s_algorithmic": gbs, "frac_hbm": gbs / 8000.0}
+                                     "GB/s_algorithmic": gbs, "frac_hbm": gbs / HBM_PEAK_GBS}
         # in a training loop: the forward in save mode, then the backward that reuses what it kept (one gather pass)
         try:
             sws = Hn.ws_tensor(B.retexo_workspace_bytes(pipe.graph.plan, Fz, B.MODES[st.mode], st.heads, B.F_SAVE))
             fout = torch.empty_like(Zb)
-
-            def forward_save():
-                Hn.aggregate(pipe.graph, st.mode, Zb, Fz, heads=st.heads, a_src=a_s, a_dst=a_d, out=fout,
-                             workspace=sws, save=True)
-
-            def backward_saved():
-                Hn.aggregate_backward(pipe.graph, st.mode, Fz, Gb, Z=Zb, heads=st.heads, a_src=a_s, a_dst=a_d,
-                                      dZ=dZb, workspace=bws, saved=sws)
-            times = []
-            for fn in (forward_save, backward_saved):
-                fn()
-                torch.cuda.synchronize()
-                e0.record()
-                for _ in range(reps):
-                    fn()
-                e1.record()
-                torch.cuda.synchronize()
-                times.append(e0.elapsed_time(e1) / reps)
-            out["aggregate_backward"].update({"forward_save_mode_ms": times[0], "backward_after_save_ms": times[1],
-                                              "GB/s_algorithmic_after_save": nnz * Fz * 4 / times[1] / 1e6})
+            t_f = timer.ms(lambda: Hn.aggregate(pipe.graph, st.mode, Zb, Fz, heads=st.heads, a_src=a_s, a_dst=a_d,
+                                                out=fout, workspace=sws, save=True), reps)
+            t_b = timer.ms(lambda: Hn.aggregate_backward(pipe.graph, st.mode, Fz, Gb, Z=Zb, heads=st.heads, a_src=a_s,
+                                                         a_dst=a_d, dZ=dZb, workspace=bws, saved=sws), reps)
+            out["aggregate_backward"].update({"forward_save_mode_ms": t_f, "backward_after_save_ms": t_b,
+                                              "GB/s_algorithmic_after_save": nnz * Fz * 4 / t_b / 1e6})
+            del sws, fout
         except B.RetexoError:
             pass                                           # layout without save mode: the plain backward stands
+        del Gb, dZb, bws
     # variant: the dominant aggregation over a table in 16-bit storage (half the gathered bytes; the stored value
     # is the float32 value rounded to nearest even, sums stay in float32)
     try:
         Z16 = Hn.store_rows(Zin, F, "bf16")               # the table the roofline figure above was measured on
         kw16 = dict(heads=dst_stage.heads, a_src=pipe.params[di][2], a_dst=pipe.params[di][3]) if gat else {}
-        run16 = lambda: Hn.aggregate_stored(pipe.graph, dst_stage.mode, Z16, F, "bf16", concat=dst_stage.concat,
-                                            out=agg_out, workspace=ws, **kw16)
-        run16()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            run16()
-        e1.record()
-        torch.cuda.synchronize()
-        ms16 = e0.elapsed_time(e1) / reps
-        out["stored_aggregation"] = {"storage": "bf16", "stage": roofline["stage"], "ms": ms16,
-                                     "fp32_ms": roofline["ms_per_launch"],
-                                     "GB/s_algorithmic": nnz * F * 2 / ms16 / 1e6}
+        ms16 = timer.ms(lambda: Hn.aggregate_stored(pipe.graph, dst_stage.mode, Z16, F, "bf16", concat=dst_stage.concat,
+                                                    out=agg_out, workspace=ws, **kw16), reps)
+        out["stored_aggregation"] = {"storage": "bf16", "stage": out["roofline"]["stage"], "ms": ms16,
+                                     "fp32_ms": agg_ms, "GB/s_algorithmic": nnz * F * 2 / ms16 / 1e6}
         del Z16
     except B.RetexoError:
         pass
-    # the partition-shaped run: one worker's share of this graph (seeded random ownership over 4 workers for
-    # the dense graph, 2 for the large sparse one, as the paper distributes them) and the pack / unpack of all
-    # its boundary rows at the first round's width
+    # the partition-shaped run: worker 0's share of this graph (seeded random ownership over 4 workers for the
+    # dense graph, 2 for the large sparse one, as the paper distributes them); the pack of what it owes its peers,
+    # the unpack of what it receives, and the first round's aggregation on its local graph
     if w.index in (3, 4):
         n_workers = 4 if w.index == 3 else 2
         owner = torch.from_numpy(np.random.Generator(np.random.Philox(key=70 + w.index))
@@ -409,25 +455,89 @@ def main():
             share = Hn.partition_share(pipe.graph, owner, n_workers, 0)
         torch.cuda.synchronize()
         share_ms = (time.perf_counter() - t0) / reps * 1e3
-        Fp = w.stages[0].d_out
-        table = pipe.outs[0][:share.n_inner + share.n_halo]                      # any resident table of that width
-        buf = Hn.halo_pack(share.recv_ids, table, Fp)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            Hn.halo_pack(share.recv_ids, table, Fp, buf=buf)
-            Hn.halo_unpack(share.recv_ids, buf, table, Fp)
-        e1.record()
-        torch.cuda.synchronize()
-        pu_ms = e0.elapsed_time(e1) / reps
+        st0 = w.stages[0]
+        Fp = st0.d_out
+        n_local = share.n_inner + share.n_halo
+        gl = torch.Generator(device="cuda").manual_seed(99)
+        table = torch.empty((n_local, wl.pad_ld(Fp)), dtype=torch.float32, device="cuda").normal_(generator=gl)
+        n_send = int(share.send_ids.numel())
+        sbuf = torch.empty((max(n_send, 1), wl.pad_ld(Fp)), dtype=torch.float32, device="cuda")
+        rbuf = torch.empty((max(share.n_halo, 1), wl.pad_ld(Fp)), dtype=torch.float32, device="cuda").normal_(generator=gl)
+
+        def exchange_compute_side():
+            Hn.halo_pack(share.send_ids, table, Fp, buf=sbuf)        # owner side: inner rows its peers need
+            Hn.halo_unpack(share.recv_ids, rbuf, table, Fp)          # receiver side: into the boundary rows
+        pu_ms = timer.ms(exchange_compute_side, reps)
+        local = Hn.make_plan(share.graph)
+        lgat = st0.mode == "gat_softmax"
+        lkw = dict(heads=st0.heads, a_src=pipe.params[0][2], a_dst=pipe.params[0][3]) if lgat else {}
+        lout = torch.empty((n_local, wl.pad_ld(st0.out_width)), dtype=torch.float32, device="cuda")
+        lws = Hn.ws_tensor(B.retexo_workspace_bytes(local.plan, Fp, B.MODES[st0.mode], st0.heads,
+                                                    B.F_SELF_CONCAT if st0.concat else 0))
+        l_ms = timer.ms(lambda: Hn.aggregate(local, st0.mode, table, Fp, concat=st0.concat, out=lout, workspace=lws,
+                                             **lkw), reps)
+        lg = algorithmic_bytes(n_local, share.graph.nnz, Fp, st0.concat, st0.heads if lgat else 0)
+        g_ms = agg_ms if di == 0 else None
         out["partition"] = {"workers": n_workers, "inner": share.n_inner, "boundary": share.n_halo,
                             "local_entries": share.graph.nnz, "share_ms_incl_size_query_and_allocation": share_ms,
-                            "pack_plus_unpack_ms": pu_ms, "rows": share.n_halo, "width": Fp,
-                            "GB/s_read_plus_write": 4.0 * share.n_halo * Fp * 4 / pu_ms / 1e6}
-    pipe.close()
-    if not args.no_cpu:
-        default_rows = w.n_nodes      # the oracle is fast enough to run every row of every stage in 10-30 s
-        out["cpu_baseline"] = cpu_baseline(w, src, dst, feats, params, args.cpu_rows or default_rows)
+                            "send_rows": n_send, "recv_rows": share.n_halo, "width": Fp,
+                            "pack_send_plus_unpack_recv_ms": pu_ms,
+                            "GB/s_read_plus_write": 2.0 * (n_send + share.n_halo) * Fp * 4 / pu_ms / 1e6,
+                            "local_round": {"what": "first round's aggregation (%s, F=%d) on worker 0's local graph: "
+                                                    "%d rows over a table of %d rows" % (st0.mode, Fp, share.n_inner, n_local),
+                                            "ms": l_ms, "algorithmic_bytes": lg,
+                                            "effective_gather_GB/s": lg / l_ms / 1e6,
+                                            "effective_gather_frac": lg / l_ms / 1e6 / HBM_PEAK_GBS,
+                                            "hbm_measured_frac": None,
+                                            "global_round_ms": g_ms,
+                                            "global_round_ms_over_workers": None if g_ms is None else g_ms / n_workers,
+                                            "share_of_global_round": None if g_ms is None else l_ms / g_ms}}
+        local.destroy()
+        del table, sbuf, rbuf, lout, lws
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2302_13053_amd import binding as B
+
+    B.load()
+    for item in args.option:
+        name, _, value = item.partition("=")
+        B.check(B.retexo_set_option(name, int(value)), "retexo_set_option(%s)" % item)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    head_index = 3 if args.config is None else args.config
+    head = bench_workload(head_index, args)
+    if args.probe:
+        return
+    out = {
+        "metric": "aggregated edge*feature GFLOP/s per lazy-MP pass (whole path: CSR build, plan, all rounds)",
+        "value": head.pop("value"),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head.pop("ms_per_step"),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "library_sources_sha256": library_source_hash(),
+    }
+    out.update(head)
+    if args.config is None:
+        # the workload whose gathers are real HBM reads, same process, same measurement
+        also = bench_workload(4, args)
+        also["unit"] = "GFLOP/s"
+        out["also"] = also
     print(json.dumps(out))
 
 

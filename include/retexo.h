@@ -455,10 +455,14 @@ int retexo_data_volumes(double n, double B, double R, double H0, double sum_H, d
 double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, double M);
 
 /* ---------------------------------------------------------------------------
- * Tuning knobs (process-wide, for experiments; defaults are chosen per shape).
+ * Tuning knobs for experiments and tests (defaults are chosen per shape).  They are ONE set of
+ * values per process, read by every launch: set them from a single thread while no other thread
+ * is inside the library, and restore the default afterwards.  Production callers never need them.
  * name: "agg_slab_cols" (0 = auto), "agg_slab_major" (-1 auto / 0 / 1),
  *       "agg_heavy_degree" (rows at least this long get a whole workgroup),
  *       "agg_parts" (source-id ranges walked one after the other: -1 auto, 1 off, 2/4/8/16),
+ *       "agg_narrow_heavy" (narrow slabs: rows whose share of ONE source range is at least this
+ *       long get a whole workgroup; default 512),
  *       "agg_max_vec" (cap on floats per lane per gather),
  *       "agg_gat_fast" (0: plain edge-softmax kernel), "agg_gat_flash" (0: ordinary rows read the
  *       source scores from the table instead of computing them from the gathered rows),

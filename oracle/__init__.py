@@ -60,6 +60,8 @@ def _load():
         lib.oracle_aggregate_backward.argtypes = [C.c_int, i64, i64, i64p, i64p, i32p, f32p, i64, C.c_int,
                                                   f32p, i64, f32p, f32p, C.c_double, f32p, i64, C.c_int,
                                                   f64p, f64p, f64p]
+        lib.oracle_aggregate_backward_slack.restype = C.c_int
+        lib.oracle_aggregate_backward_slack.argtypes = lib.oracle_aggregate_backward.argtypes + [C.c_double, f64p]
         lib.oracle_layer_grad.restype = C.c_double
         lib.oracle_layer_grad.argtypes = [i64, i64, i64, i64, f32p, i64, i32p, f32p, f32p, f32p, f32p,
                                           f64p, f64p, f64p, f64p, f64p, u8p, C.c_double]
@@ -184,9 +186,12 @@ def aggregate_abs(mode: str, row_ptr, col_idx, Z, F: int, *, heads: int = 1, a_s
 
 
 def aggregate_backward(mode: str, row_ptr, col_idx, Z, F: int, G, *, heads: int = 1, a_src=None, a_dst=None,
-                       slope: float = 0.2, self_concat: bool = False, rows=None):
+                       slope: float = 0.2, self_concat: bool = False, rows=None, kink_rel=None):
     """Gradient of ``aggregate`` with respect to its inputs, given G = dL/d(out) ([N, F or 2F] float32).
-    -> dZ float64 [n, F] for linear modes; (dZ, da_src, da_dst) for gat (da_* None when ``rows`` is given)."""
+    -> dZ float64 [n, F] for linear modes; (dZ, da_src, da_dst) for gat (da_* None when ``rows`` is given).
+    With ``kink_rel`` given, one more item is returned: slack float64 [n, F], how far each element of dZ can
+    move when the entries whose score lies within kink_rel (relative to the size of its terms) of the
+    LeakyReLU kink take the derivative of the other side (see oracle_aggregate_backward_slack)."""
     Z, ldz = _matrix(Z)
     G, ldg = _matrix(G)
     row_ptr, col_idx = _c(row_ptr, np.int64), _c(col_idx, np.int32)
@@ -207,17 +212,26 @@ def aggregate_backward(mode: str, row_ptr, col_idx, Z, F: int, G, *, heads: int 
     rows = None if rows is None else _c(rows, np.int64)
     n = n_nodes if rows is None else rows.size
     dZ = np.empty((n, F), np.float64)
-    rc = _load().oracle_aggregate_backward(MODES[mode], n_nodes, n, _p(rows, C.c_int64), _p(row_ptr, C.c_int64),
-                                           _p(col_idx, C.c_int32), _p(dinv, C.c_float), F, heads,
-                                           _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
-                                           float(slope), _p(G, C.c_float), ldg, int(self_concat),
-                                           _p(dZ, C.c_double), _p(da_s, C.c_double), _p(da_d, C.c_double))
+    args = (MODES[mode], n_nodes, n, _p(rows, C.c_int64), _p(row_ptr, C.c_int64),
+            _p(col_idx, C.c_int32), _p(dinv, C.c_float), F, heads,
+            _p(Z, C.c_float), ldz, _p(a_src, C.c_float), _p(a_dst, C.c_float),
+            float(slope), _p(G, C.c_float), ldg, int(self_concat),
+            _p(dZ, C.c_double), _p(da_s, C.c_double), _p(da_d, C.c_double))
+    slack = None
+    if kink_rel is None:
+        rc = _load().oracle_aggregate_backward(*args)
+    else:
+        slack = np.empty((n, F), np.float64)
+        rc = _load().oracle_aggregate_backward_slack(*args, float(kink_rel), _p(slack, C.c_double))
     if rc != 0:
         raise ValueError("mode %r has no backward" % mode)
+    res = (dZ,)
     if gat:
-        return dZ, (None if da_s is None else da_s.reshape(heads, F // heads)), \
-            (None if da_d is None else da_d.reshape(heads, F // heads))
-    return dZ
+        res = (dZ, (None if da_s is None else da_s.reshape(heads, F // heads)),
+               (None if da_d is None else da_d.reshape(heads, F // heads)))
+    if slack is not None:
+        return res + (slack,)
+    return res if gat else dZ
 
 
 def gat_alpha(v: int, h: int, row_ptr, col_idx, Z, F: int, heads: int, a_src, a_dst,

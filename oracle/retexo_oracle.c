@@ -283,27 +283,26 @@ void oracle_aggregate_abs(int mode, int64_t n_rows, const int64_t *rows,
         const int64_t deg = hi - lo;
         for (int64_t j = 0; j < F; ++j) o[j] = 0.0;
         if (deg == 0) continue;
-        for (int64_t j = 0; j < F; ++j) {
-            const int h = (int)(j / Dh);
-            double s = 0.0, top = -INFINITY;
-            double *alpha = NULL;
-            if (mode == ORACLE_GAT_SOFTMAX) {
-                alpha = (double *)malloc((size_t)deg * sizeof(double));
-                oracle_gat_alpha(v, h, row_ptr, col_idx, F, heads, Z, ldz, a_src, a_dst, slope, alpha);
+        const int n_blocks = (mode == ORACLE_GAT_SOFTMAX) ? heads : 1;     /* column blocks sharing coefficients */
+        double *alpha = (mode == ORACLE_GAT_SOFTMAX) ? (double *)malloc((size_t)deg * sizeof(double)) : NULL;
+        for (int h = 0; h < n_blocks; ++h) {
+            if (alpha) oracle_gat_alpha(v, h, row_ptr, col_idx, F, heads, Z, ldz, a_src, a_dst, slope, alpha);
+            for (int64_t j = h * Dh; j < (h + 1) * Dh; ++j) {
+                double s = 0.0, top = -INFINITY;
+                for (int64_t e = lo; e < hi; ++e) {
+                    const int64_t u = col_idx[e];
+                    const double z = (double)Z[u * ldz + j];
+                    double c = 1.0;
+                    if (mode == ORACLE_MEAN) c = 1.0 / (double)deg;
+                    else if (mode == ORACLE_GCN_SYM) c = (double)dinv[v] * (double)dinv[u];
+                    else if (mode == ORACLE_GAT_SOFTMAX) c = alpha[e - lo];
+                    s += fabs(c * z);
+                    if (z > top) top = z;
+                }
+                o[j] = (mode == ORACLE_MAX) ? fabs(top) : s;
             }
-            for (int64_t e = lo; e < hi; ++e) {
-                const int64_t u = col_idx[e];
-                const double z = (double)Z[u * ldz + j];
-                double c = 1.0;
-                if (mode == ORACLE_MEAN) c = 1.0 / (double)deg;
-                else if (mode == ORACLE_GCN_SYM) c = (double)dinv[v] * (double)dinv[u];
-                else if (mode == ORACLE_GAT_SOFTMAX) c = alpha[e - lo];
-                s += fabs(c * z);
-                if (z > top) top = z;
-            }
-            free(alpha);
-            o[j] = (mode == ORACLE_MAX) ? fabs(top) : s;
         }
+        free(alpha);
     }
 }
 
@@ -357,12 +356,13 @@ void oracle_gat_alpha(int64_t v, int h, const int64_t *row_ptr, const int32_t *c
  * filled.  rows given: only those rows of dZ ([n_rows, F]); da_* untouched.
  * max has no backward here (returns -1).  Returns 0 on success.
  */
-int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t *rows,
-                              const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
-                              int64_t F, int heads, const float *Z, int64_t ldz,
-                              const float *a_src, const float *a_dst, double slope,
-                              const float *G, int64_t ldg, int self_concat,
-                              double *dZ, double *da_src, double *da_dst)
+static int aggregate_backward_impl(int mode, int64_t N, int64_t n_rows, const int64_t *rows,
+                                   const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
+                                   int64_t F, int heads, const float *Z, int64_t ldz,
+                                   const float *a_src, const float *a_dst, double slope,
+                                   const float *G, int64_t ldg, int self_concat,
+                                   double *dZ, double *da_src, double *da_dst,
+                                   double kink_rel, double *slack)
 {
     if (mode == ORACLE_MAX) return -1;
     const int gat = mode == ORACLE_GAT_SOFTMAX;
@@ -403,6 +403,8 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
     }
     double *coef = (double *)malloc((size_t)(kept ? kept : 1) * heads * sizeof(double));  /* c_vu  */
     double *dp = (double *)calloc((size_t)(kept ? kept : 1) * heads, sizeof(double));     /* dL/dp */
+    /* |change of dL/dp| if the entry's score p were taken on the other side of the LeakyReLU kink (slack only) */
+    double *ks = (slack && gat) ? (double *)calloc((size_t)(kept ? kept : 1) * heads, sizeof(double)) : NULL;
 
     /* step 1: coefficient and score gradient of every needed entry */
 #pragma omp parallel for schedule(dynamic, 4)
@@ -420,18 +422,24 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
         if (deg == 0) continue;
         double *p = (double *)malloc((size_t)deg * sizeof(double));
         double *da = (double *)malloc((size_t)deg * sizeof(double));
+        double *pmag = (double *)malloc((size_t)deg * sizeof(double));   /* size of the terms of p (slack only) */
         for (int h = 0; h < heads; ++h) {
             const float *as = a_src + (int64_t)h * Dh, *ad = a_dst + (int64_t)h * Dh;
             const float *zv = Z + v * ldz + h * Dh, *gv = Ga + v * ldg + h * Dh;
-            double er = 0.0, m = -INFINITY, denom = 0.0, mean_da = 0.0;
-            for (int64_t d = 0; d < Dh; ++d) er += (double)ad[d] * (double)zv[d];
+            double er = 0.0, er_mag = 0.0, m = -INFINITY, denom = 0.0, mean_da = 0.0;
+            for (int64_t d = 0; d < Dh; ++d) {
+                er += (double)ad[d] * (double)zv[d];
+                er_mag += fabs((double)ad[d] * (double)zv[d]);
+            }
             for (int64_t e = lo; e < hi; ++e) {
                 const float *zu = Z + (int64_t)col_idx[e] * ldz + h * Dh;
-                double el = 0.0, g = 0.0;
+                double el = 0.0, g = 0.0, el_mag = 0.0;
                 for (int64_t d = 0; d < Dh; ++d) {
                     el += (double)as[d] * (double)zu[d];
+                    el_mag += fabs((double)as[d] * (double)zu[d]);
                     g += (double)gv[d] * (double)zu[d];
                 }
+                pmag[e - lo] = el_mag + er_mag;
                 p[e - lo] = el + er;
                 da[e - lo] = g;
                 if (leaky(p[e - lo], slope) > m) m = leaky(p[e - lo], slope);
@@ -441,11 +449,15 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
                 cv[j * heads + h] = exp(leaky(p[j], slope) - m) / denom;
                 mean_da += cv[j * heads + h] * da[j];
             }
-            for (int64_t j = 0; j < deg; ++j)
+            for (int64_t j = 0; j < deg; ++j) {
                 dv[j * heads + h] = cv[j * heads + h] * (da[j] - mean_da) * (p[j] > 0.0 ? 1.0 : slope);
+                if (ks && fabs(p[j]) <= kink_rel * pmag[j])
+                    ks[(off[v] + j) * heads + h] = fabs(cv[j * heads + h] * (da[j] - mean_da) * (1.0 - slope));
+            }
         }
         free(p);
         free(da);
+        free(pmag);
     }
 
     /* step 2: collect what flows into each requested node */
@@ -469,6 +481,23 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
                 for (int h = 0; h < heads; ++h)
                     for (int64_t d = 0; d < Dh; ++d) o[h * Dh + d] += dp[q + h] * (double)a_dst[h * Dh + d];
             }
+        if (slack) {
+            double *sl = slack + i * F;
+            for (int64_t j = 0; j < F; ++j) sl[j] = 0.0;
+            if (ks) {
+                for (int64_t k = t_ptr[u]; k < t_ptr[u + 1]; ++k) {
+                    const int64_t e = t_ent[k], v = t_row[k];
+                    const int64_t q = (off[v] + (e - row_ptr[v])) * heads;
+                    for (int h = 0; h < heads; ++h)
+                        for (int64_t d = 0; d < Dh; ++d) sl[h * Dh + d] += ks[q + h] * fabs((double)a_src[h * Dh + d]);
+                }
+                for (int64_t e = row_ptr[u]; e < row_ptr[u + 1]; ++e) {
+                    const int64_t q = (off[u] + (e - row_ptr[u])) * heads;
+                    for (int h = 0; h < heads; ++h)
+                        for (int64_t d = 0; d < Dh; ++d) sl[h * Dh + d] += ks[q + h] * fabs((double)a_dst[h * Dh + d]);
+                }
+            }
+        }
     }
 
     /* step 3: gradients of the attention vectors (sums over every entry of the graph) */
@@ -484,8 +513,42 @@ int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t
                     }
             }
     }
-    free(coef); free(dp); free(need); free(off); free(t_ptr); free(t_ent); free(t_row);
+    free(coef); free(dp); free(ks); free(need); free(off); free(t_ptr); free(t_ent); free(t_row);
     return 0;
+}
+
+int oracle_aggregate_backward(int mode, int64_t N, int64_t n_rows, const int64_t *rows,
+                              const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
+                              int64_t F, int heads, const float *Z, int64_t ldz,
+                              const float *a_src, const float *a_dst, double slope,
+                              const float *G, int64_t ldg, int self_concat,
+                              double *dZ, double *da_src, double *da_dst)
+{
+    return aggregate_backward_impl(mode, N, n_rows, rows, row_ptr, col_idx, dinv, F, heads, Z, ldz, a_src, a_dst,
+                                   slope, G, ldg, self_concat, dZ, da_src, da_dst, 0.0, NULL);
+}
+
+/*
+ * The same gradient, plus how much each element of dZ depends on a decision no float32 evaluation can
+ * be held to: the derivative of LeakyReLU jumps from slope to 1 at p = 0, and an entry whose score
+ * p_vu = <a_src,z_u> + <a_dst,z_v> lies within rounding of zero can land on either side.  Both values
+ * are then correct results of the method (the forward pass is continuous there).  An entry counts as
+ * undecided when |p_vu| <= kink_rel * (sum_d |a_src,d z_u,d| + sum_d |a_dst,d z_v,d|), i.e. within
+ * kink_rel of the size of the terms p is the sum of; taking the other side changes dL/dp_vu by
+ * (1 - slope) |alpha_vu (dL/dalpha_vu - c_v)|, which reaches dZ_u through |a_src| and dZ_v through |a_dst|.
+ * slack[i, :] (n_rows x F) receives the sum of those magnitudes for row rows[i]; it is zero for a row
+ * that no undecided entry touches, and zero everywhere for the modes without a kink.
+ */
+int oracle_aggregate_backward_slack(int mode, int64_t N, int64_t n_rows, const int64_t *rows,
+                                    const int64_t *row_ptr, const int32_t *col_idx, const float *dinv,
+                                    int64_t F, int heads, const float *Z, int64_t ldz,
+                                    const float *a_src, const float *a_dst, double slope,
+                                    const float *G, int64_t ldg, int self_concat,
+                                    double *dZ, double *da_src, double *da_dst,
+                                    double kink_rel, double *slack)
+{
+    return aggregate_backward_impl(mode, N, n_rows, rows, row_ptr, col_idx, dinv, F, heads, Z, ldz, a_src, a_dst,
+                                   slope, G, ldg, self_concat, dZ, da_src, da_dst, kink_rel, slack);
 }
 
 /* ---------------------------------------------------------------------------

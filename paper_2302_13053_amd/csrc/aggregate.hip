@@ -1619,11 +1619,12 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         a.er = er;
         // the plain forward over rows whose scores all come from the gathered rows needs no table
         const bool no_table = flash && !c.save && N > n_heavy && aligned_for(c.attn_dst, 4, 4);
+        // only the pipelined kernel keeps the backward's statistics: decided before anything is launched,
+        // so that the error leaves the workspace and the output untouched
+        if (c.save && !(vec == 4 && off32 && opt.gat_fast)) return RETEXO_E_FLAGS;
         if (!no_table)
             launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream, a.el_stride);
         if (c.save) {
-            // only the pipelined kernel keeps the backward's statistics
-            if (!(vec == 4 && off32 && opt.gat_fast)) return RETEXO_E_FLAGS;
             const GatWorkspace w = gat_workspace(N, c.F, c.heads, true);
             a.save_stats = (f32x4*)((char*)c.workspace + w.stats);
             a.save_pos = (float*)((char*)c.workspace + w.pos);

@@ -232,16 +232,35 @@ extern "C" int32_t retexo_plan_max_degree(const retexo_plan* p) { return p ? p->
 extern "C" const int32_t* retexo_plan_deg(const retexo_plan* p) { return p ? p->deg : nullptr; }
 extern "C" const float* retexo_plan_dinv(const retexo_plan* p) { return p ? p->dinv : nullptr; }
 
+namespace {
+// dst[i] = src[i] for i < n words; the exports are kernels (not copy nodes) so that a caller may record them
+// into a HIP graph like every other stream-ordered entry point
+__global__ __launch_bounds__(kThreads) void copy_words_kernel(int64_t n, const uint32_t* __restrict__ src,
+                                                              uint32_t* __restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+int copy_words(int64_t n, const void* src, void* dst, hipStream_t stream)
+{
+    if (n <= 0) return RETEXO_OK;
+    copy_words_kernel<<<dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+        n, (const uint32_t*)src, (uint32_t*)dst);
+    return hipGetLastError() == hipSuccess ? RETEXO_OK : RETEXO_E_HIP;
+}
+}  // namespace
+
 extern "C" int retexo_plan_export(const retexo_plan* p, int32_t* d_deg, float* d_dinv, int32_t* d_order,
                                   void* stream_)
 {
     if (!p) return RETEXO_E_NULL;
     hipStream_t stream = (hipStream_t)stream_;
-    const size_t n = (size_t)p->N;
+    const int64_t n = p->N;
     if (n == 0) return RETEXO_OK;
-    if (d_deg) RETEXO_HIP_TRY(hipMemcpyAsync(d_deg, p->deg, n * 4, hipMemcpyDeviceToDevice, stream));
-    if (d_dinv) RETEXO_HIP_TRY(hipMemcpyAsync(d_dinv, p->dinv, n * 4, hipMemcpyDeviceToDevice, stream));
-    if (d_order) RETEXO_HIP_TRY(hipMemcpyAsync(d_order, p->order, n * 4, hipMemcpyDeviceToDevice, stream));
+    if (d_deg) if (int e = copy_words(n, p->deg, d_deg, stream)) return e;
+    if (d_dinv) if (int e = copy_words(n, p->dinv, d_dinv, stream)) return e;
+    if (d_order) if (int e = copy_words(n, p->order, d_order, stream)) return e;
     return RETEXO_OK;
 }
 
@@ -252,7 +271,6 @@ extern "C" int64_t retexo_plan_export_split(const retexo_plan* p, int32_t* d_pos
     if (!p) return RETEXO_E_NULL;
     if (!p->part_ptr) return 0;
     if (d_pos)
-        RETEXO_HIP_TRY(hipMemcpyAsync(d_pos, p->part_ptr, (size_t)p->N * (kMaxParts + 1) * sizeof(int32_t),
-                                      hipMemcpyDeviceToDevice, (hipStream_t)stream_));
+        if (int e = copy_words(p->N * (kMaxParts + 1), p->part_ptr, d_pos, (hipStream_t)stream_)) return e;
     return p->part_span;
 }

@@ -7,7 +7,7 @@ import oracle
 from paper_2302_13053_amd import binding as B
 from paper_2302_13053_amd import harness as Hn
 from paper_2302_13053_amd import workloads as wl
-from parity import assert_close
+from parity import assert_close, assert_cond_close
 
 pytestmark = pytest.mark.gpu
 
@@ -94,8 +94,20 @@ def check_params(das, dad, want, what):
 ])
 def test_linear_modes_match_oracle(graphs, mode, F, ld, concat, offset):
     got, _, _, want = run_case(graphs, "skewed", mode, F, ld, 1, concat, seed=F + 3, offset=offset)
-    # narrow rows of signed terms can cancel to nothing (see the forward tests): bound by the row's terms instead
-    assert_close(got, want, tol=1e-5 if F >= 64 else 2e-4, what="%s backward F=%d" % (mode, F))
+    # every element within 1e-5 of the size of its terms.  The graph is symmetric, so dZ_u = sum_v c_vu G_v is
+    # again an aggregate of G: sum and gcn_sym with the same coefficients, mean with 1/deg of the destination
+    g, rp, ci = graphs[("skewed", mode == "gcn_sym")]
+    Gh = wl.random_matrix(g.n_nodes, 2 * F if concat else F, F + 3 + 1, ld=ld if not concat else ld + F)
+    Ga = np.ascontiguousarray(Gh[:, F:2 * F] if concat else Gh[:, :F])
+    if mode == "mean":
+        Ga = (Ga / np.maximum(np.diff(rp), 1)[:, None]).astype(np.float32)
+    mag = oracle.aggregate_abs("sum" if mode == "mean" else mode, rp, ci, Ga, F)
+    if concat:
+        mag = mag + np.abs(Gh[:, :F].astype(np.float64))
+    assert_cond_close(got, want, mag, what="%s backward F=%d" % (mode, F))
+    # rows of at least 64 columns also within 1e-5 of the row's largest magnitude
+    if F >= 64:
+        assert_close(got, want, what="%s backward F=%d" % (mode, F))
     for name in ("flat", "tiny"):
         got, _, _, want = run_case(graphs, name, mode, 96, 96, 1, concat, seed=5)
         assert_close(got, want, what="%s backward %s" % (mode, name))
@@ -211,9 +223,9 @@ def test_mid_size_graph_parameter_gradients():
     g.destroy()
 
 
-def test_full_size_products_shape_sampled_rows():
+def test_full_size_products_shape_all_rows():
     """The edge-softmax backward on the large attention workload's graph at full size (2.4 M nodes,
-    124 M entries, 4 heads of 64), on sampled rows of dZ that include the longest row.  The
+    124 M entries, 4 heads of 64), on every row of dZ.  The
     attention-vector gradients are sums over the whole graph that the oracle cannot produce at this
     size in test time; they are covered by the mid-size case above and here by a property that holds
     at any size: slope 1 leaves da_dst at rounding level."""
@@ -225,10 +237,8 @@ def test_full_size_products_shape_sampled_rows():
     rp, ci = oracle.csr_from_coo(src, dst, w.n_nodes, False)
     del src, dst
     n, F, heads = w.n_nodes, 256, 4
-    deg = np.diff(rp)
-    rng = np.random.Generator(np.random.Philox(key=61))
-    rows = np.unique(np.concatenate([rng.integers(0, n, 40), [int(np.argmax(deg))], np.flatnonzero(deg == 0)[:2],
-                                     np.flatnonzero(deg == 1)[:2]])).astype(np.int64)
+    rows = np.arange(n, dtype=np.int64)        # every row of dZ (given as a list: the oracle then skips its
+                                               # serial sum over the whole graph for the attention vectors)
     Zh, Gh = wl.random_matrix(n, F, 62), wl.random_matrix(n, F, 63)
     a_s = wl.random_matrix(heads, F // heads, 64) * np.float32(0.2)
     a_d = wl.random_matrix(heads, F // heads, 65) * np.float32(0.2)
@@ -236,10 +246,32 @@ def test_full_size_products_shape_sampled_rows():
     print("gpu backward", flush=True)
     dZ, das, dad = Hn.aggregate_backward(g, "gat_softmax", F, G, Z=Z, heads=heads, a_src=As, a_dst=Ad)
     torch.cuda.synchronize()
-    got = dZ[torch.from_numpy(rows).cuda()].cpu().numpy()[:, :F]
-    print("oracle rows", flush=True)
-    want, _, _ = oracle.aggregate_backward("gat_softmax", rp, ci, Zh, F, Gh, heads=heads, a_src=a_s, a_dst=a_d, rows=rows)
-    assert_close(got, want, what="gat backward full size")
+    print("oracle: all %d rows of dZ" % n, flush=True)
+    # The derivative of LeakyReLU jumps at a score of exactly zero.  Among the 5e8 (entry, head) scores of this
+    # graph a few lie within float32 rounding of zero, where the kernel's float32 score and the oracle's float64
+    # score can fall on different sides: both derivatives are then correct results of the method.  The oracle
+    # reports, per element of dZ, how far such undecided entries can move it (zero for almost every row); rows
+    # without any are held to the plain bound, the others to the bound plus that amount.
+    # An entry counts as undecided within 4e-6 of the size of its score's terms (64-term float32 inner products).
+    want, _, _, slack = oracle.aggregate_backward("gat_softmax", rp, ci, Zh, F, Gh, heads=heads, a_src=a_s, a_dst=a_d,
+                                                  rows=rows, kink_rel=4e-6)
+    worst = 0.0
+    n_slack = n_moved = 0
+    for lo in range(0, n, 1 << 18):
+        got = dZ[lo:lo + (1 << 18), :F].cpu().numpy().astype(np.float64)
+        w_, s_ = want[lo:lo + (1 << 18)], slack[lo:lo + (1 << 18)]
+        free = s_.max(axis=1) == 0.0
+        worst = max(worst, assert_close(got[free], w_[free], what="gat backward full size, rows %d.." % lo))
+        den = np.abs(w_[~free]).max(axis=1, keepdims=True)
+        over = np.abs(got[~free] - w_[~free]) - (1e-5 * den + s_[~free])
+        assert over.max(initial=-1.0) <= 0.0, "rows %d..: an element beyond the bound plus the kink slack by %.3e" % (lo, over.max())
+        n_slack += int((~free).sum())
+        n_moved += int(((np.abs(got[~free] - w_[~free]).max(axis=1) / den[:, 0]) > 1e-5).sum())
+    print("gat backward full size: all %d rows, worst row-normwise error %.2e on the %d rows without an undecided "
+          "entry; %d rows touch one, %d of them differ by more than 1e-5 (within the slack)"
+          % (n, worst, n - n_slack, n_slack, n_moved), flush=True)
+    del slack
+    del want
     assert np.all(np.isfinite(das.cpu().numpy())) and np.all(np.isfinite(dad.cpu().numpy()))
     _, das1, dad1 = Hn.aggregate_backward(g, "gat_softmax", F, G, Z=Z, heads=heads, a_src=As, a_dst=Ad, slope=1.0, dZ=dZ)
     torch.cuda.synchronize()

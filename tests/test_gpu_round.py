@@ -1,6 +1,6 @@
 """Whole rounds (retexo_round / retexo_transform chained as the workloads
 prescribe) against the oracle: the three small workloads end to end, and the
-two large ones stage by stage on sampled rows at full size."""
+two large ones stage by stage on every row at full size."""
 import numpy as np
 import pytest
 import torch
@@ -9,7 +9,7 @@ import oracle
 from paper_2302_13053_amd import binding as B
 from paper_2302_13053_amd import harness as Hn
 from paper_2302_13053_amd import workloads as wl
-from parity import assert_close
+from parity import assert_close, assert_cond_close
 
 pytestmark = pytest.mark.gpu
 
@@ -182,23 +182,37 @@ def test_one_partitions_share_matches_the_global_result():
         g.destroy()
 
 
-def sample_rows(rp, k, seed):
-    deg = np.diff(rp)
-    rng = np.random.Generator(np.random.Philox(key=seed))
-    heavy = np.argsort(deg)[-3:]
-    light = np.argsort(deg)[:3]
-    rnd = rng.integers(0, deg.size, k)
-    return np.unique(np.concatenate([heavy, light, rnd])).astype(np.int64)
+BLOCK = 1 << 17          # rows per comparison block: bounds the float64 temporaries at full size
+
+
+def compare_all_rows(got_dev, st, want_rows, mag_rows, what):
+    """Every row of one stage: ``got_dev`` (device, [n, ld]) against ``want_rows(block)`` (float64 rows of the
+    oracle for the int64 row ids ``block``), block by block.  Returns the oracle's rows as float32 (the next
+    stage's input), the worst row-normwise error and, when ``mag_rows`` is given, the worst element-wise error
+    relative to the size of the element's terms."""
+    n = got_dev.shape[0]
+    nxt = np.zeros((n, wl.pad_ld(st.out_width)), np.float32)
+    worst = worst_cond = 0.0
+    for lo in range(0, n, BLOCK):
+        block = np.arange(lo, min(n, lo + BLOCK), dtype=np.int64)
+        want = want_rows(block)
+        got = got_dev[lo:lo + block.size, :st.out_width].cpu().numpy()
+        worst = max(worst, assert_close(got, want, what="%s rows %d.." % (what, lo)))
+        if mag_rows is not None:
+            worst_cond = max(worst_cond, assert_cond_close(got, want, mag_rows(block), what="%s rows %d.." % (what, lo)))
+        nxt[lo:lo + block.size, :st.out_width] = want
+    return nxt, worst, worst_cond
 
 
 @pytest.mark.parametrize("idx", [3, 4])
-def test_large_workloads_full_size_sampled_rows(idx):
-    """Each stage of the two large workloads at full size, in the launch
-    configuration the benchmark uses.  Stage 0 takes the workload's own
-    features; later stages take a seeded random matrix of the right shape (a
-    chained comparison would need the oracle's full previous output).  The
-    oracle evaluates a sample of rows that includes the longest rows."""
+def test_large_workloads_full_size_all_rows(idx):
+    """Every row of every stage of the two large workloads at full size, in the launch configuration the
+    benchmark uses.  The stages are chained through the oracle: stage i runs on the float32 copy of the
+    oracle's own output of stage i-1 (uploaded), so no stage is judged on another stage's rounding.
+    Then the exact pins on the same graph: a sum over ones is the degree, a sum over small integers is
+    exact whatever the order, the self half of a concatenated output is a bit copy — for all rows."""
     w = wl.workload(idx)
+    n = w.n_nodes
     print("generating workload", idx, flush=True)
     src, dst = wl.make_graph(w)
     feats = wl.make_features(w, ld=wl.pad_ld(w.feat_dim))
@@ -208,29 +222,59 @@ def test_large_workloads_full_size_sampled_rows(idx):
     pipe.build_graph()
     torch.cuda.synchronize()
     print("oracle csr", flush=True)
-    rp, ci = oracle.csr_from_coo(src, dst, w.n_nodes, w.self_loops)
+    rp, ci = oracle.csr_from_coo(src, dst, n, w.self_loops)
     assert np.array_equal(pipe.row_ptr.cpu().numpy(), rp)
     assert np.array_equal(pipe.col_idx[:pipe.graph.nnz].cpu().numpy(), ci)
     deg, dinv, _ = Hn.plan_arrays(pipe.graph)
     odeg, odinv = oracle.degree(rp)
     assert np.array_equal(deg, odeg) and np.array_equal(dinv.view(np.uint32), odinv.view(np.uint32))
     del src, dst
-    rows = sample_rows(rp, 24 if idx == 3 else 200, seed=idx)
+    H = feats
     for i, st in enumerate(w.stages):
-        print("stage", i, st, flush=True)
-        if i == 0:
-            H = feats
-        else:
-            H = wl.random_matrix(w.n_nodes, st.d_in, 100 + i, ld=wl.pad_ld(st.d_in))
-            pipe.outs[i - 1].copy_(torch.from_numpy(H))
+        p = params[i]
+        if i > 0:
+            pipe.outs[i - 1].copy_(torch.from_numpy(H))          # the oracle's previous output, as float32
         pipe.run_stage(i)
         torch.cuda.synchronize()
-        got = pipe.outs[i][torch.from_numpy(rows).cuda()].cpu().numpy()[:, :st.out_width]
-        want = oracle_stage(st, rp, ci, H, params[i], rows=rows)
-        assert_close(got, want, what="workload %d stage %d full size" % (idx, i))
-        # property that holds at any size: the self half of a concatenated output is a bit copy
-        if st.kind == "round" and st.concat and not st.w:
-            chk = torch.from_numpy(rows[:8]).cuda()
-            assert torch.equal(pipe.outs[i][chk][:, :st.d_out], pipe.H0[chk][:, :st.d_out])
-        del H
+        what = "workload %d stage %d (%s)" % (idx, i, st.kind)
+        mag_rows = None
+        if st.kind == "transform":
+            want_rows = lambda b: oracle.transform(H, st.d_in, p.W, p.b, st.relu, rows=b)
+        elif st.kind == "head_mean":
+            want_rows = lambda b: oracle.head_mean(H[b], st.heads, st.d_out)
+        else:
+            # the round as the pipeline stores it: Z rounded to float32 (all rows, once), then aggregated
+            Z32 = H if p.W is None else oracle.transform(H, st.d_in, p.W, p.b, st.relu).astype(np.float32)
+            kw = dict(heads=st.heads, a_src=p.a_src, a_dst=p.a_dst, self_concat=st.concat)
+            want_rows = lambda b: oracle.aggregate(st.mode, rp, ci, Z32, st.d_out, rows=b, **kw)
+            if i == 0:      # the size of every element's terms, for the first (widest) aggregation
+                mag_rows = lambda b: oracle.aggregate_abs(st.mode, rp, ci, Z32, st.d_out, rows=b, **kw)
+        H, worst, worst_cond = compare_all_rows(pipe.outs[i], st, want_rows, mag_rows, what)
+        print("%s: all %d rows, worst row-normwise error %.2e, relative to the terms %.2e"
+              % (what, n, worst, worst_cond), flush=True)
+        if st.kind == "round" and st.concat:
+            Zsrc = pipe.H0 if i == 0 else None
+            if Zsrc is not None:     # identity round: the self half is a bit copy of the input, every row
+                assert torch.equal(pipe.outs[i][:, :st.d_out], Zsrc[:, :st.d_out])
+    del H
+    # exact pins on this graph, all rows, through the kernels this graph's plan selects
+    g = pipe.graph
+    F1 = w.stages[0].d_out
+    ones = torch.ones((n, wl.pad_ld(F1)), dtype=torch.float32, device="cuda")
+    out = Hn.aggregate(g, "sum", ones, F1)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:, :F1], torch.from_numpy(odeg.astype(np.float32)).cuda()[:, None].expand(n, F1))
+    out = Hn.aggregate(g, "mean", ones, F1)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:, :F1], torch.from_numpy((odeg > 0).astype(np.float32)).cuda()[:, None].expand(n, F1))
+    del ones, out
+    Fi = 64
+    ints = wl.random_matrix(n, Fi, 900 + idx, ld=Fi, kind="smallint")
+    out = Hn.aggregate(g, "sum", Hn.dev(ints), Fi, concat=True)
+    torch.cuda.synchronize()
+    for lo in range(0, n, BLOCK):
+        block = np.arange(lo, min(n, lo + BLOCK), dtype=np.int64)
+        want = oracle.aggregate("sum", rp, ci, ints, Fi, self_concat=True, rows=block)
+        assert np.array_equal(out[lo:lo + block.size, :2 * Fi].cpu().numpy().astype(np.float64), want), lo
+    print("exact pins: ones -> degree (F=%d), small integers bit-exact (F=%d), all %d rows" % (F1, Fi, n), flush=True)
     pipe.close()

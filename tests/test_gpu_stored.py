@@ -11,7 +11,7 @@ from oracle import storage as ost
 from paper_2302_13053_amd import binding as B
 from paper_2302_13053_amd import harness as Hn
 from paper_2302_13053_amd import workloads as wl
-from parity import assert_close
+from parity import assert_close, assert_cond_close
 
 pytestmark = pytest.mark.gpu
 
@@ -50,7 +50,7 @@ def test_store_rows_is_bit_exact(fmt):
     assert B.retexo_store_rows(3, 1, 1, 1, 1, 1, 1) == -4 and B.retexo_store_rows(1, 5, 9, 1, 8, 1, 9) == -3
 
 
-def run_case(graphs, name, mode, fmt, F, ld16, heads, concat, seed, kind="normal"):
+def run_case(graphs, name, mode, fmt, F, ld16, heads, concat, seed, kind="normal", with_mag=False):
     g, rp, ci = graphs[(name, mode == "gcn_sym")]
     n = g.n_nodes
     Zh = wl.random_matrix(n, F, seed, kind=kind)
@@ -69,6 +69,9 @@ def run_case(graphs, name, mode, fmt, F, ld16, heads, concat, seed, kind="normal
     got = out.cpu().numpy()
     assert np.all(got[:, ow:] == 555.0)
     want = oracle.aggregate(mode, rp, ci, stored, F, heads=heads, a_src=a_s, a_dst=a_d, self_concat=concat)
+    if with_mag:
+        mag = oracle.aggregate_abs(mode, rp, ci, stored, F, heads=heads, a_src=a_s, a_dst=a_d, self_concat=concat)
+        return got[:, :ow], want, mag
     return got[:, :ow], want
 
 
@@ -87,12 +90,15 @@ def run_case(graphs, name, mode, fmt, F, ld16, heads, concat, seed, kind="normal
 def test_stored_modes_match_oracle_on_skewed_graph(graphs, fmt, mode, F, ld16, heads, concat):
     if mode == "gat_softmax" and F % heads:
         heads = 1
-    kind = "normal" if F >= 64 else "absnormal"
-    got, want = run_case(graphs, "skewed", mode, fmt, F, ld16, heads, concat, seed=F + 31, kind=kind)
+    # signed data at every width: each element within 1e-5 of the size of its terms, and rows of at least 64
+    # columns also within 1e-5 of the row's largest magnitude
+    got, want, mag = run_case(graphs, "skewed", mode, fmt, F, ld16, heads, concat, seed=F + 31, with_mag=True)
     if mode == "max":
         assert np.array_equal(got.astype(np.float64), want)
     else:
-        assert_close(got, want, what="%s %s F=%d" % (fmt, mode, F))
+        assert_cond_close(got, want, mag, what="%s %s F=%d" % (fmt, mode, F))
+        if F >= 64:
+            assert_close(got, want, what="%s %s F=%d" % (fmt, mode, F))
     if concat:
         assert np.array_equal(got[:, :F].astype(np.float64), want[:, :F])      # self half: the stored value, widened
 
@@ -141,7 +147,7 @@ def test_stored_argument_errors(graphs):
 @pytest.mark.parametrize("idx", [3, 4])
 def test_full_size_stored_first_round(idx):
     """The first round's aggregation of the two large workloads on a bf16 table at full size (the launch
-    configuration chosen automatically), sampled rows against the oracle on the stored values."""
+    configuration chosen automatically), every row against the oracle on the stored values."""
     w = wl.workload(idx)
     print("generating workload", idx, flush=True)
     src, dst = wl.make_graph(w)
@@ -161,16 +167,16 @@ def test_full_size_stored_first_round(idx):
         kw = dict(heads=st.heads, a_src=Hn.dev(p_.a_src), a_dst=Hn.dev(p_.a_dst))
     out = Hn.aggregate_stored(g, st.mode, Z16, F, "bf16", concat=st.concat, **kw)
     torch.cuda.synchronize()
-    deg = np.diff(rp)
-    rng = np.random.Generator(np.random.Philox(key=idx))
-    rows = np.unique(np.concatenate([rng.integers(0, n, 24 if idx == 3 else 100), [int(np.argmax(deg))],
-                                     np.flatnonzero(deg == 0)[:1]])).astype(np.int64)
-    print("oracle rows", flush=True)
+    print("oracle: all %d rows" % n, flush=True)
     stored = ost.load(ost.store(Zh[:, :F], "bf16"), "bf16")
-    ref = oracle.aggregate(st.mode, rp, ci, stored, F, heads=st.heads, a_src=p_.a_src, a_dst=p_.a_dst,
-                           self_concat=st.concat, rows=rows)
-    got = out[torch.from_numpy(rows).cuda()].cpu().numpy()[:, :ref.shape[1]]
-    assert_close(got, ref, what="workload %d bf16 first round" % idx)
+    worst = 0.0
+    for lo in range(0, n, 1 << 17):
+        rows = np.arange(lo, min(n, lo + (1 << 17)), dtype=np.int64)
+        ref = oracle.aggregate(st.mode, rp, ci, stored, F, heads=st.heads, a_src=p_.a_src, a_dst=p_.a_dst,
+                               self_concat=st.concat, rows=rows)
+        got = out[lo:lo + rows.size, :ref.shape[1]].cpu().numpy()
+        worst = max(worst, assert_close(got, ref, what="workload %d bf16 first round, rows %d.." % (idx, lo)))
+    print("workload %d bf16 table: all %d rows, worst row-normwise error %.2e" % (idx, n, worst), flush=True)
     # timing beside the fp32 path (printed with -s)
     ws = Hn.ws_tensor(max(B.retexo_workspace_bytes(g.plan, F, B.MODES[st.mode], st.heads, 0), 256))
     o32 = torch.empty_like(out)
@@ -198,16 +204,22 @@ def test_full_size_stored_first_round(idx):
 def test_stored_edge_softmax_with_scores_from_gathered_rows(graphs, fmt, F, heads, concat):
     # ordinary rows compute <a_src, z_u> from the stored row they gather; long rows and head widths that are
     # not a power-of-two number of lanes read the score table: both against the oracle, and each other
-    kind = "normal" if F >= 64 else "absnormal"
-    results = {}
+    wide = F >= 64
+    results, mags = {}, {}
     try:
         for flash in (1, 0):
             B.retexo_set_option("agg_gat_flash", flash)
             for name in ("skewed", "flat", "tiny"):
-                got, want = run_case(graphs, name, "gat_softmax", fmt, F, F, heads, concat, seed=F + heads, kind=kind)
-                assert_close(got, want, what="%s gat F=%d heads=%d flash=%d %s" % (fmt, F, heads, flash, name))
+                got, want, mag = run_case(graphs, name, "gat_softmax", fmt, F, F, heads, concat, seed=F + heads,
+                                          with_mag=True)
+                what = "%s gat F=%d heads=%d flash=%d %s" % (fmt, F, heads, flash, name)
+                assert_cond_close(got, want, mag, what=what)
+                if wide:
+                    assert_close(got, want, what=what)
                 results[(flash, name)] = got
+                mags[name] = mag
     finally:
         B.retexo_set_option("agg_gat_flash", 1)
     for name in ("skewed", "flat", "tiny"):
-        assert_close(results[(1, name)], results[(0, name)].astype(np.float64), what="flash vs table " + name)
+        assert_cond_close(results[(1, name)], results[(0, name)].astype(np.float64), mags[name],
+                          what="flash vs table " + name)

@@ -258,3 +258,46 @@ def test_attention_layer_chain_matches_end_to_end_autograd():
         ref = ref.grad.numpy()
         assert np.abs(ref).max() > 1e-4, name
         assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max(), name
+
+
+def test_kink_slack_is_the_jump_across_the_leaky_relu_kink():
+    """An entry whose score is exactly zero sits on the kink of LeakyReLU; the slack output must be the size of
+    the jump dZ makes when that score moves from just below to just above zero, on the two rows the entry
+    touches, and zero on every other row.  (Pins oracle_aggregate_backward_slack against the oracle's own
+    gradient on perturbed inputs: the jump is a property of the definition, not of the slack code.)"""
+    n, F = 7, 2
+    src = np.array([0, 0, 1, 2, 3, 4, 5], np.int32)
+    dst = np.array([1, 2, 2, 3, 4, 5, 6], np.int32)
+    rp, ci = oracle.csr_from_coo(src, dst, n, False)
+    rng = np.random.Generator(np.random.Philox(key=91))
+    Z = rng.standard_normal((n, F)).astype(np.float32)
+    G = rng.standard_normal((n, F)).astype(np.float32)
+    a_src = np.array([[1.0, 0.0]], np.float32)
+    a_dst = np.array([[0.0, 1.0]], np.float32)
+    v, u = 2, 3                              # entry (v, u): p = z_u[0] + z_v[1]
+    Z[v, 1] = -0.5
+    Z[u, 0] = 0.5
+    kw = dict(heads=1, a_src=a_src, a_dst=a_dst, slope=0.2)
+    dZ, _, _, slack = oracle.aggregate_backward("gat_softmax", rp, ci, Z, F, G, kink_rel=1e-9, **kw)
+    assert np.array_equal(dZ, oracle.aggregate_backward("gat_softmax", rp, ci, Z, F, G, **kw)[0])
+    eps = np.float32(2.0 ** -20)
+    Zp, Zm = Z.copy(), Z.copy()
+    Zp[u, 0] += eps
+    Zm[u, 0] -= eps
+    jump = np.abs(oracle.aggregate_backward("gat_softmax", rp, ci, Zp, F, G, **kw)[0]
+                  - oracle.aggregate_backward("gat_softmax", rp, ci, Zm, F, G, **kw)[0])
+    touched = np.zeros(n, bool)
+    touched[[u, v]] = True
+    assert np.all(slack[~touched] == 0.0)
+    assert slack[u, 0] > 1e-3 and slack[v, 1] > 1e-3          # through a_src into row u, through a_dst into row v
+    assert slack[u, 1] == 0.0 and slack[v, 0] == 0.0          # the zero components of the attention vectors
+    assert np.allclose(slack[touched], jump[touched], rtol=0, atol=2e-5)
+    assert np.all(jump[~touched] <= 2e-5)
+    # no undecided entry: no slack; a wide band makes every entry undecided; modes without a kink have none
+    Z2 = Z.copy()
+    Z2[u, 0] = 0.75
+    assert np.all(oracle.aggregate_backward("gat_softmax", rp, ci, Z2, F, G, kink_rel=1e-9, **kw)[3] == 0.0)
+    wide = oracle.aggregate_backward("gat_softmax", rp, ci, Z2, F, G, kink_rel=10.0, **kw)[3]
+    assert np.all(wide[:, 0][np.diff(rp) > 0] > 0)
+    lin = oracle.aggregate_backward("mean", rp, ci, Z, F, G, kink_rel=1.0)
+    assert np.all(lin[1] == 0.0)
