@@ -469,7 +469,9 @@ double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, d
  *       "agg_gat_in_rows" (0: retexo_round keeps the source scores in the table even when the unused
  *       columns of its own Z rows could hold them),
  *       "agg_wide_offsets" (1: 64-bit row offsets even for tables below 4 GiB; these four exist
- *       so that tests reach every code path).
+ *       so that tests reach every code path),
+ *       "csr_sorted_keys" (1: retexo_csr_from_coo uses its general sorted-key construction, which
+ *       otherwise only graphs of more than 2^23 nodes take, instead of the bucketing one).
  * Returns RETEXO_E_FLAGS for an unknown name.
  */
 int retexo_set_option(const char* name, int64_t value);

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libretexo.so")
 
-SOURCES = ["retexo_api.hip", "csr_build.hip", "plan.hip", "transform.hip", "aggregate.hip", "aggregate_backward.hip", "aggregate_stored.hip", "train.hip", "partition.hip", "noalloc.hip"]
+SOURCES = ["retexo_api.hip", "csr_build.hip", "csr_bucket.hip", "plan.hip", "transform.hip", "aggregate.hip", "aggregate_backward.hip", "aggregate_stored.hip", "train.hip", "partition.hip", "noalloc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -17,8 +17,10 @@
 //   part2    entries -> their bucket, packed as (row - first row of the bucket) << cbits | col
 //            (both moves stage a tile in LDS ordered by destination, reserve the destination ranges
 //             with one atomic per destination and tile, and write runs)
-//   sort     one workgroup per bucket: LDS counting split on the leading key bits, rank by
-//            comparison inside the (few-entry) bins, drop repeats, count entries per row;
+//   sort     one workgroup per bucket: entries counted per row, every row given a number of column
+//            bins proportional to its length (so that a bin holds 4 to 8 entries whatever the
+//            degree), LDS counting split into those bins, rank by comparison inside a bin,
+//            drop repeats, count the kept entries per row;
 //            a bucket that does not fit LDS is worked through in key ranges, the ranges split
 //            until each fits (a single long row, a clustered row range, many repeats: all end)
 //   total    one workgroup: prefix sums over the buckets' entry counts -> nnz
@@ -41,10 +43,10 @@ constexpr int kTileEntries = 8192;       // entries per part2 tile
 constexpr int kGroupBuckets = 256;       // buckets per group
 constexpr int kMaxGroups = 1024;
 constexpr int kMaxBuckets = kGroupBuckets * kMaxGroups;
-constexpr int kBucketMax = 12288;        // entries a bucket can hold in LDS (12 per thread)
+constexpr int kBucketMax = 10240;        // entries a bucket can hold in LDS (10 per thread)
 constexpr int kTarget = kBucketMax / 2;  // entries a bucket is filled to
-constexpr int kRowSpan = 2048;           // rows per bucket at most
-constexpr int kSortBins = 4096;          // bins of the LDS split
+constexpr int kRowSpan = 1024;           // rows per bucket at most (one per thread of the sort)
+constexpr int kSortBins = kBucketMax / 4 + kRowSpan;   // bins of the LDS split: a row of c entries gets < max(1, c/4)
 constexpr int kKeysPerThread = kBucketMax / kThreads;
 constexpr int kStack = 400;              // key ranges waiting in an oversized bucket (6 levels x 63 + 1)
 
@@ -56,7 +58,19 @@ struct BucketHeader {       // start of the workspace
     uint32_t n_groups;
     uint32_t part2_tiles;
     uint32_t internal;      // a construction invariant failed (never expected)
+#ifdef RETEXO_CSR_TIMING
+    unsigned long long phase[24];   // summed 100 MHz ticks per phase of the sort kernel (thread 0 of each workgroup)
+#endif
 };
+
+#ifdef RETEXO_CSR_TIMING
+#define PHASE_INIT() unsigned long long _t_prev = wall_clock64()
+#define PHASE(hdr, i) do { if (threadIdx.x == 0) { const unsigned long long _t = wall_clock64(); \
+        atomicAdd(&(hdr)->phase[i], _t - _t_prev); _t_prev = _t; } } while (0)
+#else
+#define PHASE_INIT() do {} while (0)
+#define PHASE(hdr, i) do {} while (0)
+#endif
 
 // exclusive prefix sum over the workgroup (NW waves); `total` is the sum over all threads.
 // sc: 2 * NW + 1 words of LDS scratch, free again when the call returns.
@@ -101,6 +115,24 @@ __device__ __forceinline__ int find_segment(const uint32_t* table, int n, uint32
     return lo;
 }
 
+// arr[idx] += 1 for every lane with `active` set.  When all of them name the same element (a long row, a
+// clustered range) the wave adds their number once instead of queueing up on one LDS address.
+// Call with the whole wave (the loop around it must be uniform per wave).
+__device__ __forceinline__ void lds_count(uint32_t* arr, uint32_t idx, bool active)
+{
+    const uint64_t act = __ballot(active);
+    if (!act) return;
+    const int lane = threadIdx.x & 63;
+    const int leader = __ffsll((unsigned long long)act) - 1;
+    const uint32_t first = __shfl(idx, leader, 64);
+    const uint64_t same = __ballot(active && idx == first);
+    if (same == act) {
+        if (lane == leader) atomicAdd(&arr[first], (uint32_t)__popcll(act));
+    } else if (active) {
+        atomicAdd(&arr[idx], 1u);
+    }
+}
+
 // item i of the input: pair i for i < n_pairs, afterwards the self-loop of node i - n_pairs.
 // Returns the number of entries it yields (0, 1 or 2) as (r0,c0), (r1,c1).
 __device__ __forceinline__ int item_entries(int64_t i, int64_t n_pairs, const int32_t* __restrict__ src,
@@ -141,14 +173,18 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(
     for (int i = threadIdx.x; i < nbins; i += kThreads) mine[i] = hist[i];
 }
 
+// bin_count[b] += the counts of this block's slice of the histogram blocks (bin_count starts at zero)
+constexpr int kColsumSlices = 8;
 __global__ __launch_bounds__(256) void colsum_kernel(int nblocks, int nbins, const uint32_t* __restrict__ counts,
-                                                     uint32_t* __restrict__ bin_count)
+                                                     uint32_t* bin_count)
 {
     const int b = blockIdx.x * 256 + threadIdx.x;
     if (b >= nbins) return;
+    const int per = (nblocks + kColsumSlices - 1) / kColsumSlices;
+    const int w0 = blockIdx.y * per, w1 = w0 + per < nblocks ? w0 + per : nblocks;
     uint32_t s = 0;
-    for (int w = 0; w < nblocks; ++w) s += counts[(size_t)w * nbins + b];
-    bin_count[b] = s;
+    for (int w = w0; w < w1; ++w) s += counts[(size_t)w * nbins + b];
+    if (s) atomicAdd(&bin_count[b], s);
 }
 
 struct PlanArrays {
@@ -176,20 +212,22 @@ __device__ __forceinline__ bool starts_bucket(int bin, uint32_t off, uint32_t pr
 __global__ __launch_bounds__(kThreads) void plan_kernel(int nbins, int span_bins, const uint32_t* __restrict__ bin_count,
                                                         PlanArrays a, uint32_t bucket_capacity, BucketHeader* hdr)
 {
+    __shared__ uint32_t cnts[kMaxBins];            // the bin counts, read three times
     __shared__ uint32_t sc[2 * kWaves + 1];
-    __shared__ uint32_t sh_groups;
     if (hdr->bad_id) return;
+    for (int b = threadIdx.x; b < nbins; b += kThreads) cnts[b] = bin_count[b];
+    __syncthreads();
     const int per = (nbins + kThreads - 1) / kThreads;
-    const int b0 = threadIdx.x * per, b1 = b0 + per < nbins ? b0 + per : nbins;
+    const int b0 = threadIdx.x * per < nbins ? threadIdx.x * per : nbins, b1 = b0 + per < nbins ? b0 + per : nbins;
     uint32_t sum = 0;
-    for (int b = b0; b < b1; ++b) sum += bin_count[b];
+    for (int b = b0; b < b1; ++b) sum += cnts[b];
     uint32_t total;
     uint32_t off = block_scan_excl<kWaves>(sum, sc, total);
     uint32_t starts = 0;
     {
         uint32_t o = off;
         for (int b = b0; b < b1; ++b) {
-            const uint32_t cnt = bin_count[b], pc = b > 0 ? bin_count[b - 1] : 0u;
+            const uint32_t cnt = cnts[b], pc = b > 0 ? cnts[b - 1] : 0u;
             a.bin_off[b] = o;
             starts += starts_bucket(b, o, o - pc, cnt, pc, span_bins) ? 1u : 0u;
             o += cnt;
@@ -205,7 +243,7 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(int nbins, int span_bins
     {
         uint32_t o = off;
         for (int b = b0; b < b1; ++b) {
-            const uint32_t cnt = bin_count[b], pc = b > 0 ? bin_count[b - 1] : 0u;
+            const uint32_t cnt = cnts[b], pc = b > 0 ? cnts[b - 1] : 0u;
             if (starts_bucket(b, o, o - pc, cnt, pc, span_bins)) {
                 a.bucket_bin0[id] = (uint32_t)b;
                 a.bucket_off[id] = o;
@@ -221,7 +259,6 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(int nbins, int span_bins
         a.bucket_off[n_buckets] = total;
         hdr->n_buckets = n_buckets;
         hdr->n_groups = n_groups;
-        sh_groups = n_groups;
     }
     __syncthreads();                               // the bucket arrays are complete
     // one group per thread (n_groups <= kMaxGroups = kThreads)
@@ -397,76 +434,97 @@ __global__ __launch_bounds__(kThreads) void part2_kernel(
 
 // ---------------------------------------------------------------------------
 // sort: LDS state of one bucket
+constexpr uint32_t kMerged = 255u;       // "bits" of a key range that was put together from small pieces (never split)
 struct SortShared {
-    uint32_t keys[kBucketMax];
+    uint32_t keys[kBucketMax + 4];       // (the rank loop looks at four keys at a time)
     uint32_t bins[kSortBins + 1];
-    uint32_t rowcnt[kRowSpan];
-    uint32_t stk_base[kStack], stk_bits[kStack], stk_cnt[kStack];
+    uint32_t rowcnt[kRowSpan];           // entries per row: first all of them (to size the row's bins), then the kept ones
+    uint32_t rowmeta[kRowSpan];          // first bin of the row | (column shift of its bins << 16)
+    uint32_t stk_lo[kStack], stk_hi[kStack], stk_bits[kStack], stk_cnt[kStack];
     uint32_t sc[2 * kWaves + 1];
-    uint32_t red[2 * kWaves];
     uint32_t n, sp;
 };
 
 // Sort the n <= kBucketMax keys in sh.keys, drop repeats, append the columns to out[out_cursor ...) and add
 // the kept entries to the per-row counts.  Returns the number of kept keys (uniform over the workgroup).
-__device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int cbits, uint32_t* __restrict__ out, uint32_t out_cursor)
+__device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbits, uint32_t* __restrict__ out,
+                                  uint32_t out_cursor, BucketHeader* hdr)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    PHASE_INIT();
+    const int tid = threadIdx.x;
     const uint32_t cmask = (1u << cbits) - 1u;
-    // smallest and largest key
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (uint32_t i = tid; i < n; i += kThreads) {
-        const uint32_t k = sh.keys[i];
-        kmin = k < kmin ? k : kmin;
-        kmax = k > kmax ? k : kmax;
-    }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        const uint32_t a = __shfl_xor(kmin, m, 64), b = __shfl_xor(kmax, m, 64);
-        kmin = a < kmin ? a : kmin;
-        kmax = b > kmax ? b : kmax;
-    }
-    if (lane == 0) { sh.red[wave] = kmin; sh.red[kWaves + wave] = kmax; }
-    for (int i = tid; i <= kSortBins; i += kThreads) sh.bins[i] = 0u;
+    // On entry sh.rowcnt is what the rows have kept so far; it is saved in registers (one row per thread),
+    // the array is used for this call's raw counts, and the sum goes back at the end.
+    const uint32_t kept_before = tid < nrows ? sh.rowcnt[tid] : 0u;
+    if (tid < nrows) sh.rowcnt[tid] = 0u;                    // (thread t owns row t here; everyone else waits below)
     __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t a = sh.red[w], b = sh.red[kWaves + w];
-        kmin = a < kmin ? a : kmin;
-        kmax = b > kmax ? b : kmax;
-    }
-    const uint32_t range = kmax - kmin;
-    const int shift = range < (uint32_t)kSortBins ? 0 : (32 - __clz(range)) - 12;      // (range >> shift) < kSortBins
-
-    // counting split on the leading bits of key - kmin; the atomic's old value is the rank inside the bin
     uint32_t k[kKeysPerThread], r[kKeysPerThread];
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {                 // uniform per wave: i < n holds or fails for whole waves
+        const uint32_t i = tid + j * kThreads;                 // except in the last one, which lds_count handles
+        const bool have = i < n;
+        k[j] = have ? sh.keys[i] : 0u;
+        lds_count(sh.rowcnt, k[j] >> cbits, have);
+    }
+    __syncthreads();
+    PHASE(hdr, 3);
+    // a row of c entries gets 2^lg bins, 2^lg = the power of two at or above c, over 8 (at least one):
+    // between c/8 and c/4 bins, so that a bin holds 4 to 8 entries when the columns are spread evenly
+    uint32_t nbins_total;
+    {
+        uint32_t nsub = 0, lg = 0;
+        if (tid < nrows) {
+            const uint32_t c = sh.rowcnt[tid];
+            lg = c <= 8u ? 0u : (uint32_t)(32 - __clz(c - 1u)) - 3u;
+            lg = lg > (uint32_t)cbits ? (uint32_t)cbits : lg;
+            nsub = 1u << lg;
+        }
+        const uint32_t first = block_scan_excl<kWaves>(nsub, sh.sc, nbins_total);      // <= kSortBins
+        if (tid < nrows) sh.rowmeta[tid] = first | (((uint32_t)cbits - lg) << 16);
+    }
+    for (uint32_t i = tid; i <= nbins_total; i += kThreads) sh.bins[i] = 0u;
+    __syncthreads();
+    PHASE(hdr, 4);
+    // counting split; the atomic's old value is the rank inside the bin
+    uint32_t bin[kKeysPerThread];
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j) {
         const uint32_t i = tid + j * kThreads;
         if (i < n) {
-            k[j] = sh.keys[i];
-            r[j] = atomicAdd(&sh.bins[(k[j] - kmin) >> shift], 1u);
+            const uint32_t meta = sh.rowmeta[k[j] >> cbits];
+            bin[j] = (meta & 0xffffu) + ((k[j] & cmask) >> (meta >> 16));
+            r[j] = atomicAdd(&sh.bins[bin[j]], 1u);
         }
     }
     __syncthreads();
     {
-        constexpr int BPT = kSortBins / kThreads;
-        uint32_t c[BPT], s = 0;
+        constexpr int BPT = (kSortBins + kThreads - 1) / kThreads;
+        uint32_t c[BPT], sum = 0;
 #pragma unroll
-        for (int j = 0; j < BPT; ++j) { c[j] = sh.bins[tid * BPT + j]; s += c[j]; }
+        for (int j = 0; j < BPT; ++j) {
+            const uint32_t b = tid * BPT + j;
+            c[j] = b < nbins_total ? sh.bins[b] : 0u;
+            sum += c[j];
+        }
         uint32_t total;
-        uint32_t o = block_scan_excl<kWaves>(s, sh.sc, total);
+        uint32_t o = block_scan_excl<kWaves>(sum, sh.sc, total);
 #pragma unroll
-        for (int j = 0; j < BPT; ++j) { sh.bins[tid * BPT + j] = o; o += c[j]; }
-        if (tid == 0) sh.bins[kSortBins] = total;
+        for (int j = 0; j < BPT; ++j) {
+            const uint32_t b = tid * BPT + j;
+            if (b < nbins_total) sh.bins[b] = o;
+            o += c[j];
+        }
+        if (tid == 0) sh.bins[nbins_total] = total;
     }
     __syncthreads();
+    PHASE(hdr, 5);
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j) {
         const uint32_t i = tid + j * kThreads;
-        if (i < n) sh.keys[sh.bins[(k[j] - kmin) >> shift] + r[j]] = k[j];
+        if (i < n) sh.keys[sh.bins[bin[j]] + r[j]] = k[j];
     }
     __syncthreads();
+    PHASE(hdr, 6);
     // rank inside the bin by comparison (a bin holds a few keys); equal keys keep their order of position
     uint32_t fp[kKeysPerThread];
 #pragma unroll
@@ -474,21 +532,29 @@ __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int cbits, uint32_
         const uint32_t p = tid + j * kThreads;
         if (p < n) {
             const uint32_t key = sh.keys[p];
-            const uint32_t d = (key - kmin) >> shift;
+            const uint32_t meta = sh.rowmeta[key >> cbits];
+            const uint32_t d = (meta & 0xffffu) + ((key & cmask) >> (meta >> 16));
             const uint32_t q0 = sh.bins[d], q1 = sh.bins[d + 1];
             uint32_t below = 0;
-            for (uint32_t q = q0; q < q1; ++q) {
-                const uint32_t other = sh.keys[q];
-                below += (other < key || (other == key && q < p)) ? 1u : 0u;
+            for (uint32_t q = q0; q < q1; q += 4) {          // four independent reads per step (the array is padded)
+                const uint32_t o0 = sh.keys[q], o1 = sh.keys[q + 1], o2 = sh.keys[q + 2], o3 = sh.keys[q + 3];
+                below += (o0 < key || (o0 == key && q < p)) ? 1u : 0u;
+                below += (q + 1 < q1 && (o1 < key || (o1 == key && q + 1 < p))) ? 1u : 0u;
+                below += (q + 2 < q1 && (o2 < key || (o2 == key && q + 2 < p))) ? 1u : 0u;
+                below += (q + 3 < q1 && (o3 < key || (o3 == key && q + 3 < p))) ? 1u : 0u;
             }
             k[j] = key;
             fp[j] = q0 + below;
         }
     }
     __syncthreads();
+    PHASE(hdr, 7);
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j)
         if (tid + j * kThreads < n) sh.keys[fp[j]] = k[j];
+    __syncthreads();
+    PHASE(hdr, 8);
+    if (tid < nrows) sh.rowcnt[tid] = kept_before;           // back to "entries kept so far" (sorting is done with the raw counts)
     __syncthreads();
     // keep the first key of every run of equal keys: each thread takes a contiguous piece, reads what it keeps
     // into registers, and after the prefix sum writes it back compacted; rows are counted run by run
@@ -523,16 +589,18 @@ __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int cbits, uint32_
     }
     uint32_t total;
     const uint32_t excl = block_scan_excl<kWaves>(kept, sh.sc, total);      // its barriers separate the reads from the writes
+    PHASE(hdr, 9);
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j)
         if (keep_mask & (1u << j)) sh.keys[excl + (uint32_t)__popc(keep_mask & ((1u << j) - 1u))] = k[j];
     __syncthreads();
     for (uint32_t i = tid; i < total; i += kThreads) out[out_cursor + i] = sh.keys[i] & cmask;
     __syncthreads();
+    PHASE(hdr, 10);
     return total;
 }
 
-__global__ __launch_bounds__(kThreads) void sort_kernel(
+__global__ __launch_bounds__(kThreads, 8) void sort_kernel(
     BucketHeader* hdr, const uint32_t* __restrict__ bucket_off, const uint32_t* __restrict__ bucket_bin0,
     const uint32_t* __restrict__ packed, uint32_t* __restrict__ cols_tmp, int32_t* __restrict__ row_unique,
     uint32_t* __restrict__ bucket_total, int cbits, int s, int64_t N)
@@ -541,6 +609,7 @@ __global__ __launch_bounds__(kThreads) void sort_kernel(
     if (hdr->bad_id || hdr->internal) return;
     const uint32_t b = blockIdx.x;
     if (b >= hdr->n_buckets) return;
+    PHASE_INIT();
     const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t e0 = bucket_off[b], E = bucket_off[b + 1] - e0;
     const int64_t row0 = (int64_t)bucket_bin0[b] << s;
@@ -553,29 +622,43 @@ __global__ __launch_bounds__(kThreads) void sort_kernel(
     uint32_t* out = cols_tmp + e0;
     uint32_t out_cursor = 0;
 
+    PHASE(hdr, 1);
     if (E <= (uint32_t)kBucketMax) {
-        for (uint32_t i = tid; i < E; i += kThreads) sh.keys[i] = in[i];
+        uint32_t v[kKeysPerThread];
+#pragma unroll
+        for (int j = 0; j < kKeysPerThread; ++j) {           // all loads in flight before the first is used
+            const uint32_t i = tid + j * kThreads;
+            v[j] = i < E ? in[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kKeysPerThread; ++j) {
+            const uint32_t i = tid + j * kThreads;
+            if (i < E) sh.keys[i] = v[j];
+        }
         __syncthreads();
-        if (E > 0) out_cursor = sort_and_emit(sh, E, cbits, out, 0u);
+        PHASE(hdr, 2);
+        if (E > 0) out_cursor = sort_and_emit(sh, E, nrows, cbits, out, 0u, hdr);
     } else {
-        // The bucket does not fit: work through it in key ranges [base, base + 2^bits), lowest first.  A range
-        // that fits is gathered and sorted; one that does not is split 64 ways by its next key bits (or is a
-        // single repeated key).  Each level removes 6 key bits, so the stack stays below kStack.
-        if (tid == 0) { sh.stk_base[0] = 0u; sh.stk_bits[0] = 32u; sh.stk_cnt[0] = E; sh.sp = 1u; }
+        // The bucket does not fit: work through it in key ranges [lo, hi], lowest first.  A range that fits is
+        // gathered and sorted.  One that does not is an aligned block of 2^bits keys: it is counted in 64
+        // pieces by its next key bits, neighbouring pieces are put together into ranges that fit, and a piece
+        // that still does not fit is split again (or is a single repeated key).  Each level removes 6 key
+        // bits, so the stack stays below kStack.
+        if (tid == 0) { sh.stk_lo[0] = 0u; sh.stk_hi[0] = 0xffffffffu; sh.stk_bits[0] = 32u; sh.stk_cnt[0] = E; sh.sp = 1u; }
         __syncthreads();
         for (;;) {
             const uint32_t sp = sh.sp;
             if (sp == 0) break;
-            const uint32_t base = sh.stk_base[sp - 1], bits = sh.stk_bits[sp - 1], cnt = sh.stk_cnt[sp - 1];
+            const uint32_t lo = sh.stk_lo[sp - 1], hi = sh.stk_hi[sp - 1], bits = sh.stk_bits[sp - 1],
+                           cnt = sh.stk_cnt[sp - 1];
             __syncthreads();
             if (tid == 0) { sh.sp = sp - 1; sh.n = 0u; }
             __syncthreads();
-            const uint32_t last = bits >= 32u ? 0xffffffffu : base + ((1u << bits) - 1u);
             if (cnt <= (uint32_t)kBucketMax) {
                 for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kThreads) {      // uniform per wave
                     const uint32_t i = i0 + lane;
                     const uint32_t key = i < E ? in[i] : 0u;
-                    const bool match = i < E && key >= base && key <= last;
+                    const bool match = i < E && key >= lo && key <= hi;
                     const uint64_t mask = __ballot(match);
                     if (mask) {
                         const int leader = __ffsll((unsigned long long)mask) - 1;
@@ -587,35 +670,46 @@ __global__ __launch_bounds__(kThreads) void sort_kernel(
                 }
                 __syncthreads();
                 const uint32_t n = sh.n;                       // == cnt
-                out_cursor += sort_and_emit(sh, n, cbits, out, out_cursor);
+                out_cursor += sort_and_emit(sh, n, nrows, cbits, out, out_cursor, hdr);
             } else if (bits == 0u) {
                 // more than a bucketful of one and the same key: it is kept once
                 if (tid == 0) {
-                    out[out_cursor] = base & ((1u << cbits) - 1u);
-                    atomicAdd(&sh.rowcnt[base >> cbits], 1u);
+                    out[out_cursor] = lo & ((1u << cbits) - 1u);
+                    atomicAdd(&sh.rowcnt[lo >> cbits], 1u);
                 }
                 out_cursor += 1;
                 __syncthreads();
             } else {
                 const uint32_t cb = bits > 6u ? bits - 6u : 0u;
-                const uint32_t nchild = 1u << (bits - cb);
+                const int nchild = 1 << (bits - cb);
                 if (tid < 64) sh.bins[tid] = 0u;
                 __syncthreads();
-                for (uint32_t i = tid; i < E; i += kThreads) {
-                    const uint32_t key = in[i];
-                    if (key >= base && key <= last) atomicAdd(&sh.bins[(key - base) >> cb], 1u);
+                for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kThreads) {      // uniform per wave
+                    const uint32_t i = i0 + lane;
+                    const uint32_t key = i < E ? in[i] : 0u;
+                    const bool match = i < E && key >= lo && key <= hi;
+                    lds_count(sh.bins, match ? (key - lo) >> cb : 0u, match);
                 }
                 __syncthreads();
                 if (tid == 0) {
+                    // highest keys first, so that the lowest range is on top of the stack
                     uint32_t top = sh.sp;
-                    for (int ch = (int)nchild - 1; ch >= 0; --ch)
-                        if (sh.bins[ch]) {
-                            if (top >= (uint32_t)kStack) { hdr->internal = 1u; break; }   // cannot happen (6 levels x 63 + 1)
-                            sh.stk_base[top] = base + ((uint32_t)ch << cb);
-                            sh.stk_bits[top] = cb;
-                            sh.stk_cnt[top] = sh.bins[ch];
-                            ++top;
-                        }
+                    auto push = [&](int c0, int c1, uint32_t b_, uint32_t n_) {      // pieces c0..c1
+                        if (top >= (uint32_t)kStack) { hdr->internal = 1u; return; }  // cannot happen (6 levels x 64)
+                        sh.stk_lo[top] = lo + ((uint32_t)c0 << cb);
+                        sh.stk_hi[top] = c1 == nchild - 1 ? hi : lo + ((uint32_t)(c1 + 1) << cb) - 1u;
+                        sh.stk_bits[top] = b_;
+                        sh.stk_cnt[top] = n_;
+                        ++top;
+                    };
+                    int ch = nchild - 1;
+                    while (ch >= 0) {
+                        if (sh.bins[ch] > (uint32_t)kBucketMax) { push(ch, ch, cb, sh.bins[ch]); --ch; continue; }
+                        const int c1 = ch;
+                        uint32_t sum = 0;
+                        while (ch >= 0 && sum + sh.bins[ch] <= (uint32_t)kBucketMax) { sum += sh.bins[ch]; --ch; }
+                        if (sum) push(ch + 1, c1, kMerged, sum);
+                    }
                     sh.sp = top;
                 }
                 __syncthreads();
@@ -623,8 +717,10 @@ __global__ __launch_bounds__(kThreads) void sort_kernel(
         }
     }
     __syncthreads();
+    PHASE(hdr, 11);     // (normal path: nothing; oversized buckets: the whole key-range walk minus its sorts)
     for (int i = tid; i < nrows; i += kThreads) row_unique[row0 + i] = (int32_t)sh.rowcnt[i];
     if (tid == 0) bucket_total[b] = out_cursor;
+    PHASE(hdr, 12);
 }
 
 __global__ __launch_bounds__(kThreads) void total_kernel(BucketHeader* hdr, const uint32_t* __restrict__ bucket_total,
@@ -690,6 +786,8 @@ int column_bits(int64_t N)
     return b;
 }
 
+static_assert(sizeof(BucketHeader) <= 256, "the header has 256 bytes of the workspace");
+
 struct BucketLayout {
     int cbits, s, nbins, span_bins, hist_blocks;
     int64_t M, n_items, items_per_block, bucket_bound;
@@ -722,8 +820,8 @@ bool make_bucket_layout(int64_t n_pairs, int64_t N, int add_self_loops, BucketLa
     auto take = [&](int64_t bytes) { const int64_t at = off; off += align_up(bytes > 0 ? bytes : 4, 256); return at; };
     const int64_t m = L.M > 0 ? L.M : 1;
     L.header = take(256);
+    L.bin_count = take(4ll * L.nbins);                       // (zeroed together with the header)
     L.counts = take(4ll * L.hist_blocks * L.nbins);
-    L.bin_count = take(4ll * L.nbins);
     L.bin_off = take(4ll * (L.nbins + 1));
     L.bucket_bin0 = take(4 * (L.bucket_bound + 1));
     L.bucket_off = take(4 * (L.bucket_bound + 1));
@@ -763,10 +861,10 @@ int csr_build_bucketed(int64_t n_pairs, const int32_t* d_src, const int32_t* d_d
     PlanArrays pa{u32(L.bin_off), u32(L.bucket_bin0), u32(L.bucket_off), u32(L.bucket_cursor),
                   u32(L.group_bin0), u32(L.group_off), u32(L.group_cursor), u32(L.group_tile0)};
 
-    RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, sizeof(BucketHeader), stream));
+    RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, (size_t)(L.counts - L.header), stream));      // header and bin counts
     hist_kernel<<<dim3((unsigned)L.hist_blocks), dim3(kThreads), 0, stream>>>(
         n_pairs, d_src, d_dst, N, L.n_items, L.items_per_block, L.s, L.nbins, u32(L.counts), hdr);
-    colsum_kernel<<<dim3((unsigned)((L.nbins + 255) / 256)), dim3(256), 0, stream>>>(
+    colsum_kernel<<<dim3((unsigned)((L.nbins + 255) / 256), kColsumSlices), dim3(256), 0, stream>>>(
         L.hist_blocks, L.nbins, u32(L.counts), u32(L.bin_count));
     plan_kernel<<<dim3(1), dim3(kThreads), 0, stream>>>(L.nbins, L.span_bins, u32(L.bin_count), pa,
                                                         (uint32_t)L.bucket_bound, hdr);

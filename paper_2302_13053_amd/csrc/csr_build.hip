@@ -24,6 +24,7 @@
 #include <rocprim/iterator/transform_iterator.hpp>
 
 #include "common.hpp"
+#include "csr_bucket.hpp"
 
 namespace {
 
@@ -241,7 +242,9 @@ extern "C" int64_t retexo_csr_workspace_bytes(int64_t n_pairs, int64_t N, int ad
     if (int s = check_sizes(n_pairs, N)) return s;
     Layout L;
     if (int s = make_layout(n_pairs, N, add_self_loops, L)) return s;
-    return L.total;
+    // enough for either construction (which one runs depends on the size and on the "csr_sorted_keys" knob)
+    const int64_t bucketed = csr_bucketed_workspace_bytes(n_pairs, N, add_self_loops);
+    return bucketed > L.total ? bucketed : L.total;
 }
 
 extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const int32_t* d_dst,
@@ -262,6 +265,14 @@ extern "C" int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const 
     if (L.M > 0 && !d_col_idx && col_capacity > 0) return RETEXO_E_NULL;
 
     hipStream_t stream = (hipStream_t)stream_;
+    // Graphs of up to 2^23 nodes take the bucketing construction (csr_bucket.hip); larger ones, and every graph
+    // when the "csr_sorted_keys" knob is set, the sorted-key construction below.  Same result, bit for bit.
+    const int64_t bucketed = agg_options().csr_sorted_keys ? -1 : csr_bucketed_workspace_bytes(n_pairs, N, add_self_loops);
+    if (bucketed >= 0) {
+        if (workspace_bytes < bucketed) return RETEXO_E_WORKSPACE;
+        return csr_build_bucketed(n_pairs, d_src, d_dst, N, add_self_loops, d_row_ptr, d_col_idx, col_capacity,
+                                  h_nnz, d_workspace, stream);
+    }
     char* ws = (char*)d_workspace;
     CsrHeader* hdr = (CsrHeader*)(ws + L.header);
     uint64_t* keys_a = (uint64_t*)(ws + L.keys_a);

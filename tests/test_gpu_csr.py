@@ -204,3 +204,57 @@ def test_csr_of_heavily_repeated_and_clustered_pairs(n, self_loops):
     dst = np.concatenate([b, rep[1], rep[0], selfs, rng.integers(0, n, m // 4)]).astype(np.int32)
     perm = rng.permutation(src.size)
     check_against_oracle(src[perm], dst[perm], n, self_loops)
+
+
+def _star_and_repeats(n, seed):
+    """A node joined to most others (one row far beyond what a bucket holds in LDS), a narrow id window with
+    heavy traffic (a bucket whose keys cluster), one pair and one self pair given far more often than a bucket
+    holds entries, plus background pairs."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    hub = n // 7
+    spokes = rng.permutation(n)[: min(n - 1, 60000)]
+    win = rng.integers(n // 2, min(n, n // 2 + 40), (2, 50000))
+    rep_a, rep_b = np.full(30000, n // 3), np.full(30000, (n // 3 + 11) % n)
+    selfs = np.full(20000, n // 5)
+    bg = rng.integers(0, n, (2, 4 * n))
+    src = np.concatenate([np.full(spokes.size, hub), win[0], rep_a, rep_b, selfs, bg[0]]).astype(np.int32)
+    dst = np.concatenate([spokes, win[1], rep_b, rep_a, selfs, bg[1]]).astype(np.int32)
+    perm = rng.permutation(src.size)
+    return src[perm], dst[perm]
+
+
+@pytest.mark.parametrize("n", [300, 70001, 1 << 20])
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_csr_buckets_that_do_not_fit(n, self_loops):
+    # rows, row ranges and repeated keys with more entries than the local data share holds take the construction's
+    # key-range path; the result is the same function of the pair set
+    src, dst = _star_and_repeats(n, 100 + n % 97)
+    check_against_oracle(src, dst, n, self_loops)
+
+
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_csr_both_constructions_give_the_same_arrays(self_loops):
+    # the bucketing construction (graphs of up to 2^23 nodes) and the sorted-key construction (larger graphs, or
+    # on request) are two routes to one result
+    n = 50000
+    src, dst = _star_and_repeats(n, 5)
+    try:
+        B.retexo_set_option("csr_sorted_keys", 1)
+        check_against_oracle(src, dst, n, self_loops)
+        a = Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, self_loops)
+    finally:
+        B.retexo_set_option("csr_sorted_keys", 0)
+    b = Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, self_loops)
+    torch.cuda.synchronize()
+    assert a.nnz == b.nnz and torch.equal(a.row_ptr, b.row_ptr) and torch.equal(a.col_idx[:a.nnz], b.col_idx[:b.nnz])
+
+
+def test_csr_of_a_graph_beyond_the_bucketing_range():
+    # more than 2^23 nodes: the sorted-key construction runs by itself
+    n = (1 << 23) + 12345
+    src, dst = wl.random_pairs(n, 200000, 17, skew=1.0)
+    g = Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False)
+    torch.cuda.synchronize()
+    orp, oci = oracle.csr_from_coo(src, dst, n, False)
+    assert g.nnz == orp[-1]
+    assert np.array_equal(g.row_ptr.cpu().numpy(), orp) and np.array_equal(g.col_idx[:g.nnz].cpu().numpy(), oci)
