@@ -123,6 +123,15 @@ int retexo_csr_from_coo(int64_t n_pairs, const int32_t* d_src, const int32_t* d_
  */
 int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d_row_ptr,
                        const int32_t* d_col_idx, unsigned flags, void* stream);
+/* The same plan without any allocation and with one synchronisation instead of two, for callers that
+ * build a plan per step: the caller states the entry count (retexo_csr_from_coo reports it) and supplies
+ * the memory.  The plan's device arrays then live in d_workspace (retexo_plan_workspace_bytes(N, nnz, flags)
+ * bytes, 256-aligned), which must stay untouched until retexo_plan_destroy; destroying such a plan frees
+ * only its host structure.  RETEXO_E_CSR also when d_row_ptr[N] != nnz.  Synchronises `stream` once. */
+int64_t retexo_plan_workspace_bytes(int64_t N, int64_t nnz, unsigned flags);
+int retexo_plan_create_in(retexo_plan** out, int64_t N, int64_t nnz, const int64_t* d_row_ptr,
+                          const int32_t* d_col_idx, unsigned flags,
+                          void* d_workspace, int64_t workspace_bytes, void* stream);
 int retexo_plan_destroy(retexo_plan* plan);
 int64_t retexo_plan_num_nodes(const retexo_plan* plan);
 int64_t retexo_plan_nnz(const retexo_plan* plan);

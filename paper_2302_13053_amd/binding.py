@@ -24,7 +24,7 @@ E_CSR, E_WORKSPACE, E_ALIAS, E_HIP, E_CAPACITY = -7, -8, -9, -10, -11
 
 EXPORTS = (
     "retexo_status_string", "retexo_csr_workspace_bytes", "retexo_csr_from_coo",
-    "retexo_plan_create", "retexo_plan_destroy", "retexo_plan_num_nodes", "retexo_plan_nnz",
+    "retexo_plan_create", "retexo_plan_workspace_bytes", "retexo_plan_create_in", "retexo_plan_destroy", "retexo_plan_num_nodes", "retexo_plan_nnz",
     "retexo_plan_max_degree", "retexo_plan_deg", "retexo_plan_dinv", "retexo_plan_export",
     "retexo_plan_export_split",
     "retexo_workspace_bytes",
@@ -67,6 +67,10 @@ def load():
     lib.retexo_csr_from_coo.argtypes = [i64, vp, vp, i64, i32, vp, vp, i64, C.POINTER(i64), vp, i64, vp]
     lib.retexo_plan_create.restype = i32
     lib.retexo_plan_create.argtypes = [C.POINTER(vp), i64, vp, vp, u32, vp]
+    lib.retexo_plan_workspace_bytes.restype = i64
+    lib.retexo_plan_workspace_bytes.argtypes = [i64, i64, u32]
+    lib.retexo_plan_create_in.restype = i32
+    lib.retexo_plan_create_in.argtypes = [C.POINTER(vp), i64, i64, vp, vp, u32, vp, i64, vp]
     lib.retexo_plan_destroy.restype = i32
     lib.retexo_plan_destroy.argtypes = [vp]
     lib.retexo_plan_num_nodes.restype = i64
@@ -175,6 +179,18 @@ def retexo_plan_create(n_nodes, d_row_ptr, d_col_idx, flags=0, stream=0):
     """-> (status, plan handle or None)"""
     h = C.c_void_p()
     st = load().retexo_plan_create(C.byref(h), n_nodes, _vp(d_row_ptr), _vp(d_col_idx), flags, _vp(stream))
+    return int(st), (h.value if st == 0 else None)
+
+
+def retexo_plan_workspace_bytes(n_nodes, nnz, flags=0) -> int:
+    return int(load().retexo_plan_workspace_bytes(n_nodes, nnz, flags))
+
+
+def retexo_plan_create_in(n_nodes, nnz, d_row_ptr, d_col_idx, flags, d_workspace, workspace_bytes, stream=0):
+    """-> (status, plan handle or None); the plan's device arrays live in the caller's workspace"""
+    h = C.c_void_p()
+    st = load().retexo_plan_create_in(C.byref(h), n_nodes, nnz, _vp(d_row_ptr), _vp(d_col_idx), flags,
+                                      _vp(d_workspace), workspace_bytes, _vp(stream))
     return int(st), (h.value if st == 0 else None)
 
 

@@ -24,7 +24,7 @@ namespace {
 constexpr int kThreads = 256;
 
 __global__ __launch_bounds__(kThreads) void degree_kernel(
-    int64_t N, const int64_t* __restrict__ row_ptr, int32_t* __restrict__ deg,
+    int64_t N, int64_t nnz, const int64_t* __restrict__ row_ptr, int32_t* __restrict__ deg,
     float* __restrict__ dinv, uint32_t* __restrict__ sort_key, int32_t* __restrict__ ids,
     uint32_t* bad)
 {
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kThreads) void degree_kernel(
     if (v >= N) return;
     const int64_t lo = row_ptr[v], hi = row_ptr[v + 1];
     int64_t d = hi - lo;
-    if (d < 0 || d > 0x7fffffff || (v == 0 && lo != 0)) { atomicOr(bad, 1u); d = 0; }
+    if (d < 0 || d > 0x7fffffff || (v == 0 && lo != 0) || (v == N - 1 && hi != nnz)) { atomicOr(bad, 1u); d = 0; }
     deg[v] = (int32_t)d;
     dinv[v] = d > 0 ? 1.0f / sqrtf((float)d) : 0.0f;
     sort_key[v] = (uint32_t)d;
@@ -75,17 +75,27 @@ __global__ __launch_bounds__(kThreads) void split_rows_kernel(
             const uint32_t part = (uint32_t)col_idx[e] / sp;
             inc = part > (uint32_t)kMaxParts ? kMaxParts : (int)part;
         }
+        // inclusive prefix maximum over the lanes; columns that ascend (the usual case) are their own maximum
+        {
+            int left = __shfl_up(inc, 1);
+            if (lane == 0) left = carry;
+            if (__ballot(e < end && inc < left) != 0ull) {
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {    // inclusive prefix maximum over the lanes
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc = max(inc, o);
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int o = __shfl_up(inc, d);
+                    if (lane >= d) inc = max(inc, o);
+                }
+            }
         }
         int exc = __shfl_up(inc, 1);
         if (lane == 0) exc = -1;
         const int here = max(carry, inc), before = max(carry, exc);
         if (e < end)
             for (int k = before + 1; k <= here; ++k) part_ptr[(int64_t)k * N + s] = (int32_t)e;
-        carry = max(carry, __shfl(inc, 63));
+        // the chunk's maximum sits in its last valid lane (lanes past the row end hold -1 and, on the
+        // ascending path, were never raised)
+        const int last = end - base > 64 ? 63 : (int)(end - base - 1);
+        carry = max(carry, __shfl(inc, last));
     }
     if (lane == 0)
         for (int k = carry + 1; k <= kMaxParts; ++k) part_ptr[(int64_t)k * N + s] = (int32_t)end;
@@ -118,6 +128,92 @@ struct Readback {
 
 }  // namespace
 
+namespace {
+
+struct PlanLayout {
+    bool split;
+    int64_t o_deg, o_dinv, o_order, o_part, keep_bytes;            // what the plan keeps
+    int64_t s_kin, s_kout, s_ids, s_rb, s_tmp, scratch_bytes;      // what only its construction needs
+    size_t sort_bytes;
+};
+
+int plan_layout(int64_t N, int64_t nnz, unsigned flags, PlanLayout& L)
+{
+    const int64_t n1 = N > 0 ? N : 1;
+    // Dense-enough graphs whose feature table cannot stay in L2 get the row split that lets
+    // the aggregation walk one source-id range at a time.
+    L.split = N > 0 && nnz > 0 &&
+              ((flags & RETEXO_F_SPLIT_ROWS) ||
+               (nnz >= 64 * N && N * 128 > (4ll << 20) && N * 128 <= kMaxParts * (8ll << 20)));
+    L.o_deg = 0;
+    L.o_dinv = align_up(4 * n1, 256);
+    L.o_order = 2 * L.o_dinv;
+    L.o_part = 3 * L.o_dinv;
+    L.keep_bytes = L.o_part + (L.split ? align_up(4 * N * (kMaxParts + 1), 256) : 0);
+    L.sort_bytes = 0;
+    if (N > 0 &&
+        rocprim::radix_sort_pairs_desc(nullptr, L.sort_bytes, (uint32_t*)nullptr, (uint32_t*)nullptr,
+                                       (int32_t*)nullptr, (int32_t*)nullptr, (size_t)N, 0u, 32u,
+                                       (hipStream_t)0) != hipSuccess)
+        return RETEXO_E_HIP;
+    // scratch: keys_in, keys_out, ids_in, readback block, sort temp
+    L.s_kin = 0;
+    L.s_kout = align_up(4 * n1, 256);
+    L.s_ids = 2 * L.s_kout;
+    L.s_rb = 3 * L.s_kout;
+    L.s_tmp = L.s_rb + 256;
+    L.scratch_bytes = L.s_tmp + align_up((int64_t)L.sort_bytes, 256) + 256;
+    return RETEXO_OK;
+}
+
+// Everything after the sizes are known: the kernels, the one read-back, the host fields.  `keep` and `scratch`
+// are device memory of L.keep_bytes and L.scratch_bytes.
+int plan_fill(retexo_plan* p, const PlanLayout& L, unsigned flags, void* keep, void* scratch, hipStream_t stream)
+{
+    const int64_t N = p->N, nnz = p->nnz;
+    p->deg = (int32_t*)((char*)keep + L.o_deg);
+    p->dinv = (float*)((char*)keep + L.o_dinv);
+    p->order = (int32_t*)((char*)keep + L.o_order);
+    char* sc = (char*)scratch;
+    uint32_t* kin = (uint32_t*)(sc + L.s_kin);
+    uint32_t* kout = (uint32_t*)(sc + L.s_kout);
+    int32_t* ids = (int32_t*)(sc + L.s_ids);
+    Readback* rb = (Readback*)(sc + L.s_rb);
+
+    RETEXO_HIP_TRY(hipMemsetAsync(rb, 0, sizeof(Readback), stream));
+    if (N > 0) {
+        degree_kernel<<<dim3((unsigned)((N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            N, nnz, p->row_ptr, p->deg, p->dinv, kin, ids, &rb->bad);
+        size_t sort_bytes = L.sort_bytes;
+        RETEXO_HIP_TRY(rocprim::radix_sort_pairs_desc(sc + L.s_tmp, sort_bytes, kin, kout, ids, p->order, (size_t)N,
+                                                      0u, 32u, stream));
+        Thresholds th;
+        for (int i = 0; i < 8; ++i) th.t[i] = kPlanThresholds[i];
+        count_at_least<<<dim3(1), dim3(64), 0, stream>>>(N, kout, th, rb->counts);
+    }
+    if (L.split) {
+        // needs only the schedule order, so it runs before the host looks at the counts
+        p->part_ptr = (int32_t*)((char*)keep + L.o_part);
+        p->part_span = (N + kMaxParts - 1) / kMaxParts;
+        const int64_t rows_per_block = kThreads / 64;
+        split_rows_kernel<<<dim3((unsigned)((N + rows_per_block - 1) / rows_per_block)), dim3(kThreads), 0, stream>>>(
+            N, nnz, p->part_span, p->row_ptr, p->col_idx, p->order, p->part_ptr);
+    }
+    if ((flags & RETEXO_F_VALIDATE) && nnz > 0)
+        check_columns<<<dim3((unsigned)((nnz + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
+            nnz, N, p->col_idx, &rb->bad);
+    RETEXO_HIP_TRY(hipGetLastError());
+    Readback h;
+    RETEXO_HIP_TRY(hipMemcpyAsync(&h, rb, sizeof(h), hipMemcpyDeviceToHost, stream));
+    RETEXO_HIP_TRY(hipStreamSynchronize(stream));
+    if (h.bad) return RETEXO_E_CSR;
+    for (int i = 0; i < 8; ++i) p->rows_at_least[i] = h.counts[i];
+    p->max_degree = (int32_t)h.counts[8];
+    return RETEXO_OK;
+}
+
+}  // namespace
+
 extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d_row_ptr,
                                   const int32_t* d_col_idx, unsigned flags, void* stream_)
 {
@@ -133,12 +229,10 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
     p->N = N;
     p->row_ptr = d_row_ptr;
     p->col_idx = d_col_idx;
-
     auto fail = [&](int code) { retexo_plan_destroy(p); return code; };
 
     // The entry count decides whether the row split is built, so it is fetched first; everything the plan
     // keeps then comes from one allocation (device allocations cost tens of microseconds each).
-    const int64_t n1 = N > 0 ? N : 1;
     int64_t nnz = 0;
     if (hipMemcpyAsync(&nnz, d_row_ptr + N, sizeof(int64_t), hipMemcpyDeviceToHost, stream) != hipSuccess)
         return fail(RETEXO_E_HIP);
@@ -147,72 +241,50 @@ extern "C" int retexo_plan_create(retexo_plan** out, int64_t N, const int64_t* d
     if (nnz >= (1ll << 31)) return fail(RETEXO_E_SIZE);
     if (nnz > 0 && !d_col_idx) return fail(RETEXO_E_NULL);
     p->nnz = nnz;
-    // Dense-enough graphs whose feature table cannot stay in L2 get the row split that lets
-    // the aggregation walk one source-id range at a time.
-    const bool split = N > 0 && nnz > 0 &&
-        ((flags & RETEXO_F_SPLIT_ROWS) ||
-         (nnz >= 64 * N && N * 128 > (4ll << 20) && N * 128 <= kMaxParts * (8ll << 20)));
-    const int64_t o_deg = 0, o_dinv = align_up(4 * n1, 256), o_order = 2 * o_dinv, o_part = 3 * o_dinv;
-    const int64_t keep_bytes = o_part + (split ? align_up(4 * N * (kMaxParts + 1), 256) : 0);
-    if (hipMalloc(&p->block, (size_t)keep_bytes) != hipSuccess) return fail(RETEXO_E_HIP);
-    p->deg = (int32_t*)((char*)p->block + o_deg);
-    p->dinv = (float*)((char*)p->block + o_dinv);
-    p->order = (int32_t*)((char*)p->block + o_order);
-
-    size_t sort_bytes = 0;
-    if (N > 0 &&
-        rocprim::radix_sort_pairs_desc(nullptr, sort_bytes, (uint32_t*)nullptr, (uint32_t*)nullptr,
-                                       (int32_t*)nullptr, (int32_t*)nullptr, (size_t)N, 0u, 32u,
-                                       stream) != hipSuccess)
-        return fail(RETEXO_E_HIP);
-    // scratch: keys_in, keys_out, ids_in, readback block, sort temp
-    const int64_t o_kin = 0, o_kout = align_up(4 * n1, 256), o_ids = 2 * o_kout, o_rb = 3 * o_kout;
-    const int64_t o_tmp = o_rb + 256;
-    if (hipMalloc(&p->build_scratch, (size_t)(o_tmp + align_up((int64_t)sort_bytes, 256) + 256)) != hipSuccess)
-        return fail(RETEXO_E_HIP);
-    char* sc = (char*)p->build_scratch;
-    uint32_t* kin = (uint32_t*)(sc + o_kin);
-    uint32_t* kout = (uint32_t*)(sc + o_kout);
-    int32_t* ids = (int32_t*)(sc + o_ids);
-    Readback* rb = (Readback*)(sc + o_rb);
-
-    if (hipMemsetAsync(rb, 0, sizeof(Readback), stream) != hipSuccess) return fail(RETEXO_E_HIP);
-    if (N > 0) {
-        degree_kernel<<<dim3((unsigned)((N + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            N, d_row_ptr, p->deg, p->dinv, kin, ids, &rb->bad);
-        if (rocprim::radix_sort_pairs_desc(sc + o_tmp, sort_bytes, kin, kout, ids, p->order, (size_t)N,
-                                           0u, 32u, stream) != hipSuccess)
-            return fail(RETEXO_E_HIP);
-        Thresholds th;
-        for (int i = 0; i < 8; ++i) th.t[i] = kPlanThresholds[i];
-        count_at_least<<<dim3(1), dim3(64), 0, stream>>>(N, kout, th, rb->counts);
-    }
-    if (split) {
-        // needs only the schedule order, so it runs before the host looks at the counts
-        p->part_ptr = (int32_t*)((char*)p->block + o_part);
-        p->part_span = (N + kMaxParts - 1) / kMaxParts;
-        const int64_t rows_per_block = kThreads / 64;
-        split_rows_kernel<<<dim3((unsigned)((N + rows_per_block - 1) / rows_per_block)), dim3(kThreads), 0, stream>>>(
-            N, nnz, p->part_span, d_row_ptr, d_col_idx, p->order, p->part_ptr);
-    }
-    Readback h;
-    if (hipMemcpyAsync(&h, rb, sizeof(h), hipMemcpyDeviceToHost, stream) != hipSuccess) return fail(RETEXO_E_HIP);
-    if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
-    if (h.bad) return fail(RETEXO_E_CSR);
-    for (int i = 0; i < 8; ++i) p->rows_at_least[i] = h.counts[i];
-    p->max_degree = (int32_t)h.counts[8];
-
-    if ((flags & RETEXO_F_VALIDATE) && p->nnz > 0) {
-        check_columns<<<dim3((unsigned)((p->nnz + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-            p->nnz, N, d_col_idx, &rb->bad);
-        uint32_t bad = 0;
-        if (hipMemcpyAsync(&bad, &rb->bad, sizeof(bad), hipMemcpyDeviceToHost, stream) != hipSuccess)
-            return fail(RETEXO_E_HIP);
-        if (hipStreamSynchronize(stream) != hipSuccess) return fail(RETEXO_E_HIP);
-        if (bad) return fail(RETEXO_E_CSR);
-    }
+    PlanLayout L;
+    if (int e = plan_layout(N, nnz, flags, L)) return fail(e);
+    if (hipMalloc(&p->block, (size_t)L.keep_bytes) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (hipMalloc(&p->build_scratch, (size_t)L.scratch_bytes) != hipSuccess) return fail(RETEXO_E_HIP);
+    if (int e = plan_fill(p, L, flags, p->block, p->build_scratch, stream)) return fail(e);
     (void)hipFree(p->build_scratch);
     p->build_scratch = nullptr;
+    *out = p;
+    return RETEXO_OK;
+}
+
+extern "C" int64_t retexo_plan_workspace_bytes(int64_t N, int64_t nnz, unsigned flags)
+{
+    if (N < 0 || N >= (1ll << 31) || nnz < 0 || nnz >= (1ll << 31)) return RETEXO_E_SIZE;
+    if (flags & ~(unsigned)(RETEXO_F_VALIDATE | RETEXO_F_SPLIT_ROWS)) return RETEXO_E_FLAGS;
+    PlanLayout L;
+    if (int e = plan_layout(N, nnz, flags, L)) return e;
+    return L.keep_bytes + L.scratch_bytes;
+}
+
+extern "C" int retexo_plan_create_in(retexo_plan** out, int64_t N, int64_t nnz, const int64_t* d_row_ptr,
+                                     const int32_t* d_col_idx, unsigned flags,
+                                     void* d_workspace, int64_t workspace_bytes, void* stream_)
+{
+    if (!out) return RETEXO_E_NULL;
+    *out = nullptr;
+    if (N < 0 || N >= (1ll << 31) || nnz < 0 || nnz >= (1ll << 31)) return RETEXO_E_SIZE;
+    if (flags & ~(unsigned)(RETEXO_F_VALIDATE | RETEXO_F_SPLIT_ROWS)) return RETEXO_E_FLAGS;
+    if (!d_row_ptr || (nnz > 0 && !d_col_idx)) return RETEXO_E_NULL;
+    PlanLayout L;
+    if (int e = plan_layout(N, nnz, flags, L)) return e;
+    if (!d_workspace || ((uintptr_t)d_workspace & 255) != 0 || workspace_bytes < L.keep_bytes + L.scratch_bytes)
+        return RETEXO_E_WORKSPACE;
+    retexo_plan* p = new (std::nothrow) retexo_plan();
+    if (!p) return RETEXO_E_HIP;
+    p->N = N;
+    p->nnz = nnz;
+    p->row_ptr = d_row_ptr;
+    p->col_idx = d_col_idx;
+    // the plan's arrays live in the caller's workspace: nothing to free but the host structure
+    if (int e = plan_fill(p, L, flags, d_workspace, (char*)d_workspace + L.keep_bytes, (hipStream_t)stream_)) {
+        delete p;
+        return e;
+    }
     *out = p;
     return RETEXO_OK;
 }

@@ -67,11 +67,19 @@ def csr_from_coo(src: torch.Tensor, dst: torch.Tensor, n_nodes: int, self_loops:
     return DeviceGraph(n_nodes, nnz, row_ptr, col_idx)
 
 
-def make_plan(g: DeviceGraph, validate: bool = False, split_rows: bool = False) -> DeviceGraph:
+def make_plan(g: DeviceGraph, validate: bool = False, split_rows: bool = False,
+              workspace: Optional[torch.Tensor] = None) -> DeviceGraph:
+    """``workspace``: caller memory the plan lives in (retexo_plan_create_in: no allocation, one synchronisation);
+    it must stay untouched while the plan is in use."""
     flags = (B.F_VALIDATE if validate else 0) | (B.F_SPLIT_ROWS if split_rows else 0)
-    st, plan = B.retexo_plan_create(g.n_nodes, g.row_ptr.data_ptr(), g.col_idx.data_ptr(),
-                                    flags, _stream_ptr())
-    B.check(st, "retexo_plan_create")
+    if workspace is not None:
+        st, plan = B.retexo_plan_create_in(g.n_nodes, g.nnz, g.row_ptr.data_ptr(), g.col_idx.data_ptr(), flags,
+                                           workspace.data_ptr(), workspace.numel(), _stream_ptr())
+        B.check(st, "retexo_plan_create_in")
+    else:
+        st, plan = B.retexo_plan_create(g.n_nodes, g.row_ptr.data_ptr(), g.col_idx.data_ptr(),
+                                        flags, _stream_ptr())
+        B.check(st, "retexo_plan_create")
     g.plan = plan
     return g
 
@@ -338,13 +346,18 @@ class Pipeline:
             self.outs.append(torch.empty((self.n, pad_ld(st.out_width)), dtype=torch.float32, device="cuda"))
         self.graph: Optional[DeviceGraph] = None
         self.round_ws: Optional[torch.Tensor] = None
+        self.plan_ws: Optional[torch.Tensor] = None
 
     def build_graph(self) -> DeviceGraph:
         if self.graph is not None:
             self.graph.destroy()
         g = csr_from_coo(self.src, self.dst, self.n, self.wl.self_loops, self.csr_ws,
                          self.row_ptr, self.col_idx)
-        self.graph = make_plan(g)
+        # the plan lives in a buffer of the pipeline: a step allocates nothing
+        need = B.retexo_plan_workspace_bytes(self.n, g.nnz, 0)
+        if self.plan_ws is None or self.plan_ws.numel() < need:
+            self.plan_ws = ws_tensor(need)
+        self.graph = make_plan(g, workspace=self.plan_ws)
         if self.round_ws is None:
             need = 0
             for st in self.wl.stages:

@@ -258,3 +258,39 @@ def test_csr_of_a_graph_beyond_the_bucketing_range():
     orp, oci = oracle.csr_from_coo(src, dst, n, False)
     assert g.nnz == orp[-1]
     assert np.array_equal(g.row_ptr.cpu().numpy(), orp) and np.array_equal(g.col_idx[:g.nnz].cpu().numpy(), oci)
+
+
+@pytest.mark.parametrize("split_rows", [False, True])
+def test_plan_in_caller_memory_equals_the_allocating_plan(split_rows):
+    # retexo_plan_create_in: same arrays, no allocation, the entry count stated by the caller
+    n = 3000
+    src, dst = wl.graph_power_law(n, 60000, 2.2, 20.0, 400.0, 3)
+    g = Hn.csr_from_coo(Hn.dev(src), Hn.dev(dst), n, False)
+    a = Hn.make_plan(Hn.DeviceGraph(n, g.nnz, g.row_ptr, g.col_idx), validate=True, split_rows=split_rows)
+    flags = B.F_VALIDATE | (B.F_SPLIT_ROWS if split_rows else 0)
+    need = B.retexo_plan_workspace_bytes(n, g.nnz, flags)
+    assert need > 0
+    ws = Hn.ws_tensor(need)
+    b = Hn.make_plan(Hn.DeviceGraph(n, g.nnz, g.row_ptr, g.col_idx), validate=True, split_rows=split_rows, workspace=ws)
+    for x, y in zip(Hn.plan_arrays(a), Hn.plan_arrays(b)):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    assert B.retexo_plan_max_degree(a.plan) == B.retexo_plan_max_degree(b.plan)
+    assert B.retexo_plan_nnz(b.plan) == g.nnz
+    if split_rows:
+        sa, pa = _split_positions(a)
+        sb, pb = _split_positions(b)
+        assert sa == sb and np.array_equal(pa, pb)
+    Z = Hn.dev(wl.random_matrix(n, 40, 6))
+    assert torch.equal(Hn.aggregate(a, "mean", Z, 40)[:, :40], Hn.aggregate(b, "mean", Z, 40)[:, :40])
+    # argument errors: wrong entry count, workspace too small or misaligned
+    rp, ci = g.row_ptr.data_ptr(), g.col_idx.data_ptr()
+    st, plan = B.retexo_plan_create_in(n, g.nnz + 1, rp, ci, flags, ws.data_ptr(), ws.numel())
+    assert st == B.E_CSR and plan is None
+    st, plan = B.retexo_plan_create_in(n, g.nnz, rp, ci, flags, ws.data_ptr(), need - 1)
+    assert st == B.E_WORKSPACE and plan is None
+    st, plan = B.retexo_plan_create_in(n, g.nnz, rp, ci, flags, ws.data_ptr() + 64, ws.numel())
+    assert st == B.E_WORKSPACE and plan is None
+    st, plan = B.retexo_plan_create_in(n, g.nnz, 0, ci, flags, ws.data_ptr(), ws.numel())
+    assert st == B.E_NULL and plan is None
+    a.destroy()
+    b.destroy()
