@@ -196,6 +196,8 @@ struct PlanArrays {
     uint32_t* group_off;      // [n_groups + 1]
     uint32_t* group_cursor;   // [n_groups] part1's write positions
     uint32_t* group_tile0;    // [n_groups + 1] first part2 tile of each group
+    uint16_t* coarse_group;   // [kMaxBins / 16] per block of 16 bins: group of its first bin | (bin offset inside the
+                              // block at which the next group starts, 16 = none) << 10
 };
 
 // A bin starts a bucket when the entries before it cross a multiple of kTarget, when it is the
@@ -282,25 +284,43 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(int nbins, int span_bins
         a.group_tile0[n_groups] = n_tiles;
         hdr->part2_tiles = n_tiles;
     }
+    __syncthreads();                               // the group arrays are complete
+    // A group other than the last holds 256 buckets, i.e. at least 256 bins, so a block of 16 bins meets at most
+    // one group boundary.
+    for (int c = threadIdx.x; c < kMaxBins / 16; c += kThreads) {
+        const uint32_t first_bin = (uint32_t)c << 4;
+        uint32_t g = n_groups - 1, at = 16;
+        if (first_bin < (uint32_t)nbins) {
+            g = (uint32_t)find_segment(a.group_bin0, (int)n_groups, first_bin);
+            if (g + 1 < n_groups && a.group_bin0[g + 1] - first_bin < 16u) at = a.group_bin0[g + 1] - first_bin;
+        }
+        a.coarse_group[c] = (uint16_t)(g | (at << 10));
+    }
 }
 
 // ---------------------------------------------------------------------------
 // part1: the entries of one tile of items go to their groups as (row, col) pairs.
 __global__ __launch_bounds__(kThreads) void part1_kernel(
     int64_t n_pairs, const int32_t* __restrict__ src, const int32_t* __restrict__ dst, int64_t N, int64_t n_items, int s,
-    const uint32_t* __restrict__ group_bin0, uint32_t* group_cursor, uint32_t* __restrict__ rows_out,
+    const uint16_t* __restrict__ coarse_group, uint32_t* group_cursor, uint32_t* __restrict__ rows_out,
     uint32_t* __restrict__ cols_out, const BucketHeader* hdr)
 {
     constexpr int IPT = kItemsPerTile / kThreads;          // items per thread
-    __shared__ uint32_t gb0[kMaxGroups + 1];
     __shared__ uint32_t toff[kMaxGroups + 1];
     __shared__ uint32_t base[kMaxGroups];
     __shared__ uint32_t srow[2 * kItemsPerTile], scol[2 * kItemsPerTile];
     __shared__ uint32_t sc[2 * kWaves + 1];
+    __shared__ uint16_t coarse[kMaxBins / 16];
     if (hdr->bad_id || hdr->internal) return;
     const int G = (int)hdr->n_groups;
-    for (int i = threadIdx.x; i <= G; i += kThreads) { gb0[i] = group_bin0[i]; toff[i] = 0u; }
+    for (int i = threadIdx.x; i <= G; i += kThreads) toff[i] = 0u;
+    for (int c = threadIdx.x; c < kMaxBins / 16; c += kThreads) coarse[c] = coarse_group[c];
     __syncthreads();
+    // the group of a bin: that of its block's first bin, or the next one from the recorded offset on
+    auto group_of = [&](uint32_t bin) {
+        const uint32_t e = coarse[bin >> 4];
+        return (int)((e & 0x3ffu) + ((bin & 15u) >= (e >> 10) ? 1u : 0u));
+    };
 
     // slot 2k / 2k+1: the entries of the thread's k-th item; group kNone marks an unused slot
     constexpr uint32_t kNone = 0xffffffffu;
@@ -315,12 +335,12 @@ __global__ __launch_bounds__(kThreads) void part1_kernel(
         eg[2 * k] = eg[2 * k + 1] = kNone;
         erank[2 * k] = erank[2 * k + 1] = 0u;
         if (cnt >= 1) {
-            const int g = find_segment(gb0, G, r0 >> s);
+            const int g = group_of(r0 >> s);
             eg[2 * k] = (uint32_t)g;
             erank[2 * k] = atomicAdd(&toff[g], 1u);
         }
         if (cnt == 2) {
-            const int g = find_segment(gb0, G, r1 >> s);
+            const int g = group_of(r1 >> s);
             eg[2 * k + 1] = (uint32_t)g;
             erank[2 * k + 1] = atomicAdd(&toff[g], 1u);
         }
@@ -336,20 +356,22 @@ __global__ __launch_bounds__(kThreads) void part1_kernel(
     }
     if (threadIdx.x == 0) toff[G] = total;
     __syncthreads();
+    // ids are below 2^23, so the nine high bits of a staged row and the high bit of a staged column are free:
+    // they carry the entry's group (below 1024) to the write loop
 #pragma unroll
     for (int k = 0; k < 2 * IPT; ++k)
         if (eg[k] != kNone) {
             const uint32_t p = toff[eg[k]] + erank[k];
-            srow[p] = er[k];
-            scol[p] = ec[k];
+            srow[p] = er[k] | ((eg[k] & 0x1ffu) << 23);
+            scol[p] = ec[k] | ((eg[k] >> 9) << 23);
         }
     __syncthreads();
     for (uint32_t j = threadIdx.x; j < total; j += kThreads) {
-        const int g = find_segment(toff, G, j);            // toff[g] <= j < toff[g + 1] (empty groups repeat an offset:
-                                                           // the largest g with toff[g] <= j is the one that holds j)
+        const uint32_t r = srow[j], c = scol[j];
+        const uint32_t g = (r >> 23) | ((c >> 23) << 9);
         const uint32_t d = base[g] + (j - toff[g]);
-        rows_out[d] = srow[j];
-        cols_out[d] = scol[j];
+        rows_out[d] = r & 0x7fffffu;
+        cols_out[d] = c & 0x7fffffu;
     }
 }
 
@@ -368,6 +390,7 @@ __global__ __launch_bounds__(kThreads) void part2_kernel(
     __shared__ uint32_t toff[kGroupBuckets + 1];
     __shared__ uint32_t base[kGroupBuckets];
     __shared__ uint32_t stage[kTileEntries];
+    __shared__ uint8_t stage_lb[kTileEntries];             // local bucket of each staged entry
     __shared__ uint32_t sc[2 * kWaves + 1];
     if (hdr->bad_id || hdr->internal) return;
     const uint32_t n_buckets = hdr->n_buckets;
@@ -383,13 +406,23 @@ __global__ __launch_bounds__(kThreads) void part2_kernel(
     const int nb = (int)(first + kGroupBuckets < n_buckets ? kGroupBuckets : n_buckets - first);
     for (int i = threadIdx.x; i <= nb; i += kThreads) { bb0[i] = bucket_bin0[first + i]; toff[i] = 0u; }
     __syncthreads();
+    // the group's bins -> local bucket, looked up directly when the group spans few enough bins
+    constexpr int kDirect = 4096;
+    __shared__ uint8_t bin_lb[kDirect];
+    const uint32_t bin_first = bb0[0], bin_span = bb0[nb] - bb0[0];
+    const bool direct = bin_span <= (uint32_t)kDirect;
+    if (direct) {
+        for (uint32_t i = threadIdx.x; i < bin_span; i += kThreads)
+            bin_lb[i] = (uint8_t)find_segment(bb0, nb, bin_first + i);
+        __syncthreads();
+    }
 
     // slot k: one entry (FROM_PAIRS: slots 2k / 2k+1 are the entries of the thread's k-th item); bucket kNone = unused
     constexpr uint32_t kNone = 0xffffffffu;
     uint32_t ev[EPT], erank[EPT], eb[EPT];
     bool bad = false;
     auto take = [&](uint32_t r, uint32_t c, uint32_t& v, uint32_t& lb_out, uint32_t& rank) {
-        const int lb = find_segment(bb0, nb, r >> s);
+        const int lb = direct ? (int)bin_lb[(r >> s) - bin_first] : find_segment(bb0, nb, r >> s);
         v = ((r - (bb0[lb] << s)) << cbits) | c;
         lb_out = (uint32_t)lb;
         rank = atomicAdd(&toff[lb], 1u);
@@ -424,10 +457,14 @@ __global__ __launch_bounds__(kThreads) void part2_kernel(
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < EPT; ++k)
-        if (eb[k] != kNone) stage[toff[eb[k]] + erank[k]] = ev[k];
+        if (eb[k] != kNone) {
+            const uint32_t p = toff[eb[k]] + erank[k];
+            stage[p] = ev[k];
+            stage_lb[p] = (uint8_t)eb[k];
+        }
     __syncthreads();
     for (uint32_t j = threadIdx.x; j < total; j += kThreads) {
-        const int lb = find_segment(toff, nb, j);
+        const uint32_t lb = stage_lb[j];
         packed_out[base[lb] + (j - toff[lb])] = stage[j];
     }
 }
@@ -793,7 +830,7 @@ struct BucketLayout {
     int64_t M, n_items, items_per_block, bucket_bound;
     bool two_level;
     int64_t header, counts, bin_count, bin_off, bucket_bin0, bucket_off, bucket_cursor, bucket_total, bucket_out,
-        group_bin0, group_off, group_cursor, group_tile0, buf_a, buf_b, buf_c, row_unique, total;
+        group_bin0, group_off, group_cursor, group_tile0, coarse_group, buf_a, buf_b, buf_c, row_unique, total;
 };
 
 bool make_bucket_layout(int64_t n_pairs, int64_t N, int add_self_loops, BucketLayout& L)
@@ -832,6 +869,7 @@ bool make_bucket_layout(int64_t n_pairs, int64_t N, int add_self_loops, BucketLa
     L.group_off = take(4 * (kMaxGroups + 1));
     L.group_cursor = take(4 * kMaxGroups);
     L.group_tile0 = take(4 * (kMaxGroups + 1));
+    L.coarse_group = take(2 * (kMaxBins / 16));
     L.buf_a = take(4 * m);                                   // part1: rows; later the sorted columns of the buckets
     L.buf_b = L.two_level ? take(4 * m) : off;               // part1: columns
     L.buf_c = take(4 * m);                                   // part2: packed entries
@@ -859,7 +897,8 @@ int csr_build_bucketed(int64_t n_pairs, const int32_t* d_src, const int32_t* d_d
     BucketHeader* hdr = (BucketHeader*)(ws + L.header);
     auto u32 = [&](int64_t at) { return (uint32_t*)(ws + at); };
     PlanArrays pa{u32(L.bin_off), u32(L.bucket_bin0), u32(L.bucket_off), u32(L.bucket_cursor),
-                  u32(L.group_bin0), u32(L.group_off), u32(L.group_cursor), u32(L.group_tile0)};
+                  u32(L.group_bin0), u32(L.group_off), u32(L.group_cursor), u32(L.group_tile0),
+                  (uint16_t*)(ws + L.coarse_group)};
 
     RETEXO_HIP_TRY(hipMemsetAsync(hdr, 0, (size_t)(L.counts - L.header), stream));      // header and bin counts
     hist_kernel<<<dim3((unsigned)L.hist_blocks), dim3(kThreads), 0, stream>>>(
@@ -872,7 +911,7 @@ int csr_build_bucketed(int64_t n_pairs, const int32_t* d_src, const int32_t* d_d
     if (L.M > 0) {
         if (L.two_level) {
             part1_kernel<<<dim3(item_tiles), dim3(kThreads), 0, stream>>>(
-                n_pairs, d_src, d_dst, N, L.n_items, L.s, pa.group_bin0, pa.group_cursor, u32(L.buf_a), u32(L.buf_b), hdr);
+                n_pairs, d_src, d_dst, N, L.n_items, L.s, pa.coarse_group, pa.group_cursor, u32(L.buf_a), u32(L.buf_b), hdr);
             const unsigned tiles = (unsigned)((L.M + kTileEntries - 1) / kTileEntries + kMaxGroups);
             part2_kernel<false><<<dim3(tiles), dim3(kThreads), 0, stream>>>(
                 n_pairs, d_src, d_dst, N, L.n_items, L.s, L.cbits, u32(L.buf_a), u32(L.buf_b), pa.group_off,
