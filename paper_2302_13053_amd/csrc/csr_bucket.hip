@@ -47,7 +47,6 @@ constexpr int kBucketMax = 10240;        // entries a bucket can hold in LDS (10
 constexpr int kTarget = kBucketMax / 2;  // entries a bucket is filled to
 constexpr int kRowSpan = 1024;           // rows per bucket at most (one per thread of the sort)
 constexpr int kSortBins = kBucketMax / 4 + kRowSpan;   // bins of the LDS split: a row of c entries gets < max(1, c/4)
-constexpr int kKeysPerThread = kBucketMax / kThreads;
 constexpr int kStack = 400;              // key ranges waiting in an oversized bucket (6 levels x 63 + 1)
 
 struct BucketHeader {       // start of the workspace
@@ -58,19 +57,8 @@ struct BucketHeader {       // start of the workspace
     uint32_t n_groups;
     uint32_t part2_tiles;
     uint32_t internal;      // a construction invariant failed (never expected)
-#ifdef RETEXO_CSR_TIMING
-    unsigned long long phase[24];   // summed 100 MHz ticks per phase of the sort kernel (thread 0 of each workgroup)
-#endif
 };
 
-#ifdef RETEXO_CSR_TIMING
-#define PHASE_INIT() unsigned long long _t_prev = wall_clock64()
-#define PHASE(hdr, i) do { if (threadIdx.x == 0) { const unsigned long long _t = wall_clock64(); \
-        atomicAdd(&(hdr)->phase[i], _t - _t_prev); _t_prev = _t; } } while (0)
-#else
-#define PHASE_INIT() do {} while (0)
-#define PHASE(hdr, i) do {} while (0)
-#endif
 
 // exclusive prefix sum over the workgroup (NW waves); `total` is the sum over all threads.
 // sc: 2 * NW + 1 words of LDS scratch, free again when the call returns.
@@ -471,62 +459,74 @@ __global__ __launch_bounds__(kThreads) void part2_kernel(
 
 // ---------------------------------------------------------------------------
 // sort: LDS state of one bucket
+constexpr int kSortThreads = 1024;       // threads of the sort kernel (512 with twice the keys per thread measured 15 % slower)
+constexpr int kSortWaves = kSortThreads / 64;
+constexpr int kSortKeys = kBucketMax / kSortThreads;     // keys per thread
+constexpr int kSortRows = kRowSpan / kSortThreads;       // rows per thread
 constexpr uint32_t kMerged = 255u;       // "bits" of a key range that was put together from small pieces (never split)
 struct SortShared {
     uint32_t keys[kBucketMax + 4];       // (the rank loop looks at four keys at a time)
     uint32_t bins[kSortBins + 1];
-    uint32_t rowcnt[kRowSpan];           // entries per row: first all of them (to size the row's bins), then the kept ones
+    uint32_t rowraw[kRowSpan];           // entries per row in the keys being sorted (sizes the row's bins)
+    uint32_t rowcnt[kRowSpan];           // entries kept per row so far
     uint32_t rowmeta[kRowSpan];          // first bin of the row | (column shift of its bins << 16)
     uint32_t stk_lo[kStack], stk_hi[kStack], stk_bits[kStack], stk_cnt[kStack];
-    uint32_t sc[2 * kWaves + 1];
+    uint32_t sc[2 * kSortWaves + 1];
     uint32_t n, sp;
 };
 
 // Sort the n <= kBucketMax keys in sh.keys, drop repeats, append the columns to out[out_cursor ...) and add
 // the kept entries to the per-row counts.  Returns the number of kept keys (uniform over the workgroup).
+// On entry all threads have passed a barrier after the last write to sh.keys; on return sh.keys is free.
 __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbits, uint32_t* __restrict__ out,
-                                  uint32_t out_cursor, BucketHeader* hdr)
+                                  uint32_t out_cursor)
 {
-    PHASE_INIT();
     const int tid = threadIdx.x;
     const uint32_t cmask = (1u << cbits) - 1u;
-    // On entry sh.rowcnt is what the rows have kept so far; it is saved in registers (one row per thread),
-    // the array is used for this call's raw counts, and the sum goes back at the end.
-    const uint32_t kept_before = tid < nrows ? sh.rowcnt[tid] : 0u;
-    if (tid < nrows) sh.rowcnt[tid] = 0u;                    // (thread t owns row t here; everyone else waits below)
+    for (int i = tid; i < nrows; i += kSortThreads) sh.rowraw[i] = 0u;
+    for (int i = tid; i <= kSortBins; i += kSortThreads) sh.bins[i] = 0u;
     __syncthreads();
-    uint32_t k[kKeysPerThread], r[kKeysPerThread];
+    uint32_t k[kSortKeys], r[kSortKeys];
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {                 // uniform per wave: i < n holds or fails for whole waves
-        const uint32_t i = tid + j * kThreads;                 // except in the last one, which lds_count handles
+    for (int j = 0; j < kSortKeys; ++j) {                      // every lane runs every step (lds_count needs whole waves)
+        const uint32_t i = tid + j * kSortThreads;
         const bool have = i < n;
         k[j] = have ? sh.keys[i] : 0u;
-        lds_count(sh.rowcnt, k[j] >> cbits, have);
+        lds_count(sh.rowraw, k[j] >> cbits, have);
     }
     __syncthreads();
-    PHASE(hdr, 3);
     // a row of c entries gets 2^lg bins, 2^lg = the power of two at or above c, over 8 (at least one):
     // between c/8 and c/4 bins, so that a bin holds 4 to 8 entries when the columns are spread evenly
-    uint32_t nbins_total;
     {
-        uint32_t nsub = 0, lg = 0;
-        if (tid < nrows) {
-            const uint32_t c = sh.rowcnt[tid];
-            lg = c <= 8u ? 0u : (uint32_t)(32 - __clz(c - 1u)) - 3u;
-            lg = lg > (uint32_t)cbits ? (uint32_t)cbits : lg;
-            nsub = 1u << lg;
-        }
-        const uint32_t first = block_scan_excl<kWaves>(nsub, sh.sc, nbins_total);      // <= kSortBins
-        if (tid < nrows) sh.rowmeta[tid] = first | (((uint32_t)cbits - lg) << 16);
-    }
-    for (uint32_t i = tid; i <= nbins_total; i += kThreads) sh.bins[i] = 0u;
-    __syncthreads();
-    PHASE(hdr, 4);
-    // counting split; the atomic's old value is the rank inside the bin
-    uint32_t bin[kKeysPerThread];
+        uint32_t lg[kSortRows], nsub = 0;
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-        const uint32_t i = tid + j * kThreads;
+        for (int j = 0; j < kSortRows; ++j) {
+            const int row = tid * kSortRows + j;
+            lg[j] = 0u;
+            if (row < nrows) {
+                const uint32_t c = sh.rowraw[row];
+                lg[j] = c <= 8u ? 0u : (uint32_t)(32 - __clz(c - 1u)) - 3u;
+                lg[j] = lg[j] > (uint32_t)cbits ? (uint32_t)cbits : lg[j];
+                nsub += 1u << lg[j];
+            }
+        }
+        uint32_t nbins_total;                                  // <= kSortBins
+        uint32_t first = block_scan_excl<kSortWaves>(nsub, sh.sc, nbins_total);
+#pragma unroll
+        for (int j = 0; j < kSortRows; ++j) {
+            const int row = tid * kSortRows + j;
+            if (row < nrows) {
+                sh.rowmeta[row] = first | (((uint32_t)cbits - lg[j]) << 16);
+                first += 1u << lg[j];
+            }
+        }
+    }
+    __syncthreads();
+    // counting split; the atomic's old value is the rank inside the bin
+    uint32_t bin[kSortKeys];
+#pragma unroll
+    for (int j = 0; j < kSortKeys; ++j) {
+        const uint32_t i = tid + j * kSortThreads;
         if (i < n) {
             const uint32_t meta = sh.rowmeta[k[j] >> cbits];
             bin[j] = (meta & 0xffffu) + ((k[j] & cmask) >> (meta >> 16));
@@ -535,38 +535,36 @@ __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbi
     }
     __syncthreads();
     {
-        constexpr int BPT = (kSortBins + kThreads - 1) / kThreads;
+        constexpr int BPT = (kSortBins + kSortThreads - 1) / kSortThreads;
         uint32_t c[BPT], sum = 0;
 #pragma unroll
         for (int j = 0; j < BPT; ++j) {
-            const uint32_t b = tid * BPT + j;
-            c[j] = b < nbins_total ? sh.bins[b] : 0u;
+            const int b = tid * BPT + j;
+            c[j] = b < kSortBins ? sh.bins[b] : 0u;
             sum += c[j];
         }
         uint32_t total;
-        uint32_t o = block_scan_excl<kWaves>(sum, sh.sc, total);
+        uint32_t o = block_scan_excl<kSortWaves>(sum, sh.sc, total);
 #pragma unroll
         for (int j = 0; j < BPT; ++j) {
-            const uint32_t b = tid * BPT + j;
-            if (b < nbins_total) sh.bins[b] = o;
+            const int b = tid * BPT + j;
+            if (b < kSortBins) sh.bins[b] = o;
             o += c[j];
         }
-        if (tid == 0) sh.bins[nbins_total] = total;
+        if (tid == 0) sh.bins[kSortBins] = total;
     }
     __syncthreads();
-    PHASE(hdr, 5);
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-        const uint32_t i = tid + j * kThreads;
+    for (int j = 0; j < kSortKeys; ++j) {
+        const uint32_t i = tid + j * kSortThreads;
         if (i < n) sh.keys[sh.bins[bin[j]] + r[j]] = k[j];
     }
     __syncthreads();
-    PHASE(hdr, 6);
     // rank inside the bin by comparison (a bin holds a few keys); equal keys keep their order of position
-    uint32_t fp[kKeysPerThread];
+    uint32_t fp[kSortKeys];
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-        const uint32_t p = tid + j * kThreads;
+    for (int j = 0; j < kSortKeys; ++j) {
+        const uint32_t p = tid + j * kSortThreads;
         if (p < n) {
             const uint32_t key = sh.keys[p];
             const uint32_t meta = sh.rowmeta[key >> cbits];
@@ -585,17 +583,13 @@ __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbi
         }
     }
     __syncthreads();
-    PHASE(hdr, 7);
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j)
-        if (tid + j * kThreads < n) sh.keys[fp[j]] = k[j];
-    __syncthreads();
-    PHASE(hdr, 8);
-    if (tid < nrows) sh.rowcnt[tid] = kept_before;           // back to "entries kept so far" (sorting is done with the raw counts)
+    for (int j = 0; j < kSortKeys; ++j)
+        if (tid + j * kSortThreads < n) sh.keys[fp[j]] = k[j];
     __syncthreads();
     // keep the first key of every run of equal keys: each thread takes a contiguous piece, reads what it keeps
     // into registers, and after the prefix sum writes it back compacted; rows are counted run by run
-    const uint32_t per = (n + kThreads - 1) / kThreads;          // <= kKeysPerThread
+    const uint32_t per = (n + kSortThreads - 1) / kSortThreads;          // <= kSortKeys
     const uint32_t p0 = tid * per < n ? tid * per : n;
     const uint32_t p1 = p0 + per < n ? p0 + per : n;
     uint32_t kept = 0, keep_mask = 0;
@@ -603,7 +597,7 @@ __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbi
         uint32_t prev = p0 > 0 ? sh.keys[p0 - 1] : 0u;
         uint32_t cur_row = 0xffffffffu, run = 0;
 #pragma unroll
-        for (int j = 0; j < kKeysPerThread; ++j) {
+        for (int j = 0; j < kSortKeys; ++j) {
             const uint32_t p = p0 + j;
             if (p < p1) {
                 const uint32_t key = sh.keys[p];
@@ -625,19 +619,17 @@ __device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbi
         if (run) atomicAdd(&sh.rowcnt[cur_row], run);
     }
     uint32_t total;
-    const uint32_t excl = block_scan_excl<kWaves>(kept, sh.sc, total);      // its barriers separate the reads from the writes
-    PHASE(hdr, 9);
+    const uint32_t excl = block_scan_excl<kSortWaves>(kept, sh.sc, total);  // its barriers separate the reads from the writes
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j)
+    for (int j = 0; j < kSortKeys; ++j)
         if (keep_mask & (1u << j)) sh.keys[excl + (uint32_t)__popc(keep_mask & ((1u << j) - 1u))] = k[j];
     __syncthreads();
-    for (uint32_t i = tid; i < total; i += kThreads) out[out_cursor + i] = sh.keys[i] & cmask;
+    for (uint32_t i = tid; i < total; i += kSortThreads) out[out_cursor + i] = sh.keys[i] & cmask;
     __syncthreads();
-    PHASE(hdr, 10);
     return total;
 }
 
-__global__ __launch_bounds__(kThreads, 8) void sort_kernel(
+__global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
     BucketHeader* hdr, const uint32_t* __restrict__ bucket_off, const uint32_t* __restrict__ bucket_bin0,
     const uint32_t* __restrict__ packed, uint32_t* __restrict__ cols_tmp, int32_t* __restrict__ row_unique,
     uint32_t* __restrict__ bucket_total, int cbits, int s, int64_t N)
@@ -646,35 +638,31 @@ __global__ __launch_bounds__(kThreads, 8) void sort_kernel(
     if (hdr->bad_id || hdr->internal) return;
     const uint32_t b = blockIdx.x;
     if (b >= hdr->n_buckets) return;
-    PHASE_INIT();
     const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t e0 = bucket_off[b], E = bucket_off[b + 1] - e0;
     const int64_t row0 = (int64_t)bucket_bin0[b] << s;
     int64_t row1 = (int64_t)bucket_bin0[b + 1] << s;
     row1 = row1 < N ? row1 : N;
     const int nrows = (int)(row1 - row0);                    // <= kRowSpan
-    for (int i = tid; i < nrows; i += kThreads) sh.rowcnt[i] = 0u;
-    __syncthreads();
+    for (int i = tid; i < nrows; i += kSortThreads) sh.rowcnt[i] = 0u;
     const uint32_t* in = packed + e0;
     uint32_t* out = cols_tmp + e0;
     uint32_t out_cursor = 0;
 
-    PHASE(hdr, 1);
     if (E <= (uint32_t)kBucketMax) {
-        uint32_t v[kKeysPerThread];
+        uint32_t v[kSortKeys];
 #pragma unroll
-        for (int j = 0; j < kKeysPerThread; ++j) {           // all loads in flight before the first is used
-            const uint32_t i = tid + j * kThreads;
+        for (int j = 0; j < kSortKeys; ++j) {                // all loads in flight before the first is used
+            const uint32_t i = tid + j * kSortThreads;
             v[j] = i < E ? in[i] : 0u;
         }
 #pragma unroll
-        for (int j = 0; j < kKeysPerThread; ++j) {
-            const uint32_t i = tid + j * kThreads;
+        for (int j = 0; j < kSortKeys; ++j) {
+            const uint32_t i = tid + j * kSortThreads;
             if (i < E) sh.keys[i] = v[j];
         }
         __syncthreads();
-        PHASE(hdr, 2);
-        if (E > 0) out_cursor = sort_and_emit(sh, E, nrows, cbits, out, 0u, hdr);
+        if (E > 0) out_cursor = sort_and_emit(sh, E, nrows, cbits, out, 0u);
     } else {
         // The bucket does not fit: work through it in key ranges [lo, hi], lowest first.  A range that fits is
         // gathered and sorted.  One that does not is an aligned block of 2^bits keys: it is counted in 64
@@ -692,7 +680,7 @@ __global__ __launch_bounds__(kThreads, 8) void sort_kernel(
             if (tid == 0) { sh.sp = sp - 1; sh.n = 0u; }
             __syncthreads();
             if (cnt <= (uint32_t)kBucketMax) {
-                for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kThreads) {      // uniform per wave
+                for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kSortThreads) {  // uniform per wave
                     const uint32_t i = i0 + lane;
                     const uint32_t key = i < E ? in[i] : 0u;
                     const bool match = i < E && key >= lo && key <= hi;
@@ -707,7 +695,7 @@ __global__ __launch_bounds__(kThreads, 8) void sort_kernel(
                 }
                 __syncthreads();
                 const uint32_t n = sh.n;                       // == cnt
-                out_cursor += sort_and_emit(sh, n, nrows, cbits, out, out_cursor, hdr);
+                out_cursor += sort_and_emit(sh, n, nrows, cbits, out, out_cursor);
             } else if (bits == 0u) {
                 // more than a bucketful of one and the same key: it is kept once
                 if (tid == 0) {
@@ -721,7 +709,7 @@ __global__ __launch_bounds__(kThreads, 8) void sort_kernel(
                 const int nchild = 1 << (bits - cb);
                 if (tid < 64) sh.bins[tid] = 0u;
                 __syncthreads();
-                for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kThreads) {      // uniform per wave
+                for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kSortThreads) {  // uniform per wave
                     const uint32_t i = i0 + lane;
                     const uint32_t key = i < E ? in[i] : 0u;
                     const bool match = i < E && key >= lo && key <= hi;
@@ -754,10 +742,8 @@ __global__ __launch_bounds__(kThreads, 8) void sort_kernel(
         }
     }
     __syncthreads();
-    PHASE(hdr, 11);     // (normal path: nothing; oversized buckets: the whole key-range walk minus its sorts)
-    for (int i = tid; i < nrows; i += kThreads) row_unique[row0 + i] = (int32_t)sh.rowcnt[i];
+    for (int i = tid; i < nrows; i += kSortThreads) row_unique[row0 + i] = (int32_t)sh.rowcnt[i];
     if (tid == 0) bucket_total[b] = out_cursor;
-    PHASE(hdr, 12);
 }
 
 __global__ __launch_bounds__(kThreads) void total_kernel(BucketHeader* hdr, const uint32_t* __restrict__ bucket_total,
@@ -922,7 +908,7 @@ int csr_build_bucketed(int64_t n_pairs, const int32_t* d_src, const int32_t* d_d
                 pa.group_tile0, pa.bucket_bin0, pa.bucket_cursor, u32(L.buf_c), hdr);
         }
     }
-    sort_kernel<<<dim3((unsigned)L.bucket_bound), dim3(kThreads), 0, stream>>>(
+    sort_kernel<<<dim3((unsigned)L.bucket_bound), dim3(kSortThreads), 0, stream>>>(
         hdr, pa.bucket_off, pa.bucket_bin0, u32(L.buf_c), u32(L.buf_a), (int32_t*)(ws + L.row_unique),
         u32(L.bucket_total), L.cbits, L.s, N);
     total_kernel<<<dim3(1), dim3(kThreads), 0, stream>>>(hdr, u32(L.bucket_total), u32(L.bucket_out), col_capacity);
