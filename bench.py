@@ -57,6 +57,9 @@ def parse():
     ap.add_argument("--probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one pass, then one 1 GiB device copy (the known-size "
                          "reference for the byte counters) and one launch of the dominant aggregation; no JSON")
+    ap.add_argument("--probe-transforms", action="store_true",
+                    help="for rocprofv3 --pmc runs: one pass, then every dense transform of the workload launched "
+                         "once more on its own (the last transform dispatches of the run); no JSON")
     return ap.parse_args()
 
 
@@ -214,6 +217,17 @@ def bench_workload(index, args):
     pipe = Hn.Pipeline(w, src, dst, feats, params)
     if args.probe:
         run_probe(w, pipe, torch, Hn, wl)
+        pipe.close()
+        return None
+    if args.probe_transforms:
+        pipe.run()
+        torch.cuda.synchronize()
+        for i, st in enumerate(w.stages):
+            if st.w:
+                Hin = pipe.H0 if i == 0 else pipe.outs[i - 1]
+                Hn.transform(Hin, st.d_in, pipe.params[i][0], pipe.params[i][1], st.relu)
+                torch.cuda.synchronize()
+                print("probe: transform %d x %d -> %d" % (w.n_nodes, st.d_in, st.d_out))
         pipe.close()
         return None
     for _ in range(args.warmup):
@@ -516,7 +530,7 @@ def main():
 
     head_index = 3 if args.config is None else args.config
     head = bench_workload(head_index, args)
-    if args.probe:
+    if args.probe or args.probe_transforms:
         return
     out = {
         "metric": "aggregated edge*feature GFLOP/s per lazy-MP pass (whole path: CSR build, plan, all rounds)",

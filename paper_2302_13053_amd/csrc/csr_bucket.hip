@@ -478,8 +478,13 @@ struct SortShared {
 // Sort the n <= kBucketMax keys in sh.keys, drop repeats, append the columns to out[out_cursor ...) and add
 // the kept entries to the per-row counts.  Returns the number of kept keys (uniform over the workgroup).
 // On entry all threads have passed a barrier after the last write to sh.keys; on return sh.keys is free.
-__device__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbits, uint32_t* __restrict__ out,
-                                  uint32_t out_cursor)
+// Kept out of line on purpose.  The kernel runs two workgroups per CU (64 registers per lane); as a called
+// function this body gets a register allocation of its own and the caller's few live values cross the call
+// through scratch memory (about 1.7 GB each way per construction, visible in the byte counters).  Inlined under
+// the same cap it spills 13 registers inside its loops and the kernel is 7 % slower; inlined without the cap
+// (one workgroup per CU) 30 % slower.
+__device__ __noinline__ uint32_t sort_and_emit(SortShared& sh, uint32_t n, int nrows, int cbits,
+                                                  uint32_t* __restrict__ out, uint32_t out_cursor)
 {
     const int tid = threadIdx.x;
     const uint32_t cmask = (1u << cbits) - 1u;
@@ -649,7 +654,13 @@ __global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
     uint32_t* out = cols_tmp + e0;
     uint32_t out_cursor = 0;
 
-    if (E <= (uint32_t)kBucketMax) {
+    // A bucket that fits is loaded and sorted in one go.  One that does not is worked through in key ranges
+    // [lo, hi], lowest first: a range that fits is gathered and sorted; one that does not is an aligned block
+    // of 2^bits keys, which is counted in 64 pieces by its next key bits; neighbouring pieces are put together
+    // into ranges that fit, and a piece that still does not fit is split again (or is a single repeated key).
+    // Each level removes 6 key bits, so the stack stays below kStack.
+    const bool fits = E <= (uint32_t)kBucketMax;
+    if (fits) {
         uint32_t v[kSortKeys];
 #pragma unroll
         for (int j = 0; j < kSortKeys; ++j) {                // all loads in flight before the first is used
@@ -661,17 +672,17 @@ __global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
             const uint32_t i = tid + j * kSortThreads;
             if (i < E) sh.keys[i] = v[j];
         }
-        __syncthreads();
-        if (E > 0) out_cursor = sort_and_emit(sh, E, nrows, cbits, out, 0u);
-    } else {
-        // The bucket does not fit: work through it in key ranges [lo, hi], lowest first.  A range that fits is
-        // gathered and sorted.  One that does not is an aligned block of 2^bits keys: it is counted in 64
-        // pieces by its next key bits, neighbouring pieces are put together into ranges that fit, and a piece
-        // that still does not fit is split again (or is a single repeated key).  Each level removes 6 key
-        // bits, so the stack stays below kStack.
-        if (tid == 0) { sh.stk_lo[0] = 0u; sh.stk_hi[0] = 0xffffffffu; sh.stk_bits[0] = 32u; sh.stk_cnt[0] = E; sh.sp = 1u; }
-        __syncthreads();
-        for (;;) {
+        if (tid == 0) sh.sp = 0u;
+    } else if (tid == 0) {
+        sh.stk_lo[0] = 0u; sh.stk_hi[0] = 0xffffffffu; sh.stk_bits[0] = 32u; sh.stk_cnt[0] = E; sh.sp = 1u;
+    }
+    __syncthreads();
+    for (bool first = true;; first = false) {
+        uint32_t n;
+        if (fits) {
+            if (!first || E == 0) break;
+            n = E;
+        } else {
             const uint32_t sp = sh.sp;
             if (sp == 0) break;
             const uint32_t lo = sh.stk_lo[sp - 1], hi = sh.stk_hi[sp - 1], bits = sh.stk_bits[sp - 1],
@@ -679,24 +690,7 @@ __global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
             __syncthreads();
             if (tid == 0) { sh.sp = sp - 1; sh.n = 0u; }
             __syncthreads();
-            if (cnt <= (uint32_t)kBucketMax) {
-                for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kSortThreads) {  // uniform per wave
-                    const uint32_t i = i0 + lane;
-                    const uint32_t key = i < E ? in[i] : 0u;
-                    const bool match = i < E && key >= lo && key <= hi;
-                    const uint64_t mask = __ballot(match);
-                    if (mask) {
-                        const int leader = __ffsll((unsigned long long)mask) - 1;
-                        uint32_t at = 0;
-                        if (lane == leader) at = atomicAdd(&sh.n, (uint32_t)__popcll(mask));
-                        at = __shfl(at, leader, 64);
-                        if (match) sh.keys[at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = key;
-                    }
-                }
-                __syncthreads();
-                const uint32_t n = sh.n;                       // == cnt
-                out_cursor += sort_and_emit(sh, n, nrows, cbits, out, out_cursor);
-            } else if (bits == 0u) {
+            if (cnt > (uint32_t)kBucketMax && bits == 0u) {
                 // more than a bucketful of one and the same key: it is kept once
                 if (tid == 0) {
                     out[out_cursor] = lo & ((1u << cbits) - 1u);
@@ -704,7 +698,9 @@ __global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
                 }
                 out_cursor += 1;
                 __syncthreads();
-            } else {
+                continue;
+            }
+            if (cnt > (uint32_t)kBucketMax) {
                 const uint32_t cb = bits > 6u ? bits - 6u : 0u;
                 const int nchild = 1 << (bits - cb);
                 if (tid < 64) sh.bins[tid] = 0u;
@@ -738,8 +734,26 @@ __global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
                     sh.sp = top;
                 }
                 __syncthreads();
+                continue;
             }
+            // the range fits: gather its keys
+            for (uint32_t i0 = (uint32_t)(tid - lane); i0 < E; i0 += kSortThreads) {      // uniform per wave
+                const uint32_t i = i0 + lane;
+                const uint32_t key = i < E ? in[i] : 0u;
+                const bool match = i < E && key >= lo && key <= hi;
+                const uint64_t mask = __ballot(match);
+                if (mask) {
+                    const int leader = __ffsll((unsigned long long)mask) - 1;
+                    uint32_t at = 0;
+                    if (lane == leader) at = atomicAdd(&sh.n, (uint32_t)__popcll(mask));
+                    at = __shfl(at, leader, 64);
+                    if (match) sh.keys[at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = key;
+                }
+            }
+            __syncthreads();
+            n = sh.n;                                          // == cnt
         }
+        out_cursor += sort_and_emit(sh, n, nrows, cbits, out, out_cursor);
     }
     __syncthreads();
     for (int i = tid; i < nrows; i += kSortThreads) row_unique[row0 + i] = (int32_t)sh.rowcnt[i];
