@@ -322,9 +322,25 @@ int launch_zero(void* p, size_t bytes, hipStream_t stream)
 }
 
 namespace {
-// out[v, c] = (1 / heads) * sum_h in[v, h * C + c]; heads added in index order
-__global__ __launch_bounds__(256) void head_mean_kernel(int64_t N, int heads, int64_t C, const float* __restrict__ in,
+// out[v, c] = (1 / heads) * sum_h in[v, h * C + c]; heads added in index order.
+// A row takes 2^lg consecutive threads (2^lg >= C, the surplus idle), so that row and column come from a
+// shift and a mask and the loads of one head are consecutive addresses.
+__global__ __launch_bounds__(256) void head_mean_kernel(int64_t N, int heads, int C, int lg, const float* __restrict__ in,
                                                          int64_t ldi, float* __restrict__ out, int64_t ldo)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t v = i >> lg;
+    const int c = (int)(i & ((1 << lg) - 1));
+    if (v >= N || c >= C) return;
+    const float* row = in + v * ldi + c;
+    float s = 0.0f;
+    for (int h = 0; h < heads; ++h) s += row[h * C];
+    out[v * ldo + c] = s / (float)heads;
+}
+
+// the same for rows wider than 256 columns: one thread per element
+__global__ __launch_bounds__(256) void head_mean_wide_kernel(int64_t N, int heads, int64_t C, const float* __restrict__ in,
+                                                              int64_t ldi, float* __restrict__ out, int64_t ldo)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= N * C) return;
@@ -344,8 +360,16 @@ extern "C" int retexo_head_mean(int64_t N, int heads, int64_t C, const float* d_
     if (N == 0 || C == 0) return RETEXO_OK;
     if (!d_in || !d_out) return RETEXO_E_NULL;
     if (overlaps(d_in, extent_bytes(N, ldi, heads * C), d_out, extent_bytes(N, ldo, C))) return RETEXO_E_ALIAS;
-    head_mean_kernel<<<dim3((unsigned)((N * C + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-        N, heads, C, d_in, ldi, d_out, ldo);
+    if (C <= 256) {
+        int lg = 0;
+        while ((1ll << lg) < C) ++lg;
+        const int64_t threads = N << lg;
+        head_mean_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+            N, heads, (int)C, lg, d_in, ldi, d_out, ldo);
+    } else {
+        head_mean_wide_kernel<<<dim3((unsigned)((N * C + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+            N, heads, C, d_in, ldi, d_out, ldo);
+    }
     if (hipGetLastError() != hipSuccess) return RETEXO_E_HIP;
     return RETEXO_OK;
 }

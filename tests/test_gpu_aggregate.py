@@ -329,7 +329,8 @@ def test_in_place_concat_and_argument_errors(graphs):
     assert args(Z=0) == B.E_NULL
 
 
-@pytest.mark.parametrize("n,heads,C,ldi,ldo", [(1000, 4, 47, 188, 47), (513, 8, 7, 64, 9), (3, 1, 5, 5, 5), (0, 2, 3, 6, 3)])
+@pytest.mark.parametrize("n,heads,C,ldi,ldo", [(1000, 4, 47, 188, 47), (513, 8, 7, 64, 9), (3, 1, 5, 5, 5), (0, 2, 3, 6, 3),
+                                              (50, 2, 300, 608, 300), (77, 4, 64, 256, 64)])
 def test_head_mean(n, heads, C, ldi, ldo):
     """The last attention round's heads are averaged: plain definition (float64 mean over the head axis)."""
     X = wl.random_matrix(max(n, 1), heads * C, 5, ld=ldi)[:n]
