@@ -480,7 +480,10 @@ double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, d
  *       "agg_wide_offsets" (1: 64-bit row offsets even for tables below 4 GiB; these four exist
  *       so that tests reach every code path),
  *       "csr_sorted_keys" (1: retexo_csr_from_coo uses its general sorted-key construction, which
- *       otherwise only graphs of more than 2^23 nodes take, instead of the bucketing one).
+ *       otherwise only graphs of more than 2^23 nodes take, instead of the bucketing one),
+ *       "transform_few_blocks" (retexo_transform and the transforms inside retexo_round: a matrix
+ *       with fewer 128-row blocks, times column blocks, than this takes the kernel that splits K
+ *       over the waves of 32-row workgroups; default 128, 0 = never; RETEXO_E_SIZE if negative).
  * Returns RETEXO_E_FLAGS for an unknown name.
  */
 int retexo_set_option(const char* name, int64_t value);

@@ -86,6 +86,7 @@ extern "C" int retexo_set_option(const char* name, int64_t value)
     if (!strcmp(name, "agg_gat_in_rows")) { o.gat_in_rows = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_wide_offsets")) { o.wide_offsets = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_narrow_heavy")) { o.narrow_heavy = value; return RETEXO_OK; }
+    if (!strcmp(name, "transform_few_blocks")) { if (value < 0) return RETEXO_E_SIZE; o.few_blocks = value; return RETEXO_OK; }
     if (!strcmp(name, "csr_sorted_keys")) { o.csr_sorted_keys = value; return RETEXO_OK; }
     return RETEXO_E_FLAGS;
 }

@@ -54,14 +54,16 @@ __device__ __forceinline__ void zero4(int wanted, float (&r)[4])
 // Contract on entry: tile 0 is in LDS buffer 0 and a barrier has passed; tile 1
 // (if nk > 1) is in the caller's staging registers.  LDS tiles are k-major:
 // As[buf][k][row of the workgroup tile], Bs[buf][k][column]; a0 / b0 are the first
-// row / column of this wave's TM x TN block of 32 x 32 accumulators.
+// row / column of this wave's TM x TN block of 32 x 32 accumulators.  last_steps:
+// k-steps of the last tile that hold data (a K extent that is not a multiple of
+// kTileK leaves the others zero-filled; they are skipped).
 // ---------------------------------------------------------------------------
 #define RETEXO_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 template <int TM, int TN, int LDA, int LDB, class Put, class Fetch>
 __device__ __forceinline__ void mfma_k_loop(f32x16 (&acc)[TM][TN], const float (*As)[kTileK][LDA],
                                             const float (*Bs)[kTileK][LDB], int nk, int a0, int b0, int lane,
-                                            Put&& put, Fetch&& fetch)
+                                            Put&& put, Fetch&& fetch, int last_steps = kTileK / 2)
 {
     constexpr int NSTEP = kTileK / 2;
     static_assert(NSTEP == 8, "the schedule below is written for 8 k-steps");
@@ -80,6 +82,7 @@ __device__ __forceinline__ void mfma_k_loop(f32x16 (&acc)[TM][TN], const float (
         const bool more2 = kt + 2 < nk;
 #pragma unroll
         for (int s = 0; s < NSTEP; ++s) {
+            if (!more && s >= last_steps) break;   // the rest of a partial last tile is zeros: adds nothing, changes no bit
             const int cur = s & 1;
             int q = 0;                        // MFMAs issued in this k-step
 #pragma unroll

@@ -22,12 +22,18 @@
 // barrier per K step sits between the last two k-steps, whose operands are
 // already in registers.  Sources are clamped instead of checked (rows past the
 // end repeat the last row, columns past D_out repeat the last four), so the
-// loop carries no selects; only a partial last K tile takes a checked form.
-// Bias and ReLU are applied to the accumulators on the way out, through one
-// pointer per 32x32 tile that walks down the rows.
+// loop carries no selects; only a partial last K tile takes a checked form
+// (and the k-steps of it that hold nothing but zero fill are skipped: D_in =
+// 100 issues 50 k-steps, not 56).  Bias and ReLU are applied to the
+// accumulators on the way out: through this wave's piece of the dead tiles in
+// LDS and from there as 16-byte pieces of rows where the output allows it,
+// otherwise through one pointer per 32x32 tile that walks down the rows.
 //
-// Shapes whose rows cannot be fetched as aligned 16-byte pieces take the
-// simple kernel below it (same arithmetic, same order, checked scalar loads).
+// W rows that are not multiples of 16 bytes (41, 47, 7 output columns) keep
+// this kernel and fetch W, the small operand, element by element; H rows that
+// cannot be fetched as aligned 16-byte pieces take the simple kernel below it
+// (same arithmetic, same order, checked scalar loads).  Matrices of few rows
+// take the few-rows kernel at the end (K split over the waves of a workgroup).
 #include "common.hpp"
 #include "tiles.hpp"
 
@@ -82,8 +88,61 @@ __device__ __forceinline__ void write_out(const f32x16 (&acc)[TM][TN], const flo
     else run(std::false_type{});
 }
 
-// Aligned shapes: H rows and W rows are multiples of 16 bytes at 16-byte aligned addresses, D_out >= 4.
-template <int BM, int BN, int WGM, int WGN, bool MASKED>
+// The same epilogue for outputs whose rows allow 16-byte stores (Z and the mask 16-byte aligned, ldz, ldm and
+// D_out multiples of four): each 32 x CW block of results goes through this wave's own piece of LDS (T, 32 rows
+// of CW + 4 floats; the K loop's tiles are dead by then) and leaves as whole 16-byte pieces of rows, four times
+// fewer store instructions, each covering full cache lines.  Same values as write_out.
+template <int TM, int TN, int CW, bool MASKED>
+__device__ __forceinline__ void write_out_rows(const f32x16 (&acc)[TM][TN], const float (&bv)[TN], int64_t N, int D_out,
+                                               int64_t row_base, int col_base, int lane, int relu,
+                                               float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm,
+                                               float* __restrict__ T)
+{
+    constexpr int P = CW + 4;            // LDS pitch: rows stay 16-byte aligned, column reads spread over the banks
+    constexpr int JT = CW / 32;          // accumulator tiles per pass
+    constexpr int LPR = CW / 4;          // lanes that cover one row of the pass
+    constexpr int RPI = 64 / LPR;        // rows per store instruction
+    static_assert(TN % JT == 0, "passes cover whole tiles");
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int c4 = (lane % LPR) * 4, rsub = lane / LPR;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j0 = 0; j0 < TN; j0 += JT) {
+#pragma unroll
+            for (int jj = 0; jj < JT; ++jj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ro = 8 * (r / 4) + (r % 4) + 4 * lk;
+                    float x = acc[i][j0 + jj][r] + bv[j0 + jj];
+                    if (relu) x = fmaxf(x, 0.0f);
+                    T[ro * P + jj * 32 + lrow] = x;
+                }
+            const int col = col_base + j0 * 32 + c4;
+#pragma unroll
+            for (int s = 0; s < 32 / RPI; ++s) {
+                const int rr = s * RPI + rsub;
+                f32x4 v = *reinterpret_cast<const f32x4*>(&T[rr * P + c4]);
+                const int64_t row = row_base + i * 32 + rr;
+                if (row < N && col < D_out) {
+                    if constexpr (MASKED) {
+                        const f32x4 m = *reinterpret_cast<const f32x4*>(mask + row * ldm + col);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) v[q] = m[q] > 0.0f ? v[q] : 0.0f;
+                    }
+                    *reinterpret_cast<f32x4*>(Z + row * ldz + col) = v;
+                }
+            }
+        }
+    }
+}
+
+// Aligned shapes: H rows are multiples of 16 bytes at 16-byte aligned addresses.  WVEC: so are the rows of W
+// (D_out % 4 == 0, D_out >= 4); otherwise W — the small operand, resident in L2 — is fetched element by element
+// (same tiles, same order of arithmetic), which lets classifier-width outputs (41, 47, 7 columns) use this kernel
+// and its two-tiles-ahead prefetch of H instead of the simple kernel below.
+// ZVEC: the output (and the mask) allow 16-byte stores, see write_out_rows.
+template <int BM, int BN, int WGM, int WGN, bool MASKED, bool WVEC = true, bool ZVEC = false>
 __global__ __launch_bounds__(256, 2) void transform_kernel(
     int64_t N, int D_in, int D_out, const float* __restrict__ H, int64_t ldh,
     const float* __restrict__ W, const float* __restrict__ bias, int relu,
@@ -98,9 +157,13 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
     constexpr int B_F4 = (BN * BK / 4 + 255) / 256;
     constexpr bool B_PART = BN * BK / 4 % 256 != 0;
     static_assert(A_F4 >= 1, "tile shape");
+    // row-wise epilogue: 64 columns per pass where the tiles leave room for four waves' 32 x 68 blocks, else 32
+    constexpr int CW = (TN % 2 == 0 && 2 * BK * (LDA + LDB) >= 4 * 32 * 68) ? 64 : 32;
+    static_assert(2 * BK * (LDA + LDB) >= 4 * 32 * (CW + 4), "the epilogue's blocks fit in the tiles' memory");
 
-    __shared__ float As[2][BK][LDA];
-    __shared__ float Bs[2][BK][LDB];
+    __shared__ __align__(16) float lds[2 * BK * (LDA + LDB)];
+    float (*As)[BK][LDA] = reinterpret_cast<float (*)[BK][LDA]>(lds);
+    float (*Bs)[BK][LDB] = reinterpret_cast<float (*)[BK][LDB]>(lds + 2 * BK * LDA);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -132,13 +195,20 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
         pa[i] = H + row * ldh + k4 * 4;
         ka[i] = k4 * 4;
     }
+    int cb[B_F4][4];                          // !WVEC: column offsets of the four elements from pb (clamped to the last column)
 #pragma unroll
     for (int i = 0; i < B_F4; ++i) {
         const int id = tid + i * 256;
         const int kk = (id / (BN / 4)) % BK, n4 = id % (BN / 4);
         int n = n0 + n4 * 4;
-        n = n < D_out - 4 ? n : D_out - 4;
-        pb[i] = W + (int64_t)kk * D_out + n;
+        if constexpr (WVEC) {
+            n = n < D_out - 4 ? n : D_out - 4;
+            pb[i] = W + (int64_t)kk * D_out + n;
+        } else {
+            pb[i] = W + (int64_t)kk * D_out;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) cb[i][q] = n + q < D_out ? n + q : D_out - 1;
+        }
         kb[i] = kk;
     }
     const int64_t step_b = (int64_t)BK * D_out;
@@ -164,7 +234,18 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
         for (int i = 0; i < A_F4; ++i) pa[i] += BK;
     };
     auto fetch_b = [&](int kt) {
-        if (k_tail && kt == nk - 1) {
+        if constexpr (!WVEC) {
+            const bool tail = k_tail && kt == nk - 1;
+#pragma unroll
+            for (int i = 0; i < B_F4; ++i) {
+                const bool in = !tail || kb[i] < k_tail;
+                const float* row = in ? pb[i] : W;
+                f32x4 t;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) t[q] = row[cb[i][q]];
+                rb[i] = in ? t : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else if (k_tail && kt == nk - 1) {
 #pragma unroll
             for (int i = 0; i < B_F4; ++i) {
                 const bool in = kb[i] < k_tail;
@@ -226,10 +307,17 @@ __global__ __launch_bounds__(256, 2) void transform_kernel(
         if (half == 0) fetch_a(kt);
         else fetch_b(kt);
     };
-    mfma_k_loop<TM, TN, LDA, LDB>(acc, As, Bs, nk, wm * TM * 32, wn * TN * 32, lane, put, fetch);
+    mfma_k_loop<TM, TN, LDA, LDB>(acc, As, Bs, nk, wm * TM * 32, wn * TN * 32, lane, put, fetch,
+                                  k_tail ? (k_tail + 1) / 2 : BK / 2);
 
-    write_out<TM, TN, MASKED>(acc, bv, N, D_out, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, relu, Z, ldz, mask, ldm,
-                              m0 + BM <= N);
+    if constexpr (ZVEC) {
+        __syncthreads();                      // every wave is done with the last tile
+        write_out_rows<TM, TN, CW, MASKED>(acc, bv, N, D_out, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, relu, Z, ldz,
+                                           mask, ldm, lds + wave * 32 * (CW + 4));
+    } else {
+        write_out<TM, TN, MASKED>(acc, bv, N, D_out, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, relu, Z, ldz, mask, ldm,
+                                  m0 + BM <= N);
+    }
 }
 
 // Any shape: every element is fetched under its own check (HV / WV: the rows of H / W still allow 16-byte
@@ -367,6 +455,132 @@ __global__ __launch_bounds__(256, 2) void transform_generic_kernel(
                               m0 + BM <= N);
 }
 
+// Few rows: a matrix with so few 128-row blocks that they would leave most compute units idle (a citation
+// graph's 2,708 x 2,866 features give 22) is cut into 32-row blocks, and the K extent of each block is cut
+// over the eight waves of its workgroup.  A wave needs no LDS and no barrier in its loop: per group of 8 k it
+// fetches its operands straight into the MFMA layout — lane l holds k = 4 (l / 32) .. + 3 of row l % 32, so
+// MFMA q of the group pairs k = q (lower half-wave) with k = 4 + q (upper half-wave) — four groups at a time,
+// the next four in flight behind the MFMAs.  The eight partial tiles are then added in a fixed order (wave w + wave w + 4 in registers, then
+// ((0 + 1) + 2) + 3 through LDS), so the result is reproducible; it differs from the block kernels' only in
+// the order of the fp32 additions.
+template <int TN, bool HV, bool MASKED>
+__global__ __launch_bounds__(512) void transform_few_rows_kernel(
+    int64_t N, int D_in, int D_out, const float* __restrict__ H, int64_t ldh,
+    const float* __restrict__ W, const float* __restrict__ bias, int relu,
+    float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm)
+{
+    constexpr int BN = TN * 32, NW = 8;
+    __shared__ float part[NW / 2][32][BN];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * 32;
+    const int n0 = blockIdx.y * BN;
+
+    const int groups = (D_in + 7) / 8;
+    const int per = (groups + NW - 1) / NW;
+    const int g0 = wave * per;
+    const int g1 = g0 + per < groups ? g0 + per : groups;
+
+    int64_t row = m0 + lrow;
+    row = row < N ? row : N - 1;                 // rows past the end repeat the last one; never stored
+    const float* hp = H + row * ldh;
+    int col[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int c = n0 + j * 32 + lrow;
+        col[j] = c < D_out ? c : D_out - 1;
+    }
+
+    f32x16 acc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+
+    // operands of U groups at a time, the next U in flight behind this batch's MFMAs (a wave's loop is a chain
+    // of memory latencies; the batch is what keeps enough bytes in flight)
+    constexpr int U = 4;
+    float a[2][U][4], b[2][U][TN][4];
+    auto wanted_of = [&](int g) {                // how many of this lane's four k of group g are data
+        const int left = g < g1 ? D_in - (g * 8 + lk * 4) : 0;
+        return left < 0 ? 0 : (left < 4 ? left : 4);
+    };
+    auto fetch = [&](int gb, int slot) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = (gb + u) * 8 + lk * 4;
+            const int wanted = wanted_of(gb + u);
+            load4<HV>(hp, k, wanted, a[slot][u]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float* wr = W + (int64_t)(q < wanted ? k + q : 0) * D_out;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[slot][u][j][q] = wr[col[j]];
+            }
+        }
+    };
+    auto zero = [&](int gb, int slot) {          // what is not data was fetched from k = 0: replace it
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int wanted = wanted_of(gb + u);
+            zero4<HV>(wanted, a[slot][u]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) zero4<false>(wanted, b[slot][u][j]);
+        }
+    };
+
+    auto batch = [&](int gb, auto slot_tag) {    // slot as a type: register arrays want constant indices
+        constexpr int cur = decltype(slot_tag)::value;
+        if (gb + U < g1) fetch(gb + U, cur ^ 1);
+        RETEXO_SCHED_FENCE();
+        zero(gb, cur);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][u][q], b[cur][u][j][q], acc[j], 0, 0, 0);
+    };
+    if (g0 < g1) fetch(g0, 0);
+    for (int gb = g0; gb < g1; gb += 2 * U) {
+        batch(gb, std::integral_constant<int, 0>{});
+        if (gb + U < g1) batch(gb + U, std::integral_constant<int, 1>{});
+    }
+
+    // accumulator element r of lane l: row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32 of its tile
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[slot][8 * (r / 4) + 4 * lk + (r % 4)][j * 32 + lrow] = acc[j][r];
+    };
+    if (wave >= NW / 2) put(wave - NW / 2);
+    __syncthreads();
+    if (wave < NW / 2) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] += part[wave][8 * (r / 4) + 4 * lk + (r % 4)][j * 32 + lrow];
+    }
+    __syncthreads();
+    if (wave < NW / 2) put(wave);
+    __syncthreads();
+
+    for (int e = tid; e < 32 * BN; e += 512) {
+        const int r = e / BN, c = e % BN;
+        const int64_t orow = m0 + r;
+        const int ocol = n0 + c;
+        if (orow >= N || ocol >= D_out) continue;
+        float x = ((part[0][r][c] + part[1][r][c]) + part[2][r][c]) + part[3][r][c];
+        x += bias ? bias[ocol] : 0.0f;
+        if (relu) x = fmaxf(x, 0.0f);
+        if constexpr (MASKED) x = mask[orow * ldm + ocol] > 0.0f ? x : 0.0f;
+        Z[orow * ldz + ocol] = x;
+    }
+}
+
 // D_in == 0: the product is empty and every row is act(b); H and W are not touched (they may be NULL)
 __global__ void bias_rows_kernel(int64_t N, int D_out, const float* __restrict__ bias, int relu,
                                  float* __restrict__ Z, int64_t ldz, const float* __restrict__ mask, int64_t ldm)
@@ -392,10 +606,14 @@ void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
     const bool wv = (uintptr_t)W % 16 == 0 && D_out % 4 == 0;
     dim3 grid((unsigned)((N + BM - 1) / BM), (unsigned)((D_out + BN - 1) / BN));
     const int r = relu ? 1 : 0;
-    if (hv && wv)
+    const bool zv = (uintptr_t)Z % 16 == 0 && ldz % 4 == 0 && D_out % 4 == 0 &&
+                    (!MASKED || ((uintptr_t)mask % 16 == 0 && ldm % 4 == 0));
+    if (hv && wv && zv)
+        transform_kernel<BM, BN, WGM, WGN, MASKED, true, true><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+    else if (hv && wv)
         transform_kernel<BM, BN, WGM, WGN, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else if (hv)
-        transform_generic_kernel<BM, BN, WGM, WGN, true, false, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        transform_kernel<BM, BN, WGM, WGN, MASKED, false><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else if (wv)
         transform_generic_kernel<BM, BN, WGM, WGN, false, true, MASKED><<<grid, dim3(256), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
     else
@@ -403,10 +621,39 @@ void launch(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh,
 }
 
 template <bool MASKED>
+void launch_few_rows(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh, const float* W,
+                     const float* b, bool relu, float* Z, int64_t ldz, const float* mask, int64_t ldm,
+                     hipStream_t stream)
+{
+    const bool hv = (uintptr_t)H % 16 == 0 && ldh % 4 == 0 && D_in % 4 == 0;
+    const int r = relu ? 1 : 0;
+    const unsigned gx = (unsigned)((N + 31) / 32);
+    // 32-column tiles when 64-column ones would not give every compute unit a workgroup
+    if (D_out <= 32 || (int64_t)gx * ((D_out + 63) / 64) < 256) {
+        dim3 grid(gx, (unsigned)((D_out + 31) / 32));
+        if (hv) transform_few_rows_kernel<1, true, MASKED><<<grid, dim3(512), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        else    transform_few_rows_kernel<1, false, MASKED><<<grid, dim3(512), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+    } else {
+        dim3 grid(gx, (unsigned)((D_out + 63) / 64));
+        if (hv) transform_few_rows_kernel<2, true, MASKED><<<grid, dim3(512), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+        else    transform_few_rows_kernel<2, false, MASKED><<<grid, dim3(512), 0, stream>>>(N, (int)D_in, (int)D_out, H, ldh, W, b, r, Z, ldz, mask, ldm);
+    }
+}
+
+// Fewer 128-row blocks (times the column blocks) than the "transform_few_blocks" setting, 128 unless changed:
+// the few-rows kernel.  The choice depends on the shape only, never on alignment, so one shape always takes
+// one order of additions.
+
+template <bool MASKED>
 void launch_by_width(int64_t N, int64_t D_in, int64_t D_out, const float* H, int64_t ldh, const float* W,
                      const float* b, bool relu, float* Z, int64_t ldz, const float* mask, int64_t ldm,
                      hipStream_t stream)
 {
+    const int64_t bn = D_out <= 32 ? 32 : D_out <= 64 ? 64 : D_out <= 128 ? 128 : D_out <= 192 ? 192 : 256;
+    if ((N + 127) / 128 * ((D_out + bn - 1) / bn) < agg_options().few_blocks) {
+        launch_few_rows<MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
+        return;
+    }
     if (D_out <= 32)       launch<128, 32, 4, 1, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     else if (D_out <= 64)  launch<128, 64, 4, 1, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);
     else if (D_out <= 128) launch<128, 128, 2, 2, MASKED>(N, D_in, D_out, H, ldh, W, b, relu, Z, ldz, mask, ldm, stream);

@@ -12,6 +12,17 @@ from parity import assert_close
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["few_rows", "row_blocks"])
+def kernel_family(request):
+    """Matrices of these sizes take the few-rows kernel (K split over the waves of 32-row workgroups); every
+    test runs a second time with that kernel switched off, i.e. on the 128-row block kernels that large
+    matrices take."""
+    B.load()
+    B.check(B.retexo_set_option("transform_few_blocks", 128 if request.param == "few_rows" else 0), "set_option")
+    yield request.param
+    B.check(B.retexo_set_option("transform_few_blocks", 128), "set_option")
+
+
 def run(n, d_in, d_out, ldh, ldz, relu, bias, seed):
     H = wl.random_matrix(n, d_in, seed, ld=ldh)
     H[:, d_in:] = np.nan                                   # padding must never be read into a result
@@ -94,8 +105,8 @@ def test_transform_is_deterministic_and_rejects_alias():
 
 
 def test_transform_aligned_and_unaligned_operands_give_the_same_bits():
-    # the software-pipelined kernel (16-byte aligned rows) and the checked-load kernel (here: H and W moved
-    # by one float) do the same arithmetic in the same order
+    # 16-byte aligned rows and rows moved by one float (H and W) take different loads, never a different
+    # order of arithmetic — in either kernel family
     n, d_in, d_out = 1111, 212, 256
     H = wl.random_matrix(n, d_in, 21)
     W = wl.random_matrix(d_in, d_out, 22)
