@@ -477,6 +477,8 @@ double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, d
  *       source scores from the table instead of computing them from the gathered rows),
  *       "agg_gat_in_rows" (0: retexo_round keeps the source scores in the table even when the unused
  *       columns of its own Z rows could hold them),
+ *       "agg_gat_fold" (0: retexo_round never lets its transform write those scores, as one more
+ *       output column per head of a linear transform, and always runs the score kernel),
  *       "agg_wide_offsets" (1: 64-bit row offsets even for tables below 4 GiB; these four exist
  *       so that tests reach every code path),
  *       "csr_sorted_keys" (1: retexo_csr_from_coo uses its general sorted-key construction, which

@@ -48,7 +48,8 @@ struct AggArgs {
     int64_t ocol;          // first output column of the aggregate
     const float* el;       // <a_src, z_u> of node u, head h at el[u * el_stride + h]   (edge softmax only)
     int64_t el_stride;     // HP for the table in the workspace; ldz when the scores sit in Z's padding columns
-    const float* er;       // [N, HP]  <a_dst, z_v>
+    const float* er;       // [N, HP]  <a_dst, z_v>, or NULL:
+    const float* er_from;  // a_dst [heads, Dh]; the kernel forms <a_dst, z_v> from row v itself (pipelined kernel, one slab)
     int64_t row_begin;     // range of plan order handled by this launch
     int64_t row_count;
     int64_t F;
@@ -873,8 +874,17 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
         m[h] = -INFINITY;
         s[h] = 0.0f;
         if constexpr (TRAIN) { sp[h] = 0.0f; sn[h] = 0.0f; }
-        erv[h] = a.er[(int64_t)v * HP + h];
+        erv[h] = a.er ? a.er[(int64_t)v * HP + h] : 0.0f;
     }
+    // no table of destination scores: this row's come from the row itself.  The row is requested here and
+    // used in the first tile, behind that tile's gathers, so that its latency is not one more step of the chain.
+    f32x4 zself[NC];
+    if (!a.er) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            zself[c] = *reinterpret_cast<const f32x4*>(zbase + (uint32_t)v * rowbytes + colbytes[c]);
+    }
+    const int base0 = lo + 64 * (NW == 1 ? 0 : wave);
 
     for (int base = lo + 64 * (NW == 1 ? 0 : wave); base < hi; base += 64 * NW) {
         const int e = base + lane;
@@ -901,6 +911,25 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
         } else {
 #pragma unroll
             for (int h = 0; h < HP; ++h) elu[h] = a.el[(int64_t)my_u * a.el_stride + h];
+        }
+        if (!a.er && base == base0) {          // (uniform)
+            float pd[HP];
+#pragma unroll
+            for (int h = 0; h < HP; ++h) pd[h] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                if (!act[c]) continue;
+                const f32x4 ad = *reinterpret_cast<const f32x4*>(a.er_from + col0 + c * 256);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float t = zself[c][k] * ad[k];
+                    const int hk = hc[c][HU ? 0 : k];
+#pragma unroll
+                    for (int h = 0; h < HP; ++h) pd[h] += hk == h ? t : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < HP; ++h) erv[h] = wave_sum(pd[h]);
         }
         float scale[HP];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of wl are done
@@ -1489,6 +1518,97 @@ void launch_gat_scores(int64_t N, int64_t F, int heads, const float* Z, int64_t 
         gat_scores_kernel<8><<<dim3(gb), dim3(256), 0, stream>>>(N, F, heads, Dh, Z, ldz, a_src, a_dst, el, el_stride, er);
 }
 
+namespace {
+
+// widest gather the layout of Z allows; a partial last vector may read
+// padding columns of the same row, so the padded width must fit in ldz
+int gather_vec(const AggCall& c)
+{
+    int vec = 1;
+    if (aligned_for(c.Z, c.ldz, 4) && align_up(c.F, 4) <= c.ldz) vec = 4;
+    else if (aligned_for(c.Z, c.ldz, 2) && align_up(c.F, 2) <= c.ldz) vec = 2;
+    if (vec > agg_options().max_vec) vec = agg_options().max_vec >= 2 ? 2 : 1;
+    if (c.mode == RETEXO_GAT_SOFTMAX && vec == 2) vec = 1;
+    return vec;
+}
+
+// Which edge-softmax kernels a call takes.
+struct GatRoute {
+    int vec;
+    bool off32;     // every byte offset into Z fits 32 bits
+    bool flash;     // rows of ordinary length: source scores from the gathered rows themselves
+    bool in_rows;   // source scores kept in the unused columns of Z's own rows
+};
+GatRoute gat_route(const AggCall& c)
+{
+    const AggOptions& opt = agg_options();
+    const int64_t N = c.plan->N;
+    GatRoute r;
+    r.vec = gather_vec(c);
+    r.off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
+    const int hp = heads_padded(c.heads);
+    const int64_t Dh = c.F / c.heads;
+    const int64_t g = Dh / 4;
+    // rows of ordinary length compute the source scores from the gathered rows themselves when a head is
+    // a power-of-two group of four-float lanes; the long rows keep the table of scores
+    r.flash = r.vec == 4 && r.off32 && opt.gat_fast && opt.gat_flash && c.F <= 256 &&
+              Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 && aligned_for(c.attn_src, 4, 4);
+    // Otherwise, when Z is the library's own buffer and its rows have unused columns behind F, the source
+    // scores of a node are kept there: the gather of a row then brings them along in the row's last cache
+    // line, instead of one more line per entry from a table elsewhere.
+    r.in_rows = c.z_padding_free && !r.flash && r.vec == 4 && r.off32 && opt.gat_fast && opt.gat_in_rows &&
+                c.F % 4 == 0 && c.ldz - c.F >= hp && c.F % 32 != 0 && (c.F % 32) + hp <= 32;
+    return r;
+}
+
+// One wave per row of W (and one for b): copy the row and append its products with the heads of a_src.
+__global__ __launch_bounds__(256) void gat_fold_kernel(int D_in, int F, int heads, int Dh, int hp,
+                                                       const float* __restrict__ W, const float* __restrict__ b,
+                                                       const float* __restrict__ a_src,
+                                                       float* __restrict__ W2, float* __restrict__ b2)
+{
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k > D_in) return;
+    const float* src = k < D_in ? W + (int64_t)k * F : b;        // b == NULL: a zero bias
+    float* dst = k < D_in ? W2 + (int64_t)k * (F + hp) : b2;
+    float ps[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) ps[h] = 0.0f;
+    for (int j = lane; j < F; j += 64) {
+        const float x = src ? src[j] : 0.0f;
+        dst[j] = x;
+        const float t = x * a_src[j];
+        const int hj = j / Dh;
+#pragma unroll
+        for (int h = 0; h < 8; ++h) ps[h] += hj == h ? t : 0.0f;
+    }
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+        const float sum = wave_sum(ps[h]);
+        if (lane == 0 && h < hp) dst[F + h] = h < heads ? sum : 0.0f;
+    }
+}
+
+}  // namespace
+
+bool gat_fold_plan(const AggCall& c, int64_t D_in, int64_t avail_bytes)
+{
+    if (c.mode != RETEXO_GAT_SOFTMAX || c.save || !agg_options().gat_fold) return false;
+    const GatRoute r = gat_route(c);
+    const int64_t wide = c.F + heads_padded(c.heads);
+    // the pipelined kernel forms the destination scores from whole rows: one slab (two float4 per lane at most)
+    return r.in_rows && c.F <= 512 && agg_options().slab_cols == 0 && aligned_for(c.attn_dst, 4, 4) &&
+           (D_in + 1) * wide * (int64_t)sizeof(float) <= avail_bytes;
+}
+
+void launch_gat_fold(int64_t D_in, int64_t F, int heads, const float* W, const float* b, const float* a_src,
+                     float* W2, float* b2, hipStream_t stream)
+{
+    gat_fold_kernel<<<dim3((unsigned)((D_in + 1 + 3) / 4)), dim3(256), 0, stream>>>(
+        (int)D_in, (int)F, heads, (int)(F / heads), heads_padded(heads), W, b, a_src, W2, b2);
+}
+
 int launch_aggregate(const AggCall& c, hipStream_t stream)
 {
     const retexo_plan* p = c.plan;
@@ -1497,13 +1617,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     const AggOptions& opt = agg_options();
     const bool gat = c.mode == RETEXO_GAT_SOFTMAX;
 
-    // widest gather the layout of Z allows; a partial last vector may read
-    // padding columns of the same row, so the padded width must fit in ldz
-    int vec = 1;
-    if (aligned_for(c.Z, c.ldz, 4) && align_up(c.F, 4) <= c.ldz) vec = 4;
-    else if (aligned_for(c.Z, c.ldz, 2) && align_up(c.F, 2) <= c.ldz) vec = 2;
-    if (vec > opt.max_vec) vec = opt.max_vec >= 2 ? 2 : 1;
-    if (gat && vec == 2) vec = 1;
+    const int vec = gather_vec(c);
     const int max_nc = gat ? 2 : 3;
     int nc;
     if (opt.slab_cols > 0) nc = (int)((opt.slab_cols + 64 * vec - 1) / (64 * vec));
@@ -1526,6 +1640,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.el = nullptr;
     a.el_stride = 0;
     a.er = nullptr;
+    a.er_from = nullptr;
     a.row_begin = 0;
     a.row_count = 0;
     a.F = c.F;
@@ -1602,17 +1717,10 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         float* el = (float*)c.workspace;
         float* er = (float*)((char*)c.workspace + gat_workspace(N, c.F, c.heads, false).er);
         const bool hu = (a.Dh % vec) == 0;
-        const bool off32 = (N * c.ldz + c.F) * 4 < (1ll << 32) && !opt.wide_offsets;
+        const GatRoute route = gat_route(c);
+        const bool off32 = route.off32, flash = route.flash, in_rows = route.in_rows;
         const int g = a.Dh / 4;
-        // rows of ordinary length compute the source scores from the gathered rows themselves when a head is
-        // a power-of-two group of four-float lanes; the long rows keep the table of scores
-        const bool flash = vec == 4 && off32 && opt.gat_fast && opt.gat_flash && c.F <= 256 &&
-                           a.Dh % 4 == 0 && g <= 64 && (g & (g - 1)) == 0 && aligned_for(c.attn_src, 4, 4);
-        // Otherwise, when Z is the library's own buffer and its rows have unused columns behind F, the source
-        // scores of a node are kept there: the gather of a row then brings them along in the row's last cache
-        // line, instead of one more line per entry from a table elsewhere.
-        const bool in_rows = c.z_padding_free && !flash && vec == 4 && off32 && opt.gat_fast && opt.gat_in_rows &&
-                             c.F % 4 == 0 && c.ldz - c.F >= hp && c.F % 32 != 0 && (c.F % 32) + hp <= 32;
+        if (c.el_ready && !(in_rows && !c.save && a.nslab == 1)) return RETEXO_E_FLAGS;   // the round asked gat_fold_plan
         a.el_stride = in_rows ? c.ldz : hp;
         if (in_rows) el = const_cast<float*>(c.Z) + c.F;
         a.el = el;
@@ -1622,8 +1730,13 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
         // only the pipelined kernel keeps the backward's statistics: decided before anything is launched,
         // so that the error leaves the workspace and the output untouched
         if (c.save && !(vec == 4 && off32 && opt.gat_fast)) return RETEXO_E_FLAGS;
-        if (!no_table)
+        if (c.el_ready) {
+            // the transform wrote the source scores; every row forms its own destination scores
+            a.er = nullptr;
+            a.er_from = c.attn_dst;
+        } else if (!no_table) {
             launch_gat_scores(N, c.F, c.heads, c.Z, c.ldz, c.attn_src, c.attn_dst, el, er, stream, a.el_stride);
+        }
         if (c.save) {
             const GatWorkspace w = gat_workspace(N, c.F, c.heads, true);
             a.save_stats = (f32x4*)((char*)c.workspace + w.stats);

@@ -49,6 +49,7 @@ struct AggOptions {
     int64_t max_vec = 4;        // cap on floats per lane per gather (experiments)
     int64_t gat_fast = 1;       // pipelined edge-softmax kernel (0: the plain one)
     int64_t gat_flash = 1;      // ordinary rows: source scores from the gathered rows (0: from the table)
+    int64_t gat_fold = 1;       // retexo_round: source scores as extra output columns of a linear transform (0: score kernel)
     int64_t gat_in_rows = 1;    // retexo_round: source scores in the unused columns of its own Z rows (0: table)
     int64_t wide_offsets = 0;   // 1: use the 64-bit row-offset code paths even when 32 bits would do (tests)
     int64_t narrow_heavy = 512;  // narrow slabs: rows whose share of one source range is at least this long get a workgroup
@@ -84,8 +85,19 @@ struct AggCall {
     void* workspace;
     bool save = false;    // edge softmax: keep the backward's statistics in the workspace
     bool z_padding_free = false;   // Z is the library's own buffer: columns [F, ldz) of its rows may be written
+    bool el_ready = false;         // ... and columns [F, F + heads_padded) already hold <a_src, z_v> (see gat_fold_plan)
 };
 int launch_aggregate(const AggCall& c, hipStream_t stream);
+// Edge softmax inside a round whose transform is linear: <a_src, z_v> = h_v (W a_src) + <b, a_src> is one more
+// output column per head of the same product, so the transform can write the source scores behind the F
+// columns of its own rows at no cost and no score kernel has to read Z again.  gat_fold_plan says whether the
+// aggregation of `c` (Z, ldz, z_padding_free set as the round will set them) would use scores kept there and
+// `avail_bytes` of scratch hold the widened operands; launch_gat_fold then writes W2 = [W | W A] as
+// [D_in, F + heads_padded] and b2 = [b | b A] right behind it.  The caller runs the transform with W2, b2 and
+// F + heads_padded output columns and sets c.el_ready.
+bool gat_fold_plan(const AggCall& c, int64_t D_in, int64_t avail_bytes);
+void launch_gat_fold(int64_t D_in, int64_t F, int heads, const float* W, const float* b, const float* a_src,
+                     float* W2, float* b2, hipStream_t stream);
 // edge-softmax workspace: scores, then (save) the row statistics and the aggregate split by the sign of the score
 struct GatWorkspace { int64_t el, er, stats, pos, neg, total, ld_pos; };
 GatWorkspace gat_workspace(int64_t N, int64_t F, int heads, bool save);

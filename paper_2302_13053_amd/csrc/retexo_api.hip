@@ -83,6 +83,7 @@ extern "C" int retexo_set_option(const char* name, int64_t value)
     if (!strcmp(name, "agg_parts")) { o.parts = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_fast")) { o.gat_fast = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_flash")) { o.gat_flash = value; return RETEXO_OK; }
+    if (!strcmp(name, "agg_gat_fold")) { o.gat_fold = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_gat_in_rows")) { o.gat_in_rows = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_wide_offsets")) { o.wide_offsets = value; return RETEXO_OK; }
     if (!strcmp(name, "agg_narrow_heavy")) { o.narrow_heavy = value; return RETEXO_OK; }
@@ -427,11 +428,23 @@ extern "C" int retexo_round(const retexo_plan* plan, int mode, int64_t D_in, int
         c.Z = d_out; c.ldz = ldo; c.copy_self = false;
     } else {
         float* Zws = (float*)d_workspace;
-        if (int e = launch_transform(N, D_in, D_out, d_H, ldh, d_W, d_b, (flags & RETEXO_F_RELU) != 0,
-                                     Zws, ldz_ws, s))
-            return e;
         c.Z = Zws; c.ldz = ldz_ws; c.copy_self = false;
         c.z_padding_free = true;
+        const int64_t agg_bytes = need - z_bytes;
+        if (mode == RETEXO_GAT_SOFTMAX && N > 0 && D_out > 0 && D_in > 0 && !(flags & RETEXO_F_RELU) &&
+            gat_fold_plan(c, D_in, agg_bytes)) {
+            // the source scores leave the transform as heads_padded more columns of Z (the score tables' space
+            // is free then and holds the widened operands)
+            const int64_t wide = D_out + heads_padded(heads);
+            float* W2 = (float*)c.workspace;
+            float* b2 = W2 + D_in * wide;
+            launch_gat_fold(D_in, D_out, heads, d_W, d_b, d_attn_src, W2, b2, s);
+            if (int e = launch_transform(N, D_in, wide, d_H, ldh, W2, b2, false, Zws, ldz_ws, s)) return e;
+            c.el_ready = true;
+        } else if (int e = launch_transform(N, D_in, D_out, d_H, ldh, d_W, d_b, (flags & RETEXO_F_RELU) != 0,
+                                            Zws, ldz_ws, s)) {
+            return e;
+        }
     }
     return launch_aggregate(c, s);
 }

@@ -82,7 +82,10 @@ def test_round_separately_equals_fused_and_gcn_gat_modes():
 @pytest.mark.parametrize("n,heads,dh,seed", [(5000, 4, 47, 1), (3000, 8, 27, 2), (2000, 2, 30, 3), (1500, 4, 7, 4)])
 def test_attention_round_with_the_source_scores_kept_in_the_rows_of_z(n, heads, dh, seed):
     # head widths that are not a power-of-two number of four-float lanes: retexo_round keeps <a_src, z_u> in
-    # the unused columns of its own Z rows.  Same bits as with the score table, and parity with the oracle.
+    # the unused columns of its own Z rows.  Written there by the score kernel: same bits as with the score
+    # table.  Written there by the transform itself (as h_u (W a_src) + <b, a_src>, one more output column per
+    # head; the destination scores then come from row v inside the aggregation kernel): the same scores up to
+    # fp32 rounding.  All three: parity with the oracle.
     F = heads * dh
     assert F % 4 == 0 and F % 32 != 0
     src, dst = wl.graph_power_law(n, 12 * n, 2.2, 24.0, 3000.0, seed)
@@ -97,18 +100,21 @@ def test_attention_round_with_the_source_scores_kept_in_the_rows_of_z(n, heads, 
     ws = Hn.ws_tensor(B.retexo_workspace_bytes(g.plan, F, B.GAT_SOFTMAX, heads, 0))
     outs = []
     try:
-        for in_rows in (1, 0):
+        for in_rows, fold in ((1, 0), (0, 0), (1, 1)):
             B.retexo_set_option("agg_gat_in_rows", in_rows)
+            B.retexo_set_option("agg_gat_fold", fold)
             out = torch.full((n, wl.pad_ld(F)), -5.0, dtype=torch.float32, device="cuda")
             Hn.round_(g, st, Hn.dev(H), Hn.dev(W), Hn.dev(b), Hn.dev(a_s), Hn.dev(a_d), out, ws)
             torch.cuda.synchronize()
             outs.append(out)
     finally:
         B.retexo_set_option("agg_gat_in_rows", 1)
+        B.retexo_set_option("agg_gat_fold", 1)
     assert torch.equal(outs[0], outs[1])
-    assert bool((outs[0][:, F:] == -5.0).all())
     want = oracle.round_("gat_softmax", rp, ci, H, 60, W, b, relu=False, heads=heads, a_src=a_s, a_dst=a_d)
-    assert_close(outs[0].cpu().numpy()[:, :F], want, what="attention round, scores in the rows")
+    for out, what in ((outs[0], "score kernel"), (outs[2], "transform")):
+        assert bool((out[:, F:] == -5.0).all())
+        assert_close(out.cpu().numpy()[:, :F], want, what="attention round, scores in the rows by the " + what)
     g.destroy()
 
 
