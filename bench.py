@@ -334,10 +334,17 @@ def bench_workload(index, args):
         fl = 2.0 * n * st.d_in * st.d_out
         by = 4.0 * (n * st.d_in + n * st.d_out + st.d_in * st.d_out)
         ai = fl / by
+        # what the matrix cores are issued: whole 32-column accumulator tiles (41 columns run as 64), k in pairs
+        cols = next((t for t in (32, 64, 128, 192, 256) if st.d_out <= t), 256 * -(-st.d_out // 256))
+        fl_issued = 2.0 * n * (st.d_in + st.d_in % 2) * cols
+        balance = MFMA_F32_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS          # flop per byte where the two bounds meet
         transforms.append({"stage": "%s%d" % (st.kind, i), "shape": "%d x %d -> %d" % (n, st.d_in, st.d_out),
                            "ms_alone": tms, "TFLOP/s": fl / tms / 1e9, "frac_fp32_mfma": fl / tms / 1e9 / MFMA_F32_PEAK_TFLOPS,
+                           "issued_TFLOP/s": fl_issued / tms / 1e9,
+                           "frac_fp32_mfma_issued": fl_issued / tms / 1e9 / MFMA_F32_PEAK_TFLOPS,
                            "GB/s": by / tms / 1e6, "frac_hbm": by / tms / 1e6 / HBM_PEAK_GBS,
-                           "flop_per_byte": ai, "bound": "mfma" if ai >= 20.0 else "hbm"})
+                           "flop_per_byte": ai, "flop_per_byte_issued": fl_issued / by,
+                           "bound": "mfma" if fl_issued / by >= balance else "hbm"})
         del Zt
 
     out = {
