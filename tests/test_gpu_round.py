@@ -79,7 +79,8 @@ def test_round_separately_equals_fused_and_gcn_gat_modes():
         g.destroy()
 
 
-@pytest.mark.parametrize("n,heads,dh,seed", [(5000, 4, 47, 1), (3000, 8, 27, 2), (2000, 2, 30, 3), (1500, 4, 7, 4)])
+@pytest.mark.parametrize("n,heads,dh,seed", [(5000, 4, 47, 1), (3000, 8, 27, 2), (2000, 2, 30, 3), (1500, 4, 7, 4),
+                                             (1200, 4, 75, 5)])          # the last: two float4 per lane and row
 def test_attention_round_with_the_source_scores_kept_in_the_rows_of_z(n, heads, dh, seed):
     # head widths that are not a power-of-two number of four-float lanes: retexo_round keeps <a_src, z_u> in
     # the unused columns of its own Z rows.  Written there by the score kernel: same bits as with the score
