@@ -471,7 +471,7 @@ double retexo_gamma(double B, double R, double H0, double sum_H, double sum_C, d
  *       "agg_heavy_degree" (rows at least this long get a whole workgroup),
  *       "agg_parts" (source-id ranges walked one after the other: -1 auto, 1 off, 2/4/8/16),
  *       "agg_narrow_heavy" (narrow slabs: rows whose share of ONE source range is at least this
- *       long get a whole workgroup; default 512),
+ *       long get a whole workgroup; default 1024),
  *       "agg_max_vec" (cap on floats per lane per gather),
  *       "agg_gat_fast" (0: plain edge-softmax kernel), "agg_gat_flash" (0: ordinary rows read the
  *       source scores from the table instead of computing them from the gathered rows),

@@ -336,7 +336,7 @@ __global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
     }
     __syncthreads();
     if (!writer) return;
-    const int d = a.deg[v];
+    const int d = (a.last && a.scale == SCALE_MEAN) ? a.deg[v] : 0;      // only the mean's last range needs it
     float out_v[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -368,8 +368,9 @@ __global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
 // running-sum read, the scaling and the store are one wave-wide operation for
 // G rows, and the per-row bookkeeping is shared — which is what matters once a
 // row's share of one source range is only a few dozen entries long.
-// Neighbour ids are fetched LPG at a time per group (one per lane, the next
-// chunk a step ahead) and handed round inside the group with ds_bpermute.
+// Neighbour ids are fetched 4 LPG at a time per group (four per lane: whole
+// cache lines of col_idx, a block ahead) and handed round inside the group
+// with ds_bpermute.
 // ---------------------------------------------------------------------------
 template <int LPG, bool WEIGHTED, bool OFF32>
 __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs a)
@@ -435,73 +436,94 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
     }
 
     const int gaddr = (lane - li) * 4;      // ds_bpermute byte address of this group's lane 0
-    int nxt_u = 0;
-    float nxt_w = 0.0f;
-    if (li < len) {
-        nxt_u = a.col_idx[lo + li];
-        if (WEIGHTED) nxt_w = a.wsrc[nxt_u];
-    }
-    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int c0 = 0; c0 < maxlen; c0 += LPG) {
-        const int my_u = nxt_u;
-        const float my_w = nxt_w;
-        const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
-        {
-            const int nb = c0 + LPG + li;          // this lane's entry of the next chunk
-            nxt_u = 0;
-            nxt_w = 0.0f;
-            if (nb < len) {
-                nxt_u = a.col_idx[lo + nb];
-                if (WEIGHTED) nxt_w = a.wsrc[nxt_u];
-            }
+    // Neighbour ids: every lane of a group fetches four consecutive ids at a time, so a group reads col_idx in
+    // whole cache lines (4 LPG entries) instead of one 32-byte piece per LPG entries — the id loads were one
+    // L2 request in nine of a kernel that is bound by L2 requests.  Entry e of such a block sits in component
+    // e % 4 of the group's lane e / 4.
+    constexpr int IPL = 4;
+    constexpr int BLOCK = IPL * LPG;
+    typedef int i32x4u __attribute__((ext_vector_type(4), aligned(4)));      // 4-byte aligned 16-byte load
+    int nxt_u[IPL];
+    float nxt_w[IPL];
+    auto fetch_ids = [&](int first) {       // entries first + 4 li .. + 3 of this group's row; past its end: id 0
+        const int nb = first + IPL * li;
+        if (nb + IPL <= len) {
+            const i32x4u t = *reinterpret_cast<const i32x4u*>(a.col_idx + lo + nb);
+            nxt_u[0] = t.x; nxt_u[1] = t.y; nxt_u[2] = t.z; nxt_u[3] = t.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < IPL; ++k) nxt_u[k] = nb + k < len ? a.col_idx[lo + nb + k] : 0;
         }
-        const bool full = c0 + LPG <= minlen;      // every group still has LPG entries: no masking
+        if constexpr (WEIGHTED) {
 #pragma unroll
-        for (int i0 = 0; i0 < LPG; i0 += U) {
-            f32x4 z[U];
-            float w[U];
+            for (int k = 0; k < IPL; ++k) nxt_w[k] = nb + k < len ? a.wsrc[nxt_u[k]] : 0.0f;
+        }
+    };
+    fetch_ids(0);
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s0 = 0; s0 < maxlen; s0 += BLOCK) {
+        int my_u[IPL];
+        float my_w[IPL];
+        uint32_t my_off[IPL];
 #pragma unroll
-            for (int t = 0; t < U; ++t) {
-                const int i = i0 + t;
-                if constexpr (OFF32) {
-                    const uint32_t off =
-                        (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * i, (int)my_off) + colbytes;
-                    z[t] = *reinterpret_cast<const f32x4*>(zbase + off);
-                } else {
-                    const int u = __builtin_amdgcn_ds_bpermute(gaddr + 4 * i, my_u);
-                    z[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
-                }
-                if constexpr (WEIGHTED)
-                    w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * i, __float_as_int(my_w)));
-            }
-            if (!full) {
+        for (int k = 0; k < IPL; ++k) {
+            my_u[k] = nxt_u[k];
+            my_w[k] = WEIGHTED ? nxt_w[k] : 0.0f;
+            my_off[k] = OFF32 ? (uint32_t)my_u[k] * (uint32_t)rowbytes : 0u;
+        }
+        fetch_ids(s0 + BLOCK);              // the next block, a whole block ahead of its use
+#pragma unroll
+        for (int q = 0; q < IPL; ++q) {
+            const int c0 = s0 + q * LPG;
+            if (c0 >= maxlen) break;                   // (uniform)
+            const bool full = c0 + LPG <= minlen;      // every group still has LPG entries: no masking
+#pragma unroll
+            for (int i0 = 0; i0 < LPG; i0 += U) {
+                f32x4 z[U];
+                float w[U];
 #pragma unroll
                 for (int t = 0; t < U; ++t) {
-                    const bool ok = c0 + i0 + t < len;
-                    z[t].x = ok ? z[t].x : 0.0f;
-                    z[t].y = ok ? z[t].y : 0.0f;
-                    z[t].z = ok ? z[t].z : 0.0f;
-                    z[t].w = ok ? z[t].w : 0.0f;
+                    const int e = q * LPG + i0 + t;    // entry of the block: lane e / 4, component e % 4
+                    if constexpr (OFF32) {
+                        const uint32_t off =
+                            (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), (int)my_off[e % IPL]) + colbytes;
+                        z[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+                    } else {
+                        const int u = __builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), my_u[e % IPL]);
+                        z[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
+                    }
+                    if constexpr (WEIGHTED)
+                        w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), __float_as_int(my_w[e % IPL])));
                 }
-            }
+                if (!full) {
 #pragma unroll
-            for (int t = 0; t < U; ++t) {
-                if constexpr (WEIGHTED) {
-                    acc[0] = fmaf(w[t], z[t].x, acc[0]);
-                    acc[1] = fmaf(w[t], z[t].y, acc[1]);
-                    acc[2] = fmaf(w[t], z[t].z, acc[2]);
-                    acc[3] = fmaf(w[t], z[t].w, acc[3]);
-                } else {
-                    acc[0] += z[t].x;
-                    acc[1] += z[t].y;
-                    acc[2] += z[t].z;
-                    acc[3] += z[t].w;
+                    for (int t = 0; t < U; ++t) {
+                        const bool ok = c0 + i0 + t < len;
+                        z[t].x = ok ? z[t].x : 0.0f;
+                        z[t].y = ok ? z[t].y : 0.0f;
+                        z[t].z = ok ? z[t].z : 0.0f;
+                        z[t].w = ok ? z[t].w : 0.0f;
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < U; ++t) {
+                    if constexpr (WEIGHTED) {
+                        acc[0] = fmaf(w[t], z[t].x, acc[0]);
+                        acc[1] = fmaf(w[t], z[t].y, acc[1]);
+                        acc[2] = fmaf(w[t], z[t].z, acc[2]);
+                        acc[3] = fmaf(w[t], z[t].w, acc[3]);
+                    } else {
+                        acc[0] += z[t].x;
+                        acc[1] += z[t].y;
+                        acc[2] += z[t].z;
+                        acc[3] += z[t].w;
+                    }
                 }
             }
         }
     }
     if (!writer) return;
-    const int d = a.deg[v];
+    const int d = (a.last && a.scale == SCALE_MEAN) ? a.deg[v] : 0;      // only the mean's last range needs it
     float out_v[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {

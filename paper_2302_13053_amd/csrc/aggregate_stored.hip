@@ -322,60 +322,76 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
     }
 
     const int gaddr = (lane - li) * 4;          // ds_bpermute byte address of this group's lane 0
-    // this lane's entry of the next chunk is fetched while the current chunk is consumed
-    int nxt_u = 0;
-    float nxt_w = 0.0f;
-    if (li < len) {
-        nxt_u = a.col_idx[lo + li];
-        nxt_w = WEIGHTED ? a.wsrc[nxt_u] : 1.0f;
-    }
-    for (int c0 = 0; c0 < maxlen; c0 += LPG) {
-        const int my_u = nxt_u;
-        const float my_w = nxt_w;
-        {
-            const int nb = c0 + LPG + li;
-            nxt_u = 0;
-            nxt_w = 0.0f;
-            if (nb < len) {
-                nxt_u = a.col_idx[lo + nb];
-                nxt_w = WEIGHTED ? a.wsrc[nxt_u] : 1.0f;
-            }
+    // Neighbour ids: every lane of a group fetches four consecutive ids at a time, so a group reads col_idx in
+    // whole cache lines (32 entries) a block ahead of its use; entry e of a block sits in component e % 4 of the
+    // group's lane e / 4.  Past the end of a row: id 0 with weight zero.
+    constexpr int IPL = 4, BLOCK = IPL * LPG;
+    typedef int i32x4u __attribute__((ext_vector_type(4), aligned(4)));      // 4-byte aligned 16-byte load
+    int nxt_u[IPL];
+    float nxt_w[IPL];
+    auto fetch_ids = [&](int first) {
+        const int nb = first + IPL * li;
+        if (nb + IPL <= len) {
+            const i32x4u t = *reinterpret_cast<const i32x4u*>(a.col_idx + lo + nb);
+            nxt_u[0] = t.x; nxt_u[1] = t.y; nxt_u[2] = t.z; nxt_u[3] = t.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < IPL; ++k) nxt_u[k] = nb + k < len ? a.col_idx[lo + nb + k] : 0;
         }
-        const uint32_t my_off = (uint32_t)my_u * rowbytes;
-        const bool full = c0 + LPG <= minlen;        // every group still has LPG entries: nothing to mask
 #pragma unroll
-        for (int i0 = 0; i0 < LPG; i0 += U) {
-            u32x4 raw[U];
-            float w[U];
+        for (int k = 0; k < IPL; ++k) nxt_w[k] = nb + k < len ? (WEIGHTED ? a.wsrc[nxt_u[k]] : 1.0f) : 0.0f;
+    };
+    fetch_ids(0);
+    for (int s0 = 0; s0 < maxlen; s0 += BLOCK) {
+        uint32_t my_off[IPL];
+        float my_w[IPL];
 #pragma unroll
-            for (int t = 0; t < U; ++t) {
-                const uint32_t off = (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (i0 + t), (int)my_off) + colbytes;
-                raw[t] = *reinterpret_cast<const u32x4*>(zbase + off);
-                w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (i0 + t), __float_as_int(my_w)));
-            }
-            if (!full) {
-                // entries past the end of this group's row gathered row 0: clear their bits (both formats
-                // decode zero bits to +0), so that nothing of an unrelated row can reach the sum
+        for (int k = 0; k < IPL; ++k) {
+            my_off[k] = (uint32_t)nxt_u[k] * rowbytes;
+            my_w[k] = nxt_w[k];
+        }
+        fetch_ids(s0 + BLOCK);
+#pragma unroll
+        for (int q = 0; q < IPL; ++q) {
+            const int c0 = s0 + q * LPG;
+            if (c0 >= maxlen) break;                     // (uniform)
+            const bool full = c0 + LPG <= minlen;        // every group still has LPG entries: nothing to mask
+#pragma unroll
+            for (int i0 = 0; i0 < LPG; i0 += U) {
+                u32x4 raw[U];
+                float w[U];
 #pragma unroll
                 for (int t = 0; t < U; ++t) {
-                    const uint32_t keep = c0 + i0 + t < len ? 0xffffffffu : 0u;
-                    raw[t].x &= keep;
-                    raw[t].y &= keep;
-                    raw[t].z &= keep;
-                    raw[t].w &= keep;
+                    const int e = q * LPG + i0 + t;
+                    const uint32_t off =
+                        (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), (int)my_off[e % IPL]) + colbytes;
+                    raw[t] = *reinterpret_cast<const u32x4*>(zbase + off);
+                    w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), __float_as_int(my_w[e % IPL])));
                 }
-            }
+                if (!full) {
+                    // entries past the end of this group's row gathered row 0: clear their bits (both formats
+                    // decode zero bits to +0), so that nothing of an unrelated row can reach the sum
 #pragma unroll
-            for (int t = 0; t < U; ++t) {
-                float z[8];
-                decode8<FMT>(raw[t], z);
+                    for (int t = 0; t < U; ++t) {
+                        const uint32_t keep = c0 + i0 + t < len ? 0xffffffffu : 0u;
+                        raw[t].x &= keep;
+                        raw[t].y &= keep;
+                        raw[t].z &= keep;
+                        raw[t].w &= keep;
+                    }
+                }
 #pragma unroll
-                for (int k = 0; k < 8; ++k) acc[k] = fmaf(w[t], z[k], acc[k]);
+                for (int t = 0; t < U; ++t) {
+                    float z[8];
+                    decode8<FMT>(raw[t], z);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) acc[k] = fmaf(w[t], z[k], acc[k]);
+                }
             }
         }
     }
     if (!writer) return;
-    const int d = a.deg[v];
+    const int d = (a.last && a.scale == 1) ? a.deg[v] : 0;      // only the mean's last range needs it
     float r[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -484,7 +500,7 @@ __global__ __launch_bounds__(64 * kHeavyWaves) void stored_grouped_kernel(Stored
         for (int w = 1; w < kHeavyWaves; ++w) x += red[w][lane][k];
         if (!a.first && k < valid) x += orow[a.ocol + col + k];
         if (a.last) {
-            const int d = a.deg[v];
+            const int d = (a.last && a.scale == 1) ? a.deg[v] : 0;      // only the mean's last range needs it
             if (a.scale == 1) x = d > 0 ? x / (float)d : 0.0f;
             else if (a.scale == 2) x = x * a.dinv[v];
         }

@@ -52,7 +52,7 @@ struct AggOptions {
     int64_t gat_fold = 1;       // retexo_round: source scores as extra output columns of a linear transform (0: score kernel)
     int64_t gat_in_rows = 1;    // retexo_round: source scores in the unused columns of its own Z rows (0: table)
     int64_t wide_offsets = 0;   // 1: use the 64-bit row-offset code paths even when 32 bits would do (tests)
-    int64_t narrow_heavy = 512;  // narrow slabs: rows whose share of one source range is at least this long get a workgroup
+    int64_t narrow_heavy = 1024;  // narrow slabs: rows whose share of one source range is at least this long get a workgroup
     int64_t parts = -1;         // source-id ranges per aggregation: -1 auto, 1 = off, 2/4/8/16
     int64_t few_blocks = 128;   // dense transform: fewer 128-row blocks (times column blocks) than this take the few-rows kernel; 0 = never
     int64_t csr_sorted_keys = 0;  // 1: retexo_csr_from_coo always takes the sorted-key construction (tests)
