@@ -61,6 +61,7 @@ struct AggArgs {
     float slope;
     int copy_self;         // also write z_v into out[:, 0:F]
     int out_vec;           // aggregate slot of out is aligned for VEC-wide stores
+    int out_half;          // ... or at least for 8-byte stores (float4 gathers only)
     int self_vec;          // self slot of out is aligned for VEC-wide stores
     // source-range walk (grouped kernel only): this launch covers the entries of each row whose
     // column lies in ranges [part_lo, part_hi) of the plan's split; NULL = whole rows
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_linear_
             else if (a.scale == SCALE_GCN) x = x * a.dinv[v];
             r[k] = x;
         }
-        store_row<VEC>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+        store_row<VEC>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
         if (a.copy_self) {
             float zs[VEC];
             load_row<VEC>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -307,9 +308,15 @@ __global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
     // running sum over the source ranges walked so far (written by the previous launch)
     float prev[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (!a.first && writer) {
+        if ((a.out_vec || a.out_half) && valid >= 4) {
+            const f32x2 t0 = *reinterpret_cast<const f32x2*>(orow + a.ocol + col);
+            const f32x2 t1 = *reinterpret_cast<const f32x2*>(orow + a.ocol + col + 2);
+            prev[0] = t0.x; prev[1] = t0.y; prev[2] = t1.x; prev[3] = t1.y;
+        } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (k < valid) prev[k] = orow[a.ocol + col + k];
+            for (int k = 0; k < 4; ++k)
+                if (k < valid) prev[k] = orow[a.ocol + col + k];
+        }
     }
 
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -350,7 +357,7 @@ __global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
         }
         out_v[k] = x;
     }
-    store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0);
+    store_row<4>(orow + a.ocol + col, out_v, valid, a.out_vec != 0, a.out_half != 0);
     if (a.copy_self && a.first) {
         float zs[4];
         load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -428,6 +435,10 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
         if (a.out_vec && valid >= 4) {
             const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(orow + a.ocol + col));
             prev[0] = t.x; prev[1] = t.y; prev[2] = t.z; prev[3] = t.w;
+        } else if (a.out_half && valid >= 4) {
+            const f32x2 t0 = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(orow + a.ocol + col));
+            const f32x2 t1 = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(orow + a.ocol + col + 2));
+            prev[0] = t0.x; prev[1] = t0.y; prev[2] = t1.x; prev[3] = t1.y;
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
@@ -537,6 +548,9 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
     if (a.out_vec && valid >= 4) {
         f32x4 t = {out_v[0], out_v[1], out_v[2], out_v[3]};
         __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(orow + a.ocol + col));
+    } else if (a.out_half && valid >= 4) {
+        __builtin_nontemporal_store(f32x2{out_v[0], out_v[1]}, reinterpret_cast<f32x2*>(orow + a.ocol + col));
+        __builtin_nontemporal_store(f32x2{out_v[2], out_v[3]}, reinterpret_cast<f32x2*>(orow + a.ocol + col + 2));
     } else {
         store_row<4>(orow + a.ocol + col, out_v, valid, false);
     }
@@ -819,7 +833,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_ker
             const float den = select_head<HP>(s, hc[c][HU ? 0 : k]);
             r[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
         }
-        store_row<VEC>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+        store_row<VEC>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
         if (a.copy_self) {
             float zs[VEC];
             load_row<VEC>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -1119,7 +1133,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fas
                 r[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
             }
         }
-        store_row<4>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+        store_row<4>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
         if (a.copy_self) {
             float zs[4];
             load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -1405,7 +1419,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void agg_gat_fla
         r[2] = s > 0.0f ? acc.z / s : 0.0f;
         r[3] = s > 0.0f ? acc.w / s : 0.0f;
     }
-    store_row<4>(orow + a.ocol + col, r, 4, a.out_vec != 0);
+    store_row<4>(orow + a.ocol + col, r, 4, a.out_vec != 0, a.out_half != 0);
     if (a.copy_self) {
         float zs[4];
         load_row<4>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -1674,6 +1688,7 @@ int launch_aggregate(const AggCall& c, hipStream_t stream)
     a.slope = c.slope;
     a.copy_self = (c.self_concat && c.copy_self) ? 1 : 0;
     a.out_vec = aligned_for(c.out + a.ocol, c.ldo, vec) ? 1 : 0;
+    a.out_half = (vec == 4 && aligned_for(c.out + a.ocol, c.ldo, 2)) ? 1 : 0;
     a.self_vec = aligned_for(c.out, c.ldo, vec) ? 1 : 0;
     a.part_ptr = nullptr;
     a.n_rows = N;

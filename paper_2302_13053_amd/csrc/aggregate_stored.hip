@@ -102,9 +102,16 @@ __device__ __forceinline__ void load_stored(const uint16_t* p, float (&v)[E])
     }
 }
 
+// vec_ok: 16-byte stores; half_ok: p is at least 8-byte aligned (the aggregate half of a concatenated row of odd
+// half-width): 8-byte stores instead of one per element
 template <int E>
-__device__ __forceinline__ void store_floats(float* p, const float (&v)[E], int valid, bool vec_ok)
+__device__ __forceinline__ void store_floats(float* p, const float (&v)[E], int valid, bool vec_ok, bool half_ok = false)
 {
+    if (E % 2 == 0 && !vec_ok && half_ok && valid >= E) {
+#pragma unroll
+        for (int k = 0; k < E; k += 2) *reinterpret_cast<f32x2*>(p + k) = f32x2{v[k], v[k + 1 < E ? k + 1 : k]};
+        return;
+    }
     if (E == 8 && vec_ok && valid >= 8) {
         const f32x4 a = {v[0], v[1], v[2], v[3]}, b = {v[E > 4 ? 4 : 0], v[E > 5 ? 5 : 0], v[E > 6 ? 6 : 0], v[E > 7 ? 7 : 0]};
         *reinterpret_cast<f32x4*>(p) = a;
@@ -141,6 +148,7 @@ struct StoredArgs {
     float slope;
     int copy_self;
     int out_vec;             // aggregate half of out allows 16-byte stores
+    int out_half;            // ... or at least 8-byte stores
     int self_vec;
     const int32_t* part_ptr;
     int64_t n_rows;
@@ -244,7 +252,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void stored_line
             else if (a.scale == 2) x = x * a.dinv[v];
             r[k] = x;
         }
-        store_floats<E>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+        store_floats<E>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
         if (a.copy_self) {
             float zs[E];
             load_stored<FMT, E>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -314,6 +322,13 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
             const f32x4 p1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(orow + a.ocol + col + 4));
             acc[0] = p0.x; acc[1] = p0.y; acc[2] = p0.z; acc[3] = p0.w;
             acc[4] = p1.x; acc[5] = p1.y; acc[6] = p1.z; acc[7] = p1.w;
+        } else if (a.out_half && valid >= 8) {
+#pragma unroll
+            for (int k = 0; k < 8; k += 2) {
+                const f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(orow + a.ocol + col + k));
+                acc[k] = t.x;
+                acc[k + 1] = t.y;
+            }
         } else {
 #pragma unroll
             for (int k = 0; k < 8; ++k)
@@ -402,7 +417,7 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
         }
         r[k] = x;
     }
-    store_floats<8>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+    store_floats<8>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
     if (a.copy_self && a.first) {
         float zs[8];
         load_stored<FMT, 8>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -506,7 +521,7 @@ __global__ __launch_bounds__(64 * kHeavyWaves) void stored_grouped_kernel(Stored
         }
         r[k] = x;
     }
-    store_floats<8>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+    store_floats<8>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
     if (a.copy_self && a.first) {
         float zs[8];
         load_stored<FMT, 8>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -791,7 +806,7 @@ __global__ __launch_bounds__(64 * (NW == 1 ? kLightWaves : NW)) void stored_gat_
             const float den = select_head<HP>(s, hc[c][HU ? 0 : k]);
             r[k] = den > 0.0f ? acc[c][k] / den : 0.0f;
         }
-        store_floats<E>(orow + a.ocol + col, r, valid, a.out_vec != 0);
+        store_floats<E>(orow + a.ocol + col, r, valid, a.out_vec != 0, a.out_half != 0);
         if (a.copy_self) {
             float zs[E];
             load_stored<FMT, E>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -894,7 +909,7 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_gat_flash_kernel(Stor
     float r[E];
 #pragma unroll
     for (int k = 0; k < E; ++k) r[k] = s > 0.0f ? acc[k] / s : 0.0f;
-    store_floats<E>(orow + a.ocol + col, r, E, a.out_vec != 0);
+    store_floats<E>(orow + a.ocol + col, r, E, a.out_vec != 0, a.out_half != 0);
     if (a.copy_self) {
         float zs[E];
         load_stored<FMT, E>(a.Z + (int64_t)v * a.ldz + col, zs);
@@ -979,6 +994,7 @@ int launch_stored(const StoredCall& c, hipStream_t stream)
     a.slope = c.slope;
     a.copy_self = (c.self_concat && c.copy_self) ? 1 : 0;
     a.out_vec = aligned_rows(c.out + a.ocol, c.ldo, 4) ? 1 : 0;
+    a.out_half = ((uintptr_t)(c.out + a.ocol) % 8 == 0 && c.ldo % 2 == 0) ? 1 : 0;
     a.self_vec = aligned_rows(c.out, c.ldo, 4) ? 1 : 0;
     a.part_ptr = nullptr;
     a.n_rows = N;

@@ -27,9 +27,19 @@ __device__ __forceinline__ void load_row(const float* p, float (&v)[VEC])
     }
 }
 
+// vec_ok: p allows one VEC-wide store; half_ok (VEC == 4 only): p is 8-byte aligned, two 8-byte stores — the
+// aggregate half of a concatenated row of odd half-width (602 columns) starts 8 bytes into a 16-byte piece,
+// and four scalar stores per lane cost six times the L2 write requests of one wide store
 template <int VEC>
-__device__ __forceinline__ void store_row(float* p, const float (&v)[VEC], int valid, bool vec_ok)
+__device__ __forceinline__ void store_row(float* p, const float (&v)[VEC], int valid, bool vec_ok, bool half_ok = false)
 {
+    if constexpr (VEC == 4) {
+        if (!vec_ok && half_ok && valid >= 4) {
+            *reinterpret_cast<f32x2*>(p) = f32x2{v[0], v[1]};
+            *reinterpret_cast<f32x2*>(p + 2) = f32x2{v[2], v[3]};
+            return;
+        }
+    }
     if (vec_ok && valid >= VEC) {
         if constexpr (VEC == 4) {
             f32x4 t = {v[0], v[1], v[2], v[3]};
