@@ -337,18 +337,21 @@ __global__ __launch_bounds__(64 * kLightWaves) void stored_rowgroup_kernel(Store
     }
 
     const int gaddr = (lane - li) * 4;          // ds_bpermute byte address of this group's lane 0
-    // Neighbour ids: every lane of a group fetches four consecutive ids at a time, so a group reads col_idx in
-    // whole cache lines (32 entries) a block ahead of its use; entry e of a block sits in component e % 4 of the
-    // group's lane e / 4.  Past the end of a row: id 0 with weight zero.
-    constexpr int IPL = 4, BLOCK = IPL * LPG;
+    // Neighbour ids: every lane of a group fetches eight consecutive ids at a time, so a group reads col_idx in
+    // whole cache lines (64 entries) a block ahead of its use; entry e of a block sits in component e % 8 of the
+    // group's lane e / 8.  Past the end of a row: id 0 with weight zero.
+    constexpr int IPL = 8, BLOCK = IPL * LPG;
     typedef int i32x4u __attribute__((ext_vector_type(4), aligned(4)));      // 4-byte aligned 16-byte load
     int nxt_u[IPL];
     float nxt_w[IPL];
     auto fetch_ids = [&](int first) {
         const int nb = first + IPL * li;
         if (nb + IPL <= len) {
-            const i32x4u t = *reinterpret_cast<const i32x4u*>(a.col_idx + lo + nb);
-            nxt_u[0] = t.x; nxt_u[1] = t.y; nxt_u[2] = t.z; nxt_u[3] = t.w;
+#pragma unroll
+            for (int k = 0; k < IPL; k += 4) {
+                const i32x4u t = *reinterpret_cast<const i32x4u*>(a.col_idx + lo + nb + k);
+                nxt_u[k] = t.x; nxt_u[k + 1] = t.y; nxt_u[k + 2] = t.z; nxt_u[k + 3] = t.w;
+            }
         } else {
 #pragma unroll
             for (int k = 0; k < IPL; ++k) nxt_u[k] = nb + k < len ? a.col_idx[lo + nb + k] : 0;
