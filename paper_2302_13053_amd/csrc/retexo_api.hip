@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include "common.hpp"
+#include "tiles.hpp"
 
 namespace {
 
@@ -325,22 +326,43 @@ int launch_zero(void* p, size_t bytes, hipStream_t stream)
 
 namespace {
 // out[v, c] = (1 / heads) * sum_h in[v, h * C + c]; heads added in index order.
-// A row takes 2^lg consecutive threads (2^lg >= C, the surplus idle), so that row and column come from a
-// shift and a mask and the loads of one head are consecutive addresses.
-__global__ __launch_bounds__(256) void head_mean_kernel(int64_t N, int heads, int C, int lg, const float* __restrict__ in,
-                                                         int64_t ldi, float* __restrict__ out, int64_t ldo)
+// Rows of up to 1,024 input columns: a workgroup stages kRowsPerBlock whole rows in LDS with the widest loads
+// the layout allows (a row is one contiguous piece of memory whatever C is: 4 x 47 columns are 47 float4), then
+// every thread adds the heads of its output elements from LDS and the outputs leave as consecutive addresses.
+constexpr int kHeadMeanMaxWidth = 1024;
+template <bool VEC>
+__global__ __launch_bounds__(256) void head_mean_kernel(int64_t N, int heads, int C, int rows_per_block,
+                                                         const float* __restrict__ in, int64_t ldi,
+                                                         float* __restrict__ out, int64_t ldo)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t v = i >> lg;
-    const int c = (int)(i & ((1 << lg) - 1));
-    if (v >= N || c >= C) return;
-    const float* row = in + v * ldi + c;
-    float s = 0.0f;
-    for (int h = 0; h < heads; ++h) s += row[h * C];
-    out[v * ldo + c] = s / (float)heads;
+    __shared__ __align__(16) float stage[4 * kHeadMeanMaxWidth];
+    const int W = heads * C;                      // input columns of a row
+    const int pitch = VEC ? (W + 3) / 4 * 4 : W;  // floats per staged row (VEC: whole float4, ldi covers them)
+    const int64_t v0 = (int64_t)blockIdx.x * rows_per_block;
+    const int rows = (int)(N - v0 < rows_per_block ? N - v0 : rows_per_block);
+    if constexpr (VEC) {
+        const int per_row = pitch / 4;
+        for (int i = threadIdx.x; i < rows * per_row; i += 256) {
+            const int r = i / per_row, q = i % per_row;
+            *reinterpret_cast<f32x4*>(&stage[r * pitch + 4 * q]) =
+                *reinterpret_cast<const f32x4*>(in + (v0 + r) * ldi + 4 * q);
+        }
+    } else {
+        for (int i = threadIdx.x; i < rows * W; i += 256) {
+            const int r = i / W, q = i % W;
+            stage[r * pitch + q] = in[(v0 + r) * ldi + q];
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < rows * C; i += 256) {
+        const int r = i / C, c = i % C;
+        float sum = 0.0f;
+        for (int h = 0; h < heads; ++h) sum += stage[r * pitch + h * C + c];
+        out[(v0 + r) * ldo + c] = sum / (float)heads;
+    }
 }
 
-// the same for rows wider than 256 columns: one thread per element
+// wider rows: one thread per element
 __global__ __launch_bounds__(256) void head_mean_wide_kernel(int64_t N, int heads, int64_t C, const float* __restrict__ in,
                                                               int64_t ldi, float* __restrict__ out, int64_t ldo)
 {
@@ -362,12 +384,16 @@ extern "C" int retexo_head_mean(int64_t N, int heads, int64_t C, const float* d_
     if (N == 0 || C == 0) return RETEXO_OK;
     if (!d_in || !d_out) return RETEXO_E_NULL;
     if (overlaps(d_in, extent_bytes(N, ldi, heads * C), d_out, extent_bytes(N, ldo, C))) return RETEXO_E_ALIAS;
-    if (C <= 256) {
-        int lg = 0;
-        while ((1ll << lg) < C) ++lg;
-        const int64_t threads = N << lg;
-        head_mean_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-            N, heads, (int)C, lg, d_in, ldi, d_out, ldo);
+    if (heads * C <= kHeadMeanMaxWidth) {
+        const int W = (int)(heads * C);
+        const bool vec = (uintptr_t)d_in % 16 == 0 && ldi % 4 == 0 && (W + 3) / 4 * 4 <= ldi;
+        const int pitch = vec ? (W + 3) / 4 * 4 : W;
+        const int rows_per_block = 4 * kHeadMeanMaxWidth / pitch;          // at least 4
+        const unsigned grid = (unsigned)((N + rows_per_block - 1) / rows_per_block);
+        if (vec) head_mean_kernel<true><<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(
+                     N, heads, (int)C, rows_per_block, d_in, ldi, d_out, ldo);
+        else     head_mean_kernel<false><<<dim3(grid), dim3(256), 0, (hipStream_t)stream>>>(
+                     N, heads, (int)C, rows_per_block, d_in, ldi, d_out, ldo);
     } else {
         head_mean_wide_kernel<<<dim3((unsigned)((N * C + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
             N, heads, C, d_in, ldi, d_out, ldo);

@@ -330,7 +330,9 @@ def test_in_place_concat_and_argument_errors(graphs):
 
 
 @pytest.mark.parametrize("n,heads,C,ldi,ldo", [(1000, 4, 47, 188, 47), (513, 8, 7, 64, 9), (3, 1, 5, 5, 5), (0, 2, 3, 6, 3),
-                                              (50, 2, 300, 608, 300), (77, 4, 64, 256, 64)])
+                                              (50, 2, 300, 608, 300), (77, 4, 64, 256, 64),
+                                              (100, 3, 7, 24, 8),            # 21 input columns staged as 24
+                                              (20, 4, 300, 1200, 304)])      # rows too wide for the staging kernel
 def test_head_mean(n, heads, C, ldi, ldo):
     """The last attention round's heads are averaged: plain definition (float64 mean over the head axis)."""
     X = wl.random_matrix(max(n, 1), heads * C, 5, ld=ldi)[:n]
