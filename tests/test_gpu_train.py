@@ -42,6 +42,7 @@ def compare(got, want, what):
         assert_close(gbc[None, :], wbc[None, :], what=what + " gbc")
 
 
+@pytest.mark.usefixtures("transform_family")
 @pytest.mark.parametrize("n,d_in,h,c,ld", [
     (1000, 37, 5, 3, 37),          # nothing aligned
     (4099, 128, 64, 8, 128),       # aligned, ragged node count
@@ -210,6 +211,7 @@ def test_large_sage_layer_full_size_sampled_labels():
     compare(got, want, "full-size SAGE layer")
 
 
+@pytest.mark.usefixtures("transform_family")
 @pytest.mark.parametrize("n,d_in,h,c,ld", [
     (1000, 37, 5, 3, 37), (4099, 128, 64, 8, 128), (3000, 128, 0, 7, 128), (2500, 256, 256, 47, 256), (130, 16, 300, 5, 16),
 ])
@@ -237,6 +239,7 @@ def test_input_gradient_matches_oracle(n, d_in, h, c, ld):
         Hn.layer_grad(Xd, d_in, d(y), d(W1), d(b1), d(Wc), d(bc), workspace=ws, gX=Xd)
 
 
+@pytest.mark.usefixtures("transform_family")
 @pytest.mark.parametrize("n,d_in,d_out,ldh,ldz", [(1000, 37, 5, 37, 5), (4099, 100, 256, 128, 256), (70000, 256, 188, 256, 192),
                                                    (3, 1, 1, 1, 1), (513, 300, 700, 304, 704)])
 def test_transform_backward_matches_oracle(n, d_in, d_out, ldh, ldz):

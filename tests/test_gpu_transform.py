@@ -12,15 +12,10 @@ from parity import assert_close
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["few_rows", "row_blocks"])
-def kernel_family(request):
-    """Matrices of these sizes take the few-rows kernel (K split over the waves of 32-row workgroups); every
-    test runs a second time with that kernel switched off, i.e. on the 128-row block kernels that large
-    matrices take."""
-    B.load()
-    B.check(B.retexo_set_option("transform_few_blocks", 128 if request.param == "few_rows" else 0), "set_option")
-    yield request.param
-    B.check(B.retexo_set_option("transform_few_blocks", 128), "set_option")
+@pytest.fixture(autouse=True)
+def kernel_family(transform_family):
+    """Every test of this file runs on both kernel families."""
+    return transform_family
 
 
 def run(n, d_in, d_out, ldh, ldz, relu, bias, seed):
