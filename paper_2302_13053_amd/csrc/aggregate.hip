@@ -320,10 +320,17 @@ __global__ __launch_bounds__(64 * NW) void agg_grouped_kernel(AggArgs a)
     }
 
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    // the ids (and weights) of a wave's next tile are requested before the current tile's rows
+    int nxt_u = lo + 64 * wave + lane < hi ? a.col_idx[lo + 64 * wave + lane] : 0;
+    float nxt_w = WEIGHTED ? (lo + 64 * wave + lane < hi ? a.wsrc[nxt_u] : 0.0f) : 1.0f;
     for (int base = lo + 64 * wave; base < hi; base += 64 * NW) {
-        const int e = base + lane;
-        const int my_u = e < hi ? a.col_idx[e] : 0;
-        const float my_w = WEIGHTED ? (e < hi ? a.wsrc[my_u] : 0.0f) : 1.0f;
+        const int my_u = nxt_u;
+        const float my_w = nxt_w;
+        {
+            const int en = base + 64 * NW + lane;
+            nxt_u = en < hi ? a.col_idx[en] : 0;
+            nxt_w = WEIGHTED ? (en < hi ? a.wsrc[nxt_u] : 0.0f) : 1.0f;
+        }
         const int cnt = min(64, hi - base);
         const uint32_t my_off = OFF32 ? (uint32_t)my_u * (uint32_t)rowbytes : 0u;
         if (cnt == 64)
@@ -487,52 +494,57 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
             my_off[k] = OFF32 ? (uint32_t)my_u[k] * (uint32_t)rowbytes : 0u;
         }
         fetch_ids(s0 + BLOCK);              // the next block, a whole block ahead of its use
+        // steps of U entries; the gathers of step st + 1 are issued before those of step st are added up, so a
+        // wave has up to 2 U row pieces in flight (two register sets, picked by the parity of the unrolled step)
+        constexpr int T = BLOCK / U;
+        f32x4 z[2][U];
+        float w[2][U];
+        auto issue = [&](int e0, f32x4 (&zz)[U], float (&ww)[U]) {       // e0: first entry of the step in the block
 #pragma unroll
-        for (int q = 0; q < IPL; ++q) {
-            const int c0 = s0 + q * LPG;
+            for (int t = 0; t < U; ++t) {
+                const int e = e0 + t;              // entry of the block: lane e / IPL, component e % IPL
+                if constexpr (OFF32) {
+                    const uint32_t off =
+                        (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), (int)my_off[e % IPL]) + colbytes;
+                    zz[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+                } else {
+                    const int u = __builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), my_u[e % IPL]);
+                    zz[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
+                }
+                if constexpr (WEIGHTED)
+                    ww[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), __float_as_int(my_w[e % IPL])));
+            }
+        };
+        issue(0, z[0], w[0]);
+#pragma unroll
+        for (int st = 0; st < T; ++st) {
+            const int c0 = s0 + st * U;
             if (c0 >= maxlen) break;                   // (uniform)
-            const bool full = c0 + LPG <= minlen;      // every group still has LPG entries: no masking
-#pragma unroll
-            for (int i0 = 0; i0 < LPG; i0 += U) {
-                f32x4 z[U];
-                float w[U];
-#pragma unroll
-                for (int t = 0; t < U; ++t) {
-                    const int e = q * LPG + i0 + t;    // entry of the block: lane e / 4, component e % 4
-                    if constexpr (OFF32) {
-                        const uint32_t off =
-                            (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), (int)my_off[e % IPL]) + colbytes;
-                        z[t] = *reinterpret_cast<const f32x4*>(zbase + off);
-                    } else {
-                        const int u = __builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), my_u[e % IPL]);
-                        z[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
-                    }
-                    if constexpr (WEIGHTED)
-                        w[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), __float_as_int(my_w[e % IPL])));
-                }
-                if (!full) {
-#pragma unroll
-                    for (int t = 0; t < U; ++t) {
-                        const bool ok = c0 + i0 + t < len;
-                        z[t].x = ok ? z[t].x : 0.0f;
-                        z[t].y = ok ? z[t].y : 0.0f;
-                        z[t].z = ok ? z[t].z : 0.0f;
-                        z[t].w = ok ? z[t].w : 0.0f;
-                    }
-                }
+            if (st + 1 < T && c0 + U < maxlen) issue((st + 1) * U, z[(st + 1) & 1], w[(st + 1) & 1]);
+            f32x4 (&zc)[U] = z[st & 1];
+            float (&wc)[U] = w[st & 1];
+            if (c0 + U > minlen) {                     // some group's row ends inside this step: mask
 #pragma unroll
                 for (int t = 0; t < U; ++t) {
-                    if constexpr (WEIGHTED) {
-                        acc[0] = fmaf(w[t], z[t].x, acc[0]);
-                        acc[1] = fmaf(w[t], z[t].y, acc[1]);
-                        acc[2] = fmaf(w[t], z[t].z, acc[2]);
-                        acc[3] = fmaf(w[t], z[t].w, acc[3]);
-                    } else {
-                        acc[0] += z[t].x;
-                        acc[1] += z[t].y;
-                        acc[2] += z[t].z;
-                        acc[3] += z[t].w;
-                    }
+                    const bool ok = c0 + t < len;
+                    zc[t].x = ok ? zc[t].x : 0.0f;
+                    zc[t].y = ok ? zc[t].y : 0.0f;
+                    zc[t].z = ok ? zc[t].z : 0.0f;
+                    zc[t].w = ok ? zc[t].w : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < U; ++t) {
+                if constexpr (WEIGHTED) {
+                    acc[0] = fmaf(wc[t], zc[t].x, acc[0]);
+                    acc[1] = fmaf(wc[t], zc[t].y, acc[1]);
+                    acc[2] = fmaf(wc[t], zc[t].z, acc[2]);
+                    acc[3] = fmaf(wc[t], zc[t].w, acc[3]);
+                } else {
+                    acc[0] += zc[t].x;
+                    acc[1] += zc[t].y;
+                    acc[2] += zc[t].z;
+                    acc[3] += zc[t].w;
                 }
             }
         }
