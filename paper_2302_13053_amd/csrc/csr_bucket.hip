@@ -674,7 +674,14 @@ __global__ __launch_bounds__(kSortThreads, 8) void sort_kernel(
         }
         if (tid == 0) sh.sp = 0u;
     } else if (tid == 0) {
-        sh.stk_lo[0] = 0u; sh.stk_hi[0] = 0xffffffffu; sh.stk_bits[0] = 32u; sh.stk_cnt[0] = E; sh.sp = 1u;
+        // the walk starts at the bits the bucket's keys really use (its rows, then the columns): a bucket of
+        // eight hot rows would otherwise spend three counting passes on key bits that are all zero
+        const uint32_t kb = (uint32_t)cbits + (nrows > 1 ? 32u - (uint32_t)__clz((uint32_t)(nrows - 1)) : 0u);
+        sh.stk_lo[0] = 0u;
+        sh.stk_hi[0] = kb >= 32u ? 0xffffffffu : (1u << kb) - 1u;
+        sh.stk_bits[0] = kb >= 32u ? 32u : kb;
+        sh.stk_cnt[0] = E;
+        sh.sp = 1u;
     }
     __syncthreads();
     for (bool first = true;; first = false) {
