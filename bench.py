@@ -462,6 +462,26 @@ def extras(out, w, pipe, args, timer, reps, di, Zin, agg_out, ws, agg_ms):
         del Z16
     except B.RetexoError:
         pass
+    # The same aggregation call when every gathered row is an L2 hit: the graph keeps its rows, their lengths and
+    # their split over the source ranges, but inside each of the plan's sixteen ranges the columns are squeezed
+    # (monotonically) into a window of 1,024 sources, so that the 32-column slab of four ranges is 512 KB.  What
+    # remains is the kernels' own request rate: how close the real call is to it says what the L2 misses cost.
+    if w.index == 3 and not gat:
+        group = (n + 15) // 16                            # sources per range of the plan's split
+        col = pipe.col_idx[:nnz].to(torch.int64)
+        base = (col // group) * group
+        squeezed = (base + ((col - base) * 1024) // group).to(torch.int32)
+        del col, base
+        lg = Hn.DeviceGraph(n, int(nnz), pipe.row_ptr, squeezed)
+        Hn.make_plan(lg, split_rows=True)
+        l2_ms = timer.ms(lambda: Hn.aggregate(lg, dst_stage.mode, Zin, F, concat=dst_stage.concat, out=agg_out,
+                                              workspace=ws), reps)
+        out["roofline"]["same_call_all_gathers_in_l2"] = {
+            "what": "same rows, row lengths and range split; the columns of each of the sixteen ranges squeezed into 1024 sources",
+            "ms": l2_ms, "gather_model_TB/s": out["roofline"]["effective_gather"]["bytes"] / l2_ms / 1e9,
+            "real_call_ms_over_this": agg_ms / l2_ms}
+        lg.destroy()
+        del squeezed
     # the partition-shaped run: worker 0's share of this graph (seeded random ownership over 4 workers for the
     # dense graph, 2 for the large sparse one, as the paper distributes them); the pack of what it owes its peers,
     # the unpack of what it receives, and the first round's aggregation on its local graph
