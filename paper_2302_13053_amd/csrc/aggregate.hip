@@ -499,40 +499,39 @@ __global__ __launch_bounds__(64 * kLightWaves) void agg_rowgroup_kernel(AggArgs 
         constexpr int T = BLOCK / U;
         f32x4 z[2][U];
         float w[2][U];
-        auto issue = [&](int e0, f32x4 (&zz)[U], float (&ww)[U]) {       // e0: first entry of the step in the block
+        // e0: first entry of the step in the block, c0: the same counted from the start of the row's share.  Lanes
+        // whose group has no such entry (a shorter row of the bundle, or columns past the row width) issue no
+        // load at all: the kernel keeps the address units busy 96 % of its time, and a sixth of the gathers of a
+        // bundle are such fillers.
+        auto issue = [&](int e0, int c0, f32x4 (&zz)[U], float (&ww)[U]) {
+            const bool all = act && c0 + U <= minlen && has_row;       // no filler in this step for this lane
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 const int e = e0 + t;              // entry of the block: lane e / IPL, component e % IPL
+                const bool ok = all || (act && c0 + t < len);
+                const char* src;
                 if constexpr (OFF32) {
                     const uint32_t off =
                         (uint32_t)__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), (int)my_off[e % IPL]) + colbytes;
-                    zz[t] = *reinterpret_cast<const f32x4*>(zbase + off);
+                    src = zbase + off;
                 } else {
                     const int u = __builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), my_u[e % IPL]);
-                    zz[t] = *reinterpret_cast<const f32x4*>(zbase + (int64_t)u * rowbytes + colbytes);
+                    src = zbase + (int64_t)u * rowbytes + colbytes;
                 }
+                zz[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (ok) zz[t] = *reinterpret_cast<const f32x4*>(src);
                 if constexpr (WEIGHTED)
                     ww[t] = __int_as_float(__builtin_amdgcn_ds_bpermute(gaddr + 4 * (e / IPL), __float_as_int(my_w[e % IPL])));
             }
         };
-        issue(0, z[0], w[0]);
+        issue(0, s0, z[0], w[0]);
 #pragma unroll
         for (int st = 0; st < T; ++st) {
             const int c0 = s0 + st * U;
             if (c0 >= maxlen) break;                   // (uniform)
-            if (st + 1 < T && c0 + U < maxlen) issue((st + 1) * U, z[(st + 1) & 1], w[(st + 1) & 1]);
+            if (st + 1 < T && c0 + U < maxlen) issue((st + 1) * U, c0 + U, z[(st + 1) & 1], w[(st + 1) & 1]);
             f32x4 (&zc)[U] = z[st & 1];
             float (&wc)[U] = w[st & 1];
-            if (c0 + U > minlen) {                     // some group's row ends inside this step: mask
-#pragma unroll
-                for (int t = 0; t < U; ++t) {
-                    const bool ok = c0 + t < len;
-                    zc[t].x = ok ? zc[t].x : 0.0f;
-                    zc[t].y = ok ? zc[t].y : 0.0f;
-                    zc[t].z = ok ? zc[t].z : 0.0f;
-                    zc[t].w = ok ? zc[t].w : 0.0f;
-                }
-            }
 #pragma unroll
             for (int t = 0; t < U; ++t) {
                 if constexpr (WEIGHTED) {
